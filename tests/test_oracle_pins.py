@@ -1,0 +1,326 @@
+"""Pins the CPU oracle to things other than itself (CPU only).
+
+Product (O1): dense float64 GEMM, identity / diagonal / permutation A, exactly
+representable integers, P^T (P A) B == A B, column-slab independence, N = 1.
+Blocking (O2): brute-force tile counting on dense boolean matrices, closed forms
+(dense, diagonal, band), the bounds of Eq. 2, reconstruction of A from BCSR.
+Permutation (O3): hand-worked cases (tests/golden), invariants checked with exact
+fractions on a dense representation, planted structure, band => identity.
+"""
+import json
+import os
+from fractions import Fraction
+
+import numpy as np
+import pytest
+
+from oracle import smat_ref as R
+from workloads import random_csr, band_csr, dense_from_bits, from_bits, to_bits, make_config, Workload
+
+GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
+
+
+def _vals(w):
+    return R.decode16(w.a_bits, w.dtype), R.decode16(w.b_bits, w.dtype)
+
+
+# ------------------------------------------------------------------ decode
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_decode16_matches_generator_encoding_on_all_finite_patterns(dtype):
+    bits = np.arange(65536, dtype=np.uint16)
+    got = R.decode16(bits, dtype)
+    want = from_bits(bits, dtype)
+    finite = np.isfinite(want)
+    assert np.array_equal(got[finite], want[finite])
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+    # a few values known from the formats themselves
+    if dtype == "f16":
+        assert R.decode16([0x3C00, 0xC000, 0x0001, 0x7BFF], dtype).tolist() == [1.0, -2.0, 2.0 ** -24, 65504.0]
+    else:
+        assert R.decode16([0x3F80, 0xC000, 0x3F00], dtype).tolist() == [1.0, -2.0, 0.5]
+
+
+def test_rounding_is_nearest_even():
+    # 1 + 2^-11 lies exactly between two fp16 numbers -> even mantissa (1.0); 1 + 3*2^-11 -> 1 + 2^-9
+    assert from_bits(to_bits(np.array([1 + 2.0 ** -11, 1 + 3 * 2.0 ** -11]), "f16"), "f16").tolist() == [1.0, 1 + 2.0 ** -9]
+    assert from_bits(to_bits(np.array([1 + 2.0 ** -8, 1 + 3 * 2.0 ** -8]), "bf16"), "bf16").tolist() == [1.0, 1 + 2.0 ** -6]
+
+
+# ------------------------------------------------------------------ O1 product
+@pytest.mark.parametrize("density", [0.0, 0.05, 0.5, 1.0])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_spmm_equals_dense_gemm(density, dtype):
+    w = random_csr(48, 40, 7, density, seed=3, dtype=dtype)
+    a, b = _vals(w)
+    c, s = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, w.col_idx, a, b)
+    ad = dense_from_bits(w)
+    np.testing.assert_allclose(c, ad @ b, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(s, np.abs(ad) @ np.abs(b), rtol=1e-13, atol=1e-15)
+
+
+def _csr_of_dense(a):
+    M, K = a.shape
+    rows, cols = np.nonzero(a)
+    rp = np.zeros(M + 1, np.int64)
+    np.cumsum(np.bincount(rows, minlength=M), out=rp[1:])
+    return rp, cols.astype(np.int32), a[rows, cols]
+
+
+def test_spmm_identity_diagonal_permutation():
+    rng = np.random.default_rng(5)
+    n, N = 37, 5
+    b = rng.standard_normal((n, N))
+    rp, ci, v = _csr_of_dense(np.eye(n))
+    c, s = R.spmm_ref(n, n, N, rp, ci, v, b)
+    assert np.array_equal(c, b) and np.array_equal(s, np.abs(b))
+    d = rng.uniform(0.5, 2.0, n)
+    rp, ci, v = _csr_of_dense(np.diag(d))
+    c, _ = R.spmm_ref(n, n, N, rp, ci, v, b)
+    assert np.array_equal(c, d[:, None] * b)
+    p = rng.permutation(n)
+    pm = np.zeros((n, n))
+    pm[np.arange(n), p] = 1.0
+    rp, ci, v = _csr_of_dense(pm)
+    c, _ = R.spmm_ref(n, n, N, rp, ci, v, b)
+    assert np.array_equal(c, b[p])
+
+
+def test_spmm_small_integers_exact_and_transpose_sensitive():
+    # non-square, integer valued: any index slip (row/col swapped, wrong B row) changes the integers
+    w = random_csr(33, 50, 6, 0.2, seed=11, values="smallint", b_dist="smallint")
+    a, b = _vals(w)
+    c, _ = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, w.col_idx, a, b)
+    want = dense_from_bits(w).astype(np.int64) @ b.astype(np.int64)
+    assert np.array_equal(c, want.astype(np.float64))
+
+
+def test_spmm_row_permutation_invariance_and_slabs_and_spmv():
+    w = random_csr(64, 64, 8, 0.1, seed=2)
+    a, b = _vals(w)
+    c, _ = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, w.col_idx, a, b)
+    # (P A) B then undo P
+    p = np.random.default_rng(0).permutation(w.M)
+    cnt = np.diff(w.row_ptr)[p]
+    rp = np.zeros(w.M + 1, np.int64)
+    np.cumsum(cnt, out=rp[1:])
+    idx = np.concatenate([np.arange(w.row_ptr[r], w.row_ptr[r + 1]) for r in p]).astype(np.int64)
+    cp, _ = R.spmm_ref(w.M, w.K, w.N, rp, w.col_idx[idx], a[idx], b)
+    back = np.empty_like(cp)
+    back[p] = cp
+    assert np.array_equal(back, c)
+    # column slabs are independent
+    cl, _ = R.spmm_ref(w.M, w.K, 3, w.row_ptr, w.col_idx, a, np.ascontiguousarray(b[:, :3]))
+    assert np.array_equal(cl, c[:, :3])
+    # N = 1 is SpMV
+    c1, _ = R.spmm_ref(w.M, w.K, 1, w.row_ptr, w.col_idx, a, np.ascontiguousarray(b[:, :1]))
+    np.testing.assert_allclose(c1[:, 0], dense_from_bits(w) @ b[:, 0], rtol=1e-13, atol=1e-15)
+
+
+def test_c_spmm_equals_python_and_dense(oracle_c):
+    for seed, (M, K, N, d, dt) in enumerate([(70, 90, 9, 0.1, "f16"), (33, 17, 1, 0.5, "bf16"), (16, 16, 64, 0.0, "f16")]):
+        w = random_csr(M, K, N, d, seed=seed, dtype=dt)
+        a, b = _vals(w)
+        c_py, s_py = R.spmm_ref(M, K, N, w.row_ptr, w.col_idx, a, b)
+        c_c, s_c = oracle_c.spmm_ref_c(M, K, N, w.row_ptr, w.col_idx, a, b)
+        assert np.array_equal(c_c, c_py) and np.array_equal(s_c, s_py)
+    w = make_config("tiny")
+    a, b = _vals(w)
+    c_c, s_c = oracle_c.spmm_ref_c(w.M, w.K, w.N, w.row_ptr, w.col_idx, a, b)
+    ad = dense_from_bits(w)
+    np.testing.assert_allclose(c_c, ad @ b, rtol=1e-12, atol=1e-14)
+    np.testing.assert_allclose(s_c, np.abs(ad) @ np.abs(b), rtol=1e-12, atol=1e-14)
+
+
+# ------------------------------------------------------------------ O2 blocking
+def _patterns(w):
+    return R.block_pattern(w.M, w.row_ptr, w.col_idx)
+
+
+@pytest.mark.parametrize("shape", [(16, 16), (17, 31), (50, 70), (64, 48), (1, 1), (15, 100)])
+@pytest.mark.parametrize("density", [0.0, 0.02, 0.3, 1.0])
+def test_block_count_bruteforce_and_eq2_bounds(shape, density):
+    M, K = shape
+    w = random_csr(M, K, 1, density, seed=M * 131 + K)
+    pats = _patterns(w)
+    rng = np.random.default_rng(M + K)
+    for perm in (np.arange(M), rng.permutation(M)):
+        n_e = R.count_blocks(pats, perm)
+        dense = dense_from_bits(w) != 0
+        # uniform values are never exactly 0 here, so the value pattern is the structural one
+        assert n_e == R.count_blocks_bruteforce(dense[perm])
+        nnz = w.nnz
+        nbr, nbc = -(-M // 16), -(-K // 16)
+        assert nnz / 256 <= n_e <= min(nbr * nbc, nnz)          # Eq. 2
+
+
+def test_block_count_closed_forms():
+    # dense: every grid tile; diagonal: one tile per block row; band of half-width b on the
+    # 16-grid: block columns floor((16r-b)/16) .. floor((16r+15+b)/16), clipped to the matrix
+    M = 80
+    full = Workload("d", "f16", M, M, 1, np.arange(0, M * M + 1, M, dtype=np.int64),
+                    np.tile(np.arange(M, dtype=np.int32), M), np.ones(M * M, np.uint16), np.zeros((M, 1), np.uint16))
+    assert R.count_blocks(_patterns(full), np.arange(M)) == 25
+    diag = band_csr(100, 0, 1, seed=0)
+    assert R.count_blocks(_patterns(diag), np.arange(100)) == 7
+    for n, b in [(256, 64), (160, 5), (96, 16), (64, 200)]:
+        w = band_csr(n, b, 1, seed=1, p=1.0)
+        nbr = n // 16
+        want = sum(min(nbr - 1, (16 * r + 15 + b) // 16) - max(0, (16 * r - b) // 16) + 1 for r in range(nbr))
+        assert R.count_blocks(_patterns(w), np.arange(n)) == want
+
+
+@pytest.mark.parametrize("shape,density", [((40, 56), 0.1), ((16, 16), 1.0), ((33, 20), 0.0), ((70, 70), 0.03)])
+def test_bcsr_reconstructs_matrix(shape, density):
+    M, K = shape
+    w = random_csr(M, K, 1, density, seed=9, dtype="bf16")
+    perm = np.random.default_rng(1).permutation(M).astype(np.int32)
+    rowPtr, col, val = R.bcsr_from_csr(M, K, w.row_ptr, w.col_idx, w.a_bits, perm)
+    nbr, nbc = -(-M // 16), -(-K // 16)
+    assert rowPtr[0] == 0 and rowPtr[-1] == col.size == val.shape[0] and len(rowPtr) == nbr + 1
+    dense_bits = np.zeros((nbr * 16, nbc * 16), np.uint16)
+    for I in range(nbr):
+        cs = col[rowPtr[I]:rowPtr[I + 1]]
+        assert np.all(np.diff(cs) > 0)                           # ascending, no duplicate block
+        for n, J in zip(range(rowPtr[I], rowPtr[I + 1]), cs):
+            assert val[n].any()                                   # only nonzero blocks are stored
+            dense_bits[16 * I:16 * I + 16, 16 * J:16 * J + 16] = val[n]
+    want = np.zeros_like(dense_bits)
+    rows = np.repeat(np.arange(M), np.diff(w.row_ptr))
+    want[rows, w.col_idx] = w.a_bits
+    want[:M] = want[:M][perm]
+    assert np.array_equal(dense_bits, want)
+    assert col.size == R.count_blocks_bruteforce(want != 0)
+    f = R.bcsr_from_csr_fast(M, K, w.row_ptr, w.col_idx, w.a_bits, perm)
+    assert np.array_equal(f[0], rowPtr) and np.array_equal(f[1], col) and np.array_equal(f[2], val)
+    assert f[0].dtype == np.int32 and f[1].dtype == np.int32 and f[2].dtype == np.uint16
+
+
+def test_pattern_csr_and_count_c_equal_python(oracle_c):
+    for seed in range(6):
+        M, K = 30 + 7 * seed, 20 + 13 * seed
+        w = random_csr(M, K, 1, 0.08, seed=seed)
+        pats = _patterns(w)
+        pp, pi = oracle_c.block_pattern_csr(M, K, w.row_ptr, w.col_idx)
+        assert [list(pi[pp[r]:pp[r + 1]]) for r in range(M)] == pats
+        perm = np.random.default_rng(seed).permutation(M).astype(np.int32)
+        assert oracle_c.count_blocks_c(M, pp, pi, -(-K // 16), perm) == R.count_blocks(pats, perm)
+
+
+# ------------------------------------------------------------------ O3 permutation
+def _golden_cases():
+    with open(os.path.join(GOLDEN, "jaccard_handworked.json")) as f:
+        return json.load(f)["cases"]
+
+
+@pytest.mark.parametrize("case", _golden_cases(), ids=lambda c: c["name"])
+def test_jaccard_handworked(case, oracle_c):
+    pats = [sorted(p) for p in case["patterns"]]
+    tau = case["tau_permille"]
+    assert R.jaccard_reorder(pats, tau).tolist() == case["order"]
+    clustered = [False] * len(pats)
+    got = [R.cluster_from_seed(pats, clustered, v, tau) for v in range(len(pats)) if not clustered[v]]
+    assert got == case["clusters"]
+    pp = np.zeros(len(pats) + 1, np.int64)
+    np.cumsum([len(p) for p in pats], out=pp[1:])
+    pi = np.asarray([c for p in pats for c in p], dtype=np.int32)
+    perm, ncl = oracle_c.jaccard_reorder_c(len(pats), pp, pi, 16, tau)
+    assert perm.tolist() == case["order"] and ncl == len(case["clusters"])
+
+
+def _check_clustering_postconditions(dense_rows, clusters, tau):
+    """dense_rows: boolean [M, nbc].  Verifies, with exact fractions on the dense rows, that
+    every merge and every non-merge obeys 'distance to the union so far < tau'."""
+    M = dense_rows.shape[0]
+    done = np.zeros(M, bool)
+    t = Fraction(tau, 1000)
+    for members in clusters:
+        seed = members[0]
+        assert seed == int(np.flatnonzero(~done)[0])              # lowest unclustered row opens
+        assert members == sorted(members)
+        pc = dense_rows[seed].copy()
+        done[seed] = True
+        mset = set(members)
+        for w in range(seed + 1, M):
+            if done[w]:
+                continue
+            inter = int((dense_rows[w] & pc).sum())
+            uni = int((dense_rows[w] | pc).sum())
+            dist = Fraction(0) if uni == 0 else 1 - Fraction(inter, uni)
+            if dist < t:
+                assert w in mset, (seed, w, dist)
+                pc |= dense_rows[w]
+                done[w] = True
+            else:
+                assert w not in mset, (seed, w, dist)
+    assert done.all()
+
+
+@pytest.mark.parametrize("tau", [0, 300, 500, 700, 900, 1000])
+def test_jaccard_postconditions_random(tau, oracle_c):
+    for seed in range(8):
+        M, K = 40 + 9 * seed, 16 * (3 + seed)
+        w = random_csr(M, K, 1, [0.01, 0.03, 0.1][seed % 3], seed=seed + 50)
+        pats = _patterns(w)
+        nbc = K // 16
+        dense_rows = np.zeros((M, nbc), bool)
+        for r, p in enumerate(pats):
+            dense_rows[r, p] = True
+        clustered = [False] * M
+        clusters = [R.cluster_from_seed(pats, clustered, v, tau) for v in range(M) if not clustered[v]]
+        _check_clustering_postconditions(dense_rows, clusters, tau)
+        order = R.jaccard_reorder(pats, tau)
+        assert order.tolist() == [r for c in clusters for r in c]
+        assert sorted(order.tolist()) == list(range(M))
+        if tau == 0:
+            assert order.tolist() == list(range(M))
+        pp, pi = oracle_c.block_pattern_csr(M, K, w.row_ptr, w.col_idx)
+        perm_c, ncl = oracle_c.jaccard_reorder_c(M, pp, pi, nbc, tau)
+        assert np.array_equal(perm_c, order) and ncl == len(clusters)
+        # single-cluster entry point of the C twin, from an arbitrary mid state
+        state = np.zeros(M, np.uint8)
+        state[clusters[0]] = 1
+        if len(clusters) > 1:
+            got = oracle_c.cluster_from_seed_c(M, pp, pi, nbc, tau, state, clusters[1][0])
+            assert got.tolist() == clusters[1]
+
+
+def test_jaccard_rejects_bad_tau():
+    with pytest.raises(ValueError):
+        R.jaccard_reorder([[0]], 1001)
+    with pytest.raises(ValueError):
+        R.jaccard_reorder([[0]], -1)
+
+
+def test_planted_groups_are_recovered_exactly():
+    # G groups of 16 rows; rows of a group share one pattern, groups use disjoint block columns;
+    # rows arrive shuffled.  Distance inside a group is 0, across groups 1, so for any
+    # 0 < tau <= 1000 the clusters are the groups, and n_e drops to one block row per group.
+    rng = np.random.default_rng(7)
+    G, per = 6, 3
+    group_of_row = np.repeat(np.arange(G), 16)
+    rng.shuffle(group_of_row)
+    pats = [[g * per + k for k in range(per)] for g in group_of_row]
+    for tau in (1, 500, 1000):
+        perm, n_e, n_id, used_identity = R.choose_perm(pats, tau)
+        assert not used_identity and n_e == G * per and n_id > n_e
+        for blk in range(G):
+            assert len({group_of_row[r] for r in perm[16 * blk:16 * blk + 16]}) == 1
+        firsts = [int(np.flatnonzero(group_of_row == group_of_row[perm[16 * b]])[0]) for b in range(G)]
+        assert firsts == sorted(firsts)                           # clusters in order of their seed
+
+
+def test_band_keeps_identity_and_guard_never_worse():
+    w = band_csr(512, 64, 1, seed=3, p=0.3)
+    pats = _patterns(w)
+    perm, n_e, n_id, used_identity = R.choose_perm(pats, 700)
+    assert used_identity and perm.tolist() == list(range(512)) and n_e == n_id
+    for seed in range(5):
+        w = random_csr(96, 160, 1, 0.02, seed=seed + 20)
+        pats = _patterns(w)
+        for tau in (300, 700, 1000):
+            perm, n_e, n_id, used_identity = R.choose_perm(pats, tau)
+            assert n_e <= n_id and n_e == R.count_blocks(pats, perm)
+            assert used_identity == (perm.tolist() == list(range(96))) or n_e == n_id
+    perm, n_e, n_id, used_identity = R.choose_perm(pats, 700, reorder=False)
+    assert used_identity and n_e == n_id

@@ -1,0 +1,16 @@
+"""Seeded synthetic inputs (CSR A, dense B) shared by the tests, the bench and the oracle checks.
+
+This package holds no arithmetic of the SpMM method itself: it only draws
+random sparsity patterns and values, rounds them to 16-bit storage and hands
+the same bits to whoever asks.
+"""
+from .configs import (  # noqa: F401
+    Workload,
+    CONFIG_NAMES,
+    make_config,
+    random_csr,
+    band_csr,
+    dense_from_bits,
+    to_bits,
+    from_bits,
+)
