@@ -1,0 +1,184 @@
+#!/usr/bin/env python3
+"""Benchmark of the blocked SpMM hot path on one MI355X.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config uniform]
+
+A step is one smat_spmm call (C = A.B on the preprocessed, device-resident BCSR matrix);
+the one-time preprocessing and the device bind are timed separately and reported in
+`config`, never folded into the step time (the paper also times the kernel only, section
+Methodology).  Prints ONE JSON line: useful TFLOP/s = 2*nnz*N / t, the roofline of the
+SpMM kernel (algorithmic HBM bytes per launch / average launch duration from HIP events
+on the launch stream, against 8 TB/s) and the CPU oracle timed on the host cores.
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+
+HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
+MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 matrix peak
+
+WORKLOAD_TEXT = {
+    "tiny": "tiny unstructured 1024x1024 1% fp16, B 1024x64",
+    "uniform": "unstructured random 16384x16384 0.1% fp16, B 16384x128 (GNN-like)",
+    "banded": "banded 65536x65536 |i-j|<=64 p=0.3 fp16, B 65536x256",
+    "powerlaw": "power-law graph 262144x262144 Zipf(1.2) mean 16 fp16, B 262144x64",
+    "hidden_blocks": "hidden 16x16 blocks 32768x32768 2% fp16, B 32768x256",
+    "pruned_weight": "pruned weight 4096x4096 90% sparse bf16, B 4096x2048",
+}
+
+# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), or None
+MEASURED_TRAFFIC_BYTES = {}
+
+
+def algorithmic_bytes(n_e, nbr, M, K, N):
+    """BCSR values + block columns, rowPtr and perm read once, B read once, C written once."""
+    return n_e * (512 + 4) + (nbr + 1) * 4 + M * 4 + K * N * 2 + M * N * 4
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--config", default="uniform", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--cold", action="store_true", help="also time launches with the caches flushed in between")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+
+    import torch
+    if not torch.cuda.is_available():
+        sys.exit("bench.py: no GPU visible; the SpMM path has no CPU fallback")
+    import paper_2408_11551_amd as S
+    from workloads import make_config
+
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    w = make_config(args.config, seed=args.seed)
+
+    t0 = time.perf_counter()
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    t_pre = time.perf_counter() - t0
+    info = S.smat_get_info(h)
+    ws = torch.empty(S.smat_device_bytes(h), dtype=torch.uint8, device=dev)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    S.smat_bind_device(h, ws)
+    t_bind = time.perf_counter() - t0
+
+    B = torch.from_numpy(w.b_bits.view(np.int16).reshape(w.K, w.N)).to(dev)
+    C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        S.smat_spmm(h, B, C, w.N, stream)
+    torch.cuda.synchronize()
+
+    # timed region: exactly K steps; HIP events on the launch stream bracket the region
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        S.smat_spmm(h, B, C, w.N, stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    ev_ms = ev0.elapsed_time(ev1)
+    kernel_name = S.smat_last_kernel()
+
+    ms_per_step = wall * 1e3 / args.steps
+    kernel_ms = ev_ms / args.steps                 # average launch duration on the stream
+    useful_flop = 2.0 * w.nnz * w.N
+    stored_flop = 2.0 * info["n_blocks"] * 256 * w.N
+    bytes_alg = algorithmic_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N)
+    achieved_gbs = bytes_alg / (kernel_ms * 1e-3) / 1e9
+
+    rp, _, _ = S.smat_export_bcsr(h, with_vals=False)
+    per_row = np.diff(rp)
+
+    extra = {}
+    if args.cold:
+        flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)     # > L2 + 256 MB Infinity Cache
+        evs = []
+        for _ in range(min(args.steps, 20)):
+            flush.add_(1)
+            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            a.record(stream)
+            S.smat_spmm(h, B, C, w.N, stream)
+            b.record(stream)
+            evs.append((a, b))
+        torch.cuda.synchronize()
+        cold = np.array([a.elapsed_time(b) for a, b in evs])
+        extra["cold_ms_mean"] = float(cold.mean())
+        extra["cold_ms_min"] = float(cold.min())
+        extra["cold_gbs"] = bytes_alg / (float(cold.mean()) * 1e-3) / 1e9
+        del flush
+
+    cpu = None
+    if not args.no_cpu_baseline:
+        from oracle import cref, smat_ref
+        a64 = smat_ref.decode16(w.a_bits, w.dtype)
+        b64 = smat_ref.decode16(w.b_bits, w.dtype)
+        # bounded sample: leading rows of A holding at most ~4e9 multiply-adds (whole matrix if smaller)
+        budget = 4e9
+        rows = int(np.searchsorted(w.row_ptr * float(w.N), budget, side="right")) - 1
+        rows = max(1, min(w.M, rows))
+        nnz_s = int(w.row_ptr[rows])
+        best = float("inf")
+        for _ in range(3):
+            t0 = time.perf_counter()
+            cref.spmm_ref_c(rows, w.K, w.N, w.row_ptr[:rows + 1], w.col_idx[:nnz_s], a64[:nnz_s], b64, want_abs=False)
+            best = min(best, time.perf_counter() - t0)
+        cpu = {"value": 2.0 * nnz_s * w.N / best / 1e12, "unit": "TFLOP/s",
+               "cores": min(cref.num_threads(), len(os.sched_getaffinity(0))), "kind": "oracle",
+               "sample": f"first {rows} of {w.M} rows ({nnz_s} nnz) x N={w.N}, fp64, best of 3, {best:.4f} s"}
+
+    out = {
+        "metric": "SpMM useful TFLOP/s (2*nnz*N)",
+        "value": useful_flop / (ms_per_step * 1e-3) / 1e12,
+        "unit": "TFLOP/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": ms_per_step,
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": w.dtype,
+        "data": "synthetic",
+        "config": {
+            "workload": WORKLOAD_TEXT[args.config], "name": args.config, "seed": args.seed,
+            "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
+            "n_blocks": info["n_blocks"], "n_blocks_identity": info["n_blocks_identity"],
+            "used_identity": info["used_identity"],
+            "blocks_per_row_mean": float(per_row.mean()) if per_row.size else 0.0,
+            "blocks_per_row_std": float(per_row.std()) if per_row.size else 0.0,
+            "blocks_per_row_max": int(per_row.max()) if per_row.size else 0,
+            "preprocess_s": t_pre, "bind_s": t_bind, "kernel": kernel_name, "cache": "hot (back-to-back launches)",
+        },
+        "stored_block_tflops": stored_flop / (kernel_ms * 1e-3) / 1e12,
+        "mfma_frac_stored_blocks": stored_flop / (kernel_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
+        "kernel_ms_events": kernel_ms,
+        "roofline": {
+            "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved_gbs / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "bytes_algorithmic": bytes_alg, "kernel": kernel_name,
+        },
+        "cpu_baseline": cpu,
+    }
+    out.update(extra)
+    S.smat_destroy(h)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -1,0 +1,155 @@
+/*
+ * smat.h -- C ABI of the MI355X (gfx950) blocked SpMM library.
+ *
+ * The library computes C = A * B for a sparse A given in CSR and a dense B
+ * (paper, Background section: C in F^{M x N}, A in F^{M x K} sparse, B in
+ * F^{K x N} dense).  Following the paper's pipeline (Overview section), A is
+ * preprocessed once: its rows are permuted, A' = P A, so that fewer h x w
+ * blocks of the fixed grid hold a nonzero (Preprocessing section), A' is
+ * stored as BCSR (Data Structures section) and every multiplication then
+ * walks the stored blocks of each block row and multiplies each with the
+ * matching rows of B on the matrix units (Implementation section, Alg. 1).
+ *
+ * Conventions for every entry point
+ *   - returns a smat_status_t, never throws or aborts; on error the out
+ *     parameters are left untouched and smat_last_error() holds a message
+ *     (thread local, valid until the next call on the same thread);
+ *   - pointers marked HOST are ordinary host memory, pointers marked DEVICE
+ *     are device memory of the current HIP device, owned by the caller;
+ *   - inputs are borrowed for the duration of the call only: the handle keeps
+ *     its own host copies and the device workspace passed to smat_bind_device;
+ *   - the library never allocates or frees device memory;
+ *   - there is no CPU fallback: smat_spmm needs a bound handle and a gfx950
+ *     device, anything else is an error.
+ */
+#ifndef SMAT_H
+#define SMAT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct smat_handle smat_handle_t;   /* opaque, owned by the library */
+
+typedef enum {
+    SMAT_OK = 0,
+    SMAT_ERR_INVALID_ARG = 1,   /* null pointer, negative size, bad option value      */
+    SMAT_ERR_BAD_CSR = 2,       /* row_ptr not monotone, column out of range or not
+                                   strictly ascending inside a row                     */
+    SMAT_ERR_UNSUPPORTED = 3,   /* block size other than 16x16, sizes beyond the limits */
+    SMAT_ERR_ALLOC = 4,         /* host allocation failed                               */
+    SMAT_ERR_NOT_BOUND = 5,     /* smat_spmm before smat_bind_device                    */
+    SMAT_ERR_HIP = 6            /* a HIP runtime call failed; text in smat_last_error   */
+} smat_status_t;
+
+typedef enum { SMAT_F16 = 0, SMAT_BF16 = 1 } smat_dtype_t;   /* storage type of A and B */
+
+typedef struct {
+    int block_h;        /* block height; only 16 is accepted                            */
+    int block_w;        /* block width;  only 16 is accepted                            */
+    int reorder;        /* 0: keep the row order (P = I); 1: Jaccard clustering, kept
+                           only if it yields strictly fewer blocks than the identity    */
+    int tau_permille;   /* merge threshold of the clustering in 1/1000, 0..1000: a row w
+                           joins a cluster with column union pc iff
+                           1 - |w n pc| / |w u pc| < tau_permille / 1000                 */
+} smat_options_t;
+
+/* Default options: 16 x 16 blocks, reordering on, tau = 0.7. */
+void smat_default_options(smat_options_t *opt);
+
+/*
+ * Preprocessing (Overview and Preprocessing sections): CSR -> row permutation
+ * that lowers the number of nonzero blocks -> BCSR structure.
+ *
+ *   M, K      rows / columns of A, 0 <= M, K < 2^31
+ *   row_ptr   HOST int64[M+1], row_ptr[0] == 0, non-decreasing
+ *   col_idx   HOST int32[nnz], strictly ascending inside each row, 0 <= col < K
+ *   vals      HOST 16-bit values [nnz] (fp16 or bf16 bit patterns per dtype);
+ *             a stored value of 0 still counts as a nonzero of the pattern
+ *   opt       may be NULL (defaults)
+ *   out       receives a new handle; release it with smat_destroy
+ *
+ * The row "pattern" used by the clustering is the set of block columns
+ * floor(c / 16) a row touches.  Clusters are opened by the lowest unclustered
+ * row and scanned in ascending row order with the cluster union updated after
+ * every merge; clusters are concatenated in creation order; perm[new] = old.
+ * Runs on the host, integer arithmetic only.
+ */
+smat_status_t smat_preprocess(int64_t M, int64_t K,
+                              const int64_t *row_ptr, const int32_t *col_idx, const void *vals,
+                              smat_dtype_t dtype, const smat_options_t *opt,
+                              smat_handle_t **out);
+
+/* Sizes and counts of the preprocessed matrix: number of block rows ceil(M/16),
+ * number of stored blocks n_e (Eq. 2 bounds it), n_e under the identity order,
+ * and whether the identity order was kept.  Any out pointer may be NULL. */
+smat_status_t smat_get_info(const smat_handle_t *h, int64_t *n_block_rows, int64_t *n_blocks,
+                            int64_t *n_blocks_identity, int *used_identity);
+
+/* perm: HOST int32[M], perm[new_row] = old_row (A' = P A, Overview section). */
+smat_status_t smat_export_perm(const smat_handle_t *h, int32_t *perm);
+
+/* Canonical BCSR of A' (Data Structures section), all HOST, caller allocated:
+ *   row_ptr int32[n_block_rows+1]  offsets into col_idx per block row
+ *   col_idx int32[n_blocks]        block column of each block, ascending per block row
+ *   vals    16-bit [n_blocks*256]  one 16x16 block after the other, row-major, zero filled
+ * vals may be NULL to export the structure only. */
+smat_status_t smat_export_bcsr(const smat_handle_t *h, int32_t *row_ptr, int32_t *col_idx, void *vals);
+
+/* Bytes of device workspace smat_bind_device needs for this handle. */
+smat_status_t smat_device_bytes(const smat_handle_t *h, size_t *bytes);
+
+/*
+ * Copies the preprocessed matrix into caller-owned device memory and builds the
+ * device-side block values there (the kernel's own block layout, a per-block
+ * column-occupancy mask, and a longest-first work order of the block rows).
+ *
+ *   dev_workspace  DEVICE, 256-byte aligned, at least smat_device_bytes() bytes,
+ *                  must stay alive and untouched until smat_destroy
+ *   stream         hipStream_t (NULL = default stream); the call enqueues copies
+ *                  and kernels on it and returns after they have completed
+ */
+smat_status_t smat_bind_device(smat_handle_t *h, void *dev_workspace, size_t bytes, void *stream);
+
+/* Reads the device-side block values back and returns them in the canonical
+ * layout of smat_export_bcsr (vals: HOST 16-bit [n_blocks*256]); used to verify
+ * the device-side conversion.  Synchronises the stream. */
+smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *stream);
+
+/*
+ * C = A * B on the device (Implementation section, Alg. 1: per output tile, loop
+ * over the stored blocks of the block row, multiply-accumulate on the matrix
+ * units), fp32 accumulation, rows of C in the ORIGINAL row order of A.
+ *
+ *   dB   DEVICE, K x N row-major, element type = dtype of the handle, leading
+ *        dimension ldb >= N (in elements)
+ *   dC   DEVICE, M x N row-major fp32, leading dimension ldc >= N; every element
+ *        of the M x N window is overwritten (rows of A without entries give 0)
+ *   N    >= 1 (N = 0 is a no-op); any value, any alignment: wide vector loads
+ *        are used when N, ldb and the base address allow it
+ *   stream  hipStream_t; the call only enqueues work (no synchronisation)
+ *
+ * Concurrent calls on different streams with different dC are allowed.
+ * Limits: the bytes of B that are addressed, ((K-1)*ldb + N)*2, must stay below 2 GiB;
+ * N <= 1048560.
+ */
+smat_status_t smat_spmm(const smat_handle_t *h, const void *dB, int64_t ldb,
+                        void *dC, int64_t ldc, int64_t N, void *stream);
+
+/* Frees the host state of the handle (never device memory).  NULL is allowed. */
+void smat_destroy(smat_handle_t *h);
+
+/* Message of the last error on the calling thread ("" if none). */
+const char *smat_last_error(void);
+
+/* Name of the SpMM kernel variant chosen by the last smat_spmm on this thread
+ * (for profiles and logs). */
+const char *smat_last_kernel(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* SMAT_H */

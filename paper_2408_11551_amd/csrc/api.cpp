@@ -1,0 +1,285 @@
+// C ABI of the library (see include/smat.h): handle management, argument checks,
+// host <-> device copies.  All arithmetic of the method lives in preprocess.cpp
+// (host, integers) and kernels.hip (device).
+#include "../../include/smat.h"
+
+#include <hip/hip_runtime_api.h>
+
+#include <cstdio>
+#include <cstring>
+#include <new>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+#include "preprocess.h"
+
+struct smat_handle {
+    smat::Csr csr;
+    smat::Bcsr bcsr;
+    smat_dtype_t dtype = SMAT_F16;
+    bool bound = false;
+    smat::DeviceBcsr dev;
+    // device copies of the CSR (kept: they live in the caller's workspace anyway)
+    const int64_t* d_csr_row_ptr = nullptr;
+    const int32_t* d_csr_col_idx = nullptr;
+    const uint16_t* d_csr_vals = nullptr;
+};
+
+namespace {
+
+thread_local std::string g_error;
+thread_local const char* g_kernel = "";
+
+smat_status_t fail(smat_status_t st, const std::string& msg)
+{
+    g_error = msg;
+    return st;
+}
+
+smat_status_t hip_fail(const char* what, int err)
+{
+    return fail(SMAT_ERR_HIP, std::string(what) + ": " + hipGetErrorString(static_cast<hipError_t>(err)));
+}
+
+constexpr size_t kAlign = 256;
+size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
+
+// Workspace layout, every section aligned to 256 bytes.
+struct Layout {
+    size_t perm, row_ptr, meta, order, vals, csr_row_ptr, csr_col_idx, csr_vals, total;
+};
+
+Layout make_layout(const smat_handle& h)
+{
+    Layout l{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes); return at; };
+    const size_t nbr = static_cast<size_t>(h.bcsr.nbr), n_e = static_cast<size_t>(h.bcsr.n_blocks);
+    const size_t nnz = h.csr.col_idx.size();
+    l.perm = take(nbr * 16 * sizeof(int32_t));
+    l.row_ptr = take((nbr + 1) * sizeof(int32_t));
+    l.meta = take(n_e * 2 * sizeof(int32_t));
+    l.order = take(nbr * sizeof(int32_t));
+    l.vals = take(n_e * 512);
+    l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
+    l.csr_col_idx = take(nnz * sizeof(int32_t));
+    l.csr_vals = take(nnz * sizeof(uint16_t));
+    l.total = off ? off : kAlign;
+    return l;
+}
+
+}  // namespace
+
+extern "C" {
+
+void smat_default_options(smat_options_t* opt)
+{
+    if (!opt) return;
+    opt->block_h = 16;
+    opt->block_w = 16;
+    opt->reorder = 1;
+    opt->tau_permille = 700;
+}
+
+smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, const int32_t* col_idx,
+                              const void* vals, smat_dtype_t dtype, const smat_options_t* opt,
+                              smat_handle_t** out)
+{
+    try {
+        smat_options_t o;
+        smat_default_options(&o);
+        if (opt) o = *opt;
+        if (!out) return fail(SMAT_ERR_INVALID_ARG, "out is NULL");
+        if (M < 0 || K < 0) return fail(SMAT_ERR_INVALID_ARG, "negative matrix size");
+        if (!row_ptr) return fail(SMAT_ERR_INVALID_ARG, "row_ptr is NULL");
+        if (dtype != SMAT_F16 && dtype != SMAT_BF16) return fail(SMAT_ERR_INVALID_ARG, "unknown dtype");
+        if (o.block_h != 16 || o.block_w != 16) return fail(SMAT_ERR_UNSUPPORTED, "only 16x16 blocks are supported");
+        if (o.reorder != 0 && o.reorder != 1) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0 or 1");
+        if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
+        if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
+            return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
+        if (row_ptr[0] != 0) return fail(SMAT_ERR_BAD_CSR, "row_ptr[0] must be 0");
+        for (int64_t r = 0; r < M; ++r)
+            if (row_ptr[r + 1] < row_ptr[r]) return fail(SMAT_ERR_BAD_CSR, "row_ptr decreases at row " + std::to_string(r));
+        const int64_t nnz = row_ptr[M];
+        if (nnz > 0 && (!col_idx || !vals)) return fail(SMAT_ERR_INVALID_ARG, "col_idx or vals is NULL");
+        const std::string bad = smat::validate_csr(M, K, row_ptr, col_idx);
+        if (!bad.empty()) return fail(SMAT_ERR_BAD_CSR, bad);
+
+        smat_handle* h = new smat_handle();
+        h->dtype = dtype;
+        h->csr.M = M;
+        h->csr.K = K;
+        h->csr.row_ptr.assign(row_ptr, row_ptr + M + 1);
+        h->csr.col_idx.assign(col_idx, col_idx + nnz);
+        h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
+        smat::build_bcsr(h->csr, o.reorder != 0, o.tau_permille, h->bcsr);
+        if (h->bcsr.n_blocks >= (int64_t{1} << 31) - 2) {
+            delete h;
+            return fail(SMAT_ERR_UNSUPPORTED, "more than 2^31 blocks");
+        }
+        *out = h;
+        return SMAT_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(SMAT_ERR_ALLOC, "out of host memory in smat_preprocess");
+    } catch (const std::exception& e) {
+        return fail(SMAT_ERR_INVALID_ARG, e.what());
+    }
+}
+
+smat_status_t smat_get_info(const smat_handle_t* h, int64_t* n_block_rows, int64_t* n_blocks,
+                            int64_t* n_blocks_identity, int* used_identity)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (n_block_rows) *n_block_rows = h->bcsr.nbr;
+    if (n_blocks) *n_blocks = h->bcsr.n_blocks;
+    if (n_blocks_identity) *n_blocks_identity = h->bcsr.n_blocks_identity;
+    if (used_identity) *used_identity = h->bcsr.used_identity ? 1 : 0;
+    return SMAT_OK;
+}
+
+smat_status_t smat_export_perm(const smat_handle_t* h, int32_t* perm)
+{
+    if (!h || (!perm && h->csr.M > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    if (h->csr.M > 0) std::memcpy(perm, h->bcsr.perm.data(), sizeof(int32_t) * static_cast<size_t>(h->csr.M));
+    return SMAT_OK;
+}
+
+smat_status_t smat_export_bcsr(const smat_handle_t* h, int32_t* row_ptr, int32_t* col_idx, void* vals)
+{
+    if (!h || !row_ptr) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    if (h->bcsr.n_blocks > 0 && !col_idx) return fail(SMAT_ERR_INVALID_ARG, "col_idx is NULL");
+    try {
+        std::memcpy(row_ptr, h->bcsr.row_ptr.data(), sizeof(int32_t) * h->bcsr.row_ptr.size());
+        if (h->bcsr.n_blocks > 0)
+            std::memcpy(col_idx, h->bcsr.col_idx.data(), sizeof(int32_t) * h->bcsr.col_idx.size());
+        if (vals) smat::fill_canonical_vals(h->csr, h->bcsr, static_cast<uint16_t*>(vals));
+        return SMAT_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(SMAT_ERR_ALLOC, "out of host memory in smat_export_bcsr");
+    }
+}
+
+smat_status_t smat_device_bytes(const smat_handle_t* h, size_t* bytes)
+{
+    if (!h || !bytes) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    *bytes = make_layout(*h).total;
+    return SMAT_OK;
+}
+
+smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t bytes, void* stream)
+{
+    if (!h || !dev_workspace) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    if (reinterpret_cast<uintptr_t>(dev_workspace) % kAlign != 0)
+        return fail(SMAT_ERR_INVALID_ARG, "dev_workspace must be 256-byte aligned");
+    const Layout l = make_layout(*h);
+    if (bytes < l.total) return fail(SMAT_ERR_INVALID_ARG, "dev_workspace too small: need " + std::to_string(l.total) + " bytes");
+    try {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        char* base = static_cast<char*>(dev_workspace);
+        const smat::Bcsr& b = h->bcsr;
+        const size_t nbr = static_cast<size_t>(b.nbr), n_e = static_cast<size_t>(b.n_blocks);
+        const size_t M = static_cast<size_t>(h->csr.M), nnz = h->csr.col_idx.size();
+
+        std::vector<int32_t> perm_padded(nbr * 16, -1);
+        std::memcpy(perm_padded.data(), b.perm.data(), sizeof(int32_t) * M);
+        std::vector<int32_t> meta(n_e * 2);
+        for (size_t k = 0; k < n_e; ++k) { meta[2 * k] = b.col_idx[k]; meta[2 * k + 1] = b.col_mask[k]; }
+
+        auto up = [&](size_t off, const void* src, size_t n) -> int {
+            if (n == 0) return 0;
+            return static_cast<int>(hipMemcpyAsync(base + off, src, n, hipMemcpyHostToDevice, s));
+        };
+        int e;
+        if ((e = up(l.perm, perm_padded.data(), perm_padded.size() * 4))) return hip_fail("copy perm", e);
+        if ((e = up(l.row_ptr, b.row_ptr.data(), b.row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
+        if ((e = up(l.meta, meta.data(), meta.size() * 4))) return hip_fail("copy meta", e);
+        if ((e = up(l.order, b.order.data(), b.order.size() * 4))) return hip_fail("copy order", e);
+        if ((e = up(l.csr_row_ptr, h->csr.row_ptr.data(), (M + 1) * 8))) return hip_fail("copy csr row_ptr", e);
+        if ((e = up(l.csr_col_idx, h->csr.col_idx.data(), nnz * 4))) return hip_fail("copy csr col_idx", e);
+        if ((e = up(l.csr_vals, h->csr.vals.data(), nnz * 2))) return hip_fail("copy csr vals", e);
+
+        smat::DeviceBcsr d;
+        d.perm = reinterpret_cast<const int32_t*>(base + l.perm);
+        d.row_ptr = reinterpret_cast<const int32_t*>(base + l.row_ptr);
+        d.meta = reinterpret_cast<const int32_t*>(base + l.meta);
+        d.vals = reinterpret_cast<const uint16_t*>(base + l.vals);
+        d.order = reinterpret_cast<const int32_t*>(base + l.order);
+        d.M = h->csr.M;
+        d.K = h->csr.K;
+        d.nbr = b.nbr;
+        d.n_e = b.n_blocks;
+        int64_t longest = 0;
+        for (size_t r = 0; r < nbr; ++r) longest = std::max<int64_t>(longest, b.row_ptr[r + 1] - b.row_ptr[r]);
+        d.max_row_blocks = longest;
+        d.mean_row_blocks = nbr ? static_cast<double>(n_e) / static_cast<double>(nbr) : 0.0;
+        h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
+        h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
+        h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
+
+        if ((e = smat::launch_fill_zero(base + l.vals, n_e * 32, s))) return hip_fail("zero block values", e);
+        if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
+                                        reinterpret_cast<uint16_t*>(base + l.vals), s)))
+            return hip_fail("fill block values", e);
+        if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("bind synchronize", e);
+        h->dev = d;
+        h->bound = true;
+        return SMAT_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(SMAT_ERR_ALLOC, "out of host memory in smat_bind_device");
+    }
+}
+
+smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* stream)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "handle is not bound to a device workspace");
+    const size_t n_e = static_cast<size_t>(h->bcsr.n_blocks);
+    if (n_e == 0) return SMAT_OK;
+    if (!vals) return fail(SMAT_ERR_INVALID_ARG, "vals is NULL");
+    try {
+        std::vector<uint16_t> raw(n_e * 256);
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, n_e * 512, hipMemcpyDeviceToHost, s));
+        if (e) return hip_fail("read block values", e);
+        if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("read block values", e);
+        uint16_t* out = static_cast<uint16_t*>(vals);
+        for (size_t k = 0; k < n_e; ++k)
+            for (int r = 0; r < 16; ++r)
+                for (int c = 0; c < 16; ++c)
+                    out[k * 256 + r * 16 + c] = raw[k * 256 + ((c >> 3) * 16 + r) * 8 + (c & 7)];
+        return SMAT_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(SMAT_ERR_ALLOC, "out of host memory in smat_export_device_vals");
+    }
+}
+
+smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
+                        int64_t N, void* stream)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "smat_spmm called before smat_bind_device");
+    if (N < 0) return fail(SMAT_ERR_INVALID_ARG, "N is negative");
+    if (N == 0 || h->csr.M == 0) return SMAT_OK;
+    if (!dC || (!dB && h->csr.K > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL matrix pointer");
+    if (ldb < N || ldc < N) return fail(SMAT_ERR_INVALID_ARG, "leading dimension smaller than N");
+    if (N > 16 * 65535) return fail(SMAT_ERR_UNSUPPORTED, "N above 1048560");
+    const int64_t K = h->csr.K;
+    if (K > 0 && ((K - 1) * ldb + N) * 2 >= (int64_t{1} << 31))
+        return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
+    const char* variant = "";
+    const int e = smat::launch_spmm(h->dev, h->dtype == SMAT_BF16, dB, ldb, static_cast<float*>(dC), ldc, N,
+                                    stream, &variant);
+    g_kernel = variant;
+    if (e) return hip_fail("launch spmm", e);
+    return SMAT_OK;
+}
+
+void smat_destroy(smat_handle_t* h) { delete h; }
+
+const char* smat_last_error(void) { return g_error.c_str(); }
+
+const char* smat_last_kernel(void) { return g_kernel; }
+
+}  // extern "C"

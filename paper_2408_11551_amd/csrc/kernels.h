@@ -1,0 +1,40 @@
+// Device-side data layout and kernel launchers (gfx950).  Host code includes this
+// header without needing hipcc; streams travel as void*.
+#pragma once
+
+#include <cstddef>
+#include <cstdint>
+
+namespace smat {
+
+// Pointers into the caller's device workspace.
+//
+// vals layout ("two half panels"): block s occupies 256 halves at vals + 256*s; element
+// (row r, column c) of the block sits at half index ((c >> 3) * 16 + r) * 8 + (c & 7), i.e.
+// the block is stored as two 16 x 8 column panels, each row-major.  A wavefront that
+// multiplies two consecutive blocks as one K = 32 contraction then reads 1 KiB linearly:
+// lane l takes the 16 bytes at byte offset 16 * l of the pair.
+struct DeviceBcsr {
+    const int32_t* perm = nullptr;      // [nbr*16] new row -> old row, -1 beyond M
+    const int32_t* row_ptr = nullptr;   // [nbr+1]
+    const int32_t* meta = nullptr;      // [2*n_e] per block: block column, column-occupancy mask
+    const uint16_t* vals = nullptr;     // [256*n_e]
+    const int32_t* order = nullptr;     // [nbr] block rows, longest first
+    int64_t M = 0, K = 0, nbr = 0, n_e = 0;
+    int64_t max_row_blocks = 0;         // longest block row
+    double mean_row_blocks = 0;
+};
+
+// Sets n16 16-byte words at dst to zero.
+int launch_fill_zero(void* dst, size_t n16, void* stream);
+
+// Scatters the CSR values into the device block layout.  csr_* are device copies of the
+// caller's CSR; vals must have been zeroed.
+int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int32_t* csr_col_idx,
+                     const uint16_t* csr_vals, uint16_t* vals_out, void* stream);
+
+// C = A * B.  Returns a hipError_t as int; *variant receives a static string naming the kernel.
+int launch_spmm(const DeviceBcsr& d, bool bf16, const void* B, int64_t ldb, float* C, int64_t ldc,
+                int64_t N, void* stream, const char** variant);
+
+}  // namespace smat

@@ -1,0 +1,230 @@
+"""ctypes binding of libsmat.so: argument marshalling only, one Python function per C entry point.
+
+Host arrays are numpy arrays, device arrays are torch tensors on a HIP device (torch is used
+for device memory and streams, nothing else).  There is no fallback: if the shared library is
+missing and cannot be built, importing this module fails.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+SMAT_F16 = 0
+SMAT_BF16 = 1
+_DTYPES = {"f16": SMAT_F16, "bf16": SMAT_BF16, SMAT_F16: SMAT_F16, SMAT_BF16: SMAT_BF16}
+
+_STATUS = {0: "SMAT_OK", 1: "SMAT_ERR_INVALID_ARG", 2: "SMAT_ERR_BAD_CSR", 3: "SMAT_ERR_UNSUPPORTED",
+           4: "SMAT_ERR_ALLOC", 5: "SMAT_ERR_NOT_BOUND", 6: "SMAT_ERR_HIP"}
+
+
+class SmatError(RuntimeError):
+    def __init__(self, status: int, message: str):
+        super().__init__(f"{_STATUS.get(status, status)}: {message}")
+        self.status = status
+        self.status_name = _STATUS.get(status, str(status))
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("block_h", ctypes.c_int), ("block_w", ctypes.c_int),
+                ("reorder", ctypes.c_int), ("tau_permille", ctypes.c_int)]
+
+
+def lib_path() -> str:
+    return _build.OUT
+
+
+def _load():
+    path = lib_path()
+    if not os.path.exists(path):
+        _build.build()                      # raises if hipcc is missing or the build fails
+    lib = ctypes.CDLL(path)
+    i64, vp, sz = ctypes.c_int64, ctypes.c_void_p, ctypes.c_size_t
+    lib.smat_default_options.restype = None
+    lib.smat_default_options.argtypes = [ctypes.POINTER(_Options)]
+    lib.smat_preprocess.restype = ctypes.c_int
+    lib.smat_preprocess.argtypes = [i64, i64, vp, vp, vp, ctypes.c_int, ctypes.POINTER(_Options),
+                                    ctypes.POINTER(vp)]
+    lib.smat_get_info.restype = ctypes.c_int
+    lib.smat_get_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
+                                  ctypes.POINTER(ctypes.c_int)]
+    lib.smat_export_perm.restype = ctypes.c_int
+    lib.smat_export_perm.argtypes = [vp, vp]
+    lib.smat_export_bcsr.restype = ctypes.c_int
+    lib.smat_export_bcsr.argtypes = [vp, vp, vp, vp]
+    lib.smat_device_bytes.restype = ctypes.c_int
+    lib.smat_device_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.smat_bind_device.restype = ctypes.c_int
+    lib.smat_bind_device.argtypes = [vp, vp, sz, vp]
+    lib.smat_export_device_vals.restype = ctypes.c_int
+    lib.smat_export_device_vals.argtypes = [vp, vp, vp]
+    lib.smat_spmm.restype = ctypes.c_int
+    lib.smat_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
+    lib.smat_destroy.restype = None
+    lib.smat_destroy.argtypes = [vp]
+    lib.smat_last_error.restype = ctypes.c_char_p
+    lib.smat_last_error.argtypes = []
+    lib.smat_last_kernel.restype = ctypes.c_char_p
+    lib.smat_last_kernel.argtypes = []
+    return lib
+
+
+_lib = _load()
+
+
+def _check(status: int):
+    if status != 0:
+        raise SmatError(status, _lib.smat_last_error().decode())
+
+
+def _host(a, dtype):
+    a = np.ascontiguousarray(a, dtype=dtype)
+    return a, a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _stream_ptr(stream):
+    if stream is None:
+        import torch
+        stream = torch.cuda.current_stream()
+    if hasattr(stream, "cuda_stream"):
+        return ctypes.c_void_p(stream.cuda_stream)
+    return ctypes.c_void_p(int(stream))
+
+
+def smat_last_error() -> str:
+    return _lib.smat_last_error().decode()
+
+
+def smat_last_kernel() -> str:
+    return _lib.smat_last_kernel().decode()
+
+
+def smat_default_options() -> dict:
+    o = _Options()
+    _lib.smat_default_options(ctypes.byref(o))
+    return {"block_h": o.block_h, "block_w": o.block_w, "reorder": o.reorder, "tau_permille": o.tau_permille}
+
+
+def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
+                    block_h=16, block_w=16) -> int:
+    """row_ptr int64[M+1], col_idx int32[nnz], vals_bits uint16[nnz] (HOST) -> opaque handle."""
+    rp, rp_p = _host(row_ptr, np.int64)
+    ci, ci_p = _host(col_idx, np.int32)
+    vb, vb_p = _host(vals_bits, np.uint16)
+    if rp.size != M + 1:
+        raise ValueError("row_ptr must have M+1 entries")
+    nnz = int(rp[-1]) if rp.size else 0
+    if ci.size < nnz or vb.size < nnz:
+        raise ValueError("col_idx / vals shorter than row_ptr[M]")
+    opt = _Options(block_h, block_w, reorder, tau_permille)
+    out = ctypes.c_void_p()
+    _check(_lib.smat_preprocess(M, K, rp_p, ci_p, vb_p, _DTYPES.get(dtype, dtype), ctypes.byref(opt), ctypes.byref(out)))
+    return out.value
+
+
+def smat_get_info(h) -> dict:
+    nbr, n_e, n_id = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    used = ctypes.c_int()
+    _check(_lib.smat_get_info(h, ctypes.byref(nbr), ctypes.byref(n_e), ctypes.byref(n_id), ctypes.byref(used)))
+    return {"n_block_rows": nbr.value, "n_blocks": n_e.value, "n_blocks_identity": n_id.value,
+            "used_identity": bool(used.value)}
+
+
+def smat_export_perm(h, M) -> np.ndarray:
+    perm = np.empty(M, dtype=np.int32)
+    _check(_lib.smat_export_perm(h, perm.ctypes.data_as(ctypes.c_void_p)))
+    return perm
+
+
+def smat_export_bcsr(h, with_vals=True):
+    info = smat_get_info(h)
+    row_ptr = np.empty(info["n_block_rows"] + 1, dtype=np.int32)
+    col_idx = np.empty(info["n_blocks"], dtype=np.int32)
+    vals = np.empty((info["n_blocks"], 16, 16), dtype=np.uint16) if with_vals else None
+    _check(_lib.smat_export_bcsr(h, row_ptr.ctypes.data_as(ctypes.c_void_p),
+                                 col_idx.ctypes.data_as(ctypes.c_void_p),
+                                 vals.ctypes.data_as(ctypes.c_void_p) if with_vals else None))
+    return row_ptr, col_idx, vals
+
+
+def smat_device_bytes(h) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.smat_device_bytes(h, ctypes.byref(n)))
+    return n.value
+
+
+def smat_bind_device(h, workspace, stream=None):
+    """workspace: torch uint8 tensor on the device, at least smat_device_bytes(h) bytes, 256-byte aligned."""
+    _check(_lib.smat_bind_device(h, ctypes.c_void_p(workspace.data_ptr()),
+                                 workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
+
+
+def smat_export_device_vals(h, stream=None) -> np.ndarray:
+    n_e = smat_get_info(h)["n_blocks"]
+    vals = np.empty((n_e, 16, 16), dtype=np.uint16)
+    _check(_lib.smat_export_device_vals(h, vals.ctypes.data_as(ctypes.c_void_p), _stream_ptr(stream)))
+    return vals
+
+
+def smat_spmm(h, B, C, N=None, stream=None):
+    """B: device tensor [K, >=N] of 16-bit elements, C: device float32 tensor [M, >=N]; rows contiguous."""
+    if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
+        raise ValueError("B and C must be 2-D with unit column stride")
+    if B.element_size() != 2 or C.element_size() != 4:
+        raise ValueError("B must hold 16-bit elements and C 32-bit floats")
+    if N is None:
+        N = B.shape[1]
+    _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
+                          ctypes.c_void_p(C.data_ptr()), C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N),
+                          N, _stream_ptr(stream)))
+
+
+def smat_destroy(h):
+    if h:
+        _lib.smat_destroy(h)
+
+
+class SmatMatrix:
+    """Owns a handle and the torch workspace tensor it is bound to (memory plumbing only)."""
+
+    def __init__(self, M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
+                 device="cuda:0", bind=True):
+        self.M, self.K, self.dtype = M, K, dtype
+        self.handle = smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype,
+                                      reorder=reorder, tau_permille=tau_permille)
+        self.workspace = None
+        self.info = smat_get_info(self.handle)
+        if bind:
+            self.bind(device)
+
+    def bind(self, device="cuda:0"):
+        import torch
+        nbytes = smat_device_bytes(self.handle)
+        self.workspace = torch.empty(nbytes, dtype=torch.uint8, device=device)
+        with torch.cuda.device(self.workspace.device):
+            smat_bind_device(self.handle, self.workspace)
+        return self
+
+    def spmm(self, B, C=None, N=None):
+        import torch
+        if N is None:
+            N = B.shape[1]
+        if C is None:
+            C = torch.empty((self.M, N), dtype=torch.float32, device=B.device)
+        smat_spmm(self.handle, B, C, N)
+        return C
+
+    def close(self):
+        if self.handle:
+            smat_destroy(self.handle)
+            self.handle = None
+        self.workspace = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass

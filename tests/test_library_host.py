@@ -1,0 +1,132 @@
+"""Host side of the library (CPU only): the C ABI loads and exports every declared symbol,
+the preprocessing matches the oracle bit for bit, bad input turns into status codes."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2408_11551_amd as S
+from oracle import smat_ref as R
+from workloads import random_csr, band_csr, make_config
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "smat.h")).read()
+    header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
+    names = sorted(set(re.findall(r"\b(smat_[a-z_]+)\s*\(", header)))
+    assert {"smat_preprocess", "smat_spmm", "smat_bind_device", "smat_export_bcsr"} <= set(names)
+    lib = ctypes.CDLL(S.lib_path())
+    for n in names:
+        assert hasattr(lib, n), n
+
+
+def _oracle_structure(w, tau, reorder=True):
+    pats = R.block_pattern(w.M, w.row_ptr, w.col_idx)
+    perm, n_e, n_id, used = R.choose_perm(pats, tau, reorder=reorder)
+    return perm, n_e, n_id, used, R.bcsr_from_csr(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+
+
+@pytest.mark.parametrize("tau", [0, 300, 700, 1000])
+@pytest.mark.parametrize("shape", [(16, 16), (1, 1), (17, 40), (100, 64), (130, 333), (256, 256)])
+def test_preprocess_matches_oracle_small(shape, tau):
+    M, K = shape
+    for seed, density in enumerate([0.0, 0.01, 0.05, 0.3]):
+        w = random_csr(M, K, 1, density, seed=seed + 7 * M, dtype="bf16" if seed % 2 else "f16")
+        h = S.smat_preprocess(M, K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, tau_permille=tau)
+        try:
+            perm, n_e, n_id, used, (rp, ci, v) = _oracle_structure(w, tau)
+            info = S.smat_get_info(h)
+            assert info == {"n_block_rows": -(-M // 16), "n_blocks": n_e, "n_blocks_identity": n_id,
+                            "used_identity": used}
+            assert np.array_equal(S.smat_export_perm(h, M), perm)
+            grp, gci, gv = S.smat_export_bcsr(h)
+            assert np.array_equal(grp, rp) and np.array_equal(gci, ci) and np.array_equal(gv, v)
+        finally:
+            S.smat_destroy(h)
+
+
+def test_preprocess_structured_inputs_match_oracle(oracle_c):
+    cases = [band_csr(512, 64, 1, seed=1, p=0.3), make_config("tiny"),
+             make_config("hidden_blocks", n_grid=32, p_block=0.1, N=16)]
+    for w in cases:
+        for reorder in (0, 1):
+            h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder)
+            try:
+                pp, pi = oracle_c.block_pattern_csr(w.M, w.K, w.row_ptr, w.col_idx)
+                perm, n_e, n_id, used = oracle_c.choose_perm_c(w.M, pp, pi, -(-w.K // 16), 700, reorder=bool(reorder))
+                assert S.smat_get_info(h)["n_blocks"] == n_e and S.smat_get_info(h)["used_identity"] == used
+                assert np.array_equal(S.smat_export_perm(h, w.M), perm)
+                rp, ci, v = R.bcsr_from_csr_fast(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+                grp, gci, gv = S.smat_export_bcsr(h)
+                assert np.array_equal(grp, rp) and np.array_equal(gci, ci) and np.array_equal(gv, v)
+            finally:
+                S.smat_destroy(h)
+    # the band keeps the identity, the planted blocks do not
+    h = S.smat_preprocess(cases[0].M, cases[0].K, cases[0].row_ptr, cases[0].col_idx, cases[0].a_bits, "f16")
+    assert S.smat_get_info(h)["used_identity"]
+    S.smat_destroy(h)
+    w = cases[2]
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, "f16")
+    info = S.smat_get_info(h)
+    assert not info["used_identity"] and info["n_blocks"] < info["n_blocks_identity"]
+    S.smat_destroy(h)
+
+
+def test_uniform_config_matches_oracle(oracle_c):
+    w = make_config("uniform")
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    try:
+        pp, pi = oracle_c.block_pattern_csr(w.M, w.K, w.row_ptr, w.col_idx)
+        perm, n_e, n_id, used = oracle_c.choose_perm_c(w.M, pp, pi, w.K // 16, 700)
+        assert np.array_equal(S.smat_export_perm(h, w.M), perm)
+        rp, ci, v = R.bcsr_from_csr_fast(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+        grp, gci, gv = S.smat_export_bcsr(h)
+        assert np.array_equal(grp, rp) and np.array_equal(gci, ci) and np.array_equal(gv, v)
+        assert w.nnz / 256 <= n_e <= min((w.M // 16) * (w.K // 16), w.nnz)     # Eq. 2
+    finally:
+        S.smat_destroy(h)
+
+
+def _expect(status_name, fn):
+    with pytest.raises(S.SmatError) as e:
+        fn()
+    assert e.value.status_name == status_name, str(e.value)
+    assert S.smat_last_error() != ""
+
+
+def test_bad_input_becomes_status_codes():
+    rp = np.array([0, 2, 3], np.int64)
+    ci = np.array([1, 3, 0], np.int32)
+    v = np.ones(3, np.uint16)
+    ok = S.smat_preprocess(2, 4, rp, ci, v, "f16")
+    S.smat_destroy(ok)
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, rp, np.array([3, 1, 0], np.int32), v, "f16"))
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, rp, np.array([1, 1, 0], np.int32), v, "f16"))
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, rp, np.array([1, 4, 0], np.int32), v, "f16"))
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, rp, np.array([-1, 2, 0], np.int32), v, "f16"))
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, np.array([0, 3, 2], np.int64), ci, v, "f16"))
+    _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, np.array([1, 2, 3], np.int64), ci, v, "f16"))
+    _expect("SMAT_ERR_UNSUPPORTED", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", block_w=8))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", tau_permille=1001))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", reorder=2))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, 7))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(-1, 4, np.zeros(0, np.int64), ci, v, "f16"))
+
+
+def test_spmm_without_bind_is_an_error_not_a_fallback():
+    rp = np.array([0, 1], np.int64)
+    h = S.smat_preprocess(1, 1, rp, np.array([0], np.int32), np.array([0x3C00], np.uint16), "f16")
+    lib = ctypes.CDLL(S.lib_path())
+    lib.smat_spmm.restype = ctypes.c_int
+    lib.smat_spmm.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_int64, ctypes.c_void_p,
+                              ctypes.c_int64, ctypes.c_int64, ctypes.c_void_p]
+    assert lib.smat_spmm(h, None, 1, None, 1, 1, None) == 5          # SMAT_ERR_NOT_BOUND
+    S.smat_destroy(h)
+
+
+def test_default_options():
+    assert S.smat_default_options() == {"block_h": 16, "block_w": 16, "reorder": 1, "tau_permille": 700}
