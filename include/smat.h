@@ -134,7 +134,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
  *
  * Concurrent calls on different streams with different dC are allowed.
  * Limits: the bytes of B that are addressed, ((K-1)*ldb + N)*2, must stay below 2 GiB;
- * N <= 1048560.
+ * ldb < 2^23; N <= 1048560.
  */
 smat_status_t smat_spmm(const smat_handle_t *h, const void *dB, int64_t ldb,
                         void *dC, int64_t ldc, int64_t N, void *stream);

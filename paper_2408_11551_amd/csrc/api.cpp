@@ -5,6 +5,7 @@
 
 #include <hip/hip_runtime_api.h>
 
+#include <algorithm>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -12,6 +13,7 @@
 #include <vector>
 
 #include "kernels.h"
+#include "pair_layout.h"
 #include "preprocess.h"
 
 struct smat_handle {
@@ -19,6 +21,10 @@ struct smat_handle {
     smat::Bcsr bcsr;
     smat_dtype_t dtype = SMAT_F16;
     bool bound = false;
+    // Device-side block arrays pad every block row to an even number of blocks (the kernel
+    // multiplies blocks two at a time); the pad block has no occupied column and zero values.
+    std::vector<int32_t> dev_row_ptr;   // [nbr+1] offsets into the padded block arrays
+    int64_t n_dev_blocks = 0;
     smat::DeviceBcsr dev;
     // device copies of the CSR (kept: they live in the caller's workspace anyway)
     const int64_t* d_csr_row_ptr = nullptr;
@@ -55,11 +61,11 @@ Layout make_layout(const smat_handle& h)
     Layout l{};
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes); return at; };
-    const size_t nbr = static_cast<size_t>(h.bcsr.nbr), n_e = static_cast<size_t>(h.bcsr.n_blocks);
+    const size_t nbr = static_cast<size_t>(h.bcsr.nbr), n_e = static_cast<size_t>(h.n_dev_blocks);
     const size_t nnz = h.csr.col_idx.size();
     l.perm = take(nbr * 16 * sizeof(int32_t));
     l.row_ptr = take((nbr + 1) * sizeof(int32_t));
-    l.meta = take(n_e * 2 * sizeof(int32_t));
+    l.meta = take(n_e / 2 * smat::kPairMetaInts * sizeof(int32_t));
     l.order = take(nbr * sizeof(int32_t));
     l.vals = take(n_e * 512);
     l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
@@ -99,6 +105,8 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
+        if (M > (int64_t{1} << 32) - 1 - 16 || (M + 15) / 16 >= (int64_t{1} << 28))
+            return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
         if (row_ptr[0] != 0) return fail(SMAT_ERR_BAD_CSR, "row_ptr[0] must be 0");
         for (int64_t r = 0; r < M; ++r)
             if (row_ptr[r + 1] < row_ptr[r]) return fail(SMAT_ERR_BAD_CSR, "row_ptr decreases at row " + std::to_string(r));
@@ -115,10 +123,18 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         h->csr.col_idx.assign(col_idx, col_idx + nnz);
         h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
         smat::build_bcsr(h->csr, o.reorder != 0, o.tau_permille, h->bcsr);
-        if (h->bcsr.n_blocks >= (int64_t{1} << 31) - 2) {
-            delete h;
-            return fail(SMAT_ERR_UNSUPPORTED, "more than 2^31 blocks");
+        h->dev_row_ptr.assign(static_cast<size_t>(h->bcsr.nbr) + 1, 0);
+        int64_t padded = 0;
+        for (int64_t br = 0; br < h->bcsr.nbr; ++br) {
+            const int64_t cnt = h->bcsr.row_ptr[br + 1] - h->bcsr.row_ptr[br];
+            padded += (cnt + 1) / 2 * 2;
+            if (padded >= (int64_t{1} << 31) - 2) {
+                delete h;
+                return fail(SMAT_ERR_UNSUPPORTED, "more than 2^31 blocks");
+            }
+            h->dev_row_ptr[br + 1] = static_cast<int32_t>(padded);
         }
+        h->n_dev_blocks = padded;
         *out = h;
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
@@ -179,13 +195,33 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         hipStream_t s = static_cast<hipStream_t>(stream);
         char* base = static_cast<char*>(dev_workspace);
         const smat::Bcsr& b = h->bcsr;
-        const size_t nbr = static_cast<size_t>(b.nbr), n_e = static_cast<size_t>(b.n_blocks);
+        const size_t nbr = static_cast<size_t>(b.nbr), n_e = static_cast<size_t>(h->n_dev_blocks);
         const size_t M = static_cast<size_t>(h->csr.M), nnz = h->csr.col_idx.size();
 
         std::vector<int32_t> perm_padded(nbr * 16, -1);
         std::memcpy(perm_padded.data(), b.perm.data(), sizeof(int32_t) * M);
-        std::vector<int32_t> meta(n_e * 2);
-        for (size_t k = 0; k < n_e; ++k) { meta[2 * k] = b.col_idx[k]; meta[2 * k + 1] = b.col_mask[k]; }
+        // per-pair metadata; an odd tail is completed by a pad block: column beyond every real
+        // one (keeps the row's columns ascending), nothing occupied
+        std::vector<int32_t> meta(n_e / 2 * smat::kPairMetaInts);
+        for (size_t br = 0; br < nbr; ++br) {
+            const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
+            size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2;
+            for (int32_t s = s0; s < s1; s += 2, ++pair) {
+                int32_t* m = meta.data() + pair * smat::kPairMetaInts;
+                const bool has2 = s + 1 < s1;
+                const uint32_t occ = b.col_mask[s] | (has2 ? static_cast<uint32_t>(b.col_mask[s + 1]) << 16 : 0u);
+                m[0] = b.col_idx[s];
+                m[1] = has2 ? b.col_idx[s + 1] : 0x7FFFFFFF;
+                m[2] = static_cast<int32_t>(occ);
+                uint8_t sel[4][8];
+                std::memset(sel, 0xFF, sizeof(sel));
+                int rank = 0;
+                for (int c = 0; c < 32; ++c)
+                    if (occ >> c & 1u) { sel[smat::slot_group(rank)][smat::slot_pos(rank)] = static_cast<uint8_t>(c); ++rank; }
+                m[3] = rank;
+                std::memcpy(m + 4, sel, sizeof(sel));
+            }
+        }
 
         auto up = [&](size_t off, const void* src, size_t n) -> int {
             if (n == 0) return 0;
@@ -193,9 +229,25 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         };
         int e;
         if ((e = up(l.perm, perm_padded.data(), perm_padded.size() * 4))) return hip_fail("copy perm", e);
-        if ((e = up(l.row_ptr, b.row_ptr.data(), b.row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
+        if ((e = up(l.row_ptr, h->dev_row_ptr.data(), h->dev_row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
         if ((e = up(l.meta, meta.data(), meta.size() * 4))) return hip_fail("copy meta", e);
-        if ((e = up(l.order, b.order.data(), b.order.size() * 4))) return hip_fail("copy order", e);
+        // row class: how many B-row loads per lane a pair of the block row needs at most
+        // (occupied columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2
+        std::vector<int32_t> order_cls(nbr);
+        int max_class = 0;
+        {
+            std::vector<int8_t> cls(nbr, 0);
+            for (size_t br = 0; br < nbr; ++br) {
+                int worst = 0;
+                for (size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2; pair < static_cast<size_t>(h->dev_row_ptr[br + 1]) / 2; ++pair)
+                    worst = std::max(worst, meta[pair * smat::kPairMetaInts + 3]);
+                cls[br] = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
+                max_class = std::max<int>(max_class, cls[br]);
+            }
+            for (size_t x = 0; x < nbr; ++x)
+                order_cls[x] = b.order[x] | (static_cast<int32_t>(cls[b.order[x]]) << 28);
+        }
+        if ((e = up(l.order, order_cls.data(), order_cls.size() * 4))) return hip_fail("copy order", e);
         if ((e = up(l.csr_row_ptr, h->csr.row_ptr.data(), (M + 1) * 8))) return hip_fail("copy csr row_ptr", e);
         if ((e = up(l.csr_col_idx, h->csr.col_idx.data(), nnz * 4))) return hip_fail("copy csr col_idx", e);
         if ((e = up(l.csr_vals, h->csr.vals.data(), nnz * 2))) return hip_fail("copy csr vals", e);
@@ -209,11 +261,12 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         d.M = h->csr.M;
         d.K = h->csr.K;
         d.nbr = b.nbr;
-        d.n_e = b.n_blocks;
+        d.n_e = h->n_dev_blocks;
         int64_t longest = 0;
         for (size_t r = 0; r < nbr; ++r) longest = std::max<int64_t>(longest, b.row_ptr[r + 1] - b.row_ptr[r]);
         d.max_row_blocks = longest;
-        d.mean_row_blocks = nbr ? static_cast<double>(n_e) / static_cast<double>(nbr) : 0.0;
+        d.max_class = max_class;
+        d.mean_row_blocks = nbr ? static_cast<double>(b.n_blocks) / static_cast<double>(nbr) : 0.0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
@@ -235,20 +288,44 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
 {
     if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
     if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "handle is not bound to a device workspace");
-    const size_t n_e = static_cast<size_t>(h->bcsr.n_blocks);
+    const size_t n_e = static_cast<size_t>(h->bcsr.n_blocks), n_dev = static_cast<size_t>(h->n_dev_blocks);
     if (n_e == 0) return SMAT_OK;
     if (!vals) return fail(SMAT_ERR_INVALID_ARG, "vals is NULL");
     try {
-        std::vector<uint16_t> raw(n_e * 256);
+        std::vector<uint16_t> raw(n_dev * 256);
         hipStream_t s = static_cast<hipStream_t>(stream);
-        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, n_e * 512, hipMemcpyDeviceToHost, s));
+        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, n_dev * 512, hipMemcpyDeviceToHost, s));
         if (e) return hip_fail("read block values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("read block values", e);
         uint16_t* out = static_cast<uint16_t*>(vals);
-        for (size_t k = 0; k < n_e; ++k)
-            for (int r = 0; r < 16; ++r)
-                for (int c = 0; c < 16; ++c)
-                    out[k * 256 + r * 16 + c] = raw[k * 256 + ((c >> 3) * 16 + r) * 8 + (c & 7)];
+        std::memset(out, 0, n_e * 512);
+        for (int64_t br = 0; br < h->bcsr.nbr; ++br) {
+            const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
+            size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2;
+            for (int32_t s = s0; s < s1; s += 2, ++pair) {
+                const bool has2 = s + 1 < s1;
+                const uint32_t occ = h->bcsr.col_mask[s] |
+                                     (has2 ? static_cast<uint32_t>(h->bcsr.col_mask[s + 1]) << 16 : 0u);
+                const uint16_t* src = raw.data() + pair * smat::kPairHalves;
+                uint8_t used[smat::kPairHalves];
+                std::memset(used, 0, sizeof(used));
+                int rank = 0;
+                for (int c = 0; c < 32; ++c) {
+                    if (!(occ >> c & 1u)) continue;
+                    const int g = smat::slot_group(rank), kk = smat::slot_pos(rank);
+                    ++rank;
+                    uint16_t* blk = out + static_cast<size_t>(s + (c >> 4)) * 256;
+                    for (int r = 0; r < 16; ++r) {
+                        const int at = smat::pair_half_index(r, g, kk);
+                        blk[r * 16 + (c & 15)] = src[at];
+                        used[at] = 1;
+                    }
+                }
+                // every slot that holds no occupied column must have stayed zero
+                for (int q = 0; q < smat::kPairHalves; ++q)
+                    if (!used[q] && src[q] != 0) return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
+            }
+        }
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
         return fail(SMAT_ERR_ALLOC, "out of host memory in smat_export_device_vals");
@@ -268,6 +345,7 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     const int64_t K = h->csr.K;
     if (K > 0 && ((K - 1) * ldb + N) * 2 >= (int64_t{1} << 31))
         return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
+    if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
     const char* variant = "";
     const int e = smat::launch_spmm(h->dev, h->dtype == SMAT_BF16, dB, ldb, static_cast<float*>(dC), ldc, N,
                                     stream, &variant);

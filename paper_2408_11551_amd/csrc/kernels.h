@@ -7,22 +7,19 @@
 
 namespace smat {
 
-// Pointers into the caller's device workspace.
-//
-// vals layout ("two half panels"): block s occupies 256 halves at vals + 256*s; element
-// (row r, column c) of the block sits at half index ((c >> 3) * 16 + r) * 8 + (c & 7), i.e.
-// the block is stored as two 16 x 8 column panels, each row-major.  A wavefront that
-// multiplies two consecutive blocks as one K = 32 contraction then reads 1 KiB linearly:
-// lane l takes the 16 bytes at byte offset 16 * l of the pair.
+// Pointers into the caller's device workspace.  Block rows are padded to an even number of
+// blocks; pair P of the whole matrix covers blocks 2P and 2P+1.  See pair_layout.h for the
+// layout of a pair's values and metadata.
 struct DeviceBcsr {
     const int32_t* perm = nullptr;      // [nbr*16] new row -> old row, -1 beyond M
-    const int32_t* row_ptr = nullptr;   // [nbr+1]
-    const int32_t* meta = nullptr;      // [2*n_e] per block: block column, column-occupancy mask
+    const int32_t* row_ptr = nullptr;   // [nbr+1] block offsets (even)
+    const int32_t* meta = nullptr;      // [12 * n_e/2] per pair
     const uint16_t* vals = nullptr;     // [256*n_e]
-    const int32_t* order = nullptr;     // [nbr] block rows, longest first
+    const int32_t* order = nullptr;     // [nbr] block rows, longest first; bits 28..29: row class
     int64_t M = 0, K = 0, nbr = 0, n_e = 0;
     int64_t max_row_blocks = 0;         // longest block row
     double mean_row_blocks = 0;
+    int max_class = 0;                  // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pair)
 };
 
 // Sets n16 16-byte words at dst to zero.

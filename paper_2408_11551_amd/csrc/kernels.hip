@@ -6,6 +6,10 @@
 
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
+#include "pair_layout.h"
+
 namespace smat {
 
 typedef float f32x4 __attribute__((ext_vector_type(4)));
@@ -39,7 +43,7 @@ int launch_fill_zero(void* dst, size_t n16, void* stream)
 
 // One thread per row of A' = P A: walks the row's CSR entries, finds each entry's block in
 // the block row by binary search over the ascending block columns and stores the value at
-// its place in the two-half-panel layout.
+// its slot in the pair layout (pair_layout.h).
 __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_row_ptr,
                                  const int32_t* __restrict__ csr_col_idx,
                                  const uint16_t* __restrict__ csr_vals, uint16_t* __restrict__ vals_out)
@@ -54,14 +58,17 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
     for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
         const int c = csr_col_idx[p];
         const int bc = c >> 4;
-        int lo = hint, hi = hi0;                     // columns ascend, so the slot never moves back
+        int lo = hint, hi = hi0;                     // columns ascend, so the block never moves back
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (d.meta[2 * mid] < bc) lo = mid + 1; else hi = mid;
+            if (d.meta[static_cast<size_t>(mid >> 1) * kPairMetaInts + (mid & 1)] < bc) lo = mid + 1; else hi = mid;
         }
         hint = lo;
-        const int cc = c & 15;
-        vals_out[static_cast<size_t>(lo) * 256 + static_cast<size_t>(((cc >> 3) * 16 + rr) * 8 + (cc & 7))] = csr_vals[p];
+        const size_t pair = static_cast<size_t>(lo >> 1);
+        const int pc = (lo & 1) * 16 + (c & 15);     // column inside the pair
+        const uint32_t occ = static_cast<uint32_t>(d.meta[pair * kPairMetaInts + 2]);
+        const int rank = __popc(occ & ((1u << pc) - 1u));
+        vals_out[pair * kPairHalves + pair_half_index(rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
     }
 }
 
@@ -80,26 +87,28 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // SpMM
 // ---------------------------------------------------------------------------
 //
-// Work split: one workgroup of WAVES wavefronts per (block row, slab of 16*NT columns of
-// B and C).  Wave w of the group takes block pairs w, w+WAVES, ... of the block row, so
-// that the group as a whole streams the row's block values front to back; the partial
-// 16 x (16*NT) tiles are summed through LDS in a fixed order and scattered to the rows
-// perm[16*br + 0..15] of C.
+// Work split: one workgroup per (block row, group of SW column slabs of 16*NT columns).  The
+// group has KW*SW wavefronts: wave (ks, sl) takes block pairs ks, ks+KW, ... of the block row
+// for slab sl, so the group streams the row's block values front to back once from HBM; the
+// KW partial tiles of a slab are summed through LDS in a fixed order and scattered to the
+// rows perm[16*br + 0..15] of C.
 //
-// One MFMA 16x16x32 multiplies TWO stored blocks: k = 0..15 is the first block of the pair,
-// k = 16..31 the second.  Lane l = 16*g + i supplies, as the left operand, row i of the
-// pair's k range 8g..8g+7, which is the 16 bytes at offset 16*l of the pair in the
-// two-half-panel layout.  The right operand wants, per lane, eight k-consecutive values of
-// one column of B, while B is row-major (n-consecutive).  Instead of transposing through
-// LDS, lane (g, i) loads from each of its eight B rows the NT consecutive columns
-// n0 + NT*i .. n0 + NT*i + NT-1, and MFMA number t is defined to produce the column set
-// { n0 + NT*i + t : i = 0..15 }.  The eight halves a lane feeds to MFMA t are then half t
-// of its eight row loads (one byte-permute per two halves), and after the NT MFMAs the lane
+// One MFMA 16x16x32 multiplies a pair of stored blocks.  The left operand of lane l is the
+// 16 bytes at offset 16*l of the pair's values (pair_layout.h).  The right operand wants, per
+// lane, eight k-consecutive values of one column of B, while B is row-major (n-consecutive).
+// Instead of transposing through LDS, lane (g, i) loads from each B row of its k slots the NT
+// consecutive columns n0 + NT*i .. n0 + NT*i + NT-1, and MFMA number t is defined to produce
+// the column set { n0 + NT*i + t : i = 0..15 }.  The halves a lane feeds to MFMA t are then
+// half t of its row loads (one byte-permute per two halves), and after the NT MFMAs the lane
 // holds, for each of its four output rows 4g..4g+3, NT consecutive columns of C.
 //
-// B rows whose column in the block is empty (bit clear in the occupancy mask) are not
-// fetched: their buffer-load offset is pushed out of range, which makes the hardware
-// return zeros without touching memory.
+// Only occupied columns of a pair need a B row.  The pair layout packs them into the first
+// slots of every lane group, so a block row whose pairs hold at most 4*L occupied columns
+// runs a loop that issues exactly L row loads per lane and pair (L = 2, 4 or 8, the row's
+// "class", stored with the work order) and permutes only L/2 operand dwords.  Empty slots
+// get an out-of-range buffer offset, for which the hardware returns zeros without a memory
+// access.  The number of loads per step is fixed inside a loop on purpose: the in-order
+// load counter then lets a multiply wait for exactly the loads of the previous step.
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // B must be smaller than 2 GiB on this path
 
@@ -130,22 +139,138 @@ __device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
-template <int NT, int WAVES, bool BF16>
-__global__ __launch_bounds__(WAVES * 64)
-void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
-                 float* __restrict__ C, int64_t ldc, int N)
+// Everything a wave needs to walk its share of a block row.
+struct RowWalk {
+    const int32_t* meta;        // metadata of the row's first pair
+    const uint16_t* vals;       // values of the row's first pair
+    int npairs;                 // pairs in the row (0 if this wave's slab is beyond N)
+    int ks;                     // first pair of this wave
+    int g, lane;
+    uint32_t lane_off;          // byte offset of the lane's first column inside a B row
+    uint32_t ldb_bytes;
+    bool col_ok;
+};
+
+// The pipelined loop for one row class: L B-row loads per lane and pair.
+template <int NT, int KW, int L, bool BF16>
+__device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
 {
-    constexpr int NW = 16 * NT;                    // columns per workgroup
     constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
+    constexpr int NQ = L / 2;                      // operand dwords that carry data
+    constexpr int SD = L > 4 ? 2 : 1;              // dwords of slot bytes a lane needs
+    const int last = w.npairs - 1;
+
+    // Loads of a pair are unconditional: a pair index past the wave's share is clamped to the
+    // row's last pair (a cache hit), its data is requested but never used.
+    auto pair_at = [&](int p) -> size_t { return static_cast<size_t>(p < last ? p : last); };
+    auto load_cols = [&](int p) -> i32x2 {        // block columns of the pair (wave-uniform address)
+        return *reinterpret_cast<const i32x2*>(w.meta + pair_at(p) * kPairMetaInts);
+    };
+    auto load_sel = [&](int p, uint32_t (&sel)[SD]) {
+        const int32_t* src = w.meta + pair_at(p) * kPairMetaInts + 4 + 2 * w.g;
+#pragma unroll
+        for (int x = 0; x < SD; ++x) sel[x] = static_cast<uint32_t>(src[x]);
+    };
+    auto load_a = [&](int p) -> u32x4 {
+        return *reinterpret_cast<const u32x4*>(w.vals + pair_at(p) * kPairHalves + w.lane * 8);
+    };
+    auto issue_b = [&](const i32x2& cols, const uint32_t (&sel)[SD], uint32_t (&R)[L][ND]) {
+        // byte offsets of the two blocks' first B rows: wave-uniform, computed on the scalar unit
+        const uint32_t base0 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cols[0]) * 16u * w.ldb_bytes);
+        const uint32_t base1 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cols[1]) * 16u * w.ldb_bytes);
+#pragma unroll
+        for (int kk = 0; kk < L; ++kk) {
+            const uint32_t c = (sel[kk >> 2] >> (8 * (kk & 3))) & 0xFFu;      // pair column in slot (g, kk)
+            uint32_t off = ((c & 16u) ? base1 : base0) + __umul24(c & 15u, w.ldb_bytes) + w.lane_off;
+            off |= (c & 0x80u) << 24;          // empty slot (0xFF): push the offset out of range
+            BLoad<2 * NT>::ld(R[kk], rsrc, off);
+        }
+    };
+    auto multiply = [&](const u32x4& a_raw, const uint32_t (&R)[L][ND], uint32_t keep) {
+        const u32x4 a = a_raw & keep;
+#pragma unroll
+        for (int t = 0; t < NT; ++t) {
+            const uint32_t pick = (t & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 b = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+            for (int q = 0; q < NQ; ++q)
+                b[q] = __builtin_amdgcn_perm(R[2 * q + 1][t >> 1], R[2 * q][t >> 1], pick);
+            acc[t] = mfma_pair<BF16>(a, b, acc[t]);
+        }
+    };
+
+    // Software pipeline over the wave's pairs ks, ks+KW, ...  Per pair h: its block columns and
+    // slot bytes are requested two steps ahead, its B rows (whose addresses need them) one step
+    // ahead, its block values right after the multiply of pair h-2 has released their
+    // registers.  Two register sets alternate, so nothing is copied; the loop body handles two
+    // pairs and has no exit in the middle (an odd tail multiplies a zeroed left operand).  The
+    // scheduling barriers keep every load ahead of the multiply that precedes its use, and the
+    // prologue issues its loads in the order the loop body leaves them in flight.
+    if (w.ks >= w.npairs) return;
+    const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
+    const int iters = (count + 1) >> 1;
+    uint32_t R0[L][ND], R1[L][ND];
+    uint32_t sel0[SD], sel1[SD];
+    int p = w.ks;
+    i32x2 c0 = load_cols(p);
+    load_sel(p, sel0);
+    __builtin_amdgcn_sched_barrier(0);
+    i32x2 c1 = load_cols(p + KW);
+    load_sel(p + KW, sel1);
+    u32x4 a0 = load_a(p);
+    issue_b(c0, sel0, R0);
+    __builtin_amdgcn_sched_barrier(0);
+    u32x4 a1 = load_a(p + KW);
+    for (int it = 0; it < iters; ++it) {
+        c0 = load_cols(p + 2 * KW);
+        load_sel(p + 2 * KW, sel0);
+        issue_b(c1, sel1, R1);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(a0, R0, 0xFFFFFFFFu);
+        __builtin_amdgcn_sched_barrier(0);
+        a0 = load_a(p + 2 * KW);
+        c1 = load_cols(p + 3 * KW);
+        load_sel(p + 3 * KW, sel1);
+        issue_b(c0, sel0, R0);
+        __builtin_amdgcn_sched_barrier(0);
+        multiply(a1, R1, p + KW < w.npairs ? 0xFFFFFFFFu : 0u);
+        __builtin_amdgcn_sched_barrier(0);
+        a1 = load_a(p + 3 * KW);
+        p += 2 * KW;
+    }
+}
+
+template <int NT, int KW, int SW, int LMAX, bool BF16>
+__global__ __launch_bounds__(KW * SW * 64)
+void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
+                 float* __restrict__ C, int64_t ldc, int N, int vec_store)
+{
+    constexpr int NW = 16 * NT;                    // columns per wave
+    constexpr int WAVES = KW * SW;
     const int lane = threadIdx.x & 63;
-    const int wave = threadIdx.x >> 6;
+    const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in an SGPR
+    const int ks = wave % KW;                      // which share of the block row
+    const int sl = wave / KW;                      // which column slab of the group
     const int i = lane & 15, g = lane >> 4;
-    const int br = d.order[blockIdx.x];
-    const int n0 = blockIdx.y * NW;
+    const int entry = d.order[blockIdx.x];         // block row and its class (2 top bits used)
+    const int br = entry & 0x0FFFFFFF;
+    const int cls = entry >> 28;                   // 0: L = 2, 1: L = 4, 2: L = 8
+    const int n0 = (blockIdx.y * SW + sl) * NW;
     const int start = d.row_ptr[br], end = d.row_ptr[br + 1];
-    const int npairs = (end - start + 1) >> 1;
     const int col0 = n0 + NT * i;                  // first of this lane's NT columns
-    const bool col_ok = col0 < N;                  // N is a multiple of NT on this path
+
+    RowWalk w;
+    w.meta = d.meta + static_cast<size_t>(start >> 1) * kPairMetaInts;
+    w.vals = d.vals + static_cast<size_t>(start >> 1) * kPairHalves;
+    w.npairs = n0 < N ? (end - start) >> 1 : 0;    // block rows are padded to an even count
+    w.ks = ks;
+    w.g = g;
+    w.lane = lane;
+    // a lane whose columns lie beyond N carries the out-of-range bit in its offset
+    w.lane_off = col0 < N ? static_cast<uint32_t>(col0) * 2u : kOutOfRange;
+    w.ldb_bytes = ldb_bytes;
+    w.col_ok = col0 < N;                           // N is a multiple of NT on this path
+    const bool col_ok = w.col_ok;
 
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), 0x00020000);
@@ -154,103 +279,154 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
 #pragma unroll
     for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
-    for (int p = wave; p < npairs; p += WAVES) {
-        const int blk = start + 2 * p + (g >> 1);
-        const bool valid = blk < end;
-        int bcol = 0;
-        uint32_t mask = 0;
-        u32x4 a = u32x4{0u, 0u, 0u, 0u};
-        if (valid) {
-            const i32x2 m = *reinterpret_cast<const i32x2*>(d.meta + 2 * static_cast<size_t>(blk));
-            bcol = m[0];
-            mask = static_cast<uint32_t>(m[1]);
-            a = *reinterpret_cast<const u32x4*>(d.vals + static_cast<size_t>(blk) * 256 + ((g & 1) * 16 + i) * 8);
-        }
-        const uint32_t bits = col_ok ? ((mask >> (8 * (g & 1))) & 0xFFu) : 0u;
-        const uint32_t row0 = static_cast<uint32_t>(bcol) * 16u + 8u * (g & 1);
-        const uint32_t off0 = row0 * ldb_bytes + static_cast<uint32_t>(col0) * 2u;
-
-        uint32_t R[8][ND];
-#pragma unroll
-        for (int kk = 0; kk < 8; ++kk) {
-            const uint32_t off = ((bits >> kk) & 1u) ? off0 + kk * ldb_bytes : kOutOfRange;
-            BLoad<2 * NT>::ld(R[kk], rsrc, off);
-        }
-#pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const uint32_t sel = (t & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 b;
-#pragma unroll
-            for (int q = 0; q < 4; ++q)
-                b[q] = __builtin_amdgcn_perm(R[2 * q + 1][t >> 1], R[2 * q][t >> 1], sel);
-            acc[t] = mfma_pair<BF16>(a, b, acc[t]);
-        }
+    if constexpr (LMAX >= 8) {
+        if (cls == 2) walk_row<NT, KW, 8, BF16>(w, rsrc, acc);
     }
+    if constexpr (LMAX >= 4) {
+        if (cls == 1) walk_row<NT, KW, 4, BF16>(w, rsrc, acc);
+    }
+    if (cls == 0) walk_row<NT, KW, 2, BF16>(w, rsrc, acc);
 
     // acc[t][r] = C'[4g + r][n0 + NT*i + t]
-    if constexpr (WAVES == 1) {
+    if constexpr (KW == 1) {
+        if (col_ok) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            const int64_t out_row = d.perm[br * 16 + 4 * g + r];
-            if (out_row < 0 || !col_ok) continue;
-            float* dst = C + out_row * ldc + col0;
+            for (int r = 0; r < 4; ++r) {
+                const int64_t out_row = d.perm[br * 16 + 4 * g + r];
+                if (out_row < 0) continue;
+                float* dst = C + out_row * ldc + col0;
+                if constexpr (NT >= 4) {
+                    if (vec_store) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) dst[t] = acc[t][r];
+                        for (int t = 0; t < NT; t += 4)
+                            *reinterpret_cast<f32x4*>(dst + t) = f32x4{acc[t][r], acc[t + 1][r], acc[t + 2][r], acc[t + 3][r]};
+                        continue;
+                    }
+                }
+#pragma unroll
+                for (int t = 0; t < NT; ++t) dst[t] = acc[t][r];
+            }
         }
     } else {
-        __shared__ float red[WAVES][16][NW + 4];
+        constexpr int LD = NW + 4;                 // padded row of the reduction buffer (floats)
+        __shared__ float red[WAVES * 16 * LD];
+        float* mine = red + wave * 16 * LD;
 #pragma unroll
-        for (int r = 0; r < 4; ++r)
+        for (int r = 0; r < 4; ++r) {
+            float* dst = mine + (4 * g + r) * LD + NT * i;
+            if constexpr (NT >= 4) {
 #pragma unroll
-            for (int t = 0; t < NT; ++t) red[wave][4 * g + r][NT * i + t] = acc[t][r];
+                for (int t = 0; t < NT; t += 4)
+                    *reinterpret_cast<f32x4*>(dst + t) = f32x4{acc[t][r], acc[t + 1][r], acc[t + 2][r], acc[t + 3][r]};
+            } else {
+#pragma unroll
+                for (int t = 0; t < NT; ++t) dst[t] = acc[t][r];
+            }
+        }
         __syncthreads();
-        for (int e = threadIdx.x; e < 16 * NW; e += WAVES * 64) {
-            const int row = e / NW, c = e % NW;
-            float s = red[0][row][c];
+        const int nbase = blockIdx.y * SW * NW;
+        if constexpr (NT >= 4) {
+            // each thread sums and stores four consecutive columns
+            constexpr int Q = NW / 4;              // quads per row of one slab
+            for (int e = threadIdx.x; e < SW * 16 * Q; e += WAVES * 64) {
+                const int s = e / (16 * Q), row = (e / Q) % 16, c = (e % Q) * 4;
+                const float* src = red + (s * KW) * 16 * LD + row * LD + c;
+                f32x4 v = *reinterpret_cast<const f32x4*>(src);
 #pragma unroll
-            for (int w = 1; w < WAVES; ++w) s += red[w][row][c];
-            const int64_t out_row = d.perm[br * 16 + row];
-            if (out_row >= 0 && n0 + c < N) C[out_row * ldc + n0 + c] = s;
+                for (int w = 1; w < KW; ++w) v += *reinterpret_cast<const f32x4*>(src + w * 16 * LD);
+                const int64_t out_row = d.perm[br * 16 + row];
+                const int col = nbase + s * NW + c;
+                if (out_row < 0 || col >= N) continue;
+                float* dst = C + out_row * ldc + col;
+                if (vec_store) {
+                    *reinterpret_cast<f32x4*>(dst) = v;
+                } else {
+                    dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
+                }
+            }
+        } else {
+            for (int e = threadIdx.x; e < SW * 16 * NW; e += WAVES * 64) {
+                const int s = e / (16 * NW), row = (e / NW) % 16, c = e % NW;
+                const float* src = red + (s * KW) * 16 * LD + row * LD + c;
+                float v = src[0];
+#pragma unroll
+                for (int w = 1; w < KW; ++w) v += src[w * 16 * LD];
+                const int64_t out_row = d.perm[br * 16 + row];
+                const int col = nbase + s * NW + c;
+                if (out_row >= 0 && col < N) C[out_row * ldc + col] = v;
+            }
         }
     }
 }
 
-template <int NT, int WAVES, bool BF16>
+template <int NT, int KW, int SW, int LMAX, bool BF16>
 static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                           int64_t N, hipStream_t stream)
 {
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
-    dim3 grid(static_cast<unsigned>(d.nbr), static_cast<unsigned>(slabs));
+    dim3 grid(static_cast<unsigned>(d.nbr), static_cast<unsigned>((slabs + SW - 1) / SW));
     const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * 2) : 0u;
-    hipLaunchKernelGGL((spmm_kernel<NT, WAVES, BF16>), grid, dim3(WAVES * 64), 0, stream,
-                       d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N));
+    const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
+    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, LMAX, BF16>), grid, dim3(KW * SW * 64), 0, stream,
+                       d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
     return static_cast<int>(hipGetLastError());
+}
+
+static const char* variant_name(bool bf16, int kw, int sw, int lmax)
+{
+    static thread_local char buf[48];
+    snprintf(buf, sizeof(buf), "spmm_%s_k%ds%d_l%d", bf16 ? "bf16" : "f16", kw, sw, lmax);
+    return buf;
+}
+
+template <int NT, int LMAX, bool BF16>
+static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
+                        int64_t N, hipStream_t stream, const char** variant)
+{
+    const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
+    const bool short_rows = d.mean_row_blocks < 12.0 && d.max_row_blocks < 64;
+    // KW waves share one block row (summed through LDS); SW waves of a group take neighbouring
+    // column slabs of the same block row, so its block values reach HBM once per group.
+    if (short_rows) {
+        if (slabs >= 2) { *variant = variant_name(BF16, 1, 2, LMAX); return launch_variant<NT, 1, 2, LMAX, BF16>(d, B, ldb, C, ldc, N, stream); }
+        *variant = variant_name(BF16, 1, 1, LMAX);
+        return launch_variant<NT, 1, 1, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);
+    }
+    if (slabs >= 2) { *variant = variant_name(BF16, 4, 2, LMAX); return launch_variant<NT, 4, 2, LMAX, BF16>(d, B, ldb, C, ldc, N, stream); }
+    *variant = variant_name(BF16, 8, 1, LMAX);
+    return launch_variant<NT, 8, 1, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);
 }
 
 template <int NT, bool BF16>
 static int launch_nt(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                      int64_t N, hipStream_t stream, const char** variant)
 {
-    // short block rows: one wave per tile, no LDS reduction; long rows: split over four waves
-    if (d.mean_row_blocks < 12.0 && d.max_row_blocks < 64) {
-        *variant = BF16 ? "spmm_bf16_w1" : "spmm_f16_w1";
-        return launch_variant<NT, 1, BF16>(d, B, ldb, C, ldc, N, stream);
-    }
-    *variant = BF16 ? "spmm_bf16_w4" : "spmm_f16_w4";
-    return launch_variant<NT, 4, BF16>(d, B, ldb, C, ldc, N, stream);
+    // the kernel only carries the loops (and registers) for the row classes the matrix has
+    if (d.max_class >= 2) return launch_shape<NT, 8, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    if (d.max_class == 1) return launch_shape<NT, 4, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    return launch_shape<NT, 2, BF16>(d, B, ldb, C, ldc, N, stream, variant);
 }
 
 template <bool BF16>
 static int launch_dtype(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                         int64_t N, hipStream_t stream, const char** variant)
 {
-    // widest B row load (2*NT bytes) that N, ldb and the base address allow
+    // B row loads are 2*NT bytes wide: among the widths N, ldb and the base address allow,
+    // take the one that pads N the least (ties: the wider load).
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B);
-    auto fits = [&](int nt) { return N % nt == 0 && ldb % nt == 0 && addr % (2 * nt) == 0; };
-    if (fits(8)) return launch_nt<8, BF16>(d, B, ldb, C, ldc, N, stream, variant);
-    if (fits(4)) return launch_nt<4, BF16>(d, B, ldb, C, ldc, N, stream, variant);
-    if (fits(2)) return launch_nt<2, BF16>(d, B, ldb, C, ldc, N, stream, variant);
-    return launch_nt<1, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    int best = 1;
+    int64_t best_pad = (N + 15) / 16 * 16;
+    for (int nt = 2; nt <= 8; nt *= 2) {
+        if (N % nt != 0 || ldb % nt != 0 || addr % (2 * nt) != 0) continue;
+        const int64_t pad = (N + 16 * nt - 1) / (16 * nt) * (16 * nt);
+        if (pad <= best_pad) { best = nt; best_pad = pad; }
+    }
+    switch (best) {
+    case 8: return launch_nt<8, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    case 4: return launch_nt<4, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    case 2: return launch_nt<2, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    default: return launch_nt<1, BF16>(d, B, ldb, C, ldc, N, stream, variant);
+    }
 }
 
 int launch_spmm(const DeviceBcsr& d, bool bf16, const void* B, int64_t ldb, float* C, int64_t ldc,

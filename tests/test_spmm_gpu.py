@@ -135,12 +135,18 @@ def test_reorder_modes_agree_and_slabs_are_independent(oracle_c):
     m1, c1 = _run(w, oracle_c, reorder=1)
     m0, c0 = _run(w, oracle_c, reorder=0)
     assert S.smat_get_info(m1.handle)["n_blocks"] < S.smat_get_info(m0.handle)["n_blocks"]
-    # the same handle on a column slab of B gives the same numbers as the full call
+    # the same handle on a column slab of B: same numbers; bit for bit when the same kernel
+    # variant (hence the same summation order) serves both calls
+    full_kernel = S.smat_last_kernel()
     b = _dev_b(w)
+    c_ref, s_ref = _oracle_c(oracle_c, w)
     half = torch.empty((w.M, 16), dtype=torch.float32, device="cuda")
     S.smat_spmm(m1.handle, b[:, 16:32], half, 16)
     torch.cuda.synchronize()
-    assert np.array_equal(half.cpu().numpy(), c1[:, 16:32])
+    got = half.cpu().numpy()
+    if S.smat_last_kernel() == full_kernel:
+        assert np.array_equal(got, c1[:, 16:32])
+    assert np.all(np.abs(got - c_ref[:, 16:32]) <= REL_TIGHT * s_ref[:, 16:32] + 1e-30)
     # repeated launches are bitwise reproducible (single writer per tile, fixed summation order)
     again = m1.spmm(b)
     torch.cuda.synchronize()
