@@ -106,10 +106,11 @@ def main():
 
     extra = {}
     if args.cold:
-        flush = torch.empty(1 << 30, dtype=torch.uint8, device=dev)     # > L2 + 256 MB Infinity Cache
+        # read-only sweep over 1 GiB (> L2 + 256 MB Infinity Cache): evicts without leaving dirty lines
+        flush = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
         evs = []
         for _ in range(min(args.steps, 20)):
-            flush.add_(1)
+            flush.sum()
             a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
             a.record(stream)
             S.smat_spmm(h, B, C, w.N, stream)

@@ -64,7 +64,7 @@ void smat_default_options(smat_options_t *opt);
  * Preprocessing (Overview and Preprocessing sections): CSR -> row permutation
  * that lowers the number of nonzero blocks -> BCSR structure.
  *
- *   M, K      rows / columns of A, 0 <= M, K < 2^31
+ *   M, K      rows / columns of A, 0 <= M < 2^31 - 16, 0 <= K < 2^24
  *   row_ptr   HOST int64[M+1], row_ptr[0] == 0, non-decreasing
  *   col_idx   HOST int32[nnz], strictly ascending inside each row, 0 <= col < K
  *   vals      HOST 16-bit values [nnz] (fp16 or bf16 bit patterns per dtype);

@@ -23,8 +23,15 @@ struct smat_handle {
     bool bound = false;
     // Device-side block arrays pad every block row to an even number of blocks (the kernel
     // multiplies blocks two at a time); the pad block has no occupied column and zero values.
-    std::vector<int32_t> dev_row_ptr;   // [nbr+1] offsets into the padded block arrays
+    std::vector<int32_t> dev_row_ptr;    // [nbr+1] offsets into the padded block arrays
     int64_t n_dev_blocks = 0;
+    // Row class: how many B-row loads per lane a pair of the block row needs at most (occupied
+    // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2.  The slot table of a
+    // row takes 16 * L bytes per pair; slots_off counts 32-byte units.
+    std::vector<int8_t> row_class;       // [nbr]
+    std::vector<uint32_t> slots_off;     // [nbr]
+    uint64_t slots_units = 0;
+    int max_class = 0;
     smat::DeviceBcsr dev;
     // device copies of the CSR (kept: they live in the caller's workspace anyway)
     const int64_t* d_csr_row_ptr = nullptr;
@@ -53,7 +60,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
-    size_t perm, row_ptr, meta, order, vals, csr_row_ptr, csr_col_idx, csr_vals, total;
+    size_t perm, row_ptr, order, slots_off, slots, vals, blk_col, occ, csr_row_ptr, csr_col_idx, csr_vals, total;
 };
 
 Layout make_layout(const smat_handle& h)
@@ -65,14 +72,23 @@ Layout make_layout(const smat_handle& h)
     const size_t nnz = h.csr.col_idx.size();
     l.perm = take(nbr * 16 * sizeof(int32_t));
     l.row_ptr = take((nbr + 1) * sizeof(int32_t));
-    l.meta = take(n_e / 2 * smat::kPairMetaInts * sizeof(int32_t));
     l.order = take(nbr * sizeof(int32_t));
+    l.slots_off = take(nbr * sizeof(uint32_t));
+    l.slots = take(static_cast<size_t>(h.slots_units) * 32);
     l.vals = take(n_e * 512);
+    l.blk_col = take(n_e * sizeof(int32_t));
+    l.occ = take(n_e / 2 * sizeof(uint32_t));
     l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
     l.csr_col_idx = take(nnz * sizeof(int32_t));
     l.csr_vals = take(nnz * sizeof(uint16_t));
     l.total = off ? off : kAlign;
     return l;
+}
+
+// occupancy mask of the pair that starts at block s of a block row ending at block s1
+uint32_t pair_occupancy(const smat::Bcsr& b, int32_t s, int32_t s1)
+{
+    return b.col_mask[s] | (s + 1 < s1 ? static_cast<uint32_t>(b.col_mask[s + 1]) << 16 : 0u);
 }
 
 }  // namespace
@@ -105,8 +121,8 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
-        if (M > (int64_t{1} << 32) - 1 - 16 || (M + 15) / 16 >= (int64_t{1} << 28))
-            return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
+        if ((M + 15) / 16 >= (int64_t{1} << 28)) return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
+        if (K >= (int64_t{1} << 24)) return fail(SMAT_ERR_UNSUPPORTED, "K must be below 2^24");
         if (row_ptr[0] != 0) return fail(SMAT_ERR_BAD_CSR, "row_ptr[0] must be 0");
         for (int64_t r = 0; r < M; ++r)
             if (row_ptr[r + 1] < row_ptr[r]) return fail(SMAT_ERR_BAD_CSR, "row_ptr decreases at row " + std::to_string(r));
@@ -135,6 +151,26 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
             h->dev_row_ptr[br + 1] = static_cast<int32_t>(padded);
         }
         h->n_dev_blocks = padded;
+        const size_t nbr = static_cast<size_t>(h->bcsr.nbr);
+        h->row_class.assign(nbr, 0);
+        h->slots_off.assign(nbr, 0);
+        uint64_t units = 0;
+        for (size_t br = 0; br < nbr; ++br) {
+            const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
+            int worst = 0;
+            for (int32_t s = s0; s < s1; s += 2)
+                worst = std::max(worst, __builtin_popcount(pair_occupancy(h->bcsr, s, s1)));
+            const int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
+            h->row_class[br] = static_cast<int8_t>(cls);
+            h->max_class = std::max(h->max_class, cls);
+            h->slots_off[br] = static_cast<uint32_t>(units);
+            units += static_cast<uint64_t>((s1 - s0 + 1) / 2) << cls;       // 1, 2 or 4 units per pair
+            if (units >= (uint64_t{1} << 32)) {
+                delete h;
+                return fail(SMAT_ERR_UNSUPPORTED, "slot table too large");
+            }
+        }
+        h->slots_units = units;
         *out = h;
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
@@ -200,28 +236,37 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
 
         std::vector<int32_t> perm_padded(nbr * 16, -1);
         std::memcpy(perm_padded.data(), b.perm.data(), sizeof(int32_t) * M);
-        // per-pair metadata; an odd tail is completed by a pad block: column beyond every real
-        // one (keeps the row's columns ascending), nothing occupied
-        std::vector<int32_t> meta(n_e / 2 * smat::kPairMetaInts);
+        // slot tables (pair_layout.h), block columns and occupancy masks; an odd tail is completed
+        // by a pad block: column beyond every real one (keeps the row's columns ascending),
+        // nothing occupied
+        std::vector<uint32_t> slots(static_cast<size_t>(h->slots_units) * 8);
+        std::vector<int32_t> blk_col(n_e);
+        std::vector<uint32_t> occ_mask(n_e / 2);
+        const uint32_t no_row = static_cast<uint32_t>(h->csr.K);        // one past the last row of B
         for (size_t br = 0; br < nbr; ++br) {
             const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
-            size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2;
-            for (int32_t s = s0; s < s1; s += 2, ++pair) {
-                int32_t* m = meta.data() + pair * smat::kPairMetaInts;
+            const int L = 2 << h->row_class[br];
+            size_t blk = static_cast<size_t>(h->dev_row_ptr[br]);
+            uint32_t* table = slots.data() + static_cast<size_t>(h->slots_off[br]) * 8;
+            for (int32_t s = s0; s < s1; s += 2, blk += 2, table += 4 * L) {
                 const bool has2 = s + 1 < s1;
-                const uint32_t occ = b.col_mask[s] | (has2 ? static_cast<uint32_t>(b.col_mask[s + 1]) << 16 : 0u);
-                m[0] = b.col_idx[s];
-                m[1] = has2 ? b.col_idx[s + 1] : 0x7FFFFFFF;
-                m[2] = static_cast<int32_t>(occ);
-                uint8_t sel[4][8];
-                std::memset(sel, 0xFF, sizeof(sel));
+                const uint32_t occ = pair_occupancy(b, s, s1);
+                blk_col[blk] = b.col_idx[s];
+                blk_col[blk + 1] = has2 ? b.col_idx[s + 1] : 0x7FFFFFFF;
+                occ_mask[blk / 2] = occ;
+                for (int x = 0; x < 4 * L; ++x) table[x] = no_row;
                 int rank = 0;
-                for (int c = 0; c < 32; ++c)
-                    if (occ >> c & 1u) { sel[smat::slot_group(rank)][smat::slot_pos(rank)] = static_cast<uint8_t>(c); ++rank; }
-                m[3] = rank;
-                std::memcpy(m + 4, sel, sizeof(sel));
+                for (int c = 0; c < 32; ++c) {
+                    if (!(occ >> c & 1u)) continue;
+                    const uint32_t row = static_cast<uint32_t>(b.col_idx[s + (c >> 4)]) * 16u + static_cast<uint32_t>(c & 15);
+                    table[smat::slot_group(rank) * L + smat::slot_pos(rank)] = row;
+                    ++rank;
+                }
             }
         }
+        std::vector<int32_t> order_cls(nbr);
+        for (size_t x = 0; x < nbr; ++x)
+            order_cls[x] = b.order[x] | (static_cast<int32_t>(h->row_class[b.order[x]]) << 28);
 
         auto up = [&](size_t off, const void* src, size_t n) -> int {
             if (n == 0) return 0;
@@ -230,24 +275,11 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         int e;
         if ((e = up(l.perm, perm_padded.data(), perm_padded.size() * 4))) return hip_fail("copy perm", e);
         if ((e = up(l.row_ptr, h->dev_row_ptr.data(), h->dev_row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
-        if ((e = up(l.meta, meta.data(), meta.size() * 4))) return hip_fail("copy meta", e);
-        // row class: how many B-row loads per lane a pair of the block row needs at most
-        // (occupied columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2
-        std::vector<int32_t> order_cls(nbr);
-        int max_class = 0;
-        {
-            std::vector<int8_t> cls(nbr, 0);
-            for (size_t br = 0; br < nbr; ++br) {
-                int worst = 0;
-                for (size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2; pair < static_cast<size_t>(h->dev_row_ptr[br + 1]) / 2; ++pair)
-                    worst = std::max(worst, meta[pair * smat::kPairMetaInts + 3]);
-                cls[br] = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
-                max_class = std::max<int>(max_class, cls[br]);
-            }
-            for (size_t x = 0; x < nbr; ++x)
-                order_cls[x] = b.order[x] | (static_cast<int32_t>(cls[b.order[x]]) << 28);
-        }
         if ((e = up(l.order, order_cls.data(), order_cls.size() * 4))) return hip_fail("copy order", e);
+        if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
+        if ((e = up(l.slots, slots.data(), slots.size() * 4))) return hip_fail("copy slot tables", e);
+        if ((e = up(l.blk_col, blk_col.data(), blk_col.size() * 4))) return hip_fail("copy block columns", e);
+        if ((e = up(l.occ, occ_mask.data(), occ_mask.size() * 4))) return hip_fail("copy occupancy", e);
         if ((e = up(l.csr_row_ptr, h->csr.row_ptr.data(), (M + 1) * 8))) return hip_fail("copy csr row_ptr", e);
         if ((e = up(l.csr_col_idx, h->csr.col_idx.data(), nnz * 4))) return hip_fail("copy csr col_idx", e);
         if ((e = up(l.csr_vals, h->csr.vals.data(), nnz * 2))) return hip_fail("copy csr vals", e);
@@ -255,9 +287,12 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         smat::DeviceBcsr d;
         d.perm = reinterpret_cast<const int32_t*>(base + l.perm);
         d.row_ptr = reinterpret_cast<const int32_t*>(base + l.row_ptr);
-        d.meta = reinterpret_cast<const int32_t*>(base + l.meta);
-        d.vals = reinterpret_cast<const uint16_t*>(base + l.vals);
         d.order = reinterpret_cast<const int32_t*>(base + l.order);
+        d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
+        d.slots = reinterpret_cast<const uint32_t*>(base + l.slots);
+        d.vals = reinterpret_cast<const uint16_t*>(base + l.vals);
+        d.blk_col = reinterpret_cast<const int32_t*>(base + l.blk_col);
+        d.occ = reinterpret_cast<const uint32_t*>(base + l.occ);
         d.M = h->csr.M;
         d.K = h->csr.K;
         d.nbr = b.nbr;
@@ -265,7 +300,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         int64_t longest = 0;
         for (size_t r = 0; r < nbr; ++r) longest = std::max<int64_t>(longest, b.row_ptr[r + 1] - b.row_ptr[r]);
         d.max_row_blocks = longest;
-        d.max_class = max_class;
+        d.max_class = h->max_class;
         d.mean_row_blocks = nbr ? static_cast<double>(b.n_blocks) / static_cast<double>(nbr) : 0.0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
@@ -303,9 +338,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
             const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
             size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2;
             for (int32_t s = s0; s < s1; s += 2, ++pair) {
-                const bool has2 = s + 1 < s1;
-                const uint32_t occ = h->bcsr.col_mask[s] |
-                                     (has2 ? static_cast<uint32_t>(h->bcsr.col_mask[s + 1]) << 16 : 0u);
+                const uint32_t occ = pair_occupancy(h->bcsr, s, s1);
                 const uint16_t* src = raw.data() + pair * smat::kPairHalves;
                 uint8_t used[smat::kPairHalves];
                 std::memset(used, 0, sizeof(used));

@@ -11,15 +11,18 @@ namespace smat {
 // blocks; pair P of the whole matrix covers blocks 2P and 2P+1.  See pair_layout.h for the
 // layout of a pair's values and metadata.
 struct DeviceBcsr {
-    const int32_t* perm = nullptr;      // [nbr*16] new row -> old row, -1 beyond M
-    const int32_t* row_ptr = nullptr;   // [nbr+1] block offsets (even)
-    const int32_t* meta = nullptr;      // [12 * n_e/2] per pair
-    const uint16_t* vals = nullptr;     // [256*n_e]
-    const int32_t* order = nullptr;     // [nbr] block rows, longest first; bits 28..29: row class
+    const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
+    const int32_t* row_ptr = nullptr;    // [nbr+1] block offsets (even)
+    const int32_t* order = nullptr;      // [nbr] block rows, longest first; bits 28..29: row class
+    const uint32_t* slots_off = nullptr; // [nbr] start of the row's slot table, in 32-byte units
+    const uint32_t* slots = nullptr;     // slot tables: per pair 4 groups x L entries (L by row class)
+    const uint16_t* vals = nullptr;      // [256*n_e]
+    const int32_t* blk_col = nullptr;    // [n_e] block column per (padded) block; bind-time scatter only
+    const uint32_t* occ = nullptr;       // [n_e/2] occupancy mask per pair; bind-time scatter only
     int64_t M = 0, K = 0, nbr = 0, n_e = 0;
-    int64_t max_row_blocks = 0;         // longest block row
+    int64_t max_row_blocks = 0;          // longest block row
     double mean_row_blocks = 0;
-    int max_class = 0;                  // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pair)
+    int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pair)
 };
 
 // Sets n16 16-byte words at dst to zero.

@@ -19,6 +19,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef int i32x2 __attribute__((ext_vector_type(2)));
+typedef int i32x3 __attribute__((ext_vector_type(3)));
 
 // ---------------------------------------------------------------------------
 // bind-time kernels
@@ -61,13 +62,12 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
         int lo = hint, hi = hi0;                     // columns ascend, so the block never moves back
         while (lo < hi) {
             const int mid = (lo + hi) >> 1;
-            if (d.meta[static_cast<size_t>(mid >> 1) * kPairMetaInts + (mid & 1)] < bc) lo = mid + 1; else hi = mid;
+            if (d.blk_col[mid] < bc) lo = mid + 1; else hi = mid;
         }
         hint = lo;
         const size_t pair = static_cast<size_t>(lo >> 1);
         const int pc = (lo & 1) * 16 + (c & 15);     // column inside the pair
-        const uint32_t occ = static_cast<uint32_t>(d.meta[pair * kPairMetaInts + 2]);
-        const int rank = __popc(occ & ((1u << pc) - 1u));
+        const int rank = __popc(d.occ[pair] & ((1u << pc) - 1u));
         vals_out[pair * kPairHalves + pair_half_index(rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
     }
 }
@@ -105,29 +105,35 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // Only occupied columns of a pair need a B row.  The pair layout packs them into the first
 // slots of every lane group, so a block row whose pairs hold at most 4*L occupied columns
 // runs a loop that issues exactly L row loads per lane and pair (L = 2, 4 or 8, the row's
-// "class", stored with the work order) and permutes only L/2 operand dwords.  Empty slots
-// get an out-of-range buffer offset, for which the hardware returns zeros without a memory
-// access.  The number of loads per step is fixed inside a loop on purpose: the in-order
-// load counter then lets a multiply wait for exactly the loads of the previous step.
+// "class", stored with the work order) and permutes only L/2 operand dwords.  The slot table
+// gives the B row of every slot; empty slots name row K, one past the end of B, for which
+// the range-checked buffer load returns zeros without a memory access.  The number of loads
+// per step is fixed inside a loop on purpose: the in-order load counter then lets a multiply
+// wait for exactly the loads it needs while younger ones stay in flight.
+//
+// All loads of the loop are buffer loads whose wave-uniform part of the address travels in
+// a scalar register, so a step spends vector ALU work only on what is per lane: one
+// multiply-add per B row address and one byte-permute per operand dword.
 
 constexpr uint32_t kOutOfRange = 0x80000000u;   // B must be smaller than 2 GiB on this path
+constexpr int kRsrcFlags = 0x00020000;          // raw buffer, 32-bit data format
 
 template <int BYTES> struct BLoad;
 template <> struct BLoad<2> {
-    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off)
-    { r[0] = static_cast<uint16_t>(__builtin_amdgcn_raw_buffer_load_b16(s, off, 0, 0)); }
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { r[0] = static_cast<uint16_t>(__builtin_amdgcn_raw_buffer_load_b16(s, off, soff, 0)); }
 };
 template <> struct BLoad<4> {
-    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off)
-    { r[0] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b32(s, off, 0, 0)); }
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { r[0] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b32(s, off, soff, 0)); }
 };
 template <> struct BLoad<8> {
-    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off)
-    { i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(s, off, 0, 0); r[0] = v[0]; r[1] = v[1]; }
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(s, off, soff, 0); r[0] = v[0]; r[1] = v[1]; }
 };
 template <> struct BLoad<16> {
-    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off)
-    { i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s, off, 0, 0); r[0] = v[0]; r[1] = v[1]; r[2] = v[2]; r[3] = v[3]; }
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s, off, soff, 0); r[0] = v[0]; r[1] = v[1]; r[2] = v[2]; r[3] = v[3]; }
 };
 
 template <bool BF16>
@@ -141,53 +147,62 @@ __device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
 
 // Everything a wave needs to walk its share of a block row.
 struct RowWalk {
-    const int32_t* meta;        // metadata of the row's first pair
+    const uint32_t* slots;      // slot table of the row's first pair
     const uint16_t* vals;       // values of the row's first pair
     int npairs;                 // pairs in the row (0 if this wave's slab is beyond N)
     int ks;                     // first pair of this wave
     int g, lane;
     uint32_t lane_off;          // byte offset of the lane's first column inside a B row
     uint32_t ldb_bytes;
-    bool col_ok;
 };
 
-// The pipelined loop for one row class: L B-row loads per lane and pair.
-template <int NT, int KW, int L, bool BF16>
-__device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
-{
-    constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
-    constexpr int NQ = L / 2;                      // operand dwords that carry data
-    constexpr int SD = L > 4 ? 2 : 1;              // dwords of slot bytes a lane needs
-    const int last = w.npairs - 1;
+// Per-class pieces shared by the two pipelines below.
+template <int NT, int L, bool BF16>
+struct PairOps {
+    static constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
+    static constexpr int NQ = L / 2;                      // operand dwords that carry data
+    __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
+    uint32_t slots_voff, vals_voff, lane_off, ldb_bytes;
+    int last;
 
-    // Loads of a pair are unconditional: a pair index past the wave's share is clamped to the
-    // row's last pair (a cache hit), its data is requested but never used.
-    auto pair_at = [&](int p) -> size_t { return static_cast<size_t>(p < last ? p : last); };
-    auto load_cols = [&](int p) -> i32x2 {        // block columns of the pair (wave-uniform address)
-        return *reinterpret_cast<const i32x2*>(w.meta + pair_at(p) * kPairMetaInts);
-    };
-    auto load_sel = [&](int p, uint32_t (&sel)[SD]) {
-        const int32_t* src = w.meta + pair_at(p) * kPairMetaInts + 4 + 2 * w.g;
+    __device__ __forceinline__ PairOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
+        : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * 16u),
+          lane_off(w.lane_off), ldb_bytes(w.ldb_bytes), last(w.npairs - 1)
+    {
+        slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npairs * 16 * L, kRsrcFlags);
+        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * 1024, kRsrcFlags);
+        none_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, 0, kRsrcFlags);
+    }
+    // Loads of a pair are unconditional: a pair index past the row's end is clamped to the
+    // row's last pair (a cache hit).  All of this is scalar arithmetic.
+    __device__ __forceinline__ uint32_t clamp(int p) const { return static_cast<uint32_t>(p < last ? p : last); }
+    // B rows of the lane group's L slots
+    __device__ __forceinline__ void load_slots(int p, uint32_t (&m)[L]) const
+    {
+        const uint32_t soff = clamp(p) * (16u * L);
+        if constexpr (L == 2) {
+            BLoad<8>::ld(m, slots_rsrc, slots_voff, soff);
+        } else {
 #pragma unroll
-        for (int x = 0; x < SD; ++x) sel[x] = static_cast<uint32_t>(src[x]);
-    };
-    auto load_a = [&](int p) -> u32x4 {
-        return *reinterpret_cast<const u32x4*>(w.vals + pair_at(p) * kPairHalves + w.lane * 8);
-    };
-    auto issue_b = [&](const i32x2& cols, const uint32_t (&sel)[SD], uint32_t (&R)[L][ND]) {
-        // byte offsets of the two blocks' first B rows: wave-uniform, computed on the scalar unit
-        const uint32_t base0 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cols[0]) * 16u * w.ldb_bytes);
-        const uint32_t base1 = __builtin_amdgcn_readfirstlane(static_cast<uint32_t>(cols[1]) * 16u * w.ldb_bytes);
-#pragma unroll
-        for (int kk = 0; kk < L; ++kk) {
-            const uint32_t c = (sel[kk >> 2] >> (8 * (kk & 3))) & 0xFFu;      // pair column in slot (g, kk)
-            uint32_t off = ((c & 16u) ? base1 : base0) + __umul24(c & 15u, w.ldb_bytes) + w.lane_off;
-            off |= (c & 0x80u) << 24;          // empty slot (0xFF): push the offset out of range
-            BLoad<2 * NT>::ld(R[kk], rsrc, off);
+            for (int x = 0; x < L; x += 4) BLoad<16>::ld(m + x, slots_rsrc, slots_voff + 4u * x, soff);
         }
-    };
-    auto multiply = [&](const u32x4& a_raw, const uint32_t (&R)[L][ND], uint32_t keep) {
-        const u32x4 a = a_raw & keep;
+    }
+    // block values; `live` false (a step past the wave's last pair) reads zeros instead
+    __device__ __forceinline__ u32x4 load_a(int p, bool live) const
+    {
+        uint32_t r[4];
+        if (live) BLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
+        else BLoad<16>::ld(r, none_rsrc, vals_voff, 0u);
+        return u32x4{r[0], r[1], r[2], r[3]};
+    }
+    __device__ __forceinline__ void issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][ND]) const
+    {
+#pragma unroll
+        for (int kk = 0; kk < L; ++kk)
+            BLoad<2 * NT>::ld(R[kk], b_rsrc, __umul24(m[kk], ldb_bytes) + lane_off, 0u);
+    }
+    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][ND], f32x4 (&acc)[NT]) const
+    {
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const uint32_t pick = (t & 1) ? 0x07060302u : 0x05040100u;
@@ -197,46 +212,106 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
                 b[q] = __builtin_amdgcn_perm(R[2 * q + 1][t >> 1], R[2 * q][t >> 1], pick);
             acc[t] = mfma_pair<BF16>(a, b, acc[t]);
         }
-    };
+    }
+};
 
-    // Software pipeline over the wave's pairs ks, ks+KW, ...  Per pair h: its block columns and
-    // slot bytes are requested two steps ahead, its B rows (whose addresses need them) one step
-    // ahead, its block values right after the multiply of pair h-2 has released their
-    // registers.  Two register sets alternate, so nothing is copied; the loop body handles two
-    // pairs and has no exit in the middle (an odd tail multiplies a zeroed left operand).  The
-    // scheduling barriers keep every load ahead of the multiply that precedes its use, and the
-    // prologue issues its loads in the order the loop body leaves them in flight.
+// Pipeline for the dense class (L = 8), two register sets.  Per pair h: its slot table is
+// requested two steps ahead, its B rows (whose addresses need it) one step ahead, its block
+// values right after the multiply of pair h-2 has released their registers.  The loop body
+// handles two pairs and has no exit in the middle (an odd tail multiplies zeros).  The
+// scheduling barriers keep every load ahead of the multiply that precedes its use, and the
+// prologue issues its loads in the order the loop body leaves them in flight.
+template <int NT, int KW, int L, bool BF16>
+__device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
+{
+    using Ops = PairOps<NT, L, BF16>;
     if (w.ks >= w.npairs) return;
+    const Ops ops(w, rsrc);
     const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
     const int iters = (count + 1) >> 1;
-    uint32_t R0[L][ND], R1[L][ND];
-    uint32_t sel0[SD], sel1[SD];
+    uint32_t R0[L][Ops::ND], R1[L][Ops::ND];
+    uint32_t m0[L], m1[L];
     int p = w.ks;
-    i32x2 c0 = load_cols(p);
-    load_sel(p, sel0);
+    ops.load_slots(p, m0);
     __builtin_amdgcn_sched_barrier(0);
-    i32x2 c1 = load_cols(p + KW);
-    load_sel(p + KW, sel1);
-    u32x4 a0 = load_a(p);
-    issue_b(c0, sel0, R0);
+    ops.load_slots(p + KW, m1);
+    u32x4 a0 = ops.load_a(p, true);
+    ops.issue_b(m0, R0);
     __builtin_amdgcn_sched_barrier(0);
-    u32x4 a1 = load_a(p + KW);
+    u32x4 a1 = ops.load_a(p + KW, count > 1);
     for (int it = 0; it < iters; ++it) {
-        c0 = load_cols(p + 2 * KW);
-        load_sel(p + 2 * KW, sel0);
-        issue_b(c1, sel1, R1);
+        const int h = 2 * it;                              // pair of this wave multiplied first
+        ops.load_slots(p + 2 * KW, m0);
+        ops.issue_b(m1, R1);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(a0, R0, 0xFFFFFFFFu);
+        ops.multiply(a0, R0, acc);
         __builtin_amdgcn_sched_barrier(0);
-        a0 = load_a(p + 2 * KW);
-        c1 = load_cols(p + 3 * KW);
-        load_sel(p + 3 * KW, sel1);
-        issue_b(c0, sel0, R0);
+        a0 = ops.load_a(p + 2 * KW, h + 2 < count);
+        ops.load_slots(p + 3 * KW, m1);
+        ops.issue_b(m0, R0);
         __builtin_amdgcn_sched_barrier(0);
-        multiply(a1, R1, p + KW < w.npairs ? 0xFFFFFFFFu : 0u);
+        ops.multiply(a1, R1, acc);
         __builtin_amdgcn_sched_barrier(0);
-        a1 = load_a(p + 3 * KW);
+        a1 = ops.load_a(p + 3 * KW, h + 3 < count);
         p += 2 * KW;
+    }
+}
+
+// Pipeline for the sparse classes (L = 2, 4), whose row buffers are small: four-slot rings.
+// While pair h is multiplied, the loads in flight are the B rows and block values of pairs
+// h+1..h+3 and the slot tables of pairs h+4..h+6 (pair x has its slot table requested at step
+// x-6, its B rows and values at step x-3) -- about three pairs per wave in flight.  The loop
+// body is four steps without an exit; steps past the wave's last pair multiply zeros.
+template <int NT, int KW, int L, bool BF16>
+__device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
+{
+    using Ops = PairOps<NT, L, BF16>;
+    static_assert(L <= 4, "the deep ring is meant for the sparse classes");
+    if (w.ks >= w.npairs) return;
+    const Ops ops(w, rsrc);
+    const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
+    const int iters = (count + 3) >> 2;
+    uint32_t R[4][L][Ops::ND];
+    u32x4 a[4];
+    uint32_t m[4][L];
+    const int p0 = w.ks;
+    auto pair_of = [&](int h) { return p0 + h * KW; };     // h-th pair of this wave
+    // prologue = steps -6 .. -1 of the loop without their multiplies
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+        ops.load_slots(pair_of(h), m[h]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+#pragma unroll
+    for (int h = 0; h < 3; ++h) {
+        uint32_t mh[L];
+#pragma unroll
+        for (int x = 0; x < L; ++x) mh[x] = m[h][x];
+        ops.load_slots(pair_of(h + 3), m[(h + 3) & 3]);
+        __builtin_amdgcn_sched_barrier(0);
+        a[h] = ops.load_a(pair_of(h), h < count);
+        ops.issue_b(mh, R[h]);
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    int h0 = 0;
+    for (int it = 0; it < iters; ++it) {
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int h = h0 + u;                          // pair of this wave multiplied in this step
+            // the table of pair h+6 takes the ring slot of pair h+2, whose B rows went out a step
+            // ago; it is requested first: a later step waits for it and should wait for nothing younger
+            uint32_t mh[L];
+#pragma unroll
+            for (int x = 0; x < L; ++x) mh[x] = m[(u + 3) & 3][x];
+            ops.load_slots(pair_of(h + 6), m[(u + 2) & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+            a[(u + 3) & 3] = ops.load_a(pair_of(h + 3), h + 3 < count);
+            ops.issue_b(mh, R[(u + 3) & 3]);
+            __builtin_amdgcn_sched_barrier(0);
+            ops.multiply(a[u], R[u], acc);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        h0 += 4;
     }
 }
 
@@ -258,22 +333,21 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     const int n0 = (blockIdx.y * SW + sl) * NW;
     const int start = d.row_ptr[br], end = d.row_ptr[br + 1];
     const int col0 = n0 + NT * i;                  // first of this lane's NT columns
+    const bool col_ok = col0 < N;                  // N is a multiple of NT on this path
 
     RowWalk w;
-    w.meta = d.meta + static_cast<size_t>(start >> 1) * kPairMetaInts;
+    w.slots = d.slots + static_cast<size_t>(d.slots_off[br]) * 8;     // offsets count 32-byte units
     w.vals = d.vals + static_cast<size_t>(start >> 1) * kPairHalves;
     w.npairs = n0 < N ? (end - start) >> 1 : 0;    // block rows are padded to an even count
     w.ks = ks;
     w.g = g;
     w.lane = lane;
     // a lane whose columns lie beyond N carries the out-of-range bit in its offset
-    w.lane_off = col0 < N ? static_cast<uint32_t>(col0) * 2u : kOutOfRange;
+    w.lane_off = col_ok ? static_cast<uint32_t>(col0) * 2u : kOutOfRange;
     w.ldb_bytes = ldb_bytes;
-    w.col_ok = col0 < N;                           // N is a multiple of NT on this path
-    const bool col_ok = w.col_ok;
 
     const __amdgpu_buffer_rsrc_t rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), 0x00020000);
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
 
     f32x4 acc[NT];
 #pragma unroll
@@ -283,9 +357,9 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
         if (cls == 2) walk_row<NT, KW, 8, BF16>(w, rsrc, acc);
     }
     if constexpr (LMAX >= 4) {
-        if (cls == 1) walk_row<NT, KW, 4, BF16>(w, rsrc, acc);
+        if (cls == 1) walk_row_deep<NT, KW, 4, BF16>(w, rsrc, acc);
     }
-    if (cls == 0) walk_row<NT, KW, 2, BF16>(w, rsrc, acc);
+    if (cls == 0) walk_row_deep<NT, KW, 2, BF16>(w, rsrc, acc);
 
     // acc[t][r] = C'[4g + r][n0 + NT*i + t]
     if constexpr (KW == 1) {
@@ -383,18 +457,36 @@ template <int NT, int LMAX, bool BF16>
 static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                         int64_t N, hipStream_t stream, const char** variant)
 {
+    // SW waves of a group take neighbouring column slabs of the same block row, so its block
+    // values reach HBM once per group; KW waves share one block row (partial tiles summed
+    // through LDS).  Splitting a row costs a pipeline fill and a reduction per extra wave, so
+    // KW is the smallest split for which (a) the longest row, walked at about 0.25 us per
+    // pair and wave, stays below half of what the launch needs at ~5 TB/s, and (b) the
+    // launch has at least two waves for every SIMD of the chip.
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
-    const bool short_rows = d.mean_row_blocks < 12.0 && d.max_row_blocks < 64;
-    // KW waves share one block row (summed through LDS); SW waves of a group take neighbouring
-    // column slabs of the same block row, so its block values reach HBM once per group.
-    if (short_rows) {
-        if (slabs >= 2) { *variant = variant_name(BF16, 1, 2, LMAX); return launch_variant<NT, 1, 2, LMAX, BF16>(d, B, ldb, C, ldc, N, stream); }
-        *variant = variant_name(BF16, 1, 1, LMAX);
-        return launch_variant<NT, 1, 1, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);
+    const int sw = slabs >= 2 ? 2 : 1;
+    const int64_t groups = d.nbr * ((slabs + sw - 1) / sw);
+    const double stream_us = (static_cast<double>(d.n_e) * 512.0 + static_cast<double>(d.M) * N * 4.0 +
+                              static_cast<double>(d.K) * N * 2.0) / 5.0e6;
+    const double longest_us = static_cast<double>(d.max_row_blocks) * 0.5 * 0.25;
+    int kw = 1;
+    while (kw < 8 && d.mean_row_blocks >= 8.0 * kw &&
+           (longest_us / kw > 0.5 * stream_us || groups * sw * kw < 2048)) kw *= 2;
+#define SMAT_LAUNCH(KW_, SW_)                                                              \
+    do {                                                                                   \
+        *variant = variant_name(BF16, KW_, SW_, LMAX);                                     \
+        return launch_variant<NT, KW_, SW_, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);     \
+    } while (0)
+    if (sw == 2) {
+        if (kw >= 4) SMAT_LAUNCH(4, 2);
+        if (kw == 2) SMAT_LAUNCH(2, 2);
+        SMAT_LAUNCH(1, 2);
     }
-    if (slabs >= 2) { *variant = variant_name(BF16, 4, 2, LMAX); return launch_variant<NT, 4, 2, LMAX, BF16>(d, B, ldb, C, ldc, N, stream); }
-    *variant = variant_name(BF16, 8, 1, LMAX);
-    return launch_variant<NT, 8, 1, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);
+    if (kw == 8) SMAT_LAUNCH(8, 1);
+    if (kw == 4) SMAT_LAUNCH(4, 1);
+    if (kw == 2) SMAT_LAUNCH(2, 1);
+    SMAT_LAUNCH(1, 1);
+#undef SMAT_LAUNCH
 }
 
 template <int NT, bool BF16>

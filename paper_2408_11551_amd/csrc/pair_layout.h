@@ -15,19 +15,19 @@
 // Block values: 512 halves per pair; lane l = 16 g + i of the wavefront owns halves
 // [8 l, 8 l + 8): row i of the pair, k slots 8 g .. 8 g + 7.
 //
-// Metadata: 12 int32 per pair
-//   [0] block column of the first block      [1] block column of the second block
-//   [2] 32-bit occupancy mask (bit c: column c of the first block, bit 16 + c: of the second)
-//   [3] number of occupied columns
-//   [4 + 2 g], [5 + 2 g]  for lane group g: eight bytes, byte kk = pair column (0..31) held in
-//                         slot (g, kk), or 0xFF if the slot is empty
+// Slot table: for every pair, 4 lane groups x L entries of 32 bits, L = 2, 4 or 8 by the
+// class of the block row (the most occupied pair of the row has at most 4 L occupied
+// columns); entry [g][kk] is the row of B that slot (g, kk) multiplies, or K (one past the
+// last row) for an empty slot.  A lane reads its group's L entries with one or two loads.
+// Two more arrays serve the bind-time value scatter only: the block column of every block
+// and the pair's 32-bit occupancy mask (bit c: column c of the first block, bit 16 + c: of
+// the second).
 #pragma once
 
 #include <cstdint>
 
 namespace smat {
 
-constexpr int kPairMetaInts = 12;
 constexpr int kPairHalves = 512;
 
 #if defined(__HIPCC__)
