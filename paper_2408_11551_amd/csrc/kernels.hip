@@ -154,6 +154,7 @@ struct RowWalk {
     int g, lane;
     uint32_t lane_off;          // byte offset of the lane's first column inside a B row
     uint32_t ldb_bytes;
+    uint32_t no_row;            // the slot table's mark for an empty slot: K
 };
 
 // Per-class pieces shared by the two pipelines below.
@@ -162,12 +163,12 @@ struct PairOps {
     static constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
     static constexpr int NQ = L / 2;                      // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
-    uint32_t slots_voff, vals_voff, lane_off, ldb_bytes;
+    uint32_t slots_voff, vals_voff, lane_off, ldb_bytes, no_row;
     int last;
 
     __device__ __forceinline__ PairOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
         : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * 16u),
-          lane_off(w.lane_off), ldb_bytes(w.ldb_bytes), last(w.npairs - 1)
+          lane_off(w.lane_off), ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npairs - 1)
     {
         slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npairs * 16 * L, kRsrcFlags);
         vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * 1024, kRsrcFlags);
@@ -195,21 +196,42 @@ struct PairOps {
         else BLoad<16>::ld(r, none_rsrc, vals_voff, 0u);
         return u32x4{r[0], r[1], r[2], r[3]};
     }
-    __device__ __forceinline__ void issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][ND]) const
+    // Occupied columns fill the slots group by group, so position kk is empty in every group
+    // as soon as it is empty in group 0 (lane 0).  In the sparse classes a pair therefore has
+    // a wave-uniform "level": the number of leading positions that hold anything, rounded up
+    // to 1, 2 or 4; only that many B rows are requested, and the multiply permutes only the
+    // operand dwords they feed.  Returns the level.
+    __device__ __forceinline__ int issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][ND]) const
     {
+        int level = L;
+        if constexpr (L == 2) {
+            level = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(m[1])) == no_row ? 1 : 2;
+        } else if constexpr (L == 4) {
+            level = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(m[1])) == no_row ? 1
+                  : static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(m[2])) == no_row ? 2 : 4;
+        }
 #pragma unroll
         for (int kk = 0; kk < L; ++kk)
-            BLoad<2 * NT>::ld(R[kk], b_rsrc, __umul24(m[kk], ldb_bytes) + lane_off, 0u);
+            if (kk < level) BLoad<2 * NT>::ld(R[kk], b_rsrc, __umul24(m[kk], ldb_bytes) + lane_off, 0u);
+        return level;
     }
-    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][ND], f32x4 (&acc)[NT]) const
+    // Rows above the pair's level were not requested: their registers hold stale data and are
+    // replaced by zeros (a select on a wave-uniform condition) before the permutes.
+    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][ND], int level, f32x4 (&acc)[NT]) const
     {
+        uint32_t S[L][ND];
+#pragma unroll
+        for (int kk = 0; kk < L; ++kk)
+#pragma unroll
+            for (int x = 0; x < ND; ++x)
+                S[kk][x] = (L == 8 || kk == 0 || kk < level) ? R[kk][x] : 0u;
 #pragma unroll
         for (int t = 0; t < NT; ++t) {
             const uint32_t pick = (t & 1) ? 0x07060302u : 0x05040100u;
             u32x4 b = u32x4{0u, 0u, 0u, 0u};
 #pragma unroll
             for (int q = 0; q < NQ; ++q)
-                b[q] = __builtin_amdgcn_perm(R[2 * q + 1][t >> 1], R[2 * q][t >> 1], pick);
+                b[q] = __builtin_amdgcn_perm(S[2 * q + 1][t >> 1], S[2 * q][t >> 1], pick);
             acc[t] = mfma_pair<BF16>(a, b, acc[t]);
         }
     }
@@ -244,13 +266,13 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
         ops.load_slots(p + 2 * KW, m0);
         ops.issue_b(m1, R1);
         __builtin_amdgcn_sched_barrier(0);
-        ops.multiply(a0, R0, acc);
+        ops.multiply(a0, R0, L, acc);
         __builtin_amdgcn_sched_barrier(0);
         a0 = ops.load_a(p + 2 * KW, h + 2 < count);
         ops.load_slots(p + 3 * KW, m1);
         ops.issue_b(m0, R0);
         __builtin_amdgcn_sched_barrier(0);
-        ops.multiply(a1, R1, acc);
+        ops.multiply(a1, R1, L, acc);
         __builtin_amdgcn_sched_barrier(0);
         a1 = ops.load_a(p + 3 * KW, h + 3 < count);
         p += 2 * KW;
@@ -274,6 +296,7 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
     uint32_t R[4][L][Ops::ND];
     u32x4 a[4];
     uint32_t m[4][L];
+    int level[4];
     const int p0 = w.ks;
     auto pair_of = [&](int h) { return p0 + h * KW; };     // h-th pair of this wave
     // prologue = steps -6 .. -1 of the loop without their multiplies
@@ -290,7 +313,7 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
         ops.load_slots(pair_of(h + 3), m[(h + 3) & 3]);
         __builtin_amdgcn_sched_barrier(0);
         a[h] = ops.load_a(pair_of(h), h < count);
-        ops.issue_b(mh, R[h]);
+        level[h] = ops.issue_b(mh, R[h]);
         __builtin_amdgcn_sched_barrier(0);
     }
     int h0 = 0;
@@ -306,9 +329,9 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
             ops.load_slots(pair_of(h + 6), m[(u + 2) & 3]);
             __builtin_amdgcn_sched_barrier(0);
             a[(u + 3) & 3] = ops.load_a(pair_of(h + 3), h + 3 < count);
-            ops.issue_b(mh, R[(u + 3) & 3]);
+            level[(u + 3) & 3] = ops.issue_b(mh, R[(u + 3) & 3]);
             __builtin_amdgcn_sched_barrier(0);
-            ops.multiply(a[u], R[u], acc);
+            ops.multiply(a[u], R[u], level[u], acc);
             __builtin_amdgcn_sched_barrier(0);
         }
         h0 += 4;
@@ -345,6 +368,7 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     // a lane whose columns lie beyond N carries the out-of-range bit in its offset
     w.lane_off = col_ok ? static_cast<uint32_t>(col0) * 2u : kOutOfRange;
     w.ldb_bytes = ldb_bytes;
+    w.no_row = static_cast<uint32_t>(d.K);
 
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
