@@ -136,6 +136,18 @@ template <> struct BLoad<16> {
     { i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s, off, soff, 0); r[0] = v[0]; r[1] = v[1]; r[2] = v[2]; r[3] = v[3]; }
 };
 
+// Same loads with the non-temporal hint: the block values and slot tables stream through
+// once and should not push the rows of B out of the L2.
+template <int BYTES> struct SLoad;
+template <> struct SLoad<8> {
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(s, off, soff, 2); r[0] = v[0]; r[1] = v[1]; }
+};
+template <> struct SLoad<16> {
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s, off, soff, 2); r[0] = v[0]; r[1] = v[1]; r[2] = v[2]; r[3] = v[3]; }
+};
+
 template <bool BF16>
 __device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
 {
@@ -152,24 +164,28 @@ struct RowWalk {
     int npairs;                 // pairs in the row (0 if this wave's slab is beyond N)
     int ks;                     // first pair of this wave
     int g, lane;
-    uint32_t lane_off;          // byte offset of the lane's first column inside a B row
+    uint32_t lane_off[2];       // per column chunk: byte offset of the lane's first column inside a B row
     uint32_t ldb_bytes;
     uint32_t no_row;            // the slot table's mark for an empty slot: K
+    bool stream;                // block values and slot tables are read with the non-temporal hint
 };
 
 // Per-class pieces shared by the two pipelines below.
-template <int NT, int L, bool BF16>
+template <int NT, int L, int NCH, bool BF16>
 struct PairOps {
     static constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
     static constexpr int NQ = L / 2;                      // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
-    uint32_t slots_voff, vals_voff, lane_off, ldb_bytes, no_row;
+    uint32_t slots_voff, vals_voff, lane_off[NCH], ldb_bytes, no_row;
     int last;
+    bool stream;
 
     __device__ __forceinline__ PairOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
         : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * 16u),
-          lane_off(w.lane_off), ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npairs - 1)
+          ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npairs - 1), stream(w.stream)
     {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
         slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npairs * 16 * L, kRsrcFlags);
         vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * 1024, kRsrcFlags);
         none_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, 0, kRsrcFlags);
@@ -182,18 +198,23 @@ struct PairOps {
     {
         const uint32_t soff = clamp(p) * (16u * L);
         if constexpr (L == 2) {
-            BLoad<8>::ld(m, slots_rsrc, slots_voff, soff);
+            if (stream) SLoad<8>::ld(m, slots_rsrc, slots_voff, soff);
+            else BLoad<8>::ld(m, slots_rsrc, slots_voff, soff);
         } else {
 #pragma unroll
-            for (int x = 0; x < L; x += 4) BLoad<16>::ld(m + x, slots_rsrc, slots_voff + 4u * x, soff);
+            for (int x = 0; x < L; x += 4) {
+                if (stream) SLoad<16>::ld(m + x, slots_rsrc, slots_voff + 4u * x, soff);
+                else BLoad<16>::ld(m + x, slots_rsrc, slots_voff + 4u * x, soff);
+            }
         }
     }
     // block values; `live` false (a step past the wave's last pair) reads zeros instead
     __device__ __forceinline__ u32x4 load_a(int p, bool live) const
     {
         uint32_t r[4];
-        if (live) BLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
-        else BLoad<16>::ld(r, none_rsrc, vals_voff, 0u);
+        if (!live) BLoad<16>::ld(r, none_rsrc, vals_voff, 0u);
+        else if (stream) SLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
+        else BLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
         return u32x4{r[0], r[1], r[2], r[3]};
     }
     // Occupied columns fill the slots group by group, so position kk is empty in every group
@@ -201,7 +222,7 @@ struct PairOps {
     // a wave-uniform "level": the number of leading positions that hold anything, rounded up
     // to 1, 2 or 4; only that many B rows are requested, and the multiply permutes only the
     // operand dwords they feed.  Returns the level.
-    __device__ __forceinline__ int issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][ND]) const
+    __device__ __forceinline__ int issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][NCH][ND]) const
     {
         int level = L;
         if constexpr (L == 2) {
@@ -212,27 +233,34 @@ struct PairOps {
         }
 #pragma unroll
         for (int kk = 0; kk < L; ++kk)
-            if (kk < level) BLoad<2 * NT>::ld(R[kk], b_rsrc, __umul24(m[kk], ldb_bytes) + lane_off, 0u);
+            if (kk < level) {
+                const uint32_t row_off = __umul24(m[kk], ldb_bytes);
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) BLoad<2 * NT>::ld(R[kk][c], b_rsrc, row_off + lane_off[c], 0u);
+            }
         return level;
     }
     // Rows above the pair's level were not requested: their registers hold stale data and are
     // replaced by zeros (a select on a wave-uniform condition) before the permutes.
-    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][ND], int level, f32x4 (&acc)[NT]) const
+    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][NCH][ND], int level, f32x4 (&acc)[NCH * NT]) const
     {
-        uint32_t S[L][ND];
 #pragma unroll
-        for (int kk = 0; kk < L; ++kk)
+        for (int c = 0; c < NCH; ++c) {
+            uint32_t S[L][ND];
 #pragma unroll
-            for (int x = 0; x < ND; ++x)
-                S[kk][x] = (L == 8 || kk == 0 || kk < level) ? R[kk][x] : 0u;
+            for (int kk = 0; kk < L; ++kk)
 #pragma unroll
-        for (int t = 0; t < NT; ++t) {
-            const uint32_t pick = (t & 1) ? 0x07060302u : 0x05040100u;
-            u32x4 b = u32x4{0u, 0u, 0u, 0u};
+                for (int x = 0; x < ND; ++x)
+                    S[kk][x] = (L == 8 || kk == 0 || kk < level) ? R[kk][c][x] : 0u;
 #pragma unroll
-            for (int q = 0; q < NQ; ++q)
-                b[q] = __builtin_amdgcn_perm(S[2 * q + 1][t >> 1], S[2 * q][t >> 1], pick);
-            acc[t] = mfma_pair<BF16>(a, b, acc[t]);
+            for (int t = 0; t < NT; ++t) {
+                const uint32_t pick = (t & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 b = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                for (int q = 0; q < NQ; ++q)
+                    b[q] = __builtin_amdgcn_perm(S[2 * q + 1][t >> 1], S[2 * q][t >> 1], pick);
+                acc[c * NT + t] = mfma_pair<BF16>(a, b, acc[c * NT + t]);
+            }
         }
     }
 };
@@ -243,15 +271,15 @@ struct PairOps {
 // handles two pairs and has no exit in the middle (an odd tail multiplies zeros).  The
 // scheduling barriers keep every load ahead of the multiply that precedes its use, and the
 // prologue issues its loads in the order the loop body leaves them in flight.
-template <int NT, int KW, int L, bool BF16>
-__device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
+template <int NT, int KW, int L, int NCH, bool BF16>
+__device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NCH * NT])
 {
-    using Ops = PairOps<NT, L, BF16>;
+    using Ops = PairOps<NT, L, NCH, BF16>;
     if (w.ks >= w.npairs) return;
     const Ops ops(w, rsrc);
     const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
     const int iters = (count + 1) >> 1;
-    uint32_t R0[L][Ops::ND], R1[L][Ops::ND];
+    uint32_t R0[L][NCH][Ops::ND], R1[L][NCH][Ops::ND];
     uint32_t m0[L], m1[L];
     int p = w.ks;
     ops.load_slots(p, m0);
@@ -284,16 +312,16 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
 // h+1..h+3 and the slot tables of pairs h+4..h+6 (pair x has its slot table requested at step
 // x-6, its B rows and values at step x-3) -- about three pairs per wave in flight.  The loop
 // body is four steps without an exit; steps past the wave's last pair multiply zeros.
-template <int NT, int KW, int L, bool BF16>
-__device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NT])
+template <int NT, int KW, int L, int NCH, bool BF16>
+__device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NCH * NT])
 {
-    using Ops = PairOps<NT, L, BF16>;
+    using Ops = PairOps<NT, L, NCH, BF16>;
     static_assert(L <= 4, "the deep ring is meant for the sparse classes");
     if (w.ks >= w.npairs) return;
     const Ops ops(w, rsrc);
     const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
     const int iters = (count + 3) >> 2;
-    uint32_t R[4][L][Ops::ND];
+    uint32_t R[4][L][NCH][Ops::ND];
     u32x4 a[4];
     uint32_t m[4][L];
     int level[4];
@@ -338,12 +366,13 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
     }
 }
 
-template <int NT, int KW, int SW, int LMAX, bool BF16>
+template <int NT, int KW, int SW, int NCH, int LMAX, bool BF16>
 __global__ __launch_bounds__(KW * SW * 64)
 void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
-                 float* __restrict__ C, int64_t ldc, int N, int vec_store)
+                 float* __restrict__ C, int64_t ldc, int N, int vec_store, int stream_hint)
 {
-    constexpr int NW = 16 * NT;                    // columns per wave
+    constexpr int NW = 16 * NT;                    // columns per chunk (one set of NT MFMAs)
+    constexpr int WC = NCH * NW;                   // columns per wave
     constexpr int WAVES = KW * SW;
     const int lane = threadIdx.x & 63;
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);   // wave-uniform, kept in an SGPR
@@ -353,10 +382,8 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     const int entry = d.order[blockIdx.x];         // block row and its class (2 top bits used)
     const int br = entry & 0x0FFFFFFF;
     const int cls = entry >> 28;                   // 0: L = 2, 1: L = 4, 2: L = 8
-    const int n0 = (blockIdx.y * SW + sl) * NW;
+    const int n0 = (blockIdx.y * SW + sl) * WC;
     const int start = d.row_ptr[br], end = d.row_ptr[br + 1];
-    const int col0 = n0 + NT * i;                  // first of this lane's NT columns
-    const bool col_ok = col0 < N;                  // N is a multiple of NT on this path
 
     RowWalk w;
     w.slots = d.slots + static_cast<size_t>(d.slots_off[br]) * 8;     // offsets count 32-byte units
@@ -365,75 +392,88 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     w.ks = ks;
     w.g = g;
     w.lane = lane;
-    // a lane whose columns lie beyond N carries the out-of-range bit in its offset
-    w.lane_off = col_ok ? static_cast<uint32_t>(col0) * 2u : kOutOfRange;
+    int col0[NCH];                                 // first of this lane's NT columns, per chunk
+#pragma unroll
+    for (int c = 0; c < NCH; ++c) {
+        col0[c] = n0 + c * NW + NT * i;
+        // a lane whose columns lie beyond N carries the out-of-range bit in its offset
+        // (N is a multiple of NT on this path, so a lane's columns are all in or all out)
+        w.lane_off[c] = col0[c] < N ? static_cast<uint32_t>(col0[c]) * 2u : kOutOfRange;
+    }
     w.ldb_bytes = ldb_bytes;
     w.no_row = static_cast<uint32_t>(d.K);
+    w.stream = stream_hint != 0;
 
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
 
-    f32x4 acc[NT];
+    f32x4 acc[NCH * NT];
 #pragma unroll
-    for (int t = 0; t < NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
+    for (int t = 0; t < NCH * NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
 
     if constexpr (LMAX >= 8) {
-        if (cls == 2) walk_row<NT, KW, 8, BF16>(w, rsrc, acc);
+        if (cls == 2) walk_row<NT, KW, 8, NCH, BF16>(w, rsrc, acc);
     }
     if constexpr (LMAX >= 4) {
-        if (cls == 1) walk_row_deep<NT, KW, 4, BF16>(w, rsrc, acc);
+        if (cls == 1) walk_row_deep<NT, KW, 4, NCH, BF16>(w, rsrc, acc);
     }
-    if (cls == 0) walk_row_deep<NT, KW, 2, BF16>(w, rsrc, acc);
+    if (cls == 0) walk_row_deep<NT, KW, 2, NCH, BF16>(w, rsrc, acc);
 
-    // acc[t][r] = C'[4g + r][n0 + NT*i + t]
+    // acc[c*NT + t][r] = C'[4g + r][n0 + c*NW + NT*i + t]
     if constexpr (KW == 1) {
-        if (col_ok) {
+#pragma unroll
+        for (int c = 0; c < NCH; ++c) {
+            if (col0[c] >= N) continue;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
                 const int64_t out_row = d.perm[br * 16 + 4 * g + r];
                 if (out_row < 0) continue;
-                float* dst = C + out_row * ldc + col0;
+                float* dst = C + out_row * ldc + col0[c];
                 if constexpr (NT >= 4) {
                     if (vec_store) {
 #pragma unroll
                         for (int t = 0; t < NT; t += 4)
-                            *reinterpret_cast<f32x4*>(dst + t) = f32x4{acc[t][r], acc[t + 1][r], acc[t + 2][r], acc[t + 3][r]};
+                            *reinterpret_cast<f32x4*>(dst + t) =
+                                f32x4{acc[c * NT + t][r], acc[c * NT + t + 1][r], acc[c * NT + t + 2][r], acc[c * NT + t + 3][r]};
                         continue;
                     }
                 }
 #pragma unroll
-                for (int t = 0; t < NT; ++t) dst[t] = acc[t][r];
+                for (int t = 0; t < NT; ++t) dst[t] = acc[c * NT + t][r];
             }
         }
     } else {
-        constexpr int LD = NW + 4;                 // padded row of the reduction buffer (floats)
+        constexpr int LD = WC + 4;                 // padded row of the reduction buffer (floats)
         __shared__ float red[WAVES * 16 * LD];
         float* mine = red + wave * 16 * LD;
 #pragma unroll
-        for (int r = 0; r < 4; ++r) {
-            float* dst = mine + (4 * g + r) * LD + NT * i;
-            if constexpr (NT >= 4) {
+        for (int c = 0; c < NCH; ++c)
 #pragma unroll
-                for (int t = 0; t < NT; t += 4)
-                    *reinterpret_cast<f32x4*>(dst + t) = f32x4{acc[t][r], acc[t + 1][r], acc[t + 2][r], acc[t + 3][r]};
-            } else {
+            for (int r = 0; r < 4; ++r) {
+                float* dst = mine + (4 * g + r) * LD + c * NW + NT * i;
+                if constexpr (NT >= 4) {
 #pragma unroll
-                for (int t = 0; t < NT; ++t) dst[t] = acc[t][r];
+                    for (int t = 0; t < NT; t += 4)
+                        *reinterpret_cast<f32x4*>(dst + t) =
+                            f32x4{acc[c * NT + t][r], acc[c * NT + t + 1][r], acc[c * NT + t + 2][r], acc[c * NT + t + 3][r]};
+                } else {
+#pragma unroll
+                    for (int t = 0; t < NT; ++t) dst[t] = acc[c * NT + t][r];
+                }
             }
-        }
         __syncthreads();
-        const int nbase = blockIdx.y * SW * NW;
+        const int nbase = blockIdx.y * SW * WC;
         if constexpr (NT >= 4) {
             // each thread sums and stores four consecutive columns
-            constexpr int Q = NW / 4;              // quads per row of one slab
+            constexpr int Q = WC / 4;              // quads per row of one wave's slab
             for (int e = threadIdx.x; e < SW * 16 * Q; e += WAVES * 64) {
                 const int s = e / (16 * Q), row = (e / Q) % 16, c = (e % Q) * 4;
                 const float* src = red + (s * KW) * 16 * LD + row * LD + c;
                 f32x4 v = *reinterpret_cast<const f32x4*>(src);
 #pragma unroll
-                for (int w = 1; w < KW; ++w) v += *reinterpret_cast<const f32x4*>(src + w * 16 * LD);
+                for (int x = 1; x < KW; ++x) v += *reinterpret_cast<const f32x4*>(src + x * 16 * LD);
                 const int64_t out_row = d.perm[br * 16 + row];
-                const int col = nbase + s * NW + c;
+                const int col = nbase + s * WC + c;
                 if (out_row < 0 || col >= N) continue;
                 float* dst = C + out_row * ldc + col;
                 if (vec_store) {
@@ -443,37 +483,41 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
                 }
             }
         } else {
-            for (int e = threadIdx.x; e < SW * 16 * NW; e += WAVES * 64) {
-                const int s = e / (16 * NW), row = (e / NW) % 16, c = e % NW;
+            for (int e = threadIdx.x; e < SW * 16 * WC; e += WAVES * 64) {
+                const int s = e / (16 * WC), row = (e / WC) % 16, c = e % WC;
                 const float* src = red + (s * KW) * 16 * LD + row * LD + c;
                 float v = src[0];
 #pragma unroll
-                for (int w = 1; w < KW; ++w) v += src[w * 16 * LD];
+                for (int x = 1; x < KW; ++x) v += src[x * 16 * LD];
                 const int64_t out_row = d.perm[br * 16 + row];
-                const int col = nbase + s * NW + c;
+                const int col = nbase + s * WC + c;
                 if (out_row >= 0 && col < N) C[out_row * ldc + col] = v;
             }
         }
     }
 }
 
-template <int NT, int KW, int SW, int LMAX, bool BF16>
+template <int NT, int KW, int SW, int NCH, int LMAX, bool BF16>
 static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                           int64_t N, hipStream_t stream)
 {
-    const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
-    dim3 grid(static_cast<unsigned>(d.nbr), static_cast<unsigned>((slabs + SW - 1) / SW));
+    const int64_t per_group = 16 * NT * NCH * SW;          // columns of one workgroup
+    dim3 grid(static_cast<unsigned>(d.nbr), static_cast<unsigned>((N + per_group - 1) / per_group));
     const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * 2) : 0u;
     const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
-    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, LMAX, BF16>), grid, dim3(KW * SW * 64), 0, stream,
-                       d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
+    // Block values that are read once per launch (a single group per block row) and are too many
+    // to stay in the 256 MB Infinity Cache between launches are streamed past the L2, which
+    // then keeps the rows of B.
+    const int stream_hint = (grid.y == 1 && SW == 1 && static_cast<double>(d.n_e) * 512.0 > 200e6) ? 1 : 0;
+    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, BF16>), grid, dim3(KW * SW * 64), 0, stream,
+                       d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());
 }
 
-static const char* variant_name(bool bf16, int kw, int sw, int lmax)
+static const char* variant_name(bool bf16, int kw, int sw, int nch, int lmax)
 {
     static thread_local char buf[48];
-    snprintf(buf, sizeof(buf), "spmm_%s_k%ds%d_l%d", bf16 ? "bf16" : "f16", kw, sw, lmax);
+    snprintf(buf, sizeof(buf), "spmm_%s_k%ds%dc%d_l%d", bf16 ? "bf16" : "f16", kw, sw, nch, lmax);
     return buf;
 }
 
@@ -481,35 +525,51 @@ template <int NT, int LMAX, bool BF16>
 static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                         int64_t N, hipStream_t stream, const char** variant)
 {
-    // SW waves of a group take neighbouring column slabs of the same block row, so its block
-    // values reach HBM once per group; KW waves share one block row (partial tiles summed
-    // through LDS).  Splitting a row costs a pipeline fill and a reduction per extra wave, so
-    // KW is the smallest split for which (a) the longest row, walked at about 0.25 us per
-    // pair and wave, stays below half of what the launch needs at ~5 TB/s, and (b) the
-    // launch has at least two waves for every SIMD of the chip.
+    // A wave covers NCH chunks of 16*NT columns with one read of the block values; SW waves of
+    // a group take neighbouring slabs of the same block row, so its block values reach HBM once
+    // per group; KW waves share one block row (partial tiles summed through LDS).  Splitting a
+    // row costs a pipeline fill and a reduction per extra wave, so KW is the smallest split for
+    // which (a) the longest row, walked at about 0.25 us per pair and wave, stays below half of
+    // what the launch needs at ~5 TB/s, and (b) the launch has at least two waves for every
+    // SIMD of the chip.
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
-    const int sw = slabs >= 2 ? 2 : 1;
-    const int64_t groups = d.nbr * ((slabs + sw - 1) / sw);
+    const int nch = (NT == 8 && LMAX < 8 && slabs >= 2) ? 2 : 1;     // the dense class has no registers to spare
+    const int64_t wave_slabs = (slabs + nch - 1) / nch;
+    const int sw = wave_slabs >= 2 ? 2 : 1;
+    const int64_t groups = d.nbr * ((wave_slabs + sw - 1) / sw);
     const double stream_us = (static_cast<double>(d.n_e) * 512.0 + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * 2.0) / 5.0e6;
     const double longest_us = static_cast<double>(d.max_row_blocks) * 0.5 * 0.25;
     int kw = 1;
     while (kw < 8 && d.mean_row_blocks >= 8.0 * kw &&
            (longest_us / kw > 0.5 * stream_us || groups * sw * kw < 2048)) kw *= 2;
-#define SMAT_LAUNCH(KW_, SW_)                                                              \
-    do {                                                                                   \
-        *variant = variant_name(BF16, KW_, SW_, LMAX);                                     \
-        return launch_variant<NT, KW_, SW_, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);     \
+    if (nch == 2 && kw > 4) kw = 4;
+#define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
+    do {                                                                                        \
+        *variant = variant_name(BF16, KW_, SW_, NCH_, LMAX);                                    \
+        return launch_variant<NT, KW_, SW_, NCH_, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);    \
     } while (0)
-    if (sw == 2) {
-        if (kw >= 4) SMAT_LAUNCH(4, 2);
-        if (kw == 2) SMAT_LAUNCH(2, 2);
-        SMAT_LAUNCH(1, 2);
+    if constexpr (NT == 8 && LMAX < 8) {
+        if (nch == 2) {
+            if (sw == 2) {
+                if (kw >= 4) SMAT_LAUNCH(4, 2, 2);
+                if (kw == 2) SMAT_LAUNCH(2, 2, 2);
+                SMAT_LAUNCH(1, 2, 2);
+            }
+            if (kw >= 4) SMAT_LAUNCH(4, 1, 2);
+            if (kw == 2) SMAT_LAUNCH(2, 1, 2);
+            SMAT_LAUNCH(1, 1, 2);
+        }
     }
-    if (kw == 8) SMAT_LAUNCH(8, 1);
-    if (kw == 4) SMAT_LAUNCH(4, 1);
-    if (kw == 2) SMAT_LAUNCH(2, 1);
-    SMAT_LAUNCH(1, 1);
+    if (sw == 2) {
+        if (kw >= 4) SMAT_LAUNCH(4, 2, 1);
+        if (kw == 2) SMAT_LAUNCH(2, 2, 1);
+        SMAT_LAUNCH(1, 2, 1);
+    }
+    if (kw == 8) SMAT_LAUNCH(8, 1, 1);
+    if (kw == 4) SMAT_LAUNCH(4, 1, 1);
+    if (kw == 2) SMAT_LAUNCH(2, 1, 1);
+    SMAT_LAUNCH(1, 1, 1);
 #undef SMAT_LAUNCH
 }
 
