@@ -32,8 +32,9 @@ WORKLOAD_TEXT = {
     "pruned_weight": "pruned weight 4096x4096 90% sparse bf16, B 4096x2048",
 }
 
-# HBM bytes per launch from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs (see profiles/), or None
-MEASURED_TRAFFIC_BYTES = {}
+# HBM-side bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
+# profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after a 256 MiB calibration copy), or None
+MEASURED_TRAFFIC_BYTES = {"uniform": 164.1e6, "powerlaw": 2782e6, "hidden_blocks": 910e6}
 
 
 def algorithmic_bytes(n_e, nbr, M, K, N):
@@ -50,6 +51,8 @@ def main():
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--cold", action="store_true", help="also time launches with the caches flushed in between")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run one 256 MiB device-to-device copy first (known traffic, scales the profiler's byte counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -77,6 +80,13 @@ def main():
     B = torch.from_numpy(w.b_bits.view(np.int16).reshape(w.K, w.N)).to(dev)
     C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        src = torch.ones(1 << 26, dtype=torch.int32, device=dev)        # 256 MiB read + 256 MiB written
+        dst = torch.empty_like(src)
+        dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         S.smat_spmm(h, B, C, w.N, stream)
