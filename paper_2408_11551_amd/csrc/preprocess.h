@@ -24,7 +24,7 @@ struct Bcsr {
     std::vector<int32_t> row_ptr;    // [nbr+1]
     std::vector<int32_t> col_idx;    // [n_e]
     std::vector<uint16_t> col_mask;  // [n_e] bit c set iff column c of the block holds a stored entry
-    std::vector<int32_t> order;      // [nbr] block rows, longest first (ties: lower index first)
+    std::vector<int32_t> order;      // [nbr] block rows in launch order (see build_bcsr)
     int64_t n_blocks = 0, n_blocks_identity = 0;
     bool used_identity = true;
     int64_t n_clusters = 0;
