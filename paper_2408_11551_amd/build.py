@@ -3,16 +3,27 @@ from __future__ import annotations
 
 import os
 import subprocess
+from concurrent.futures import ThreadPoolExecutor
 
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
+OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libsmat.so")
-SOURCES = ["api.cpp", "preprocess.cpp", "kernels.hip"]
-HEADERS = ["kernels.h", "preprocess.h", os.path.join("..", "..", "include", "smat.h")]
+# source -> extra flags
+SOURCES = {
+    "api.cpp": [],
+    "preprocess.cpp": [],
+    "kernels.hip": [],
+    # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
+    # MFMA results live in ordinary VGPRs (one wave per SIMD leaves room for 256 of them)
+    # instead of being shuffled between the two register files
+    "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+}
+HEADERS = ["kernels.h", "preprocess.h", "pair_layout.h", os.path.join("..", "..", "include", "smat.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
-    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
+    "--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC",
     "-Wall", "-Wextra", "-Wno-unused-parameter",
     # keep the compiler from forming packed fp32 VALU instructions
     "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",
@@ -23,14 +34,25 @@ def is_stale() -> bool:
     if not os.path.exists(OUT):
         return True
     built = os.path.getmtime(OUT)
-    deps = [os.path.join(CSRC, f) for f in SOURCES + HEADERS] + [os.path.abspath(__file__)]
+    deps = [os.path.join(CSRC, f) for f in list(SOURCES) + HEADERS] + [os.path.abspath(__file__)]
     return any(os.path.getmtime(d) > built for d in deps)
+
+
+def _compile(item):
+    src, extra = item
+    obj = os.path.join(OBJ, src + ".o")
+    cmd = [HIPCC, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
+    subprocess.run(cmd, check=True)
+    return obj
 
 
 def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return OUT
-    cmd = [HIPCC, *FLAGS, "-x", "hip", *[os.path.join(CSRC, f) for f in SOURCES], "-o", OUT]
+    os.makedirs(OBJ, exist_ok=True)
+    with ThreadPoolExecutor(max_workers=4) as pool:
+        objs = list(pool.map(_compile, SOURCES.items()))
+    cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)

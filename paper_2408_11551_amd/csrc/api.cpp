@@ -32,7 +32,15 @@ struct smat_handle {
     std::vector<uint32_t> slots_off;     // [nbr]
     uint64_t slots_units = 0;
     int max_class = 0;
-    smat::DeviceBcsr dev;
+    // Dense path (kernels.h, DenseTiles): complete super rows of sixteen block rows whose block
+    // columns overlap enough.  row_dense marks the block rows it covers.
+    std::vector<int32_t> dense_super, step_ptr, step_cols;
+    std::vector<uint32_t> step_rows, step_base;
+    std::vector<uint8_t> row_dense;      // [nbr]
+    uint64_t dense_slots = 0;
+    smat::DeviceBcsr dev;                // launch over every block row
+    smat::DeviceBcsr dev_rest;           // launch over the block rows the dense path does not cover
+    smat::DenseTiles tiles;
     // device copies of the CSR (kept: they live in the caller's workspace anyway)
     const int64_t* d_csr_row_ptr = nullptr;
     const int32_t* d_csr_col_idx = nullptr;
@@ -60,7 +68,8 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
-    size_t perm, row_ptr, order, slots_off, slots, vals, blk_col, occ, csr_row_ptr, csr_col_idx, csr_vals, total;
+    size_t perm, row_ptr, order, order_rest, slots_off, slots, vals, blk_col, occ, csr_row_ptr, csr_col_idx, csr_vals;
+    size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, total;
 };
 
 Layout make_layout(const smat_handle& h)
@@ -73,6 +82,7 @@ Layout make_layout(const smat_handle& h)
     l.perm = take(nbr * 16 * sizeof(int32_t));
     l.row_ptr = take((nbr + 1) * sizeof(int32_t));
     l.order = take(nbr * sizeof(int32_t));
+    l.order_rest = take(nbr * sizeof(int32_t));
     l.slots_off = take(nbr * sizeof(uint32_t));
     l.slots = take(static_cast<size_t>(h.slots_units) * 32);
     l.vals = take(n_e * 512);
@@ -81,6 +91,12 @@ Layout make_layout(const smat_handle& h)
     l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
     l.csr_col_idx = take(nnz * sizeof(int32_t));
     l.csr_vals = take(nnz * sizeof(uint16_t));
+    l.t_super = take(h.dense_super.size() * sizeof(int32_t));
+    l.t_ptr = take(h.step_ptr.size() * sizeof(int32_t));
+    l.t_cols = take(h.step_cols.size() * sizeof(int32_t));
+    l.t_rows = take(h.step_rows.size() * sizeof(uint32_t));
+    l.t_base = take(h.step_base.size() * sizeof(uint32_t));
+    l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
     l.total = off ? off : kAlign;
     return l;
 }
@@ -89,6 +105,72 @@ Layout make_layout(const smat_handle& h)
 uint32_t pair_occupancy(const smat::Bcsr& b, int32_t s, int32_t s1)
 {
     return b.col_mask[s] | (s + 1 < s1 ? static_cast<uint32_t>(b.col_mask[s + 1]) << 16 : 0u);
+}
+
+// Decides which complete super rows (sixteen block rows) go to the dense path and lays out
+// their steps.  A super row qualifies when walking the union of its block columns wastes
+// little: at least 8 union columns, at least 35 % of the (block row, union column) grid
+// stored, and blocks whose columns are mostly occupied (>= 8 of 16 on average; blocks with a
+// few occupied columns are cheaper on the per-row path, which fetches only those rows of B).
+void plan_dense_tiles(smat_handle& h)
+{
+    const smat::Bcsr& b = h.bcsr;
+    const int64_t nbr = b.nbr;
+    h.row_dense.assign(static_cast<size_t>(nbr), 0);
+    h.step_ptr.assign(1, 0);
+    std::vector<int32_t> uni;
+    for (int64_t s = 0; (s + 1) * 16 <= nbr; ++s) {
+        const int32_t lo = b.row_ptr[s * 16], hi = b.row_ptr[s * 16 + 16];
+        if (hi - lo < 64) continue;
+        uni.assign(b.col_idx.begin() + lo, b.col_idx.begin() + hi);
+        std::sort(uni.begin(), uni.end());
+        uni.erase(std::unique(uni.begin(), uni.end()), uni.end());
+        int64_t occupied = 0;
+        for (int32_t k = lo; k < hi; ++k) occupied += __builtin_popcount(b.col_mask[k]);
+        const int64_t n_uni = static_cast<int64_t>(uni.size()), n_blk = hi - lo;
+        if (n_uni < 8 || n_blk * 20 < 7 * 16 * n_uni || occupied < 8 * n_blk) continue;
+        const int64_t steps = (n_uni + 1) / 2;
+        if (steps * 16 >= (int64_t{1} << 21) || h.dense_slots + static_cast<uint64_t>(steps) * 16 >= (uint64_t{1} << 31)) continue;
+        h.dense_super.push_back(static_cast<int32_t>(s));
+        for (int j = 0; j < 16; ++j) h.row_dense[static_cast<size_t>(s * 16 + j)] = 1;
+        for (int64_t q = 0; q < steps; ++q) {
+            const int32_t c0 = uni[2 * q], c1 = 2 * q + 1 < n_uni ? uni[2 * q + 1] : 0x7FFFFFFF;
+            uint32_t rows = 0;
+            for (int j = 0; j < 16; ++j) {
+                const int32_t* first = b.col_idx.data() + b.row_ptr[s * 16 + j];
+                const int32_t* last = b.col_idx.data() + b.row_ptr[s * 16 + j + 1];
+                if (std::binary_search(first, last, c0) || std::binary_search(first, last, c1)) rows |= 1u << j;
+            }
+            h.step_cols.push_back(c0);
+            h.step_cols.push_back(c1);
+            h.step_rows.push_back(rows);
+            h.step_base.push_back(static_cast<uint32_t>(h.dense_slots));
+            h.dense_slots += static_cast<uint64_t>(__builtin_popcount(rows));
+        }
+        h.step_ptr.push_back(static_cast<int32_t>(h.step_rows.size()));
+    }
+}
+
+// Launch statistics over a subset of block rows.
+void row_stats(const smat_handle& h, bool skip_dense, smat::DeviceBcsr& d)
+{
+    const smat::Bcsr& b = h.bcsr;
+    int64_t longest = 0, blocks = 0, rows = 0, padded = 0;
+    int cls = 0;
+    for (int64_t br = 0; br < b.nbr; ++br) {
+        if (skip_dense && h.row_dense[static_cast<size_t>(br)]) continue;
+        const int64_t len = b.row_ptr[br + 1] - b.row_ptr[br];
+        longest = std::max(longest, len);
+        blocks += len;
+        padded += (len + 1) / 2 * 2;
+        cls = std::max<int>(cls, h.row_class[static_cast<size_t>(br)]);
+        ++rows;
+    }
+    d.n_order = rows;
+    d.n_e = padded;
+    d.max_row_blocks = longest;
+    d.mean_row_blocks = rows ? static_cast<double>(blocks) / static_cast<double>(rows) : 0.0;
+    d.max_class = cls;
 }
 
 }  // namespace
@@ -171,6 +253,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
             }
         }
         h->slots_units = units;
+        plan_dense_tiles(*h);
         *out = h;
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
@@ -264,9 +347,12 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
                 }
             }
         }
-        std::vector<int32_t> order_cls(nbr);
-        for (size_t x = 0; x < nbr; ++x)
+        std::vector<int32_t> order_cls(nbr), order_rest;
+        order_rest.reserve(nbr);
+        for (size_t x = 0; x < nbr; ++x) {
             order_cls[x] = b.order[x] | (static_cast<int32_t>(h->row_class[b.order[x]]) << 28);
+            if (!h->row_dense[static_cast<size_t>(b.order[x])]) order_rest.push_back(order_cls[x]);
+        }
 
         auto up = [&](size_t off, const void* src, size_t n) -> int {
             if (n == 0) return 0;
@@ -276,6 +362,12 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         if ((e = up(l.perm, perm_padded.data(), perm_padded.size() * 4))) return hip_fail("copy perm", e);
         if ((e = up(l.row_ptr, h->dev_row_ptr.data(), h->dev_row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
         if ((e = up(l.order, order_cls.data(), order_cls.size() * 4))) return hip_fail("copy order", e);
+        if ((e = up(l.order_rest, order_rest.data(), order_rest.size() * 4))) return hip_fail("copy order", e);
+        if ((e = up(l.t_super, h->dense_super.data(), h->dense_super.size() * 4))) return hip_fail("copy tiles", e);
+        if ((e = up(l.t_ptr, h->step_ptr.data(), h->step_ptr.size() * 4))) return hip_fail("copy tiles", e);
+        if ((e = up(l.t_cols, h->step_cols.data(), h->step_cols.size() * 4))) return hip_fail("copy tiles", e);
+        if ((e = up(l.t_rows, h->step_rows.data(), h->step_rows.size() * 4))) return hip_fail("copy tiles", e);
+        if ((e = up(l.t_base, h->step_base.data(), h->step_base.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
         if ((e = up(l.slots, slots.data(), slots.size() * 4))) return hip_fail("copy slot tables", e);
         if ((e = up(l.blk_col, blk_col.data(), blk_col.size() * 4))) return hip_fail("copy block columns", e);
@@ -296,12 +388,18 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         d.M = h->csr.M;
         d.K = h->csr.K;
         d.nbr = b.nbr;
-        d.n_e = h->n_dev_blocks;
-        int64_t longest = 0;
-        for (size_t r = 0; r < nbr; ++r) longest = std::max<int64_t>(longest, b.row_ptr[r + 1] - b.row_ptr[r]);
-        d.max_row_blocks = longest;
-        d.max_class = h->max_class;
-        d.mean_row_blocks = nbr ? static_cast<double>(b.n_blocks) / static_cast<double>(nbr) : 0.0;
+        smat::DeviceBcsr d_rest = d;
+        row_stats(*h, false, d);
+        row_stats(*h, true, d_rest);
+        d_rest.order = reinterpret_cast<const int32_t*>(base + l.order_rest);
+        smat::DenseTiles tiles;
+        tiles.super_rows = reinterpret_cast<const int32_t*>(base + l.t_super);
+        tiles.step_ptr = reinterpret_cast<const int32_t*>(base + l.t_ptr);
+        tiles.step_cols = reinterpret_cast<const int32_t*>(base + l.t_cols);
+        tiles.step_rows = reinterpret_cast<const uint32_t*>(base + l.t_rows);
+        tiles.step_base = reinterpret_cast<const uint32_t*>(base + l.t_base);
+        tiles.vals = reinterpret_cast<const uint16_t*>(base + l.t_vals);
+        tiles.n = static_cast<int32_t>(h->dense_super.size());
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
@@ -310,8 +408,14 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
                                         reinterpret_cast<uint16_t*>(base + l.vals), s)))
             return hip_fail("fill block values", e);
+        if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 64, s))) return hip_fail("zero tile values", e);
+        if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
+                                         reinterpret_cast<uint16_t*>(base + l.t_vals), s)))
+            return hip_fail("fill tile values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("bind synchronize", e);
         h->dev = d;
+        h->dev_rest = d_rest;
+        h->tiles = tiles;
         h->bound = true;
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
@@ -379,10 +483,23 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (K > 0 && ((K - 1) * ldb + N) * 2 >= (int64_t{1} << 31))
         return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
     if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
+    // The dense path needs 16-byte rows of B at 8-column granularity; otherwise every block row
+    // goes through the per-row kernel.
+    const bool bf16 = h->dtype == SMAT_BF16;
+    const bool use_tiles = h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
     const char* variant = "";
-    const int e = smat::launch_spmm(h->dev, h->dtype == SMAT_BF16, dB, ldb, static_cast<float*>(dC), ldc, N,
-                                    stream, &variant);
-    g_kernel = variant;
+    thread_local std::string name;
+    int e = 0;
+    if (use_tiles) {
+        if (h->dev_rest.n_order > 0)
+            e = smat::launch_spmm(h->dev_rest, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);
+        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream);
+        name = std::string(bf16 ? "spmm_dense_bf16" : "spmm_dense_f16") + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
+        g_kernel = name.c_str();
+    } else {
+        e = smat::launch_spmm(h->dev, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);
+        g_kernel = variant;
+    }
     if (e) return hip_fail("launch spmm", e);
     return SMAT_OK;
 }

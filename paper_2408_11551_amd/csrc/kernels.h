@@ -13,7 +13,8 @@ namespace smat {
 struct DeviceBcsr {
     const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
     const int32_t* row_ptr = nullptr;    // [nbr+1] block offsets (even)
-    const int32_t* order = nullptr;      // [nbr] block rows, longest first; bits 28..29: row class
+    const int32_t* order = nullptr;      // [n_order] block rows in launch order; bits 28..29: row class
+    int64_t n_order = 0;                 // rows the per-row kernel is launched for
     const uint32_t* slots_off = nullptr; // [nbr] start of the row's slot table, in 32-byte units
     const uint32_t* slots = nullptr;     // slot tables: per pair 4 groups x L entries (L by row class)
     const uint16_t* vals = nullptr;      // [256*n_e]
@@ -23,6 +24,21 @@ struct DeviceBcsr {
     int64_t max_row_blocks = 0;          // longest block row
     double mean_row_blocks = 0;
     int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pair)
+};
+
+// Block-dense parts of the matrix: "super rows" of sixteen consecutive block rows whose block
+// columns overlap enough to be walked together (kernels_dense.hip).  The union of a super
+// row's block columns, ascending, is cut into steps of two block columns; step q stores 1 KiB
+// for every block row that has one of its two columns (bit j of step_rows), back to back
+// from slot step_base[q].
+struct DenseTiles {
+    const int32_t* super_rows = nullptr;   // [n] super row index s: block rows 16 s .. 16 s + 15
+    const int32_t* step_ptr = nullptr;     // [n+1] offsets into the step arrays
+    const int32_t* step_cols = nullptr;    // [2 * steps] block columns of a step (INT_MAX: none)
+    const uint32_t* step_rows = nullptr;   // [steps] 16-bit mask of block rows present in the step
+    const uint32_t* step_base = nullptr;   // [steps] first 1 KiB slot of the step
+    const uint16_t* vals = nullptr;        // [512 * slots]
+    int32_t n = 0;
 };
 
 // Sets n16 16-byte words at dst to zero.
@@ -36,5 +52,13 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // C = A * B.  Returns a hipError_t as int; *variant receives a static string naming the kernel.
 int launch_spmm(const DeviceBcsr& d, bool bf16, const void* B, int64_t ldb, float* C, int64_t ldc,
                 int64_t N, void* stream, const char** variant);
+
+// Scatters the CSR values of the dense super rows into the tile layout (vals zeroed before).
+int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,
+                      const int32_t* csr_col_idx, const uint16_t* csr_vals, uint16_t* vals_out, void* stream);
+
+// C rows of the dense super rows.  Needs N, ldb multiples of 8 and B aligned to 16 bytes.
+int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
+                      float* C, int64_t ldc, int64_t N, void* stream);
 
 }  // namespace smat

@@ -502,7 +502,8 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float
                           int64_t N, hipStream_t stream)
 {
     const int64_t per_group = 16 * NT * NCH * SW;          // columns of one workgroup
-    dim3 grid(static_cast<unsigned>(d.nbr), static_cast<unsigned>((N + per_group - 1) / per_group));
+    if (d.n_order == 0) return 0;
+    dim3 grid(static_cast<unsigned>(d.n_order), static_cast<unsigned>((N + per_group - 1) / per_group));
     const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * 2) : 0u;
     const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
     // Block values that are read once per launch (a single group per block row) and are too many
@@ -536,7 +537,7 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* 
     const int nch = (NT == 8 && LMAX < 8 && slabs >= 2) ? 2 : 1;     // the dense class has no registers to spare
     const int64_t wave_slabs = (slabs + nch - 1) / nch;
     const int sw = wave_slabs >= 2 ? 2 : 1;
-    const int64_t groups = d.nbr * ((wave_slabs + sw - 1) / sw);
+    const int64_t groups = d.n_order * ((wave_slabs + sw - 1) / sw);
     const double stream_us = (static_cast<double>(d.n_e) * 512.0 + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * 2.0) / 5.0e6;
     const double longest_us = static_cast<double>(d.max_row_blocks) * 0.5 * 0.25;

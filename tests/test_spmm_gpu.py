@@ -99,6 +99,38 @@ def test_small_shapes_all_load_widths(shape, oracle_c):
     m.close()
 
 
+DENSE_SHAPES = [
+    # M, K, N, density, dtype: at least one complete super row of sixteen block rows with
+    # well-filled blocks, so the block-dense path runs (alone or next to the per-row kernel)
+    (256, 128, 128, 0.5, "f16"),
+    (512, 256, 136, 0.15, "bf16"),
+    (272, 130, 8, 0.3, "f16"),
+    (1024, 512, 264, 0.12, "f16"),
+    (300, 700, 64, 0.2, "bf16"),
+]
+
+
+@pytest.mark.parametrize("shape", DENSE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+def test_block_dense_path(shape, oracle_c):
+    M, K, N, density, dtype = shape
+    w = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, b_dist="normal")
+    m, _ = _run(w, oracle_c, ldb=N + 8, ldc=N + 4)
+    assert S.smat_last_kernel().startswith("spmm_dense"), S.smat_last_kernel()
+    # integer-valued copy: exact, so a misplaced value or B row cannot hide in the tolerance
+    wi = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, values="smallint", b_dist="smallint")
+    mi = S.SmatMatrix(wi.M, wi.K, wi.row_ptr, wi.col_idx, wi.a_bits, wi.dtype)
+    c = mi.spmm(_dev_b(wi))
+    torch.cuda.synchronize()
+    c_ref, _ = _oracle_c(oracle_c, wi)
+    assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+    # a width the dense path does not take (N not a multiple of 8) falls back to the per-row kernel
+    w2 = random_csr(M, K, 12, density, seed=M + K, dtype=dtype, b_dist="normal")
+    m2, _ = _run(w2, oracle_c)
+    assert not S.smat_last_kernel().startswith("spmm_dense")
+    for x in (m, mi, m2):
+        x.close()
+
+
 def test_small_integers_are_exact(oracle_c):
     # every partial sum is an integer below 2^24: any rounding order gives the same fp32 result
     for dtype in ("f16", "bf16"):
