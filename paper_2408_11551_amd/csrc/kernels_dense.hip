@@ -140,15 +140,16 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
         stage[1] = buf_load16(b_rsrc, __umul24(row1 < no_row ? row1 : no_row, ldb_bytes) + st_off, 0u);
     };
     // Values of the wave's four block rows for step q.  A block row without data in the step
-    // reads out of range (zeros) and multiplies zeros: no branches in the loop body.
-    auto load_a = [&](int q, u32x4 (&a)[RM]) {
+    // (or any block row in a step past the last one, `live` false) reads out of range (zeros)
+    // and multiplies zeros: no branches in the loop body.
+    auto load_a = [&](int q, bool live, u32x4 (&a)[RM]) {
         const uint32_t rows = t.step_rows[q];
         const uint32_t base = t.step_base[q] - first_slot;
 #pragma unroll
         for (int r = 0; r < RM; ++r) {
             const int j = RM * wave + r;
             const uint32_t slot = base + __popc(rows & ((1u << j) - 1u));
-            const uint32_t absent = (rows >> j & 1u) ? 0u : kOutOfRange;      // wave-uniform
+            const uint32_t absent = (live && (rows >> j & 1u)) ? 0u : kOutOfRange;      // wave-uniform
             a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
         }
     };
@@ -159,41 +160,57 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 #pragma unroll
         for (int x = 0; x < NT; ++x) acc[r][x] = f32x4{0.f, 0.f, 0.f, 0.f};
 
+    // Software pipeline, four-slot register rings (no copies, loop body of four steps without
+    // an exit; steps past the last one read zeros as block values).  While step s is multiplied, the B panels of steps
+    // s+2 and s+3 and the block values of steps s+1..s+3 are on their way from memory; the panel
+    // of step s+1 is copied into the other LDS buffer at the end of step s.
     if (nq > 0) {
-        u32x4 stage[2];
-        u32x4 a_cur[RM], a_nxt[RM];
-        load_panel(q0, stage);
-        load_a(q0, a_cur);
-        panel[0][st_row][st_chunk] = stage[0];
-        panel[0][16 + st_row][st_chunk] = stage[1];
+        u32x4 stage[4][2];
+        u32x4 a[4][RM];
+        auto step_of = [&](int s) { return q0 + (s < nq ? s : nq - 1); };   // clamped: a cache hit, unused
+        // prologue: steps 0..2 requested, panel of step 0 in LDS
+        load_panel(step_of(0), stage[0]);
+        load_a(step_of(0), true, a[0]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_panel(step_of(1), stage[1]);
+        load_a(step_of(1), 1 < nq, a[1]);
+        __builtin_amdgcn_sched_barrier(0);
+        load_panel(step_of(2), stage[2]);
+        load_a(step_of(2), 2 < nq, a[2]);
+        __builtin_amdgcn_sched_barrier(0);
+        panel[0][st_row][st_chunk] = stage[0][0];
+        panel[0][16 + st_row][st_chunk] = stage[0][1];
         __syncthreads();
-        for (int s = 0; s < nq; ++s) {
-            const int buf = s & 1;
-            // next step's global loads first (the last step re-reads itself: a cache hit, unused)
-            const int qn = q0 + (s + 1 < nq ? s + 1 : s);
-            load_panel(qn, stage);
-            load_a(qn, a_nxt);
-            // B rows of this lane's k range: row 8g + kk, columns 8i .. 8i+7
-            u32x4 R[8];
+        const int iters = (nq + 3) >> 2;
+        int s0 = 0;
+        for (int it = 0; it < iters; ++it) {
 #pragma unroll
-            for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][i];
-            __builtin_amdgcn_sched_barrier(0);
+            for (int u = 0; u < 4; ++u) {
+                const int s = s0 + u;
+                const int buf = u & 1;
+                load_panel(step_of(s + 3), stage[(u + 3) & 3]);
+                load_a(step_of(s + 3), s + 3 < nq, a[(u + 3) & 3]);
+                // B rows of this lane's k range: row 8g + kk, columns 8i .. 8i+7
+                u32x4 R[8];
 #pragma unroll
-            for (int x = 0; x < NT; ++x) {
-                const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 b;
+                for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][i];
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                for (int qd = 0; qd < 4; ++qd)
-                    b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
+                for (int x = 0; x < NT; ++x) {
+                    const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
+                    u32x4 b;
 #pragma unroll
-                for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pair<BF16>(a_cur[r], b, acc[r][x]);
+                    for (int qd = 0; qd < 4; ++qd)
+                        b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
+#pragma unroll
+                    for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pair<BF16>(a[u][r], b, acc[r][x]);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+                panel[buf ^ 1][st_row][st_chunk] = stage[(u + 1) & 3][0];
+                panel[buf ^ 1][16 + st_row][st_chunk] = stage[(u + 1) & 3][1];
+                __syncthreads();
             }
-            __builtin_amdgcn_sched_barrier(0);
-            panel[buf ^ 1][st_row][st_chunk] = stage[0];
-            panel[buf ^ 1][16 + st_row][st_chunk] = stage[1];
-#pragma unroll
-            for (int r = 0; r < RM; ++r) a_cur[r] = a_nxt[r];
-            __syncthreads();
+            s0 += 4;
         }
     }
 
