@@ -109,8 +109,8 @@ uint32_t pair_occupancy(const smat::Bcsr& b, int32_t s, int32_t s1)
 
 // Decides which complete super rows (sixteen block rows) go to the dense path and lays out
 // their steps.  A super row qualifies when walking the union of its block columns wastes
-// little: at least 8 union columns, at least 35 % of the (block row, union column) grid
-// stored, and blocks whose columns are mostly occupied (>= 8 of 16 on average; blocks with a
+// little: at least 8 union columns, at least half of the (block row, union column) grid
+// stored (a band of 37 % fill measured slower here than on the per-row kernel), and blocks whose columns are mostly occupied (>= 8 of 16 on average; blocks with a
 // few occupied columns are cheaper on the per-row path, which fetches only those rows of B).
 void plan_dense_tiles(smat_handle& h)
 {
@@ -128,7 +128,7 @@ void plan_dense_tiles(smat_handle& h)
         int64_t occupied = 0;
         for (int32_t k = lo; k < hi; ++k) occupied += __builtin_popcount(b.col_mask[k]);
         const int64_t n_uni = static_cast<int64_t>(uni.size()), n_blk = hi - lo;
-        if (n_uni < 8 || n_blk * 20 < 7 * 16 * n_uni || occupied < 8 * n_blk) continue;
+        if (n_uni < 8 || n_blk * 2 < 16 * n_uni || occupied < 8 * n_blk) continue;
         const int64_t steps = (n_uni + 1) / 2;
         if (steps * 16 >= (int64_t{1} << 21) || h.dense_slots + static_cast<uint64_t>(steps) * 16 >= (uint64_t{1} << 31)) continue;
         h.dense_super.push_back(static_cast<int32_t>(s));
@@ -400,6 +400,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.step_base = reinterpret_cast<const uint32_t*>(base + l.t_base);
         tiles.vals = reinterpret_cast<const uint16_t*>(base + l.t_vals);
         tiles.n = static_cast<int32_t>(h->dense_super.size());
+        tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
@@ -493,8 +494,9 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (use_tiles) {
         if (h->dev_rest.n_order > 0)
             e = smat::launch_spmm(h->dev_rest, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);
-        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream);
-        name = std::string(bf16 ? "spmm_dense_bf16" : "spmm_dense_f16") + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
+        const char* dense_variant = "";
+        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &dense_variant);
+        name = std::string(dense_variant) + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
         g_kernel = name.c_str();
     } else {
         e = smat::launch_spmm(h->dev, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);

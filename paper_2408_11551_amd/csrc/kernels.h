@@ -39,6 +39,7 @@ struct DenseTiles {
     const uint32_t* step_base = nullptr;   // [steps] first 1 KiB slot of the step
     const uint16_t* vals = nullptr;        // [512 * slots]
     int32_t n = 0;
+    double mean_steps = 0;                 // steps per super row, on average
 };
 
 // Sets n16 16-byte words at dst to zero.
@@ -59,6 +60,6 @@ int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* c
 
 // C rows of the dense super rows.  Needs N, ldb multiples of 8 and B aligned to 16 bytes.
 int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
-                      float* C, int64_t ldc, int64_t N, void* stream);
+                      float* C, int64_t ldc, int64_t N, void* stream, const char** variant);
 
 }  // namespace smat
