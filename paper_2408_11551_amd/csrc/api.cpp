@@ -29,7 +29,7 @@ struct smat_handle {
     // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2.  The slot table of a
     // row takes 16 * L bytes per pair; slots_off counts 32-byte units.
     std::vector<int8_t> row_class;       // [nbr]
-    std::vector<uint32_t> slots_off;     // [nbr]
+    std::vector<uint32_t> slots_off;     // [nbr+1]; also locates the row's block values (256 bytes per unit)
     uint64_t slots_units = 0;
     int max_class = 0;
     // Dense path (kernels.h, DenseTiles): complete super rows of sixteen block rows whose block
@@ -83,9 +83,9 @@ Layout make_layout(const smat_handle& h)
     l.row_ptr = take((nbr + 1) * sizeof(int32_t));
     l.order = take(nbr * sizeof(int32_t));
     l.order_rest = take(nbr * sizeof(int32_t));
-    l.slots_off = take(nbr * sizeof(uint32_t));
+    l.slots_off = take((nbr + 1) * sizeof(uint32_t));
     l.slots = take(static_cast<size_t>(h.slots_units) * 32);
-    l.vals = take(n_e * 512);
+    l.vals = take(static_cast<size_t>(h.slots_units) * 256);
     l.blk_col = take(n_e * sizeof(int32_t));
     l.occ = take(n_e / 2 * sizeof(uint32_t));
     l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
@@ -235,7 +235,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         h->n_dev_blocks = padded;
         const size_t nbr = static_cast<size_t>(h->bcsr.nbr);
         h->row_class.assign(nbr, 0);
-        h->slots_off.assign(nbr, 0);
+        h->slots_off.assign(nbr + 1, 0);
         uint64_t units = 0;
         for (size_t br = 0; br < nbr; ++br) {
             const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
@@ -252,6 +252,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
                 return fail(SMAT_ERR_UNSUPPORTED, "slot table too large");
             }
         }
+        h->slots_off[nbr] = static_cast<uint32_t>(units);
         h->slots_units = units;
         plan_dense_tiles(*h);
         *out = h;
@@ -405,7 +406,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
 
-        if ((e = smat::launch_fill_zero(base + l.vals, n_e * 32, s))) return hip_fail("zero block values", e);
+        if ((e = smat::launch_fill_zero(base + l.vals, static_cast<size_t>(h->slots_units) * 16, s))) return hip_fail("zero block values", e);
         if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
                                         reinterpret_cast<uint16_t*>(base + l.vals), s)))
             return hip_fail("fill block values", e);
@@ -428,24 +429,25 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
 {
     if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
     if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "handle is not bound to a device workspace");
-    const size_t n_e = static_cast<size_t>(h->bcsr.n_blocks), n_dev = static_cast<size_t>(h->n_dev_blocks);
+    const size_t n_e = static_cast<size_t>(h->bcsr.n_blocks);
     if (n_e == 0) return SMAT_OK;
     if (!vals) return fail(SMAT_ERR_INVALID_ARG, "vals is NULL");
     try {
-        std::vector<uint16_t> raw(n_dev * 256);
+        std::vector<uint16_t> raw(static_cast<size_t>(h->slots_units) * 128);
         hipStream_t s = static_cast<hipStream_t>(stream);
-        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, n_dev * 512, hipMemcpyDeviceToHost, s));
+        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, raw.size() * 2, hipMemcpyDeviceToHost, s));
         if (e) return hip_fail("read block values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("read block values", e);
         uint16_t* out = static_cast<uint16_t*>(vals);
         std::memset(out, 0, n_e * 512);
         for (int64_t br = 0; br < h->bcsr.nbr; ++br) {
             const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
-            size_t pair = static_cast<size_t>(h->dev_row_ptr[br]) / 2;
-            for (int32_t s = s0; s < s1; s += 2, ++pair) {
+            const int L = 2 << h->row_class[static_cast<size_t>(br)];
+            const int halves = smat::pair_halves(L);
+            const uint16_t* src = raw.data() + static_cast<size_t>(h->slots_off[static_cast<size_t>(br)]) * 128;
+            for (int32_t s = s0; s < s1; s += 2, src += halves) {
                 const uint32_t occ = pair_occupancy(h->bcsr, s, s1);
-                const uint16_t* src = raw.data() + pair * smat::kPairHalves;
-                uint8_t used[smat::kPairHalves];
+                uint8_t used[512];
                 std::memset(used, 0, sizeof(used));
                 int rank = 0;
                 for (int c = 0; c < 32; ++c) {
@@ -454,13 +456,13 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
                     ++rank;
                     uint16_t* blk = out + static_cast<size_t>(s + (c >> 4)) * 256;
                     for (int r = 0; r < 16; ++r) {
-                        const int at = smat::pair_half_index(r, g, kk);
+                        const int at = smat::pair_half_index(L, r, g, kk);
                         blk[r * 16 + (c & 15)] = src[at];
                         used[at] = 1;
                     }
                 }
                 // every slot that holds no occupied column must have stayed zero
-                for (int q = 0; q < smat::kPairHalves; ++q)
+                for (int q = 0; q < halves; ++q)
                     if (!used[q] && src[q] != 0) return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
             }
         }

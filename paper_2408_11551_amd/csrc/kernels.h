@@ -15,9 +15,9 @@ struct DeviceBcsr {
     const int32_t* row_ptr = nullptr;    // [nbr+1] block offsets (even)
     const int32_t* order = nullptr;      // [n_order] block rows in launch order; bits 28..29: row class
     int64_t n_order = 0;                 // rows the per-row kernel is launched for
-    const uint32_t* slots_off = nullptr; // [nbr] start of the row's slot table, in 32-byte units
+    const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table in 32-byte units, and of its values in 256-byte units
     const uint32_t* slots = nullptr;     // slot tables: per pair 4 groups x L entries (L by row class)
-    const uint16_t* vals = nullptr;      // [256*n_e]
+    const uint16_t* vals = nullptr;      // block values: per pair 64 L halves (L by row class)
     const int32_t* blk_col = nullptr;    // [n_e] block column per (padded) block; bind-time scatter only
     const uint32_t* occ = nullptr;       // [n_e/2] occupancy mask per pair; bind-time scatter only
     int64_t M = 0, K = 0, nbr = 0, n_e = 0;

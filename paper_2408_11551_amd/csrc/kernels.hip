@@ -55,6 +55,11 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
     const int64_t br = i >> 4;
     const int rr = static_cast<int>(i & 15);
     const int lo0 = d.row_ptr[br], hi0 = d.row_ptr[br + 1];
+    if (hi0 == lo0) return;
+    // class of the block row from the size of its slot table: 1, 2 or 4 units per pair
+    const uint32_t unit0 = d.slots_off[br];
+    const int L = 2 * static_cast<int>((d.slots_off[br + 1] - unit0) / static_cast<uint32_t>((hi0 - lo0) >> 1));
+    uint16_t* row_vals = vals_out + static_cast<size_t>(unit0) * 128;
     int hint = lo0;
     for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
         const int c = csr_col_idx[p];
@@ -68,7 +73,7 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
         const size_t pair = static_cast<size_t>(lo >> 1);
         const int pc = (lo & 1) * 16 + (c & 15);     // column inside the pair
         const int rank = __popc(d.occ[pair] & ((1u << pc) - 1u));
-        vals_out[pair * kPairHalves + pair_half_index(rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
+        row_vals[(pair - static_cast<size_t>(lo0 >> 1)) * pair_halves(L) + pair_half_index(L, rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
     }
 }
 
@@ -139,6 +144,10 @@ template <> struct BLoad<16> {
 // Same loads with the non-temporal hint: the block values and slot tables stream through
 // once and should not push the rows of B out of the L2.
 template <int BYTES> struct SLoad;
+template <> struct SLoad<4> {
+    static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
+    { r[0] = static_cast<uint32_t>(__builtin_amdgcn_raw_buffer_load_b32(s, off, soff, 2)); }
+};
 template <> struct SLoad<8> {
     static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
     { i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(s, off, soff, 2); r[0] = v[0]; r[1] = v[1]; }
@@ -181,13 +190,13 @@ struct PairOps {
     bool stream;
 
     __device__ __forceinline__ PairOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
-        : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * 16u),
+        : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * (2u * L)),
           ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npairs - 1), stream(w.stream)
     {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
         slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npairs * 16 * L, kRsrcFlags);
-        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * 1024, kRsrcFlags);
+        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * (128 * L), kRsrcFlags);
         none_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, 0, kRsrcFlags);
     }
     // Loads of a pair are unconditional: a pair index past the row's end is clamped to the
@@ -208,13 +217,14 @@ struct PairOps {
             }
         }
     }
-    // block values; `live` false (a step past the wave's last pair) reads zeros instead
+    // block values: the lane's L halves (the other operand dwords multiply nothing and stay
+    // zero); `live` false (a step past the wave's last pair) reads zeros instead
     __device__ __forceinline__ u32x4 load_a(int p, bool live) const
     {
-        uint32_t r[4];
-        if (!live) BLoad<16>::ld(r, none_rsrc, vals_voff, 0u);
-        else if (stream) SLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
-        else BLoad<16>::ld(r, vals_rsrc, vals_voff, clamp(p) * 1024u);
+        uint32_t r[4] = {0u, 0u, 0u, 0u};
+        if (!live) BLoad<2 * L>::ld(r, none_rsrc, vals_voff, 0u);
+        else if (stream) SLoad<2 * L>::ld(r, vals_rsrc, vals_voff, clamp(p) * (128u * L));
+        else BLoad<2 * L>::ld(r, vals_rsrc, vals_voff, clamp(p) * (128u * L));
         return u32x4{r[0], r[1], r[2], r[3]};
     }
     // Occupied columns fill the slots group by group, so position kk is empty in every group
@@ -387,7 +397,7 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
 
     RowWalk w;
     w.slots = d.slots + static_cast<size_t>(d.slots_off[br]) * 8;     // offsets count 32-byte units
-    w.vals = d.vals + static_cast<size_t>(start >> 1) * kPairHalves;
+    w.vals = d.vals + static_cast<size_t>(d.slots_off[br]) * 128;      // 256 bytes of values per unit
     w.npairs = n0 < N ? (end - start) >> 1 : 0;    // block rows are padded to an even count
     w.ks = ks;
     w.g = g;
