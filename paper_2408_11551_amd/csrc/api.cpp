@@ -9,11 +9,12 @@
 #include <cstdio>
 #include <cstring>
 #include <new>
+#include <stdexcept>
 #include <string>
 #include <vector>
 
 #include "kernels.h"
-#include "pair_layout.h"
+#include "pack_layout.h"
 #include "preprocess.h"
 
 struct smat_handle {
@@ -21,15 +22,20 @@ struct smat_handle {
     smat::Bcsr bcsr;
     smat_dtype_t dtype = SMAT_F16;
     bool bound = false;
-    // Device-side block arrays pad every block row to an even number of blocks (the kernel
-    // multiplies blocks two at a time); the pad block has no occupied column and zero values.
-    std::vector<int32_t> dev_row_ptr;    // [nbr+1] offsets into the padded block arrays
-    int64_t n_dev_blocks = 0;
-    // Row class: how many B-row loads per lane a pair of the block row needs at most (occupied
+    // Packs (pack_layout.h): every block row is cut, from the left, into runs of consecutive
+    // blocks that hold at most 32 occupied columns together; a pack is what one matrix
+    // instruction multiplies.
+    std::vector<int32_t> pack_ptr;       // [nbr+1] pack offsets per block row
+    std::vector<int32_t> pack_first;     // [n_packs+1] first stored block of every pack
+    std::vector<int32_t> blk_pack;       // [n_blocks] pack of the block, counted inside its block row
+    std::vector<uint32_t> blk_meta;      // [n_blocks] column mask | occupied columns of the pack before the block << 16
+    std::vector<int32_t> order;          // [nbr] block rows in launch order
+    // Row class: how many B-row loads per lane a pack of the block row needs at most (occupied
     // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2.  The slot table of a
-    // row takes 16 * L bytes per pair; slots_off counts 32-byte units.
+    // row takes 16 * L bytes per pack and its values 128 * L bytes; slots_off counts 32-byte
+    // units of the former, which are 256-byte units of the latter.
     std::vector<int8_t> row_class;       // [nbr]
-    std::vector<uint32_t> slots_off;     // [nbr+1]; also locates the row's block values (256 bytes per unit)
+    std::vector<uint32_t> slots_off;     // [nbr+1]
     uint64_t slots_units = 0;
     int max_class = 0;
     // Dense path (kernels.h, DenseTiles): complete super rows of sixteen block rows whose block
@@ -68,7 +74,8 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
-    size_t perm, row_ptr, order, order_rest, slots_off, slots, vals, blk_col, occ, csr_row_ptr, csr_col_idx, csr_vals;
+    size_t perm, work, work_rest, slots, vals, pack_ptr, slots_off, blk_ptr, blk_col, blk_pack, blk_meta;
+    size_t csr_row_ptr, csr_col_idx, csr_vals;
     size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, total;
 };
 
@@ -77,17 +84,19 @@ Layout make_layout(const smat_handle& h)
     Layout l{};
     size_t off = 0;
     auto take = [&](size_t bytes) { const size_t at = off; off = align_up(off + bytes); return at; };
-    const size_t nbr = static_cast<size_t>(h.bcsr.nbr), n_e = static_cast<size_t>(h.n_dev_blocks);
+    const size_t nbr = static_cast<size_t>(h.bcsr.nbr), n_e = static_cast<size_t>(h.bcsr.n_blocks);
     const size_t nnz = h.csr.col_idx.size();
     l.perm = take(nbr * 16 * sizeof(int32_t));
-    l.row_ptr = take((nbr + 1) * sizeof(int32_t));
-    l.order = take(nbr * sizeof(int32_t));
-    l.order_rest = take(nbr * sizeof(int32_t));
-    l.slots_off = take((nbr + 1) * sizeof(uint32_t));
+    l.work = take(nbr * 16);
+    l.work_rest = take(nbr * 16);
     l.slots = take(static_cast<size_t>(h.slots_units) * 32);
     l.vals = take(static_cast<size_t>(h.slots_units) * 256);
+    l.pack_ptr = take((nbr + 1) * sizeof(int32_t));
+    l.slots_off = take((nbr + 1) * sizeof(uint32_t));
+    l.blk_ptr = take((nbr + 1) * sizeof(int32_t));
     l.blk_col = take(n_e * sizeof(int32_t));
-    l.occ = take(n_e / 2 * sizeof(uint32_t));
+    l.blk_pack = take(n_e * sizeof(int32_t));
+    l.blk_meta = take(n_e * sizeof(uint32_t));
     l.csr_row_ptr = take((static_cast<size_t>(h.csr.M) + 1) * sizeof(int64_t));
     l.csr_col_idx = take(nnz * sizeof(int32_t));
     l.csr_vals = take(nnz * sizeof(uint16_t));
@@ -99,12 +108,6 @@ Layout make_layout(const smat_handle& h)
     l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
     l.total = off ? off : kAlign;
     return l;
-}
-
-// occupancy mask of the pair that starts at block s of a block row ending at block s1
-uint32_t pair_occupancy(const smat::Bcsr& b, int32_t s, int32_t s1)
-{
-    return b.col_mask[s] | (s + 1 < s1 ? static_cast<uint32_t>(b.col_mask[s + 1]) << 16 : 0u);
 }
 
 // Decides which complete super rows (sixteen block rows) go to the dense path and lays out
@@ -151,25 +154,67 @@ void plan_dense_tiles(smat_handle& h)
     }
 }
 
+// Cuts every block row into packs and derives the row classes (pack_layout.h).
+void plan_packs(smat_handle& h)
+{
+    const smat::Bcsr& b = h.bcsr;
+    const size_t nbr = static_cast<size_t>(b.nbr), n_e = b.col_idx.size();
+    h.pack_ptr.assign(nbr + 1, 0);
+    h.pack_first.clear();
+    h.blk_pack.assign(n_e, 0);
+    h.blk_meta.assign(n_e, 0);
+    h.row_class.assign(nbr, 0);
+    h.slots_off.assign(nbr + 1, 0);
+    h.max_class = 0;
+    uint64_t units = 0;
+    for (size_t br = 0; br < nbr; ++br) {
+        const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
+        int in_pack = 0, worst = 0, pack = -1;
+        for (int32_t s = s0; s < s1; ++s) {
+            const int cols = __builtin_popcount(b.col_mask[s]);
+            if (pack < 0 || in_pack + cols > smat::kPackColumns) {
+                ++pack;
+                in_pack = 0;
+                h.pack_first.push_back(s);
+            }
+            h.blk_pack[static_cast<size_t>(s)] = pack;
+            h.blk_meta[static_cast<size_t>(s)] = static_cast<uint32_t>(b.col_mask[s]) | static_cast<uint32_t>(in_pack) << 16;
+            in_pack += cols;
+            worst = std::max(worst, in_pack);
+        }
+        const int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
+        h.row_class[br] = static_cast<int8_t>(cls);
+        h.max_class = std::max(h.max_class, cls);
+        h.slots_off[br] = static_cast<uint32_t>(units);
+        units += static_cast<uint64_t>(pack + 1) << cls;                  // 1, 2 or 4 units per pack
+        if (units >= (uint64_t{1} << 32)) throw std::length_error("slot table too large");
+        h.pack_ptr[br + 1] = static_cast<int32_t>(h.pack_first.size());
+    }
+    h.pack_first.push_back(static_cast<int32_t>(n_e));
+    h.slots_off[nbr] = static_cast<uint32_t>(units);
+    h.slots_units = units;
+    smat::work_order(h.pack_ptr, h.order);
+}
+
 // Launch statistics over a subset of block rows.
 void row_stats(const smat_handle& h, bool skip_dense, smat::DeviceBcsr& d)
 {
-    const smat::Bcsr& b = h.bcsr;
-    int64_t longest = 0, blocks = 0, rows = 0, padded = 0;
+    int64_t longest = 0, packs = 0, rows = 0, units = 0;
     int cls = 0;
-    for (int64_t br = 0; br < b.nbr; ++br) {
+    for (int64_t br = 0; br < h.bcsr.nbr; ++br) {
         if (skip_dense && h.row_dense[static_cast<size_t>(br)]) continue;
-        const int64_t len = b.row_ptr[br + 1] - b.row_ptr[br];
+        const int64_t len = h.pack_ptr[static_cast<size_t>(br) + 1] - h.pack_ptr[static_cast<size_t>(br)];
         longest = std::max(longest, len);
-        blocks += len;
-        padded += (len + 1) / 2 * 2;
+        packs += len;
+        units += len << h.row_class[static_cast<size_t>(br)];
         cls = std::max<int>(cls, h.row_class[static_cast<size_t>(br)]);
         ++rows;
     }
     d.n_order = rows;
-    d.n_e = padded;
-    d.max_row_blocks = longest;
-    d.mean_row_blocks = rows ? static_cast<double>(blocks) / static_cast<double>(rows) : 0.0;
+    d.n_packs = packs;
+    d.stream_bytes = units * (256 + 32);
+    d.max_row_packs = longest;
+    d.mean_row_packs = rows ? static_cast<double>(packs) / static_cast<double>(rows) : 0.0;
     d.max_class = cls;
 }
 
@@ -221,39 +266,12 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         h->csr.col_idx.assign(col_idx, col_idx + nnz);
         h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
         smat::build_bcsr(h->csr, o.reorder != 0, o.tau_permille, h->bcsr);
-        h->dev_row_ptr.assign(static_cast<size_t>(h->bcsr.nbr) + 1, 0);
-        int64_t padded = 0;
-        for (int64_t br = 0; br < h->bcsr.nbr; ++br) {
-            const int64_t cnt = h->bcsr.row_ptr[br + 1] - h->bcsr.row_ptr[br];
-            padded += (cnt + 1) / 2 * 2;
-            if (padded >= (int64_t{1} << 31) - 2) {
-                delete h;
-                return fail(SMAT_ERR_UNSUPPORTED, "more than 2^31 blocks");
-            }
-            h->dev_row_ptr[br + 1] = static_cast<int32_t>(padded);
+        try {
+            plan_packs(*h);
+        } catch (const std::length_error& e) {
+            delete h;
+            return fail(SMAT_ERR_UNSUPPORTED, e.what());
         }
-        h->n_dev_blocks = padded;
-        const size_t nbr = static_cast<size_t>(h->bcsr.nbr);
-        h->row_class.assign(nbr, 0);
-        h->slots_off.assign(nbr + 1, 0);
-        uint64_t units = 0;
-        for (size_t br = 0; br < nbr; ++br) {
-            const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
-            int worst = 0;
-            for (int32_t s = s0; s < s1; s += 2)
-                worst = std::max(worst, __builtin_popcount(pair_occupancy(h->bcsr, s, s1)));
-            const int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
-            h->row_class[br] = static_cast<int8_t>(cls);
-            h->max_class = std::max(h->max_class, cls);
-            h->slots_off[br] = static_cast<uint32_t>(units);
-            units += static_cast<uint64_t>((s1 - s0 + 1) / 2) << cls;       // 1, 2 or 4 units per pair
-            if (units >= (uint64_t{1} << 32)) {
-                delete h;
-                return fail(SMAT_ERR_UNSUPPORTED, "slot table too large");
-            }
-        }
-        h->slots_off[nbr] = static_cast<uint32_t>(units);
-        h->slots_units = units;
         plan_dense_tiles(*h);
         *out = h;
         return SMAT_OK;
@@ -315,44 +333,38 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         hipStream_t s = static_cast<hipStream_t>(stream);
         char* base = static_cast<char*>(dev_workspace);
         const smat::Bcsr& b = h->bcsr;
-        const size_t nbr = static_cast<size_t>(b.nbr), n_e = static_cast<size_t>(h->n_dev_blocks);
+        const size_t nbr = static_cast<size_t>(b.nbr), n_e = b.col_idx.size();
         const size_t M = static_cast<size_t>(h->csr.M), nnz = h->csr.col_idx.size();
 
         std::vector<int32_t> perm_padded(nbr * 16, -1);
         std::memcpy(perm_padded.data(), b.perm.data(), sizeof(int32_t) * M);
-        // slot tables (pair_layout.h), block columns and occupancy masks; an odd tail is completed
-        // by a pad block: column beyond every real one (keeps the row's columns ascending),
-        // nothing occupied
-        std::vector<uint32_t> slots(static_cast<size_t>(h->slots_units) * 8);
-        std::vector<int32_t> blk_col(n_e);
-        std::vector<uint32_t> occ_mask(n_e / 2);
-        const uint32_t no_row = static_cast<uint32_t>(h->csr.K);        // one past the last row of B
+        // slot tables (pack_layout.h): the B row of every occupied column of every pack
+        std::vector<uint32_t> slots(static_cast<size_t>(h->slots_units) * 8, static_cast<uint32_t>(h->csr.K));
         for (size_t br = 0; br < nbr; ++br) {
-            const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
             const int L = 2 << h->row_class[br];
-            size_t blk = static_cast<size_t>(h->dev_row_ptr[br]);
             uint32_t* table = slots.data() + static_cast<size_t>(h->slots_off[br]) * 8;
-            for (int32_t s = s0; s < s1; s += 2, blk += 2, table += 4 * L) {
-                const bool has2 = s + 1 < s1;
-                const uint32_t occ = pair_occupancy(b, s, s1);
-                blk_col[blk] = b.col_idx[s];
-                blk_col[blk + 1] = has2 ? b.col_idx[s + 1] : 0x7FFFFFFF;
-                occ_mask[blk / 2] = occ;
-                for (int x = 0; x < 4 * L; ++x) table[x] = no_row;
+            for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, table += 4 * L) {
                 int rank = 0;
-                for (int c = 0; c < 32; ++c) {
-                    if (!(occ >> c & 1u)) continue;
-                    const uint32_t row = static_cast<uint32_t>(b.col_idx[s + (c >> 4)]) * 16u + static_cast<uint32_t>(c & 15);
-                    table[smat::slot_group(rank) * L + smat::slot_pos(rank)] = row;
-                    ++rank;
-                }
+                for (int32_t s = h->pack_first[static_cast<size_t>(pk)]; s < h->pack_first[static_cast<size_t>(pk) + 1]; ++s)
+                    for (int c = 0; c < 16; ++c) {
+                        if (!(b.col_mask[s] >> c & 1u)) continue;
+                        table[smat::slot_group(rank) * L + smat::slot_pos(rank)] =
+                            static_cast<uint32_t>(b.col_idx[s]) * 16u + static_cast<uint32_t>(c);
+                        ++rank;
+                    }
             }
         }
-        std::vector<int32_t> order_cls(nbr), order_rest;
-        order_rest.reserve(nbr);
+        // launch tables: all block rows, and those the dense path does not cover
+        std::vector<int32_t> work(nbr * 4), work_rest;
+        work_rest.reserve(nbr * 4);
         for (size_t x = 0; x < nbr; ++x) {
-            order_cls[x] = b.order[x] | (static_cast<int32_t>(h->row_class[b.order[x]]) << 28);
-            if (!h->row_dense[static_cast<size_t>(b.order[x])]) order_rest.push_back(order_cls[x]);
+            const size_t br = static_cast<size_t>(h->order[x]);
+            int32_t* rec = work.data() + 4 * x;
+            rec[0] = static_cast<int32_t>(br) | (static_cast<int32_t>(h->row_class[br]) << 28);
+            rec[1] = h->pack_ptr[br + 1] - h->pack_ptr[br];
+            rec[2] = static_cast<int32_t>(h->slots_off[br]);
+            rec[3] = 0;
+            if (!h->row_dense[br]) work_rest.insert(work_rest.end(), rec, rec + 4);
         }
 
         auto up = [&](size_t off, const void* src, size_t n) -> int {
@@ -361,38 +373,43 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         };
         int e;
         if ((e = up(l.perm, perm_padded.data(), perm_padded.size() * 4))) return hip_fail("copy perm", e);
-        if ((e = up(l.row_ptr, h->dev_row_ptr.data(), h->dev_row_ptr.size() * 4))) return hip_fail("copy row_ptr", e);
-        if ((e = up(l.order, order_cls.data(), order_cls.size() * 4))) return hip_fail("copy order", e);
-        if ((e = up(l.order_rest, order_rest.data(), order_rest.size() * 4))) return hip_fail("copy order", e);
+        if ((e = up(l.work, work.data(), work.size() * 4))) return hip_fail("copy launch table", e);
+        if ((e = up(l.work_rest, work_rest.data(), work_rest.size() * 4))) return hip_fail("copy launch table", e);
         if ((e = up(l.t_super, h->dense_super.data(), h->dense_super.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.t_ptr, h->step_ptr.data(), h->step_ptr.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.t_cols, h->step_cols.data(), h->step_cols.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.t_rows, h->step_rows.data(), h->step_rows.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.t_base, h->step_base.data(), h->step_base.size() * 4))) return hip_fail("copy tiles", e);
-        if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
         if ((e = up(l.slots, slots.data(), slots.size() * 4))) return hip_fail("copy slot tables", e);
-        if ((e = up(l.blk_col, blk_col.data(), blk_col.size() * 4))) return hip_fail("copy block columns", e);
-        if ((e = up(l.occ, occ_mask.data(), occ_mask.size() * 4))) return hip_fail("copy occupancy", e);
+        if ((e = up(l.pack_ptr, h->pack_ptr.data(), h->pack_ptr.size() * 4))) return hip_fail("copy pack offsets", e);
+        if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
+        if ((e = up(l.blk_ptr, b.row_ptr.data(), b.row_ptr.size() * 4))) return hip_fail("copy block offsets", e);
+        if ((e = up(l.blk_col, b.col_idx.data(), n_e * 4))) return hip_fail("copy block columns", e);
+        if ((e = up(l.blk_pack, h->blk_pack.data(), n_e * 4))) return hip_fail("copy block packs", e);
+        if ((e = up(l.blk_meta, h->blk_meta.data(), n_e * 4))) return hip_fail("copy block masks", e);
         if ((e = up(l.csr_row_ptr, h->csr.row_ptr.data(), (M + 1) * 8))) return hip_fail("copy csr row_ptr", e);
         if ((e = up(l.csr_col_idx, h->csr.col_idx.data(), nnz * 4))) return hip_fail("copy csr col_idx", e);
         if ((e = up(l.csr_vals, h->csr.vals.data(), nnz * 2))) return hip_fail("copy csr vals", e);
+        // the host vectors above must outlive the asynchronous copies: synchronised below, before they go
 
         smat::DeviceBcsr d;
         d.perm = reinterpret_cast<const int32_t*>(base + l.perm);
-        d.row_ptr = reinterpret_cast<const int32_t*>(base + l.row_ptr);
-        d.order = reinterpret_cast<const int32_t*>(base + l.order);
-        d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
+        d.work = reinterpret_cast<const int32_t*>(base + l.work);
         d.slots = reinterpret_cast<const uint32_t*>(base + l.slots);
         d.vals = reinterpret_cast<const uint16_t*>(base + l.vals);
+        d.pack_ptr = reinterpret_cast<const int32_t*>(base + l.pack_ptr);
+        d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
+        d.blk_ptr = reinterpret_cast<const int32_t*>(base + l.blk_ptr);
         d.blk_col = reinterpret_cast<const int32_t*>(base + l.blk_col);
-        d.occ = reinterpret_cast<const uint32_t*>(base + l.occ);
+        d.blk_pack = reinterpret_cast<const int32_t*>(base + l.blk_pack);
+        d.blk_meta = reinterpret_cast<const uint32_t*>(base + l.blk_meta);
         d.M = h->csr.M;
         d.K = h->csr.K;
         d.nbr = b.nbr;
         smat::DeviceBcsr d_rest = d;
         row_stats(*h, false, d);
         row_stats(*h, true, d_rest);
-        d_rest.order = reinterpret_cast<const int32_t*>(base + l.order_rest);
+        d_rest.work = reinterpret_cast<const int32_t*>(base + l.work_rest);
         smat::DenseTiles tiles;
         tiles.super_rows = reinterpret_cast<const int32_t*>(base + l.t_super);
         tiles.step_ptr = reinterpret_cast<const int32_t*>(base + l.t_ptr);
@@ -440,25 +457,25 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("read block values", e);
         uint16_t* out = static_cast<uint16_t*>(vals);
         std::memset(out, 0, n_e * 512);
-        for (int64_t br = 0; br < h->bcsr.nbr; ++br) {
-            const int32_t s0 = h->bcsr.row_ptr[br], s1 = h->bcsr.row_ptr[br + 1];
-            const int L = 2 << h->row_class[static_cast<size_t>(br)];
-            const int halves = smat::pair_halves(L);
-            const uint16_t* src = raw.data() + static_cast<size_t>(h->slots_off[static_cast<size_t>(br)]) * 128;
-            for (int32_t s = s0; s < s1; s += 2, src += halves) {
-                const uint32_t occ = pair_occupancy(h->bcsr, s, s1);
+        for (size_t br = 0; br < static_cast<size_t>(h->bcsr.nbr); ++br) {
+            const int L = 2 << h->row_class[br];
+            const int halves = smat::pack_halves(L);
+            const uint16_t* src = raw.data() + static_cast<size_t>(h->slots_off[br]) * 128;
+            for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, src += halves) {
                 uint8_t used[512];
                 std::memset(used, 0, sizeof(used));
                 int rank = 0;
-                for (int c = 0; c < 32; ++c) {
-                    if (!(occ >> c & 1u)) continue;
-                    const int g = smat::slot_group(rank), kk = smat::slot_pos(rank);
-                    ++rank;
-                    uint16_t* blk = out + static_cast<size_t>(s + (c >> 4)) * 256;
-                    for (int r = 0; r < 16; ++r) {
-                        const int at = smat::pair_half_index(L, r, g, kk);
-                        blk[r * 16 + (c & 15)] = src[at];
-                        used[at] = 1;
+                for (int32_t s = h->pack_first[static_cast<size_t>(pk)]; s < h->pack_first[static_cast<size_t>(pk) + 1]; ++s) {
+                    uint16_t* blk = out + static_cast<size_t>(s) * 256;
+                    for (int c = 0; c < 16; ++c) {
+                        if (!(h->bcsr.col_mask[s] >> c & 1u)) continue;
+                        const int g = smat::slot_group(rank), kk = smat::slot_pos(rank);
+                        ++rank;
+                        for (int r = 0; r < 16; ++r) {
+                            const int at = smat::pack_half_index(L, r, g, kk);
+                            blk[r * 16 + c] = src[at];
+                            used[at] = 1;
+                        }
                     }
                 }
                 // every slot that holds no occupied column must have stayed zero

@@ -7,23 +7,30 @@
 
 namespace smat {
 
-// Pointers into the caller's device workspace.  Block rows are padded to an even number of
-// blocks; pair P of the whole matrix covers blocks 2P and 2P+1.  See pair_layout.h for the
-// layout of a pair's values and metadata.
+// Pointers into the caller's device workspace.  See pack_layout.h for packs, their values and
+// their slot tables.
 struct DeviceBcsr {
     const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
-    const int32_t* row_ptr = nullptr;    // [nbr+1] block offsets (even)
-    const int32_t* order = nullptr;      // [n_order] block rows in launch order; bits 28..29: row class
+    // Launch table, one record of four words per workgroup of the per-row kernel, in launch
+    // order: block row | row class << 28, number of packs, start of the row's slot table in
+    // 32-byte units (its values start at the same count of 256-byte units), 0.
+    const int32_t* work = nullptr;       // [4 * n_order]
     int64_t n_order = 0;                 // rows the per-row kernel is launched for
-    const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table in 32-byte units, and of its values in 256-byte units
-    const uint32_t* slots = nullptr;     // slot tables: per pair 4 groups x L entries (L by row class)
-    const uint16_t* vals = nullptr;      // block values: per pair 64 L halves (L by row class)
-    const int32_t* blk_col = nullptr;    // [n_e] block column per (padded) block; bind-time scatter only
-    const uint32_t* occ = nullptr;       // [n_e/2] occupancy mask per pair; bind-time scatter only
-    int64_t M = 0, K = 0, nbr = 0, n_e = 0;
-    int64_t max_row_blocks = 0;          // longest block row
-    double mean_row_blocks = 0;
-    int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pair)
+    const uint32_t* slots = nullptr;     // slot tables: per pack 4 groups x L entries (L by row class)
+    const uint16_t* vals = nullptr;      // block values: per pack 64 L halves
+    // bind-time value scatter only
+    const int32_t* pack_ptr = nullptr;   // [nbr+1] pack offsets per block row
+    const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table, 32-byte units
+    const int32_t* blk_ptr = nullptr;    // [nbr+1] stored-block offsets per block row
+    const int32_t* blk_col = nullptr;    // [n_blocks] block column, ascending inside a block row
+    const int32_t* blk_pack = nullptr;   // [n_blocks] pack of the block, counted inside its block row
+    const uint32_t* blk_meta = nullptr;  // [n_blocks] occupancy mask | occupied columns of the pack before the block << 16
+    int64_t M = 0, K = 0, nbr = 0;
+    int64_t n_packs = 0;                 // packs of the rows in the launch table
+    int64_t stream_bytes = 0;            // values + slot tables of those rows
+    int64_t max_row_packs = 0;           // longest block row
+    double mean_row_packs = 0;
+    int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pack)
 };
 
 // Block-dense parts of the matrix: "super rows" of sixteen consecutive block rows whose block

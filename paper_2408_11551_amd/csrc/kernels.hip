@@ -8,7 +8,7 @@
 
 #include <cstdio>
 
-#include "pair_layout.h"
+#include "pack_layout.h"
 
 namespace smat {
 
@@ -44,7 +44,7 @@ int launch_fill_zero(void* dst, size_t n16, void* stream)
 
 // One thread per row of A' = P A: walks the row's CSR entries, finds each entry's block in
 // the block row by binary search over the ascending block columns and stores the value at
-// its slot in the pair layout (pair_layout.h).
+// its slot in the block's pack (pack_layout.h).
 __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_row_ptr,
                                  const int32_t* __restrict__ csr_col_idx,
                                  const uint16_t* __restrict__ csr_vals, uint16_t* __restrict__ vals_out)
@@ -54,11 +54,12 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
     const int64_t r = d.perm[i];
     const int64_t br = i >> 4;
     const int rr = static_cast<int>(i & 15);
-    const int lo0 = d.row_ptr[br], hi0 = d.row_ptr[br + 1];
-    if (hi0 == lo0) return;
-    // class of the block row from the size of its slot table: 1, 2 or 4 units per pair
+    const int lo0 = d.blk_ptr[br], hi0 = d.blk_ptr[br + 1];
+    const int npacks = d.pack_ptr[br + 1] - d.pack_ptr[br];
+    if (npacks == 0) return;
+    // class of the block row from the size of its slot table: 1, 2 or 4 units per pack
     const uint32_t unit0 = d.slots_off[br];
-    const int L = 2 * static_cast<int>((d.slots_off[br + 1] - unit0) / static_cast<uint32_t>((hi0 - lo0) >> 1));
+    const int L = 2 * static_cast<int>((d.slots_off[br + 1] - unit0) / static_cast<uint32_t>(npacks));
     uint16_t* row_vals = vals_out + static_cast<size_t>(unit0) * 128;
     int hint = lo0;
     for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
@@ -70,10 +71,9 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
             if (d.blk_col[mid] < bc) lo = mid + 1; else hi = mid;
         }
         hint = lo;
-        const size_t pair = static_cast<size_t>(lo >> 1);
-        const int pc = (lo & 1) * 16 + (c & 15);     // column inside the pair
-        const int rank = __popc(d.occ[pair] & ((1u << pc) - 1u));
-        row_vals[(pair - static_cast<size_t>(lo0 >> 1)) * pair_halves(L) + pair_half_index(L, rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
+        const uint32_t meta = d.blk_meta[lo];
+        const int rank = static_cast<int>(meta >> 16) + __popc(meta & 0xFFFFu & ((1u << (c & 15)) - 1u));
+        row_vals[static_cast<size_t>(d.blk_pack[lo]) * pack_halves(L) + pack_half_index(L, rr, slot_group(rank), slot_pos(rank))] = csr_vals[p];
     }
 }
 
@@ -93,13 +93,14 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // ---------------------------------------------------------------------------
 //
 // Work split: one workgroup per (block row, group of SW column slabs of 16*NT columns).  The
-// group has KW*SW wavefronts: wave (ks, sl) takes block pairs ks, ks+KW, ... of the block row
+// group has KW*SW wavefronts: wave (ks, sl) takes packs ks, ks+KW, ... of the block row
 // for slab sl, so the group streams the row's block values front to back once from HBM; the
 // KW partial tiles of a slab are summed through LDS in a fixed order and scattered to the
 // rows perm[16*br + 0..15] of C.
 //
-// One MFMA 16x16x32 multiplies a pair of stored blocks.  The left operand of lane l is the
-// 16 bytes at offset 16*l of the pair's values (pair_layout.h).  The right operand wants, per
+// One MFMA 16x16x32 multiplies a pack: the consecutive stored blocks of the block row that
+// fit its 32 k slots with their occupied columns (pack_layout.h).  The left operand of lane l
+// is the lane's 2*L bytes of the pack's values.  The right operand wants, per
 // lane, eight k-consecutive values of one column of B, while B is row-major (n-consecutive).
 // Instead of transposing through LDS, lane (g, i) loads from each B row of its k slots the NT
 // consecutive columns n0 + NT*i .. n0 + NT*i + NT-1, and MFMA number t is defined to produce
@@ -107,9 +108,9 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // half t of its row loads (one byte-permute per two halves), and after the NT MFMAs the lane
 // holds, for each of its four output rows 4g..4g+3, NT consecutive columns of C.
 //
-// Only occupied columns of a pair need a B row.  The pair layout packs them into the first
-// slots of every lane group, so a block row whose pairs hold at most 4*L occupied columns
-// runs a loop that issues exactly L row loads per lane and pair (L = 2, 4 or 8, the row's
+// Only occupied columns of a pack need a B row.  The layout puts them into the first
+// slots of every lane group, so a block row whose packs hold at most 4*L occupied columns
+// runs a loop that issues exactly L row loads per lane and pack (L = 2, 4 or 8, the row's
 // "class", stored with the work order) and permutes only L/2 operand dwords.  The slot table
 // gives the B row of every slot; empty slots name row K, one past the end of B, for which
 // the range-checked buffer load returns zeros without a memory access.  The number of loads
@@ -158,7 +159,7 @@ template <> struct SLoad<16> {
 };
 
 template <bool BF16>
-__device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
+__device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 {
     if constexpr (BF16)
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -168,10 +169,10 @@ __device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
 
 // Everything a wave needs to walk its share of a block row.
 struct RowWalk {
-    const uint32_t* slots;      // slot table of the row's first pair
-    const uint16_t* vals;       // values of the row's first pair
-    int npairs;                 // pairs in the row (0 if this wave's slab is beyond N)
-    int ks;                     // first pair of this wave
+    const uint32_t* slots;      // slot table of the row's first pack
+    const uint16_t* vals;       // values of the row's first pack
+    int npacks;                 // packs in the row (0 if this wave's slab is beyond N)
+    int ks;                     // first pack of this wave
     int g, lane;
     uint32_t lane_off[2];       // per column chunk: byte offset of the lane's first column inside a B row
     uint32_t ldb_bytes;
@@ -181,7 +182,7 @@ struct RowWalk {
 
 // Per-class pieces shared by the two pipelines below.
 template <int NT, int L, int NCH, bool BF16>
-struct PairOps {
+struct PackOps {
     static constexpr int ND = NT >= 2 ? NT / 2 : 1;       // dwords per B row load
     static constexpr int NQ = L / 2;                      // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
@@ -189,18 +190,18 @@ struct PairOps {
     int last;
     bool stream;
 
-    __device__ __forceinline__ PairOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
+    __device__ __forceinline__ PackOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
         : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * (2u * L)),
-          ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npairs - 1), stream(w.stream)
+          ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npacks - 1), stream(w.stream)
     {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
-        slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npairs * 16 * L, kRsrcFlags);
-        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npairs * (128 * L), kRsrcFlags);
+        slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npacks * 16 * L, kRsrcFlags);
+        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, w.npacks * (128 * L), kRsrcFlags);
         none_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint16_t*>(w.vals), 0, 0, kRsrcFlags);
     }
-    // Loads of a pair are unconditional: a pair index past the row's end is clamped to the
-    // row's last pair (a cache hit).  All of this is scalar arithmetic.
+    // Loads of a pack are unconditional: a pack index past the row's end is clamped to the
+    // row's last pack (a cache hit).  All of this is scalar arithmetic.
     __device__ __forceinline__ uint32_t clamp(int p) const { return static_cast<uint32_t>(p < last ? p : last); }
     // B rows of the lane group's L slots
     __device__ __forceinline__ void load_slots(int p, uint32_t (&m)[L]) const
@@ -218,7 +219,7 @@ struct PairOps {
         }
     }
     // block values: the lane's L halves (the other operand dwords multiply nothing and stay
-    // zero); `live` false (a step past the wave's last pair) reads zeros instead
+    // zero); `live` false (a step past the wave's last pack) reads zeros instead
     __device__ __forceinline__ u32x4 load_a(int p, bool live) const
     {
         uint32_t r[4] = {0u, 0u, 0u, 0u};
@@ -228,7 +229,7 @@ struct PairOps {
         return u32x4{r[0], r[1], r[2], r[3]};
     }
     // Occupied columns fill the slots group by group, so position kk is empty in every group
-    // as soon as it is empty in group 0 (lane 0).  In the sparse classes a pair therefore has
+    // as soon as it is empty in group 0 (lane 0).  In the sparse classes a pack therefore has
     // a wave-uniform "level": the number of leading positions that hold anything, rounded up
     // to 1, 2 or 4; only that many B rows are requested, and the multiply permutes only the
     // operand dwords they feed.  Returns the level.
@@ -250,7 +251,7 @@ struct PairOps {
             }
         return level;
     }
-    // Rows above the pair's level were not requested: their registers hold stale data and are
+    // Rows above the pack's level were not requested: their registers hold stale data and are
     // replaced by zeros (a select on a wave-uniform condition) before the permutes.
     __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][NCH][ND], int level, f32x4 (&acc)[NCH * NT]) const
     {
@@ -269,25 +270,25 @@ struct PairOps {
 #pragma unroll
                 for (int q = 0; q < NQ; ++q)
                     b[q] = __builtin_amdgcn_perm(S[2 * q + 1][t >> 1], S[2 * q][t >> 1], pick);
-                acc[c * NT + t] = mfma_pair<BF16>(a, b, acc[c * NT + t]);
+                acc[c * NT + t] = mfma_pack<BF16>(a, b, acc[c * NT + t]);
             }
         }
     }
 };
 
-// Pipeline for the dense class (L = 8), two register sets.  Per pair h: its slot table is
+// Pipeline for the dense class (L = 8), two register sets.  Per pack h: its slot table is
 // requested two steps ahead, its B rows (whose addresses need it) one step ahead, its block
-// values right after the multiply of pair h-2 has released their registers.  The loop body
-// handles two pairs and has no exit in the middle (an odd tail multiplies zeros).  The
+// values right after the multiply of pack h-2 has released their registers.  The loop body
+// handles two packs and has no exit in the middle (an odd tail multiplies zeros).  The
 // scheduling barriers keep every load ahead of the multiply that precedes its use, and the
 // prologue issues its loads in the order the loop body leaves them in flight.
 template <int NT, int KW, int L, int NCH, bool BF16>
 __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NCH * NT])
 {
-    using Ops = PairOps<NT, L, NCH, BF16>;
-    if (w.ks >= w.npairs) return;
+    using Ops = PackOps<NT, L, NCH, BF16>;
+    if (w.ks >= w.npacks) return;
     const Ops ops(w, rsrc);
-    const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
+    const int count = (w.npacks - w.ks + KW - 1) / KW;     // packs of this wave
     const int iters = (count + 1) >> 1;
     uint32_t R0[L][NCH][Ops::ND], R1[L][NCH][Ops::ND];
     uint32_t m0[L], m1[L];
@@ -300,7 +301,7 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
     __builtin_amdgcn_sched_barrier(0);
     u32x4 a1 = ops.load_a(p + KW, count > 1);
     for (int it = 0; it < iters; ++it) {
-        const int h = 2 * it;                              // pair of this wave multiplied first
+        const int h = 2 * it;                              // pack of this wave multiplied first
         ops.load_slots(p + 2 * KW, m0);
         ops.issue_b(m1, R1);
         __builtin_amdgcn_sched_barrier(0);
@@ -318,29 +319,29 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
 }
 
 // Pipeline for the sparse classes (L = 2, 4), whose row buffers are small: four-slot rings.
-// While pair h is multiplied, the loads in flight are the B rows and block values of pairs
-// h+1..h+3 and the slot tables of pairs h+4..h+6 (pair x has its slot table requested at step
-// x-6, its B rows and values at step x-3) -- about three pairs per wave in flight.  The loop
-// body is four steps without an exit; steps past the wave's last pair multiply zeros.
+// While pack h is multiplied, the loads in flight are the B rows and block values of packs
+// h+1..h+3 and the slot tables of packs h+4..h+6 (pack x has its slot table requested at step
+// x-6, its B rows and values at step x-3) -- about three packs per wave in flight.  The loop
+// body is four steps without an exit; steps past the wave's last pack multiply zeros.
 template <int NT, int KW, int L, int NCH, bool BF16>
 __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, f32x4 (&acc)[NCH * NT])
 {
-    using Ops = PairOps<NT, L, NCH, BF16>;
+    using Ops = PackOps<NT, L, NCH, BF16>;
     static_assert(L <= 4, "the deep ring is meant for the sparse classes");
-    if (w.ks >= w.npairs) return;
+    if (w.ks >= w.npacks) return;
     const Ops ops(w, rsrc);
-    const int count = (w.npairs - w.ks + KW - 1) / KW;     // pairs of this wave
+    const int count = (w.npacks - w.ks + KW - 1) / KW;     // packs of this wave
     const int iters = (count + 3) >> 2;
     uint32_t R[4][L][NCH][Ops::ND];
     u32x4 a[4];
     uint32_t m[4][L];
     int level[4];
     const int p0 = w.ks;
-    auto pair_of = [&](int h) { return p0 + h * KW; };     // h-th pair of this wave
+    auto pack_of = [&](int h) { return p0 + h * KW; };     // h-th pack of this wave
     // prologue = steps -6 .. -1 of the loop without their multiplies
 #pragma unroll
     for (int h = 0; h < 3; ++h) {
-        ops.load_slots(pair_of(h), m[h]);
+        ops.load_slots(pack_of(h), m[h]);
         __builtin_amdgcn_sched_barrier(0);
     }
 #pragma unroll
@@ -348,9 +349,9 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
         uint32_t mh[L];
 #pragma unroll
         for (int x = 0; x < L; ++x) mh[x] = m[h][x];
-        ops.load_slots(pair_of(h + 3), m[(h + 3) & 3]);
+        ops.load_slots(pack_of(h + 3), m[(h + 3) & 3]);
         __builtin_amdgcn_sched_barrier(0);
-        a[h] = ops.load_a(pair_of(h), h < count);
+        a[h] = ops.load_a(pack_of(h), h < count);
         level[h] = ops.issue_b(mh, R[h]);
         __builtin_amdgcn_sched_barrier(0);
     }
@@ -358,15 +359,15 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
     for (int it = 0; it < iters; ++it) {
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
-            const int h = h0 + u;                          // pair of this wave multiplied in this step
-            // the table of pair h+6 takes the ring slot of pair h+2, whose B rows went out a step
+            const int h = h0 + u;                          // pack of this wave multiplied in this step
+            // the table of pack h+6 takes the ring slot of pack h+2, whose B rows went out a step
             // ago; it is requested first: a later step waits for it and should wait for nothing younger
             uint32_t mh[L];
 #pragma unroll
             for (int x = 0; x < L; ++x) mh[x] = m[(u + 3) & 3][x];
-            ops.load_slots(pair_of(h + 6), m[(u + 2) & 3]);
+            ops.load_slots(pack_of(h + 6), m[(u + 2) & 3]);
             __builtin_amdgcn_sched_barrier(0);
-            a[(u + 3) & 3] = ops.load_a(pair_of(h + 3), h + 3 < count);
+            a[(u + 3) & 3] = ops.load_a(pack_of(h + 3), h + 3 < count);
             level[(u + 3) & 3] = ops.issue_b(mh, R[(u + 3) & 3]);
             __builtin_amdgcn_sched_barrier(0);
             ops.multiply(a[u], R[u], level[u], acc);
@@ -389,16 +390,15 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     const int ks = wave % KW;                      // which share of the block row
     const int sl = wave / KW;                      // which column slab of the group
     const int i = lane & 15, g = lane >> 4;
-    const int entry = d.order[blockIdx.x];         // block row and its class (2 top bits used)
-    const int br = entry & 0x0FFFFFFF;
-    const int cls = entry >> 28;                   // 0: L = 2, 1: L = 4, 2: L = 8
+    const i32x4 rec = reinterpret_cast<const i32x4*>(d.work)[blockIdx.x];   // one record of the launch table
+    const int br = rec[0] & 0x0FFFFFFF;
+    const int cls = rec[0] >> 28;                  // 0: L = 2, 1: L = 4, 2: L = 8
     const int n0 = (blockIdx.y * SW + sl) * WC;
-    const int start = d.row_ptr[br], end = d.row_ptr[br + 1];
 
     RowWalk w;
-    w.slots = d.slots + static_cast<size_t>(d.slots_off[br]) * 8;     // offsets count 32-byte units
-    w.vals = d.vals + static_cast<size_t>(d.slots_off[br]) * 128;      // 256 bytes of values per unit
-    w.npairs = n0 < N ? (end - start) >> 1 : 0;    // block rows are padded to an even count
+    w.slots = d.slots + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * 8;      // 32 bytes of slot table per unit
+    w.vals = d.vals + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * 128;      // 256 bytes of values per unit
+    w.npacks = n0 < N ? rec[1] : 0;
     w.ks = ks;
     w.g = g;
     w.lane = lane;
@@ -519,7 +519,7 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float
     // Block values that are read once per launch (a single group per block row) and are too many
     // to stay in the 256 MB Infinity Cache between launches are streamed past the L2, which
     // then keeps the rows of B.
-    const int stream_hint = (grid.y == 1 && SW == 1 && static_cast<double>(d.n_e) * 512.0 > 200e6) ? 1 : 0;
+    const int stream_hint = (grid.y == 1 && SW == 1 && static_cast<double>(d.stream_bytes) > 200e6) ? 1 : 0;
     hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, BF16>), grid, dim3(KW * SW * 64), 0, stream,
                        d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());
@@ -540,7 +540,7 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* 
     // a group take neighbouring slabs of the same block row, so its block values reach HBM once
     // per group; KW waves share one block row (partial tiles summed through LDS).  Splitting a
     // row costs a pipeline fill and a reduction per extra wave, so KW is the smallest split for
-    // which (a) the longest row, walked at about 0.25 us per pair and wave, stays below half of
+    // which (a) the longest row, walked at about 0.25 us per pack and wave, stays below half of
     // what the launch needs at ~5 TB/s, and (b) the launch has at least two waves for every
     // SIMD of the chip.
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
@@ -548,11 +548,11 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* 
     const int64_t wave_slabs = (slabs + nch - 1) / nch;
     const int sw = wave_slabs >= 2 ? 2 : 1;
     const int64_t groups = d.n_order * ((wave_slabs + sw - 1) / sw);
-    const double stream_us = (static_cast<double>(d.n_e) * 512.0 + static_cast<double>(d.M) * N * 4.0 +
+    const double stream_us = (static_cast<double>(d.stream_bytes) + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * 2.0) / 5.0e6;
-    const double longest_us = static_cast<double>(d.max_row_blocks) * 0.5 * 0.25;
+    const double longest_us = static_cast<double>(d.max_row_packs) * 0.25;
     int kw = 1;
-    while (kw < 8 && d.mean_row_blocks >= 8.0 * kw &&
+    while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
            (longest_us / kw > 0.5 * stream_us || groups * sw * kw < 2048)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \

@@ -37,7 +37,7 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
 }
 
 template <bool BF16>
-__device__ __forceinline__ f32x4 mfma_pair(u32x4 a, u32x4 b, f32x4 c)
+__device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 {
     if constexpr (BF16)
         return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
@@ -181,7 +181,7 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                             b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
 #pragma unroll
                         for (int r = 0; r < RM; ++r)
-                            acc[r][c * NT + x] = mfma_pair<BF16>(a[u][r], b, acc[r][c * NT + x]);
+                            acc[r][c * NT + x] = mfma_pack<BF16>(a[u][r], b, acc[r][c * NT + x]);
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }

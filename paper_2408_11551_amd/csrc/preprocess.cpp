@@ -260,34 +260,40 @@ void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out)
         }
     }
 
-    // Work order.  Workgroups are handed to the eight XCDs of the chip round-robin (workgroup w
-    // runs on XCD w mod 8), and every XCD has its own L2.
-    //  * Block rows of similar length (longest <= 1.25 x mean): position w gets a row from the
+}
+
+void work_order(const std::vector<int32_t>& cost_ptr, std::vector<int32_t>& order)
+{
+    // Workgroups are handed to the eight XCDs of the chip round-robin (workgroup w runs on XCD
+    // w mod 8), and every XCD has its own L2.
+    //  * Block rows of similar cost (longest <= 1.25 x mean): position w gets a row from the
     //    (w mod 8)-th of eight contiguous ranges of block rows, so that each XCD walks a contiguous
     //    part of the matrix and neighbouring block rows, which tend to touch the same rows of B
     //    (band and mesh matrices), share that XCD's L2.
     //  * Otherwise: longest block rows first, so that the tail of a launch is made of short
     //    ones; the round-robin then gives every XCD the same mix of lengths.
-    out.order.resize(out.nbr);
+    const int64_t nbr = static_cast<int64_t>(cost_ptr.size()) - 1;
+    order.resize(static_cast<size_t>(nbr > 0 ? nbr : 0));
+    if (nbr <= 0) return;
     int64_t longest = 0;
-    for (int64_t br = 0; br < out.nbr; ++br)
-        longest = std::max<int64_t>(longest, out.row_ptr[br + 1] - out.row_ptr[br]);
-    const bool even_rows = out.nbr > 0 && 4 * longest * out.nbr <= 5 * static_cast<int64_t>(out.col_idx.size());
+    for (int64_t br = 0; br < nbr; ++br)
+        longest = std::max<int64_t>(longest, cost_ptr[br + 1] - cost_ptr[br]);
+    const bool even_rows = 4 * longest * nbr <= 5 * static_cast<int64_t>(cost_ptr[nbr]);
     if (even_rows) {
         constexpr int kXcds = 8;
         int64_t begin[kXcds + 1];
-        for (int x = 0; x <= kXcds; ++x) begin[x] = out.nbr * x / kXcds;
+        for (int x = 0; x <= kXcds; ++x) begin[x] = nbr * x / kXcds;
         int64_t next[kXcds];
         for (int x = 0; x < kXcds; ++x) next[x] = begin[x];
-        for (int64_t w = 0; w < out.nbr; ++w) {
+        for (int64_t w = 0; w < nbr; ++w) {
             int x = static_cast<int>(w % kXcds);
             while (next[x] >= begin[x + 1]) x = (x + 1) % kXcds;     // that range is used up: take the next one
-            out.order[w] = static_cast<int32_t>(next[x]++);
+            order[w] = static_cast<int32_t>(next[x]++);
         }
     } else {
-        std::iota(out.order.begin(), out.order.end(), 0);
-        std::stable_sort(out.order.begin(), out.order.end(), [&](int32_t x, int32_t y) {
-            return (out.row_ptr[x + 1] - out.row_ptr[x]) > (out.row_ptr[y + 1] - out.row_ptr[y]);
+        std::iota(order.begin(), order.end(), 0);
+        std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+            return (cost_ptr[x + 1] - cost_ptr[x]) > (cost_ptr[y + 1] - cost_ptr[y]);
         });
     }
 }

@@ -24,7 +24,6 @@ struct Bcsr {
     std::vector<int32_t> row_ptr;    // [nbr+1]
     std::vector<int32_t> col_idx;    // [n_e]
     std::vector<uint16_t> col_mask;  // [n_e] bit c set iff column c of the block holds a stored entry
-    std::vector<int32_t> order;      // [nbr] block rows in launch order (see build_bcsr)
     int64_t n_blocks = 0, n_blocks_identity = 0;
     bool used_identity = true;
     int64_t n_clusters = 0;
@@ -45,8 +44,12 @@ int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_
 int64_t count_blocks(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr,
                      const std::vector<int32_t>& pat_idx, const int32_t* perm);
 
-// Full pipeline: patterns -> (optional) clustering -> guard -> BCSR structure, masks, work order.
+// Full pipeline: patterns -> (optional) clustering -> guard -> BCSR structure and column masks.
 void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out);
+
+// Launch order of the block rows, given their cost as a row_ptr-like prefix array
+// (cost of row br = cost_ptr[br+1] - cost_ptr[br]).
+void work_order(const std::vector<int32_t>& cost_ptr, std::vector<int32_t>& order);
 
 // Canonical block values (row-major 16x16 per block, zero filled) for export.
 void fill_canonical_vals(const Csr& a, const Bcsr& b, uint16_t* vals);
