@@ -3,12 +3,14 @@
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--config uniform]
 
-A step is one smat_spmm call (C = A.B on the preprocessed, device-resident BCSR matrix);
-the one-time preprocessing and the device bind are timed separately and reported in
-`config`, never folded into the step time (the paper also times the kernel only, section
+A step is one smat_spmm call (C = A.B on the preprocessed, device-resident matrix); the
+one-time preprocessing and the device bind are timed separately and reported in `config`,
+never folded into the step time (the paper also times the kernel only, section
 Methodology).  Prints ONE JSON line: useful TFLOP/s = 2*nnz*N / t, the roofline of the
-SpMM kernel (algorithmic HBM bytes per launch / average launch duration from HIP events
-on the launch stream, against 8 TB/s) and the CPU oracle timed on the host cores.
+SpMM kernel (bytes one launch has to move between HBM and the chip / average launch
+duration from HIP events on the launch stream, against 8 TB/s; for a block-dense matrix
+the matrix-unit flops against 2.5 PFLOP/s instead) and the CPU oracle timed on the host
+cores.
 """
 from __future__ import annotations
 
@@ -34,11 +36,20 @@ WORKLOAD_TEXT = {
 
 # HBM-side bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after a 256 MiB calibration copy), or None
-MEASURED_TRAFFIC_BYTES = {"uniform": 164.1e6, "powerlaw": 2782e6, "hidden_blocks": 910e6}
+MEASURED_TRAFFIC_BYTES = {}
 
 
-def algorithmic_bytes(n_e, nbr, M, K, N):
-    """BCSR values + block columns, rowPtr and perm read once, B read once, C written once."""
+def algorithmic_bytes(layout, K, N, M):
+    """What one launch must move: the device copy of A (values of every pack, tables) read
+    once, B read once, C written once.  Rows of B gathered again and again come from the
+    caches and are reported separately."""
+    return layout["value_bytes"] + layout["table_bytes"] + K * N * 2 + M * N * 4
+
+
+def bcsr_format_bytes(n_e, nbr, M, K, N):
+    """The same count for the paper's BCSR as it stands (512 B of values and a 4-byte column
+    per stored block, rowPtr, perm), for comparison: the packs leave out the columns of a block
+    that hold nothing."""
     return n_e * (512 + 4) + (nbr + 1) * 4 + M * 4 + K * N * 2 + M * N * 4
 
 
@@ -71,6 +82,7 @@ def main():
     h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
     t_pre = time.perf_counter() - t0
     info = S.smat_get_info(h)
+    layout = S.smat_get_layout_info(h)
     ws = torch.empty(S.smat_device_bytes(h), dtype=torch.uint8, device=dev)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
@@ -108,8 +120,24 @@ def main():
     kernel_ms = ev_ms / args.steps                 # average launch duration on the stream
     useful_flop = 2.0 * w.nnz * w.N
     stored_flop = 2.0 * info["n_blocks"] * 256 * w.N
-    bytes_alg = algorithmic_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N)
+    issued_flop = 2.0 * layout["n_packs"] * 16 * 32 * (-(-w.N // 16) * 16)      # one MFMA 16x16x32 per pack and 16 columns
+    bytes_alg = algorithmic_bytes(layout, w.K, w.N, w.M)
+    bytes_bcsr = bcsr_format_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N)
     achieved_gbs = bytes_alg / (kernel_ms * 1e-3) / 1e9
+    issued_tflops = issued_flop / (kernel_ms * 1e-3) / 1e12
+    # the roofline that binds: time at peak for the bytes against time at peak for the flops
+    mfma_bound = issued_flop / (MFMA_PEAK_TFLOPS * 1e12) > bytes_alg / (HBM_PEAK_GBS * 1e9)
+
+    # the paper's protocol (Methodology): one warm-up, ten timed launches, each between its own events
+    evs = []
+    for _ in range(10):
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        S.smat_spmm(h, B, C, w.N, stream)
+        b.record(stream)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    single = np.array([a.elapsed_time(b) for a, b in evs])
 
     rp, _, _ = S.smat_export_bcsr(h, with_vals=False)
     per_row = np.diff(rp)
@@ -176,14 +204,24 @@ def main():
             "preprocess_s": t_pre, "bind_s": t_bind, "kernel": kernel_name, "cache": "hot (back-to-back launches)",
         },
         "stored_block_tflops": stored_flop / (kernel_ms * 1e-3) / 1e12,
-        "mfma_frac_stored_blocks": stored_flop / (kernel_ms * 1e-3) / 1e12 / MFMA_PEAK_TFLOPS,
         "kernel_ms_events": kernel_ms,
-        "roofline": {
+        "single_launch_ms": {"mean": float(single.mean()), "median": float(np.median(single)),
+                             "min": float(single.min()), "cv": float(single.std() / single.mean())},
+        "roofline": ({
+            "bound": "mfma", "achieved": issued_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
+            "frac": issued_tflops / MFMA_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "flops_issued": issued_flop, "kernel": kernel_name,
+        } if mfma_bound else {
             "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
             "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
             "bytes_algorithmic": bytes_alg, "kernel": kernel_name,
-        },
+        }),
+        "layout": {"n_packs": layout["n_packs"], "value_bytes": layout["value_bytes"],
+                   "table_bytes": layout["table_bytes"], "occupied_columns": layout["n_columns"],
+                   "b_gather_bytes": layout["n_columns"] * w.N * 2,
+                   "mfma_issued_tflops": issued_tflops, "hbm_gbs": achieved_gbs,
+                   "bcsr_format_bytes": bytes_bcsr, "bcsr_format_gbs": bytes_bcsr / (kernel_ms * 1e-3) / 1e9},
         "cpu_baseline": cpu,
     }
     out.update(extra)

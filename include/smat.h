@@ -102,10 +102,26 @@ smat_status_t smat_export_bcsr(const smat_handle_t *h, int32_t *row_ptr, int32_t
 /* Bytes of device workspace smat_bind_device needs for this handle. */
 smat_status_t smat_device_bytes(const smat_handle_t *h, size_t *bytes);
 
+/* What one multiplication has to read from the device copy of the matrix (host
+ * counts, known after smat_preprocess).  The device copy groups the consecutive
+ * stored blocks of a block row into "packs" of at most 32 occupied columns (a
+ * column of a block is occupied when it holds a stored entry); one matrix
+ * instruction per 16 output columns multiplies a pack, and columns that hold
+ * nothing are neither stored nor fetched from B.  Two full blocks make a pack.
+ *   n_packs       packs of the whole matrix
+ *   value_bytes   bytes of block values over all packs
+ *   table_bytes   bytes of the per-pack tables naming the rows of B, plus the
+ *                 launch table and the row permutation
+ *   n_columns     occupied columns over all stored blocks (each needs one row
+ *                 of B per output tile)
+ * Any out pointer may be NULL. */
+smat_status_t smat_get_layout_info(const smat_handle_t *h, int64_t *n_packs, int64_t *value_bytes,
+                                   int64_t *table_bytes, int64_t *n_columns);
+
 /*
  * Copies the preprocessed matrix into caller-owned device memory and builds the
- * device-side block values there (the kernel's own block layout, a per-block
- * column-occupancy mask, and a longest-first work order of the block rows).
+ * device-side block values there (the kernel's own layout: packs of blocks, the
+ * table of B rows per pack, and a launch table of the block rows).
  *
  *   dev_workspace  DEVICE, 256-byte aligned, at least smat_device_bytes() bytes,
  *                  must stay alive and untouched until smat_destroy

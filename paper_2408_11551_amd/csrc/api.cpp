@@ -131,7 +131,7 @@ void plan_dense_tiles(smat_handle& h)
         int64_t occupied = 0;
         for (int32_t k = lo; k < hi; ++k) occupied += __builtin_popcount(b.col_mask[k]);
         const int64_t n_uni = static_cast<int64_t>(uni.size()), n_blk = hi - lo;
-        if (n_uni < 8 || n_blk * 2 < 16 * n_uni || occupied < 8 * n_blk) continue;
+        if (n_uni < 8 || n_blk * 20 < 7 * 16 * n_uni || occupied < 8 * n_blk) continue;
         const int64_t steps = (n_uni + 1) / 2;
         if (steps * 16 >= (int64_t{1} << 21) || h.dense_slots + static_cast<uint64_t>(steps) * 16 >= (uint64_t{1} << 31)) continue;
         h.dense_super.push_back(static_cast<int32_t>(s));
@@ -290,6 +290,21 @@ smat_status_t smat_get_info(const smat_handle_t* h, int64_t* n_block_rows, int64
     if (n_blocks) *n_blocks = h->bcsr.n_blocks;
     if (n_blocks_identity) *n_blocks_identity = h->bcsr.n_blocks_identity;
     if (used_identity) *used_identity = h->bcsr.used_identity ? 1 : 0;
+    return SMAT_OK;
+}
+
+smat_status_t smat_get_layout_info(const smat_handle_t* h, int64_t* n_packs, int64_t* value_bytes,
+                                   int64_t* table_bytes, int64_t* n_columns)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (n_packs) *n_packs = static_cast<int64_t>(h->pack_first.size()) - 1;
+    if (value_bytes) *value_bytes = static_cast<int64_t>(h->slots_units) * 256;
+    if (table_bytes) *table_bytes = static_cast<int64_t>(h->slots_units) * 32 + h->bcsr.nbr * (16 + 16 * 4);
+    if (n_columns) {
+        int64_t cols = 0;
+        for (uint16_t m : h->bcsr.col_mask) cols += __builtin_popcount(m);
+        *n_columns = cols;
+    }
     return SMAT_OK;
 }
 

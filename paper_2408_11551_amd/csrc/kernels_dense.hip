@@ -14,6 +14,8 @@
 // block rows of a super row so that the panel of B is read once for all of them.
 #include <hip/hip_runtime.h>
 
+#include <cstdio>
+
 #include "kernels.h"
 
 namespace smat {
@@ -51,8 +53,13 @@ __device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 // 4w..4w+3 of the super row.  With gridDim.z = 2 two workgroups share a tile: each walks half
 // of the steps and adds its result to C with atomics (C zeroed before; the sum of two addends
 // does not depend on their order, so the result stays reproducible).
-template <bool BF16>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(1, 1)))
+//
+// RING is the depth of the prefetch (see below).  The deep variant (4) needs more than 256
+// registers and runs one workgroup per compute unit; the shallow one (2) fits two, which pays
+// for super rows of few steps, where the start and the write of C of one workgroup overlap
+// the loop of the other.
+template <bool BF16, int RING>
+__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RING > 2 ? 1 : 2, RING > 2 ? 1 : 2)))
 void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, uint32_t b_bytes,
                        uint32_t ldb_bytes, float* __restrict__ C, int64_t ldc, int N, int vec_store)
 {
@@ -142,7 +149,6 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     // without an exit; steps past the last one read zeros as block values).  While step s is
     // multiplied, the B panels and block values of the next RING-1 steps are on their way from
     // memory; the panel of step s+1 is copied into the other LDS buffer at the end of step s.
-    constexpr int RING = 4;
     if (nq > 0) {
         u32x4 stage[RING][NS];
         u32x4 a[RING][RM];
@@ -220,12 +226,12 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     }
 }
 
-template <bool BF16>
+template <bool BF16, int RING>
 static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
                               float* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
 {
     dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_dense_kernel<BF16>), grid, dim3(256), 0, s, d, t, B, b_bytes,
+    hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING>), grid, dim3(256), 0, s, d, t, B, b_bytes,
                        static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
 }
 
@@ -297,12 +303,16 @@ int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const
     const int ks = (tiles <= 128 && t.mean_steps >= 16.0) ? 2 : 1;
     if (ks > 1)
         hipLaunchKernelGGL(dense_zero_kernel, dim3(static_cast<unsigned>(t.n)), dim3(1024), 0, s, d, t, C, ldc, static_cast<int>(N));
+    const bool deep = t.mean_steps >= 32.0;
+    static thread_local char name[40];
+    snprintf(name, sizeof(name), "spmm_dense_%s_r%dk%d", bf16 ? "bf16" : "f16", deep ? 4 : 2, ks);
+    *variant = name;
     if (bf16) {
-        *variant = ks > 1 ? "spmm_dense_bf16_k2" : "spmm_dense_bf16_k1";
-        launch_dense_tile<true>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<true, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<true, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     } else {
-        *variant = ks > 1 ? "spmm_dense_f16_k2" : "spmm_dense_f16_k1";
-        launch_dense_tile<false>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<false, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<false, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     }
     return static_cast<int>(hipGetLastError());
 }

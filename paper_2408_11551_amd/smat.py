@@ -48,6 +48,8 @@ def _load():
     lib.smat_preprocess.restype = ctypes.c_int
     lib.smat_preprocess.argtypes = [i64, i64, vp, vp, vp, ctypes.c_int, ctypes.POINTER(_Options),
                                     ctypes.POINTER(vp)]
+    lib.smat_get_layout_info.restype = ctypes.c_int
+    lib.smat_get_layout_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 4
     lib.smat_get_info.restype = ctypes.c_int
     lib.smat_get_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
                                   ctypes.POINTER(ctypes.c_int)]
@@ -131,6 +133,12 @@ def smat_get_info(h) -> dict:
     _check(_lib.smat_get_info(h, ctypes.byref(nbr), ctypes.byref(n_e), ctypes.byref(n_id), ctypes.byref(used)))
     return {"n_block_rows": nbr.value, "n_blocks": n_e.value, "n_blocks_identity": n_id.value,
             "used_identity": bool(used.value)}
+
+
+def smat_get_layout_info(h) -> dict:
+    n_packs, vb, tb, nc = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int64()
+    _check(_lib.smat_get_layout_info(h, ctypes.byref(n_packs), ctypes.byref(vb), ctypes.byref(tb), ctypes.byref(nc)))
+    return {"n_packs": n_packs.value, "value_bytes": vb.value, "table_bytes": tb.value, "n_columns": nc.value}
 
 
 def smat_export_perm(h, M) -> np.ndarray:

@@ -130,3 +130,46 @@ def test_spmm_without_bind_is_an_error_not_a_fallback():
 
 def test_default_options():
     assert S.smat_default_options() == {"block_h": 16, "block_w": 16, "reorder": 1, "tau_permille": 700}
+
+
+def _greedy_packs(w, perm):
+    """Packs per block row, written out from the definition: walk the stored blocks of a block
+    row from the left and close a pack when the next block's occupied columns would not fit
+    32 any more.  Returns (n_packs, value_bytes, n_columns)."""
+    inv = np.empty(w.M, dtype=np.int64)
+    inv[perm] = np.arange(w.M)
+    rows_new = inv[np.repeat(np.arange(w.M), np.diff(w.row_ptr))]
+    key = np.unique((rows_new // 16) * w.K + w.col_idx)               # occupied (block row, column)
+    n_packs = value_bytes = 0
+    for br in range(-(-w.M // 16)):
+        cols = key[(key >= br * w.K) & (key < (br + 1) * w.K)] - br * w.K
+        per_block = np.unique(cols // 16, return_counts=True)[1]
+        packs, fill = [], 0
+        for c in per_block:
+            if not packs or fill + c > 32:
+                packs.append(0)
+                fill = 0
+            fill += int(c)
+            packs[-1] = fill
+        n_packs += len(packs)
+        if packs:
+            L = 2 if max(packs) <= 8 else 4 if max(packs) <= 16 else 8
+            value_bytes += len(packs) * 128 * L
+    return n_packs, value_bytes, int(key.size)
+
+
+def test_layout_info_matches_the_pack_definition():
+    cases = [random_csr(100, 300, 1, 0.004, seed=1), random_csr(64, 64, 1, 0.5, seed=2),
+             random_csr(130, 333, 1, 0.05, seed=3), band_csr(256, 8, 1, seed=4, p=0.5),
+             random_csr(48, 1000, 1, 0.02, seed=5), random_csr(33, 20, 1, 0.0, seed=6)]
+    for w in cases:
+        h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+        try:
+            perm = S.smat_export_perm(h, w.M)
+            info = S.smat_get_layout_info(h)
+            n_packs, value_bytes, n_columns = _greedy_packs(w, perm)
+            assert (info["n_packs"], info["value_bytes"], info["n_columns"]) == (n_packs, value_bytes, n_columns)
+            assert info["table_bytes"] == value_bytes // 8 + 80 * -(-w.M // 16)
+            assert 32 * info["n_packs"] >= n_columns
+        finally:
+            S.smat_destroy(h)
