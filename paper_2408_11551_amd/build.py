@@ -18,8 +18,10 @@ SOURCES = {
     # MFMA results live in ordinary VGPRs (one wave per SIMD leaves room for 256 of them)
     # instead of being shuffled between the two register files
     "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    # the 256-column tile: 256 accumulators per lane, in the accumulation registers (default)
+    "kernels_dense_wide.hip": [],
 }
-HEADERS = ["kernels.h", "preprocess.h", "pair_layout.h", os.path.join("..", "..", "include", "smat.h")]
+HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "dense_kernel.inc.h", os.path.join("..", "..", "include", "smat.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -7,7 +7,6 @@
 #include <hip/hip_runtime.h>
 
 #include <cstdio>
-#include <cstdlib>
 
 #include "pack_layout.h"
 
@@ -556,7 +555,6 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* 
     while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
            (longest_us / kw > 0.5 * stream_us || groups * sw * kw < 2048)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
-    if (const char* t = getenv("SMAT_TUNE_KW")) kw = atoi(t);   // TUNING ONLY
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \
         *variant = variant_name(BF16, KW_, SW_, NCH_, LMAX);                                    \

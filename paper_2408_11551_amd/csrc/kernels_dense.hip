@@ -12,228 +12,11 @@
 // This is still the paper's scheme (Implementation section, Alg. 1): per output tile, loop over
 // stored blocks and multiply-accumulate on the matrix units; the loop is merely shared by the
 // block rows of a super row so that the panel of B is read once for all of them.
-#include <hip/hip_runtime.h>
-
 #include <cstdio>
 
-#include "kernels.h"
+#include "dense_kernel.inc.h"
 
 namespace smat {
-
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-
-namespace {
-
-constexpr uint32_t kOutOfRange = 0x80000000u;
-constexpr int kRsrcFlags = 0x00020000;
-
-__device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
-{
-    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
-    return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), static_cast<uint32_t>(v[2]), static_cast<uint32_t>(v[3])};
-}
-
-template <bool BF16>
-__device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
-{
-    if constexpr (BF16)
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-}
-
-}  // namespace
-
-// C rows of the dense super rows, 128 columns per workgroup; 4 waves, wave w owns block rows
-// 4w..4w+3 of the super row.  With gridDim.z = 2 two workgroups share a tile: each walks half
-// of the steps and adds its result to C with atomics (C zeroed before; the sum of two addends
-// does not depend on their order, so the result stays reproducible).
-//
-// RING is the depth of the prefetch (see below).  The deep variant (4) needs more than 256
-// registers and runs one workgroup per compute unit; the shallow one (2) fits two, which pays
-// for super rows of few steps, where the start and the write of C of one workgroup overlap
-// the loop of the other.
-template <bool BF16, int RING>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(RING > 2 ? 1 : 2, RING > 2 ? 1 : 2)))
-void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, uint32_t b_bytes,
-                       uint32_t ldb_bytes, float* __restrict__ C, int64_t ldc, int N, int vec_store)
-{
-    constexpr int NCH = 1;                         // 128-column chunks per workgroup
-    constexpr int NT = 8;                          // columns per lane; 16 lanes cover a 128-column chunk
-    constexpr int RM = 4;                          // block rows per wave
-    constexpr int NS = 2 * NCH;                    // 16-byte pieces of the panel a thread stages per step
-    __shared__ u32x4 panel[2][32][16 * NCH];       // two buffers of 32 B rows x (128 * NCH) halves
-
-    const int tid = threadIdx.x;
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int i = lane & 15, g = lane >> 4;
-    const int sidx = blockIdx.x;
-    const int super = t.super_rows[sidx];
-    const int n0 = blockIdx.y * (128 * NCH);
-    const int q_first = t.step_ptr[sidx], q_last = t.step_ptr[sidx + 1];
-    const int ks = static_cast<int>(gridDim.z);
-    const int per = (q_last - q_first + ks - 1) / ks;
-    const int q0 = q_first + static_cast<int>(blockIdx.z) * per;
-    const int q1 = q0 + per < q_last ? q0 + per : q_last;
-    const int nq = q1 > q0 ? q1 - q0 : 0;
-
-    const __amdgpu_buffer_rsrc_t b_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
-    // tile values of this workgroup's steps q0..q1-1 are stored back to back
-    const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
-    const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
-    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(t.vals) + static_cast<size_t>(first_slot) * 512, 0,
-        static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
-
-    // staging of the B panel: thread tid copies, per chunk, 16 bytes of rows (tid >> 4) and 16 + (tid >> 4)
-    const int st_row = tid >> 4, st_chunk = tid & 15;
-    uint32_t st_off[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int st_col = n0 + 128 * c + NT * st_chunk;
-        st_off[c] = st_col < N ? static_cast<uint32_t>(st_col) * 2u : kOutOfRange;
-    }
-    const uint32_t no_row = static_cast<uint32_t>(d.K);
-    const int nbc = static_cast<int>((d.K + 15) >> 4);
-
-    auto load_panel = [&](int q, u32x4 (&stage)[NS]) {
-        const int c0 = t.step_cols[2 * static_cast<size_t>(q)], c1 = t.step_cols[2 * static_cast<size_t>(q) + 1];
-        // rows past K (ragged last block column, or no second column) are out of range: zeros
-        uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
-        uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
-        row0 = row0 < no_row ? row0 : no_row;
-        row1 = row1 < no_row ? row1 : no_row;
-        const uint32_t off0 = __umul24(row0, ldb_bytes), off1 = __umul24(row1, ldb_bytes);
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            stage[2 * c] = buf_load16(b_rsrc, off0 + st_off[c], 0u);
-            stage[2 * c + 1] = buf_load16(b_rsrc, off1 + st_off[c], 0u);
-        }
-    };
-    auto store_panel = [&](int buf, const u32x4 (&stage)[NS]) {
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            panel[buf][st_row][16 * c + st_chunk] = stage[2 * c];
-            panel[buf][16 + st_row][16 * c + st_chunk] = stage[2 * c + 1];
-        }
-    };
-    // Values of the wave's four block rows for step q.  A block row without data in the step
-    // (or any block row in a step past the last one, `live` false) reads out of range (zeros)
-    // and multiplies zeros: no branches in the loop body.
-    auto load_a = [&](int q, bool live, u32x4 (&a)[RM]) {
-        const uint32_t rows = t.step_rows[q];
-        const uint32_t base = t.step_base[q] - first_slot;
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const int j = RM * wave + r;
-            const uint32_t slot = base + __popc(rows & ((1u << j) - 1u));
-            const uint32_t absent = (live && (rows >> j & 1u)) ? 0u : kOutOfRange;      // wave-uniform
-            a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
-        }
-    };
-
-    f32x4 acc[RM][NCH * NT];
-#pragma unroll
-    for (int r = 0; r < RM; ++r)
-#pragma unroll
-        for (int x = 0; x < NCH * NT; ++x) acc[r][x] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-    // Software pipeline with register rings of RING slots (no copies; the loop body is RING steps
-    // without an exit; steps past the last one read zeros as block values).  While step s is
-    // multiplied, the B panels and block values of the next RING-1 steps are on their way from
-    // memory; the panel of step s+1 is copied into the other LDS buffer at the end of step s.
-    if (nq > 0) {
-        u32x4 stage[RING][NS];
-        u32x4 a[RING][RM];
-        auto step_of = [&](int s) { return q0 + (s < nq ? s : nq - 1); };   // clamped: a cache hit, unused
-        // prologue: steps 0..RING-2 requested, panel of step 0 in LDS
-#pragma unroll
-        for (int h = 0; h < RING - 1; ++h) {
-            load_panel(step_of(h), stage[h]);
-            load_a(step_of(h), h < nq, a[h]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        store_panel(0, stage[0]);
-        __syncthreads();
-        const int iters = (nq + RING - 1) / RING;
-        int s0 = 0;
-        for (int it = 0; it < iters; ++it) {
-#pragma unroll
-            for (int u = 0; u < RING; ++u) {
-                const int s = s0 + u;
-                const int buf = u & 1;
-                load_panel(step_of(s + RING - 1), stage[(u + RING - 1) % RING]);
-                load_a(step_of(s + RING - 1), s + RING - 1 < nq, a[(u + RING - 1) % RING]);
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    // B rows of this lane's k range: row 8g + kk, columns 128c + 8i .. 128c + 8i+7
-                    u32x4 R[8];
-#pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][16 * c + i];
-                    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                    for (int x = 0; x < NT; ++x) {
-                        const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
-                        u32x4 b;
-#pragma unroll
-                        for (int qd = 0; qd < 4; ++qd)
-                            b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
-#pragma unroll
-                        for (int r = 0; r < RM; ++r)
-                            acc[r][c * NT + x] = mfma_pack<BF16>(a[u][r], b, acc[r][c * NT + x]);
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                store_panel(buf ^ 1, stage[(u + 1) % RING]);
-                __syncthreads();
-            }
-            s0 += RING;
-        }
-    }
-
-    // acc[r][c*8 + x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 128c + 8i + x]
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int col0 = n0 + 128 * c + NT * i;
-        if (col0 >= N) continue;
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const int64_t br = static_cast<int64_t>(super) * 16 + RM * wave + r;
-#pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                const int64_t out_row = d.perm[br * 16 + 4 * g + y];
-                if (out_row < 0) continue;
-                float* dst = C + out_row * ldc + col0;
-                if (ks > 1) {
-#pragma unroll
-                    for (int x = 0; x < NT; ++x) atomicAdd(dst + x, acc[r][c * NT + x][y]);
-                } else if (vec_store) {
-                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[r][c * NT][y], acc[r][c * NT + 1][y], acc[r][c * NT + 2][y], acc[r][c * NT + 3][y]};
-                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[r][c * NT + 4][y], acc[r][c * NT + 5][y], acc[r][c * NT + 6][y], acc[r][c * NT + 7][y]};
-                } else {
-#pragma unroll
-                    for (int x = 0; x < NT; ++x) dst[x] = acc[r][c * NT + x][y];
-                }
-            }
-        }
-    }
-}
-
-template <bool BF16, int RING>
-static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
-                              float* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
-{
-    dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING>), grid, dim3(256), 0, s, d, t, B, b_bytes,
-                       static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
-}
 
 // Scatter of the CSR values into the tile layout: one thread per row of a dense super row.
 // A tile step q holds, for every block row of the super row that has one of the step's two
@@ -279,17 +62,9 @@ int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* c
     return static_cast<int>(hipGetLastError());
 }
 
-// Sets the C rows of the dense super rows to zero (used before a launch whose workgroups
-// add their share of the k range with atomics).
-__global__ void dense_zero_kernel(DeviceBcsr d, DenseTiles t, float* __restrict__ C, int64_t ldc, int N)
-{
-    const int64_t first = static_cast<int64_t>(t.super_rows[blockIdx.x]) * 256;
-    for (int rr = threadIdx.x >> 6; rr < 256; rr += blockDim.x >> 6) {
-        const int64_t out_row = d.perm[first + rr];
-        if (out_row < 0) continue;
-        for (int c = threadIdx.x & 63; c < N; c += 64) C[out_row * ldc + c] = 0.f;
-    }
-}
+// 256-column tiles, compiled in kernels_dense_wide.hip
+void launch_dense_wide(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, uint32_t b_bytes,
+                       int64_t ldb, float* C, int64_t ldc, int64_t N, int vec_store, void* stream);
 
 int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
                       float* C, int64_t ldc, int64_t N, void* stream, const char** variant)
@@ -298,21 +73,24 @@ int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const
     const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * 2) : 0u;
     const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
     hipStream_t s = static_cast<hipStream_t>(stream);
-    // Too few tiles to give every compute unit one: two workgroups per tile, each half of the steps.
-    const int64_t tiles = static_cast<int64_t>(t.n) * ((N + 127) / 128);
-    const int ks = (tiles <= 128 && t.mean_steps >= 16.0) ? 2 : 1;
-    if (ks > 1)
-        hipLaunchKernelGGL(dense_zero_kernel, dim3(static_cast<unsigned>(t.n)), dim3(1024), 0, s, d, t, C, ldc, static_cast<int>(N));
+    // Tile width: 256 columns when the super rows are long (the loop, not its start and end,
+    // is what counts) and there are enough wide tiles for every compute unit; the wide tile
+    // moves a third fewer bytes per matrix instruction (measured: 9 % faster at N = 4096,
+    // slower at N = 2048 where it leaves half of the chip idle).
     const bool deep = t.mean_steps >= 32.0;
+    const bool wide = deep && static_cast<int64_t>(t.n) * ((N + 255) / 256) >= 240;
     static thread_local char name[40];
-    snprintf(name, sizeof(name), "spmm_dense_%s_r%dk%d", bf16 ? "bf16" : "f16", deep ? 4 : 2, ks);
+    if (wide) snprintf(name, sizeof(name), "spmm_dense_%s_w", bf16 ? "bf16" : "f16");
+    else snprintf(name, sizeof(name), "spmm_dense_%s_r%d", bf16 ? "bf16" : "f16", deep ? 4 : 2);
     *variant = name;
-    if (bf16) {
-        if (deep) launch_dense_tile<true, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<true, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    if (wide) {
+        launch_dense_wide(d, t, bf16, B, b_bytes, ldb, C, ldc, N, vec_store, stream);
+    } else if (bf16) {
+        if (deep) launch_dense_tile<true, 4>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<true, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     } else {
-        if (deep) launch_dense_tile<false, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<false, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<false, 4>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<false, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     }
     return static_cast<int>(hipGetLastError());
 }

@@ -100,24 +100,26 @@ def test_small_shapes_all_load_widths(shape, oracle_c):
 
 
 DENSE_SHAPES = [
-    # M, K, N, density, dtype: at least one complete super row of sixteen block rows with
-    # well-filled blocks, so the block-dense path runs (alone or next to the per-row kernel)
-    (256, 128, 128, 0.5, "f16"),
-    (512, 256, 136, 0.15, "bf16"),
-    (272, 130, 8, 0.3, "f16"),
-    (1024, 512, 264, 0.12, "f16"),
-    (300, 700, 64, 0.2, "bf16"),
+    # M, K, N, density, dtype, variant of the dense kernel: at least one complete super row of
+    # sixteen block rows with well-filled blocks, so the block-dense path runs (alone or next to
+    # the per-row kernel).  r2/r4: 128-column tiles with shallow/deep prefetch, w: 256-column tiles
+    (256, 128, 128, 0.5, "f16", "r2"),
+    (512, 256, 136, 0.15, "bf16", "r2"),
+    (272, 130, 8, 0.3, "f16", "r2"),
+    (1024, 512, 264, 0.12, "f16", "r2"),
+    (300, 700, 64, 0.2, "bf16", "r2"),
+    (256, 1040, 136, 0.1, "f16", "r4"),
+    (512, 1100, 264, 0.12, "bf16", "r4"),
+    (512, 1100, 30728, 0.12, "f16", "w"),
 ]
 
 
 @pytest.mark.parametrize("shape", DENSE_SHAPES, ids=lambda s: "x".join(map(str, s)))
 def test_block_dense_path(shape, oracle_c):
-    M, K, N, density, dtype = shape
+    M, K, N, density, dtype, kind = shape
     w = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, b_dist="normal")
     m, _ = _run(w, oracle_c, ldb=N + 8, ldc=N + 4)
-    assert S.smat_last_kernel().startswith("spmm_dense"), S.smat_last_kernel()
-    # few tiles and long super rows: two workgroups per tile, added with atomics onto zeroed C
-    assert S.smat_last_kernel().split("+")[0].endswith("k2") == (K >= 512), S.smat_last_kernel()
+    assert S.smat_last_kernel().split("+")[0] == f"spmm_dense_{dtype}_{kind}", S.smat_last_kernel()
     # integer-valued copy: exact, so a misplaced value or B row cannot hide in the tolerance
     wi = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, values="smallint", b_dist="smallint")
     mi = S.SmatMatrix(wi.M, wi.K, wi.row_ptr, wi.col_idx, wi.a_bits, wi.dtype)
