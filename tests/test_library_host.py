@@ -9,7 +9,7 @@ import pytest
 
 import paper_2408_11551_amd as S
 from oracle import smat_ref as R
-from workloads import random_csr, band_csr, make_config
+from workloads import OCCUPANCY_SPEC, occupancy_csr, random_csr, band_csr, make_config
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -173,3 +173,20 @@ def test_layout_info_matches_the_pack_definition():
             assert 32 * info["n_packs"] >= n_columns
         finally:
             S.smat_destroy(h)
+
+
+def test_layout_info_on_prescribed_occupancies():
+    w = occupancy_csr(OCCUPANCY_SPEC, K=16 * 64 + 5, N=1, seed=11)
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=0)
+    try:
+        perm = S.smat_export_perm(h, w.M)
+        assert np.array_equal(perm, np.arange(w.M))
+        info = S.smat_get_layout_info(h)
+        n_packs, value_bytes, n_columns = _greedy_packs(w, perm)
+        assert (info["n_packs"], info["value_bytes"], info["n_columns"]) == (n_packs, value_bytes, n_columns)
+        # by hand: 3 + 2 + 1 + 2 + 1 + 1 + 0 + 1 + 1 + 4 packs (row 1: 11+11 | 11+10+1; row 9: ten
+        # blocks of three columns per pack); classes 8, 8, 8, 8, 2, 4, -, 2, 8, 8
+        assert n_packs == 16
+        assert value_bytes == 1024 * (3 + 2 + 1 + 2 + 1 + 4) + 256 * (1 + 1) + 512 * 1
+    finally:
+        S.smat_destroy(h)

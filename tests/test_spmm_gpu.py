@@ -17,7 +17,7 @@ torch = pytest.importorskip("torch")
 
 import paper_2408_11551_amd as S            # noqa: E402
 from oracle import smat_ref as R            # noqa: E402
-from workloads import random_csr, band_csr, make_config, Workload  # noqa: E402
+from workloads import random_csr, band_csr, occupancy_csr, OCCUPANCY_SPEC, make_config, Workload  # noqa: E402
 
 REL_BAR = 1e-2        # stated tolerance
 REL_TIGHT = 2e-4      # derived from fp32 accumulation, see module docstring
@@ -133,6 +133,38 @@ def test_block_dense_path(shape, oracle_c):
     assert not S.smat_last_kernel().startswith("spmm_dense")
     for x in (m, mi, m2):
         x.close()
+
+
+@pytest.mark.parametrize("N", [8, 40, 128, 272])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
+    # block rows with prescribed occupied columns per block: packs of 16+16, a third block that
+    # does not fit, 32 and 33 single columns, one row per class, an empty row, a ragged last
+    # block column -- all three loops of the per-row kernel run in one launch; integer values,
+    # so the result is exact and a column in the wrong slot cannot hide
+    w = occupancy_csr(OCCUPANCY_SPEC, K=16 * 64 + 5, N=N, seed=11 + N, dtype=dtype)
+    for reorder in (0, 1):
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder)
+        c = m.spmm(_dev_b(w))
+        torch.cuda.synchronize()
+        c_ref, _ = _oracle_c(oracle_c, w)
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+        assert S.smat_last_kernel().endswith("_l8")
+        perm = S.smat_export_perm(m.handle, w.M)
+        _, _, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+        assert np.array_equal(S.smat_export_device_vals(m.handle), v)
+        m.close()
+    # the same rows without the class-8 ones: the kernel that carries only the sparse loops
+    sparse_rows = [OCCUPANCY_SPEC[4], OCCUPANCY_SPEC[5], [], OCCUPANCY_SPEC[7], [(2, 3), (9, 5)]]
+    for spec, suffix in ((sparse_rows, "_l4"), ([sparse_rows[0], [], sparse_rows[3]], "_l2")):
+        w2 = occupancy_csr(spec, K=16 * 64 + 5, N=N, seed=5 + N, dtype=dtype)
+        m = S.SmatMatrix(w2.M, w2.K, w2.row_ptr, w2.col_idx, w2.a_bits, w2.dtype, reorder=0)
+        c = m.spmm(_dev_b(w2))
+        torch.cuda.synchronize()
+        c_ref, _ = _oracle_c(oracle_c, w2)
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+        assert S.smat_last_kernel().endswith(suffix), S.smat_last_kernel()
+        m.close()
 
 
 def test_small_integers_are_exact(oracle_c):

@@ -10,6 +10,8 @@ from .configs import (  # noqa: F401
     make_config,
     random_csr,
     band_csr,
+    occupancy_csr,
+    OCCUPANCY_SPEC,
     dense_from_bits,
     to_bits,
     from_bits,

@@ -140,6 +140,52 @@ def band_csr(M: int, b: int, N: int, seed: int, p: float = 1.0, dtype: str = F16
                     to_bits(v, dtype), _dense_b(rng, M, N, b_dist, dtype))
 
 
+# block rows whose blocks have a prescribed number of occupied columns: pack boundaries
+# (16+16, 11+11 then a third that does not fit, 32 single columns, 33), one block row per row
+# class (<= 8, <= 16, <= 32 occupied columns in its fullest pack), an empty block row, a
+# ragged last block column
+OCCUPANCY_SPEC = [
+    [(0, 16), (1, 16), (2, 16), (5, 16), (9, 16)],
+    [(0, 11), (3, 11), (4, 11), (7, 10), (8, 1)],
+    [(c, 1) for c in range(0, 64, 2)],
+    [(c, 1) for c in range(0, 66, 2)],
+    [(3, 2), (10, 3), (40, 3)],
+    [(1, 5), (2, 4), (60, 7)],
+    [],
+    [(0, 1)],
+    [(62, 9), (63, 8), (64, 3)],
+    [(c, 3) for c in range(20, 52)],
+]
+
+
+def occupancy_csr(spec, K: int, N: int, seed: int, dtype: str = F16, b_dist: str = "smallint",
+                  name: str | None = None) -> Workload:
+    """Matrix with a prescribed number of occupied columns per 16 x 16 block.
+
+    spec[r] is a list of (block column, number of occupied columns) for block row r (16 rows);
+    every occupied column (chosen at random inside its block) gets a stored entry in a random
+    non-empty subset of the 16 rows.  Values are small integers.  Serves the tests of how blocks
+    with few occupied columns are grouped on the device.
+    """
+    rng = np.random.default_rng([seed, 3000, len(spec), K])
+    M = 16 * len(spec)
+    keys = []
+    for r, blocks in enumerate(spec):
+        for bc, ncols in blocks:
+            width = min(16, K - 16 * bc)
+            cols = 16 * bc + np.sort(rng.choice(width, size=min(ncols, width), replace=False))
+            for c in cols:
+                rows = np.nonzero(rng.random(16) < 0.4)[0]
+                if rows.size == 0:
+                    rows = rng.integers(0, 16, size=1)
+                keys.extend((16 * r + rows).astype(np.int64) * K + int(c))
+    keys = np.unique(np.asarray(keys, dtype=np.int64))
+    row_ptr, col_idx = _csr_from_keys(keys, M, K)
+    v = rng.integers(1, 5, size=keys.size) * rng.choice([-1.0, 1.0], size=keys.size)
+    return Workload(name or f"occupancy_{M}x{K}", dtype, M, K, N, row_ptr, col_idx,
+                    to_bits(v, dtype), _dense_b(rng, K, N, b_dist, dtype))
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations
 # --------------------------------------------------------------------------
