@@ -55,9 +55,13 @@ typedef struct {
     int tau_permille;   /* merge threshold of the clustering in 1/1000, 0..1000: a row w
                            joins a cluster with column union pc iff
                            1 - |w n pc| / |w u pc| < tau_permille / 1000                 */
+    int dense_tiles;    /* block-dense regions (sixteen block rows sharing most of their
+                           block columns) have a kernel of their own that stages panels of
+                           B in LDS: 0 = take it where an estimate says it is faster,
+                           1 = take it wherever it applies, -1 = never                    */
 } smat_options_t;
 
-/* Default options: 16 x 16 blocks, reordering on, tau = 0.7. */
+/* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0. */
 void smat_default_options(smat_options_t *opt);
 
 /*

@@ -6,6 +6,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cmath>
 #include <cstdio>
 #include <cstring>
 #include <new>
@@ -21,6 +22,7 @@ struct smat_handle {
     smat::Csr csr;
     smat::Bcsr bcsr;
     smat_dtype_t dtype = SMAT_F16;
+    int dense_mode = 0;                  // option dense_tiles
     bool bound = false;
     // Packs (pack_layout.h): every block row is cut, from the left, into runs of consecutive
     // blocks that hold at most 32 occupied columns together; a pack is what one matrix
@@ -44,6 +46,7 @@ struct smat_handle {
     std::vector<uint32_t> step_rows, step_base;
     std::vector<uint8_t> row_dense;      // [nbr]
     uint64_t dense_slots = 0;
+    int64_t dense_columns = 0;           // occupied columns over the blocks of the dense super rows
     smat::DeviceBcsr dev;                // launch over every block row
     smat::DeviceBcsr dev_rest;           // launch over the block rows the dense path does not cover
     smat::DenseTiles tiles;
@@ -110,17 +113,19 @@ Layout make_layout(const smat_handle& h)
     return l;
 }
 
-// Decides which complete super rows (sixteen block rows) go to the dense path and lays out
+// Decides which complete super rows (sixteen block rows) may go to the dense path and lays out
 // their steps.  A super row qualifies when walking the union of its block columns wastes
-// little: at least 8 union columns, at least half of the (block row, union column) grid
-// stored (a band of 37 % fill measured slower here than on the per-row kernel), and blocks whose columns are mostly occupied (>= 8 of 16 on average; blocks with a
+// little: at least 8 union columns, at least 35 % of the (block row, union column) grid
+// stored, and blocks whose columns are mostly occupied (>= 8 of 16 on average; blocks with a
 // few occupied columns are cheaper on the per-row path, which fetches only those rows of B).
+// With the option dense_tiles = -1 nothing qualifies.
 void plan_dense_tiles(smat_handle& h)
 {
     const smat::Bcsr& b = h.bcsr;
     const int64_t nbr = b.nbr;
     h.row_dense.assign(static_cast<size_t>(nbr), 0);
     h.step_ptr.assign(1, 0);
+    if (h.dense_mode < 0) return;
     std::vector<int32_t> uni;
     for (int64_t s = 0; (s + 1) * 16 <= nbr; ++s) {
         const int32_t lo = b.row_ptr[s * 16], hi = b.row_ptr[s * 16 + 16];
@@ -135,6 +140,7 @@ void plan_dense_tiles(smat_handle& h)
         const int64_t steps = (n_uni + 1) / 2;
         if (steps * 16 >= (int64_t{1} << 21) || h.dense_slots + static_cast<uint64_t>(steps) * 16 >= (uint64_t{1} << 31)) continue;
         h.dense_super.push_back(static_cast<int32_t>(s));
+        h.dense_columns += occupied;
         for (int j = 0; j < 16; ++j) h.row_dense[static_cast<size_t>(s * 16 + j)] = 1;
         for (int64_t q = 0; q < steps; ++q) {
             const int32_t c0 = uni[2 * q], c1 = 2 * q + 1 < n_uni ? uni[2 * q + 1] : 0x7FFFFFFF;
@@ -229,6 +235,7 @@ void smat_default_options(smat_options_t* opt)
     opt->block_w = 16;
     opt->reorder = 1;
     opt->tau_permille = 700;
+    opt->dense_tiles = 0;
 }
 
 smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, const int32_t* col_idx,
@@ -246,6 +253,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (o.block_h != 16 || o.block_w != 16) return fail(SMAT_ERR_UNSUPPORTED, "only 16x16 blocks are supported");
         if (o.reorder != 0 && o.reorder != 1) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0 or 1");
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
+        if (o.dense_tiles < -1 || o.dense_tiles > 1) return fail(SMAT_ERR_INVALID_ARG, "dense_tiles must be -1, 0 or 1");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
         if ((M + 15) / 16 >= (int64_t{1} << 28)) return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
@@ -260,6 +268,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
 
         smat_handle* h = new smat_handle();
         h->dtype = dtype;
+        h->dense_mode = o.dense_tiles;
         h->csr.M = M;
         h->csr.K = K;
         h->csr.row_ptr.assign(row_ptr, row_ptr + M + 1);
@@ -519,9 +528,20 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
         return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
     if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
     // The dense path needs 16-byte rows of B at 8-column granularity; otherwise every block row
-    // goes through the per-row kernel.
+    // goes through the per-row kernel.  It also has to pay: a tile walks its steps at about
+    // 0.7 us each with little to overlap them, so few tiles leave most of the chip idle, while
+    // the per-row kernel fetches every occupied column's row of B again for every block row but
+    // spreads that over all compute units (about 10 TB/s of L1 fills).  Both estimates are
+    // measured rates; the faster path is taken.
     const bool bf16 = h->dtype == SMAT_BF16;
-    const bool use_tiles = h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
+    bool use_tiles = h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
+    if (h->dense_mode < 0) use_tiles = false;
+    if (use_tiles && h->dense_mode == 0) {
+        const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
+        const double t_tiles = std::ceil(tiles / 256.0) * (h->tiles.mean_steps * 0.7 + 4.0);
+        const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
+        use_tiles = t_tiles <= t_rows;
+    }
     const char* variant = "";
     thread_local std::string name;
     int e = 0;

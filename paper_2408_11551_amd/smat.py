@@ -30,7 +30,7 @@ class SmatError(RuntimeError):
 
 class _Options(ctypes.Structure):
     _fields_ = [("block_h", ctypes.c_int), ("block_w", ctypes.c_int),
-                ("reorder", ctypes.c_int), ("tau_permille", ctypes.c_int)]
+                ("reorder", ctypes.c_int), ("tau_permille", ctypes.c_int), ("dense_tiles", ctypes.c_int)]
 
 
 def lib_path() -> str:
@@ -107,11 +107,12 @@ def smat_last_kernel() -> str:
 def smat_default_options() -> dict:
     o = _Options()
     _lib.smat_default_options(ctypes.byref(o))
-    return {"block_h": o.block_h, "block_w": o.block_w, "reorder": o.reorder, "tau_permille": o.tau_permille}
+    return {"block_h": o.block_h, "block_w": o.block_w, "reorder": o.reorder, "tau_permille": o.tau_permille,
+            "dense_tiles": o.dense_tiles}
 
 
 def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
-                    block_h=16, block_w=16) -> int:
+                    block_h=16, block_w=16, dense_tiles=0) -> int:
     """row_ptr int64[M+1], col_idx int32[nnz], vals_bits uint16[nnz] (HOST) -> opaque handle."""
     rp, rp_p = _host(row_ptr, np.int64)
     ci, ci_p = _host(col_idx, np.int32)
@@ -121,7 +122,7 @@ def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_
     nnz = int(rp[-1]) if rp.size else 0
     if ci.size < nnz or vb.size < nnz:
         raise ValueError("col_idx / vals shorter than row_ptr[M]")
-    opt = _Options(block_h, block_w, reorder, tau_permille)
+    opt = _Options(block_h, block_w, reorder, tau_permille, dense_tiles)
     out = ctypes.c_void_p()
     _check(_lib.smat_preprocess(M, K, rp_p, ci_p, vb_p, _DTYPES.get(dtype, dtype), ctypes.byref(opt), ctypes.byref(out)))
     return out.value
@@ -199,10 +200,10 @@ class SmatMatrix:
     """Owns a handle and the torch workspace tensor it is bound to (memory plumbing only)."""
 
     def __init__(self, M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
-                 device="cuda:0", bind=True):
+                 dense_tiles=0, device="cuda:0", bind=True):
         self.M, self.K, self.dtype = M, K, dtype
         self.handle = smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype,
-                                      reorder=reorder, tau_permille=tau_permille)
+                                      reorder=reorder, tau_permille=tau_permille, dense_tiles=dense_tiles)
         self.workspace = None
         self.info = smat_get_info(self.handle)
         if bind:

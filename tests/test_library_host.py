@@ -129,7 +129,8 @@ def test_spmm_without_bind_is_an_error_not_a_fallback():
 
 
 def test_default_options():
-    assert S.smat_default_options() == {"block_h": 16, "block_w": 16, "reorder": 1, "tau_permille": 700}
+    assert S.smat_default_options() == {"block_h": 16, "block_w": 16, "reorder": 1, "tau_permille": 700,
+                                        "dense_tiles": 0}
 
 
 def _greedy_packs(w, perm):

@@ -48,8 +48,9 @@ def _check_c(got, c_ref, s_ref, w):
     assert np.all(got[empty] == 0.0)
 
 
-def _run(w, oracle_c, reorder=1, tau=700, ldb=None, ldc=None, poison=True):
-    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder, tau_permille=tau)
+def _run(w, oracle_c, reorder=1, tau=700, ldb=None, ldc=None, poison=True, dense_tiles=0):
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder, tau_permille=tau,
+                     dense_tiles=dense_tiles)
     try:
         b = _dev_b(w, ldb)
         ldc = ldc or w.N
@@ -118,20 +119,26 @@ DENSE_SHAPES = [
 def test_block_dense_path(shape, oracle_c):
     M, K, N, density, dtype, kind = shape
     w = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, b_dist="normal")
-    m, _ = _run(w, oracle_c, ldb=N + 8, ldc=N + 4)
+    m, _ = _run(w, oracle_c, ldb=N + 8, ldc=N + 4, dense_tiles=1)
     assert S.smat_last_kernel().split("+")[0] == f"spmm_dense_{dtype}_{kind}", S.smat_last_kernel()
     # integer-valued copy: exact, so a misplaced value or B row cannot hide in the tolerance
     wi = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, values="smallint", b_dist="smallint")
-    mi = S.SmatMatrix(wi.M, wi.K, wi.row_ptr, wi.col_idx, wi.a_bits, wi.dtype)
+    mi = S.SmatMatrix(wi.M, wi.K, wi.row_ptr, wi.col_idx, wi.a_bits, wi.dtype, dense_tiles=1)
     c = mi.spmm(_dev_b(wi))
     torch.cuda.synchronize()
+    assert S.smat_last_kernel().startswith("spmm_dense")
     c_ref, _ = _oracle_c(oracle_c, wi)
     assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
     # a width the dense path does not take (N not a multiple of 8) falls back to the per-row kernel
     w2 = random_csr(M, K, 12, density, seed=M + K, dtype=dtype, b_dist="normal")
-    m2, _ = _run(w2, oracle_c)
+    m2, _ = _run(w2, oracle_c, dense_tiles=1)
     assert not S.smat_last_kernel().startswith("spmm_dense")
-    for x in (m, mi, m2):
+    # switched off, the same matrix goes through the per-row kernel; with the automatic choice
+    # either path must give the result (the choice itself is checked on the full-size workloads)
+    m3, _ = _run(w, oracle_c, dense_tiles=-1)
+    assert not S.smat_last_kernel().startswith("spmm_dense")
+    m4, _ = _run(w, oracle_c, dense_tiles=0)
+    for x in (m, mi, m2, m3, m4):
         x.close()
 
 
@@ -289,6 +296,8 @@ def test_config_full_parity(name, oracle_c):
     _structure_parity_full(w, m, oracle_c)
     if name == "banded":
         assert S.smat_get_info(m.handle)["used_identity"]                        # band => P = I
+    # the automatic choice sends the block-dense workloads to the tile kernel, the others not
+    assert S.smat_last_kernel().startswith("spmm_dense") == (name in ("banded", "pruned_weight"))
     m.close()
 
 

@@ -10,6 +10,7 @@ from .configs import (  # noqa: F401
     make_config,
     random_csr,
     band_csr,
+    band_full_csr,
     occupancy_csr,
     OCCUPANCY_SPEC,
     dense_from_bits,

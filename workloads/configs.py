@@ -140,6 +140,24 @@ def band_csr(M: int, b: int, N: int, seed: int, p: float = 1.0, dtype: str = F16
                     to_bits(v, dtype), _dense_b(rng, M, N, b_dist, dtype))
 
 
+def band_full_csr(M: int, b: int, N: int, seed: int, dtype: str = F16, b_dist: str = "uniform",
+                  name: str | None = None) -> Workload:
+    """Square band matrix with every in-band entry stored (|i-j| <= b), built without sorting so
+    that it stays cheap up to the dense case b >= M-1 (the band experiment of the
+    synthetic-matrix section: 16384 x 16384, b = 64 ... 16384)."""
+    rng = np.random.default_rng([seed, 2500, M, b])
+    i = np.arange(M, dtype=np.int64)
+    first = np.maximum(i - b, 0)
+    last = np.minimum(i + b, M - 1)
+    row_ptr = np.zeros(M + 1, dtype=np.int64)
+    np.cumsum(last - first + 1, out=row_ptr[1:])
+    nnz = int(row_ptr[-1])
+    col_idx = (np.arange(nnz, dtype=np.int64) - np.repeat(row_ptr[:-1] - first, last - first + 1)).astype(np.int32)
+    v = rng.random(nnz, dtype=np.float32) * 2.0 - 1.0
+    return Workload(name or f"bandfull_{M}_b{b}", dtype, M, M, N, row_ptr, col_idx,
+                    to_bits(v, dtype), _dense_b(rng, M, N, b_dist, dtype))
+
+
 # block rows whose blocks have a prescribed number of occupied columns: pack boundaries
 # (16+16, 11+11 then a third that does not fit, 32 single columns, 33), one block row per row
 # class (<= 8, <= 16, <= 32 occupied columns in its fullest pack), an empty block row, a
