@@ -87,8 +87,20 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     const uint32_t no_row = static_cast<uint32_t>(d.K);
     const int nbc = static_cast<int>((d.K + 15) >> 4);
 
-    auto load_panel = [&](int q, u32x4 (&stage)[NS]) {
-        const int c0 = t.step_cols[2 * static_cast<size_t>(q)], c1 = t.step_cols[2 * static_cast<size_t>(q) + 1];
+    // What a step's loads need to know, fetched with scalar loads one step before it is used:
+    // a scalar load that is waited for right away costs a few hundred cycles in which the wave,
+    // alone on its SIMD, does nothing.
+    struct StepMeta { int c0, c1; uint32_t rows, base; };
+    auto fetch_meta = [&](int q) {
+        StepMeta m;
+        m.c0 = t.step_cols[2 * static_cast<size_t>(q)];
+        m.c1 = t.step_cols[2 * static_cast<size_t>(q) + 1];
+        m.rows = t.step_rows[q];
+        m.base = t.step_base[q];
+        return m;
+    };
+    auto load_panel = [&](const StepMeta& m, u32x4 (&stage)[NS]) {
+        const int c0 = m.c0, c1 = m.c1;
         // rows past K (ragged last block column, or no second column) are out of range: zeros
         uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
         uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
@@ -111,9 +123,9 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     // Values of the wave's four block rows for step q.  A block row without data in the step
     // (or any block row in a step past the last one, `live` false) reads out of range (zeros)
     // and multiplies zeros: no branches in the loop body.
-    auto load_a = [&](int q, bool live, u32x4 (&a)[RM]) {
-        const uint32_t rows = t.step_rows[q];
-        const uint32_t base = t.step_base[q] - first_slot;
+    auto load_a = [&](const StepMeta& m, bool live, u32x4 (&a)[RM]) {
+        const uint32_t rows = m.rows;
+        const uint32_t base = m.base - first_slot;
 #pragma unroll
         for (int r = 0; r < RM; ++r) {
             const int j = RM * wave + r;
@@ -141,15 +153,18 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
             u32x4 stage[NS];
             u32x4 a_cur[RM], a_next[RM];
             auto step_of = [&](int s) { return q0 + (s < nq ? s : nq - 1); };
-            load_panel(step_of(0), stage);
-            load_a(step_of(0), true, a_cur);
+            StepMeta meta = fetch_meta(step_of(0));
+            load_panel(meta, stage);
+            load_a(meta, true, a_cur);
+            meta = fetch_meta(step_of(1));
             __builtin_amdgcn_sched_barrier(0);
             store_panel(0, stage);
             __syncthreads();
             int buf = 0;
             for (int s = 0; s < nq; ++s) {
-                load_panel(step_of(s + 1), stage);
-                load_a(step_of(s + 1), s + 1 < nq, a_next);
+                load_panel(meta, stage);
+                load_a(meta, s + 1 < nq, a_next);
+                meta = fetch_meta(step_of(s + 2));
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     u32x4 R[8];
@@ -184,10 +199,12 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
         // prologue: steps 0..RING-2 requested, panel of step 0 in LDS
 #pragma unroll
         for (int h = 0; h < RING - 1; ++h) {
-            load_panel(step_of(h), stage[h]);
-            load_a(step_of(h), h < nq, a[h]);
+            const StepMeta m = fetch_meta(step_of(h));
+            load_panel(m, stage[h]);
+            load_a(m, h < nq, a[h]);
             __builtin_amdgcn_sched_barrier(0);
         }
+        StepMeta meta = fetch_meta(step_of(RING - 1));
         store_panel(0, stage[0]);
         __syncthreads();
         const int iters = (nq + RING - 1) / RING;
@@ -197,8 +214,9 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
             for (int u = 0; u < RING; ++u) {
                 const int s = s0 + u;
                 const int buf = u & 1;
-                load_panel(step_of(s + RING - 1), stage[(u + RING - 1) % RING]);
-                load_a(step_of(s + RING - 1), s + RING - 1 < nq, a[(u + RING - 1) % RING]);
+                load_panel(meta, stage[(u + RING - 1) % RING]);
+                load_a(meta, s + RING - 1 < nq, a[(u + RING - 1) % RING]);
+                meta = fetch_meta(step_of(s + RING));
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     // B rows of this lane's k range: row 8g + kk, columns 128c + 8i .. 128c + 8i+7
