@@ -9,6 +9,7 @@
 #include <cmath>
 #include <cstdio>
 #include <cstring>
+#include <memory>
 #include <new>
 #include <stdexcept>
 #include <string>
@@ -266,7 +267,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         const std::string bad = smat::validate_csr(M, K, row_ptr, col_idx);
         if (!bad.empty()) return fail(SMAT_ERR_BAD_CSR, bad);
 
-        smat_handle* h = new smat_handle();
+        std::unique_ptr<smat_handle> h(new smat_handle());      // freed if anything below throws
         h->dtype = dtype;
         h->dense_mode = o.dense_tiles;
         h->csr.M = M;
@@ -278,11 +279,10 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         try {
             plan_packs(*h);
         } catch (const std::length_error& e) {
-            delete h;
             return fail(SMAT_ERR_UNSUPPORTED, e.what());
         }
         plan_dense_tiles(*h);
-        *out = h;
+        *out = h.release();
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
         return fail(SMAT_ERR_ALLOC, "out of host memory in smat_preprocess");

@@ -525,10 +525,10 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float
     return static_cast<int>(hipGetLastError());
 }
 
-static const char* variant_name(bool bf16, int kw, int sw, int nch, int lmax)
+static const char* variant_name(bool bf16, int nt, int kw, int sw, int nch, int lmax)
 {
     static thread_local char buf[48];
-    snprintf(buf, sizeof(buf), "spmm_%s_k%ds%dc%d_l%d", bf16 ? "bf16" : "f16", kw, sw, nch, lmax);
+    snprintf(buf, sizeof(buf), "spmm_%s_n%dk%ds%dc%d_l%d", bf16 ? "bf16" : "f16", nt, kw, sw, nch, lmax);
     return buf;
 }
 
@@ -557,7 +557,7 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, float* 
     if (nch == 2 && kw > 4) kw = 4;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \
-        *variant = variant_name(BF16, KW_, SW_, NCH_, LMAX);                                    \
+        *variant = variant_name(BF16, NT, KW_, SW_, NCH_, LMAX);                                    \
         return launch_variant<NT, KW_, SW_, NCH_, LMAX, BF16>(d, B, ldb, C, ldc, N, stream);    \
     } while (0)
     if constexpr (NT == 8 && LMAX < 8) {
@@ -598,15 +598,18 @@ template <bool BF16>
 static int launch_dtype(const DeviceBcsr& d, const void* B, int64_t ldb, float* C, int64_t ldc,
                         int64_t N, hipStream_t stream, const char** variant)
 {
-    // B row loads are 2*NT bytes wide: among the widths N, ldb and the base address allow,
-    // take the one that pads N the least (ties: the wider load).
+    // B row loads are 2*NT bytes wide and a wave covers 16*NT columns per pass over its packs.
+    // Among the widths N, ldb and the base address allow, take the one with the least
+    // (passes x cost of a pass); the relative cost of a pass, 1 : 1.05 : 1.4 : 1.65 for
+    // NT = 1, 2, 4, 8, was measured on two workloads at N = 8 ... 1000 (ties: the wider load).
     const uintptr_t addr = reinterpret_cast<uintptr_t>(B);
+    const double pass_cost[9] = {0, 1.0, 1.05, 0, 1.4, 0, 0, 0, 1.65};
     int best = 1;
-    int64_t best_pad = (N + 15) / 16 * 16;
+    double best_cost = static_cast<double>((N + 15) / 16);
     for (int nt = 2; nt <= 8; nt *= 2) {
         if (N % nt != 0 || ldb % nt != 0 || addr % (2 * nt) != 0) continue;
-        const int64_t pad = (N + 16 * nt - 1) / (16 * nt) * (16 * nt);
-        if (pad <= best_pad) { best = nt; best_pad = pad; }
+        const double cost = static_cast<double>((N + 16 * nt - 1) / (16 * nt)) * pass_cost[nt];
+        if (cost <= best_cost) { best = nt; best_cost = cost; }
     }
     switch (best) {
     case 8: return launch_nt<8, BF16>(d, B, ldb, C, ldc, N, stream, variant);

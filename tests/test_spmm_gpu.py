@@ -89,6 +89,10 @@ def test_small_shapes_all_load_widths(shape, oracle_c):
     M, K, N, density, dtype = shape
     w = random_csr(M, K, N, density, seed=M + K + N, dtype=dtype, b_dist="normal")
     m, _ = _run(w, oracle_c)
+    # the load width (columns per lane) the library picked: all four occur in this list
+    expect_nt = {16: 1, 1: 1, 3: 1, 64: 4, 8: 1, 24: 2, 100: 4, 130: 2, 256: 8, 7: 1}[N]
+    if w.nnz:
+        assert f"_n{expect_nt}k" in S.smat_last_kernel(), S.smat_last_kernel()
     # structure and device-side block values, bit-exact
     pats = R.block_pattern(M, w.row_ptr, w.col_idx)
     perm, n_e, n_id, used = R.choose_perm(pats, 700)
