@@ -152,7 +152,9 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
  *        are used when N, ldb and the base address allow it
  *   stream  hipStream_t; the call only enqueues work (no synchronisation)
  *
- * Concurrent calls on different streams with different dC are allowed.
+ * Calls on DIFFERENT handles may run concurrently on different streams.  Two calls on the
+ * same handle must not overlap in time: the handle's workspace holds the scratch area in
+ * which a launch with few block-dense tiles keeps partial tiles.
  * Limits: the bytes of B that are addressed, ((K-1)*ldb + N)*2, must stay below 2 GiB;
  * ldb < 2^23; N <= 1048560.
  */

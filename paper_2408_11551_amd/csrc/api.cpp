@@ -74,13 +74,16 @@ smat_status_t hip_fail(const char* what, int err)
 }
 
 constexpr size_t kAlign = 256;
+// Partial tiles of dense launches that split a tile's steps over several workgroups: at most
+// 512 partial tiles of 256 x 128 floats are ever in use.
+constexpr size_t kTileScratchBytes = size_t{512} * 256 * 128 * 4;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
     size_t perm, work, work_rest, slots, vals, pack_ptr, slots_off, blk_ptr, blk_col, blk_pack, blk_meta;
     size_t csr_row_ptr, csr_col_idx, csr_vals;
-    size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, total;
+    size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, t_scratch, total;
 };
 
 Layout make_layout(const smat_handle& h)
@@ -110,6 +113,7 @@ Layout make_layout(const smat_handle& h)
     l.t_rows = take(h.step_rows.size() * sizeof(uint32_t));
     l.t_base = take(h.step_base.size() * sizeof(uint32_t));
     l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
+    l.t_scratch = take(h.dense_super.empty() ? 0 : kTileScratchBytes);
     l.total = off ? off : kAlign;
     return l;
 }
@@ -441,6 +445,8 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.step_rows = reinterpret_cast<const uint32_t*>(base + l.t_rows);
         tiles.step_base = reinterpret_cast<const uint32_t*>(base + l.t_base);
         tiles.vals = reinterpret_cast<const uint16_t*>(base + l.t_vals);
+        tiles.scratch = h->dense_super.empty() ? nullptr : reinterpret_cast<float*>(base + l.t_scratch);
+        tiles.scratch_bytes = h->dense_super.empty() ? 0 : kTileScratchBytes;
         tiles.n = static_cast<int32_t>(h->dense_super.size());
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
@@ -538,7 +544,9 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (h->dense_mode < 0) use_tiles = false;
     if (use_tiles && h->dense_mode == 0) {
         const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
-        const double t_tiles = std::ceil(tiles / 256.0) * (h->tiles.mean_steps * 0.7 + 4.0);
+        const int ks = smat::dense_split(h->tiles, N);
+        double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * 0.7 + 4.0);
+        if (ks > 1) t_tiles += 3.0 + tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
         const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
         use_tiles = t_tiles <= t_rows;
     }

@@ -39,9 +39,10 @@ __device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 }  // namespace
 
 // C rows of the dense super rows, 128 columns per workgroup; 4 waves, wave w owns block rows
-// 4w..4w+3 of the super row.  (Splitting the steps of a tile over two workgroups that add
-// their halves with atomics was measured and dropped: the fp32 atomics of a 4096 x 1024 tile
-// set cost three times what the idle compute units would have gained.)
+// 4w..4w+3 of the super row.  With gridDim.z > 1 the steps of a tile are split over that many
+// workgroups; each writes its partial 256 x 128 tile to the scratch area and a second kernel
+// adds the partial tiles in a fixed order (reproducible; fp32 atomics on C were measured at
+// three times the cost of the idle compute units they were meant to fill).
 //
 // RING is the depth of the prefetch (see below).  The deep variant (4) needs more than 256
 // registers and runs one workgroup per compute unit; the shallow one (2) fits two, which pays
@@ -64,7 +65,11 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     const int sidx = blockIdx.x;
     const int super = t.super_rows[sidx];
     const int n0 = blockIdx.y * (128 * NCH);
-    const int q0 = t.step_ptr[sidx], q1 = t.step_ptr[sidx + 1];
+    const int ks = static_cast<int>(gridDim.z);    // workgroups sharing this tile's steps
+    const int q_first = t.step_ptr[sidx], q_last = t.step_ptr[sidx + 1];
+    const int per = (q_last - q_first + ks - 1) / ks;
+    const int q0 = min(q_first + static_cast<int>(blockIdx.z) * per, q_last);
+    const int q1 = min(q0 + per, q_last);
     const int nq = q1 - q0;
 
     const __amdgpu_buffer_rsrc_t b_rsrc =
@@ -245,6 +250,22 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     }
 
     // acc[r][c*8 + x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 128c + 8i + x]
+    if constexpr (NCH == 1) {
+        if (ks > 1) {
+            // partial tile, row-major 256 x 128 floats, at [(tile * ks + z)]
+            const size_t tile = static_cast<size_t>(sidx) * gridDim.y + blockIdx.y;
+            float* part = t.scratch + (tile * ks + blockIdx.z) * (256 * 128);
+#pragma unroll
+            for (int r = 0; r < RM; ++r)
+#pragma unroll
+                for (int y = 0; y < 4; ++y) {
+                    float* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
+                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
+                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
+                }
+            return;
+        }
+    }
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         const int col0 = n0 + 128 * c + NT * i;
@@ -270,10 +291,10 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 }
 
 template <bool BF16, int RING, int NCH = 1>
-static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, const void* B, uint32_t b_bytes, int64_t ldb,
+static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
                               float* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
 {
-    dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 128 * NCH - 1) / (128 * NCH)));
+    dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 128 * NCH - 1) / (128 * NCH)), static_cast<unsigned>(ks));
     hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING, NCH>), grid, dim3(256), 0, s, d, t, B, b_bytes,
                        static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
 }

@@ -45,6 +45,8 @@ struct DenseTiles {
     const uint32_t* step_rows = nullptr;   // [steps] 16-bit mask of block rows present in the step
     const uint32_t* step_base = nullptr;   // [steps] first 1 KiB slot of the step
     const uint16_t* vals = nullptr;        // [512 * slots]
+    float* scratch = nullptr;              // partial tiles of launches that split the steps of a tile
+    size_t scratch_bytes = 0;
     int32_t n = 0;
     double mean_steps = 0;                 // steps per super row, on average
 };
@@ -64,6 +66,9 @@ int launch_spmm(const DeviceBcsr& d, bool bf16, const void* B, int64_t ldb, floa
 // Scatters the CSR values of the dense super rows into the tile layout (vals zeroed before).
 int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,
                       const int32_t* csr_col_idx, const uint16_t* csr_vals, uint16_t* vals_out, void* stream);
+
+// Workgroups per 128-column tile the dense launch would use for this N (1: no split).
+int dense_split(const DenseTiles& t, int64_t N);
 
 // C rows of the dense super rows.  Needs N, ldb multiples of 8 and B aligned to 16 bytes.
 int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,

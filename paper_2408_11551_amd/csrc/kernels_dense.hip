@@ -12,6 +12,7 @@
 // This is still the paper's scheme (Implementation section, Alg. 1): per output tile, loop over
 // stored blocks and multiply-accumulate on the matrix units; the loop is merely shared by the
 // block rows of a super row so that the panel of B is read once for all of them.
+#include <algorithm>
 #include <cstdio>
 
 #include "dense_kernel.inc.h"
@@ -62,6 +63,56 @@ int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* c
     return static_cast<int>(hipGetLastError());
 }
 
+// Adds the ks partial tiles of every (super row, 128-column slab) in the order 0 .. ks-1 and
+// writes the rows to C.  Eight workgroups per tile (32 rows each); a thread sums four groups of
+// four columns and has all its loads in flight at once.
+__global__ __launch_bounds__(256)
+void dense_reduce_kernel(DeviceBcsr d, DenseTiles t, int ks, float* __restrict__ C, int64_t ldc, int N, int vec_store)
+{
+    const int super = t.super_rows[blockIdx.x];
+    const int n0 = blockIdx.y * 128;
+    const size_t tile = static_cast<size_t>(blockIdx.x) * gridDim.y + blockIdx.y;
+    const float* part = t.scratch + tile * ks * (256 * 128);
+    f32x4 v[4];
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int e = static_cast<int>(blockIdx.z) * 1024 + j * 256 + static_cast<int>(threadIdx.x);
+        v[j] = *reinterpret_cast<const f32x4*>(part + e * 4);
+    }
+    for (int z = 1; z < ks; ++z)
+#pragma unroll
+        for (int j = 0; j < 4; ++j) {
+            const int e = static_cast<int>(blockIdx.z) * 1024 + j * 256 + static_cast<int>(threadIdx.x);
+            v[j] += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(z) * (256 * 128) + e * 4);
+        }
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+        const int e = static_cast<int>(blockIdx.z) * 1024 + j * 256 + static_cast<int>(threadIdx.x);
+        const int row = e >> 5, c = (e & 31) * 4;
+        const int64_t out_row = d.perm[static_cast<int64_t>(super) * 256 + row];
+        if (out_row < 0 || n0 + c >= N) continue;             // N is a multiple of 8 on this path
+        float* dst = C + out_row * ldc + n0 + c;
+        if (vec_store) {
+            *reinterpret_cast<f32x4*>(dst) = v[j];
+        } else {
+            dst[0] = v[j][0]; dst[1] = v[j][1]; dst[2] = v[j][2]; dst[3] = v[j][3];
+        }
+    }
+}
+
+// How many workgroups share the steps of a 128-column tile: as many as fit the 256 compute
+// units in one round, as long as each keeps at least eight steps and the partial tiles fit the
+// scratch area.
+int dense_split(const DenseTiles& t, int64_t N)
+{
+    const int64_t tiles = static_cast<int64_t>(t.n) * ((N + 127) / 128);
+    if (tiles <= 0 || tiles > 128 || t.scratch == nullptr) return 1;
+    int64_t ks = std::min<int64_t>(8, 256 / tiles);
+    ks = std::min<int64_t>(ks, static_cast<int64_t>(t.mean_steps / 8.0));
+    ks = std::min<int64_t>(ks, static_cast<int64_t>(t.scratch_bytes / (static_cast<size_t>(tiles) * 256 * 128 * 4)));
+    return ks < 2 ? 1 : static_cast<int>(ks);
+}
+
 // 256-column tiles, compiled in kernels_dense_wide.hip
 void launch_dense_wide(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, uint32_t b_bytes,
                        int64_t ldb, float* C, int64_t ldc, int64_t N, int vec_store, void* stream);
@@ -79,19 +130,24 @@ int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const
     // slower at N = 2048 where it leaves half of the chip idle).
     const bool deep = t.mean_steps >= 32.0;
     const bool wide = deep && static_cast<int64_t>(t.n) * ((N + 255) / 256) >= 240;
+    const int ks = wide ? 1 : dense_split(t, N);
     static thread_local char name[40];
     if (wide) snprintf(name, sizeof(name), "spmm_dense_%s_w", bf16 ? "bf16" : "f16");
+    else if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_r%dk%d", bf16 ? "bf16" : "f16", deep ? 4 : 2, ks);
     else snprintf(name, sizeof(name), "spmm_dense_%s_r%d", bf16 ? "bf16" : "f16", deep ? 4 : 2);
     *variant = name;
     if (wide) {
         launch_dense_wide(d, t, bf16, B, b_bytes, ldb, C, ldc, N, vec_store, stream);
     } else if (bf16) {
-        if (deep) launch_dense_tile<true, 4>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<true, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<true, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<true, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     } else {
-        if (deep) launch_dense_tile<false, 4>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<false, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<false, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<false, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     }
+    if (ks > 1)
+        hipLaunchKernelGGL(dense_reduce_kernel, dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8), dim3(256), 0, s,
+                           d, t, ks, C, ldc, static_cast<int>(N), vec_store);
     return static_cast<int>(hipGetLastError());
 }
 

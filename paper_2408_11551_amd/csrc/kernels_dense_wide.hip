@@ -13,8 +13,8 @@ void launch_dense_wide(const DeviceBcsr& d, const DenseTiles& t, bool bf16, cons
                        int64_t ldb, float* C, int64_t ldc, int64_t N, int vec_store, void* stream)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
-    if (bf16) launch_dense_tile<true, 2, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    else launch_dense_tile<false, 2, 2>(d, t, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    if (bf16) launch_dense_tile<true, 2, 2>(d, t, 1, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    else launch_dense_tile<false, 2, 2>(d, t, 1, B, b_bytes, ldb, C, ldc, N, vec_store, s);
 }
 
 }  // namespace smat
