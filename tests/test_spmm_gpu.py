@@ -236,6 +236,43 @@ def test_reorder_modes_agree_and_slabs_are_independent(oracle_c):
     m1.close()
 
 
+def test_graph_capture_and_replay(oracle_c):
+    # smat_spmm only enqueues kernels (no allocation, no memset, no synchronisation), so it can be
+    # captured in a HIP graph; every replay must give the eager result, also on the path that
+    # keeps partial tiles in the workspace (two kernels) and with other work between the replays
+    cases = [(random_csr(300, 500, 72, 0.02, seed=3, dtype="f16", b_dist="normal"), 0),
+             (random_csr(256, 4112, 72, 0.1, seed=4, dtype="bf16", b_dist="normal"), 1)]
+    for w, dense in cases:
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=dense)
+        b = _dev_b(w)
+        eager = m.spmm(b).clone()
+        torch.cuda.synchronize()
+        name = S.smat_last_kernel()
+        c = torch.zeros((w.M, w.N), dtype=torch.float32, device="cuda")
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            S.smat_spmm(m.handle, b, c, w.N)                      # warm-up on the capture stream
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            S.smat_spmm(m.handle, b, c, w.N)
+        assert S.smat_last_kernel() == name
+        for rep in range(4):
+            c.fill_(float("nan"))
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert torch.equal(c, eager), f"replay {rep} of {name}"
+            other = m.spmm(b)                                     # eager work between the replays
+            torch.cuda.synchronize()
+            assert torch.equal(other, eager)
+        c_ref, s_ref = _oracle_c(oracle_c, w)
+        _check_c(eager.cpu().numpy(), c_ref, s_ref, w)
+        m.close()
+
+
 def test_empty_and_degenerate_inputs(oracle_c):
     z = Workload("zero", "f16", 40, 50, 12, np.zeros(41, np.int64), np.zeros(0, np.int32), np.zeros(0, np.uint16),
                  np.ones((50, 12), np.uint16))
