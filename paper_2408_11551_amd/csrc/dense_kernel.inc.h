@@ -48,19 +48,29 @@ __device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 // registers and runs one workgroup per compute unit; the shallow one (2) fits two, which pays
 // for super rows of few steps, where the start and the write of C of one workgroup overlap
 // the loop of the other.
-template <bool BF16, int RING, int NCH>
-__global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu((RING > 2 || NCH > 1) ? 1 : 2, (RING > 2 || NCH > 1) ? 1 : 2)))
+//
+// KG = 2 puts two such groups of four waves into one workgroup: group 0 walks the even steps of
+// the tile, group 1 the odd ones, each with its own panel buffers, and at the end group 1 hands
+// its accumulators to group 0 through LDS.  A SIMD then holds two waves whose LDS reads,
+// barrier waits and matrix instructions overlap, which one wave alone cannot do.
+template <bool BF16, int RING, int NCH, int KG = 1>
+__global__ __launch_bounds__(256 * KG)
+__attribute__((amdgpu_waves_per_eu((KG == 1 && (RING > 2 || NCH > 1)) ? 1 : 2, (KG == 1 && (RING > 2 || NCH > 1)) ? 1 : 2)))
 void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, uint32_t b_bytes,
                        uint32_t ldb_bytes, float* __restrict__ C, int64_t ldc, int N, int vec_store)
 {
     constexpr int NT = 8;                          // columns per lane; 16 lanes cover a 128-column chunk
     constexpr int RM = 4;                          // block rows per wave
     constexpr int NS = 2 * NCH;                    // 16-byte pieces of the panel a thread stages per step
-    __shared__ u32x4 panel[2][32][16 * NCH];       // two buffers of 32 B rows x (128 * NCH) halves
+    static_assert(KG == 1 || (RING <= 3 && NCH == 1), "two wave groups: at most 256 registers, 128 columns");
+    constexpr int NBUF = RING == 3 ? 3 : 2;        // panel buffers; the loop body of RING steps keeps their indices constant
+    __shared__ u32x4 panel_all[KG][NBUF][32][16 * NCH];   // per wave group, buffers of 32 B rows x (128 * NCH) halves
 
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x & 255;             // thread inside its wave group
     const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
+    const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
+    u32x4 (*panel)[32][16 * NCH] = panel_all[kg];
     const int i = lane & 15, g = lane >> 4;
     const int sidx = blockIdx.x;
     const int super = t.super_rows[sidx];
@@ -200,27 +210,29 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     if (nq > 0) {
         u32x4 stage[RING][NS];
         u32x4 a[RING][RM];
-        auto step_of = [&](int s) { return q0 + (s < nq ? s : nq - 1); };   // clamped: a cache hit, unused
+        // step s of this wave group is step kg + KG * s of the tile
+        auto live_step = [&](int s) { return kg + KG * s < nq; };
+        auto step_of = [&](int s) { return q0 + (live_step(s) ? kg + KG * s : nq - 1); };   // clamped: a cache hit, unused
         // prologue: steps 0..RING-2 requested, panel of step 0 in LDS
 #pragma unroll
         for (int h = 0; h < RING - 1; ++h) {
             const StepMeta m = fetch_meta(step_of(h));
             load_panel(m, stage[h]);
-            load_a(m, h < nq, a[h]);
+            load_a(m, live_step(h), a[h]);
             __builtin_amdgcn_sched_barrier(0);
         }
         StepMeta meta = fetch_meta(step_of(RING - 1));
         store_panel(0, stage[0]);
         __syncthreads();
-        const int iters = (nq + RING - 1) / RING;
+        const int iters = ((nq + KG - 1) / KG + RING - 1) / RING;      // the same for both groups: they share the barriers
         int s0 = 0;
         for (int it = 0; it < iters; ++it) {
 #pragma unroll
             for (int u = 0; u < RING; ++u) {
                 const int s = s0 + u;
-                const int buf = u & 1;
+                const int buf = u % NBUF;
                 load_panel(meta, stage[(u + RING - 1) % RING]);
-                load_a(meta, s + RING - 1 < nq, a[(u + RING - 1) % RING]);
+                load_a(meta, live_step(s + RING - 1), a[(u + RING - 1) % RING]);
                 meta = fetch_meta(step_of(s + RING));
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
@@ -242,11 +254,40 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
-                store_panel(buf ^ 1, stage[(u + 1) % RING]);
+                store_panel((u + 1) % NBUF, stage[(u + 1) % RING]);
                 __syncthreads();
             }
             s0 += RING;
         }
+    }
+
+    if constexpr (KG == 2) {
+        // group 1 hands its accumulators to group 0, two block rows per wave at a time (64 KiB)
+        __shared__ float handover[4 * 2 * NT * 4 * 64];
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (kg == 1) {
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                    for (int x = 0; x < NT; ++x)
+#pragma unroll
+                        for (int y = 0; y < 4; ++y)
+                            handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane] = acc[2 * half + rr][x][y];
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                    for (int x = 0; x < NT; ++x)
+#pragma unroll
+                        for (int y = 0; y < 4; ++y)
+                            acc[2 * half + rr][x][y] += handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
+            }
+            __syncthreads();
+        }
+        if (kg == 1) return;
     }
 
     // acc[r][c*8 + x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 128c + 8i + x]
@@ -290,12 +331,12 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     }
 }
 
-template <bool BF16, int RING, int NCH = 1>
+template <bool BF16, int RING, int NCH = 1, int KG = 1>
 static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
                               float* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
 {
     dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 128 * NCH - 1) / (128 * NCH)), static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING, NCH>), grid, dim3(256), 0, s, d, t, B, b_bytes,
+    hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING, NCH, KG>), grid, dim3(256 * KG), 0, s, d, t, B, b_bytes,
                        static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
 }
 

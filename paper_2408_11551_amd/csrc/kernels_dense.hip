@@ -133,16 +133,16 @@ int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const
     const int ks = wide ? 1 : dense_split(t, N);
     static thread_local char name[40];
     if (wide) snprintf(name, sizeof(name), "spmm_dense_%s_w", bf16 ? "bf16" : "f16");
-    else if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_r%dk%d", bf16 ? "bf16" : "f16", deep ? 4 : 2, ks);
-    else snprintf(name, sizeof(name), "spmm_dense_%s_r%d", bf16 ? "bf16" : "f16", deep ? 4 : 2);
+    else if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", bf16 ? "bf16" : "f16", deep ? 2 : 1, ks);
+    else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", bf16 ? "bf16" : "f16", deep ? 2 : 1);
     *variant = name;
     if (wide) {
         launch_dense_wide(d, t, bf16, B, b_bytes, ldb, C, ldc, N, vec_store, stream);
     } else if (bf16) {
-        if (deep) launch_dense_tile<true, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<true, 2, 1, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
         else launch_dense_tile<true, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     } else {
-        if (deep) launch_dense_tile<false, 4>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        if (deep) launch_dense_tile<false, 2, 1, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
         else launch_dense_tile<false, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     }
     if (ks > 1)

@@ -107,16 +107,18 @@ def test_small_shapes_all_load_widths(shape, oracle_c):
 DENSE_SHAPES = [
     # M, K, N, density, dtype, variant of the dense kernel: at least one complete super row of
     # sixteen block rows with well-filled blocks, so the block-dense path runs (alone or next to
-    # the per-row kernel).  r2/r4: 128-column tiles with shallow/deep prefetch, kX: the steps of
-    # a tile split over X workgroups whose partial tiles a second kernel adds, w: 256-column tiles
-    (256, 128, 128, 0.5, "f16", "r2"),
-    (512, 256, 136, 0.15, "bf16", "r2"),
-    (272, 130, 8, 0.3, "f16", "r2"),
-    (1024, 512, 264, 0.12, "f16", "r2k2"),
-    (300, 700, 64, 0.2, "bf16", "r2k2"),
-    (256, 1040, 136, 0.1, "f16", "r4k4"),
-    (512, 1100, 264, 0.12, "bf16", "r4k4"),
-    (256, 4112, 72, 0.1, "bf16", "r4k8"),
+    # the per-row kernel).  g1/g2: 128-column tiles walked by one group of four waves or by two
+    # (even and odd steps), kX: the steps of a tile split over X workgroups whose partial tiles a
+    # second kernel adds, w: 256-column tiles
+    (256, 128, 128, 0.5, "f16", "g1"),
+    (512, 256, 136, 0.15, "bf16", "g1"),
+    (272, 130, 8, 0.3, "f16", "g1"),
+    (1024, 512, 264, 0.12, "f16", "g1k2"),
+    (300, 700, 64, 0.2, "bf16", "g1k2"),
+    (256, 1040, 136, 0.1, "f16", "g2k4"),
+    (512, 1100, 264, 0.12, "bf16", "g2k4"),
+    (256, 4112, 72, 0.1, "bf16", "g2k8"),
+    (256, 1056, 384, 0.1, "f16", "g2k4"),
     (512, 1100, 30728, 0.12, "f16", "w"),
 ]
 
