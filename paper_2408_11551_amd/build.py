@@ -15,13 +15,10 @@ SOURCES = {
     "preprocess.cpp": [],
     "kernels.hip": [],
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
-    # MFMA results live in ordinary VGPRs (one wave per SIMD leaves room for 256 of them)
-    # instead of being shuffled between the two register files
+    # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    # the 256-column tile: 256 accumulators per lane, in the accumulation registers (default)
-    "kernels_dense_wide.hip": [],
 }
-HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "dense_kernel.inc.h", os.path.join("..", "..", "include", "smat.h")]
+HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", os.path.join("..", "..", "include", "smat.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

@@ -109,7 +109,7 @@ DENSE_SHAPES = [
     # sixteen block rows with well-filled blocks, so the block-dense path runs (alone or next to
     # the per-row kernel).  g1/g2: 128-column tiles walked by one group of four waves or by two
     # (even and odd steps), kX: the steps of a tile split over X workgroups whose partial tiles a
-    # second kernel adds, w: 256-column tiles
+    # second kernel adds
     (256, 128, 128, 0.5, "f16", "g1"),
     (512, 256, 136, 0.15, "bf16", "g1"),
     (272, 130, 8, 0.3, "f16", "g1"),
@@ -119,7 +119,7 @@ DENSE_SHAPES = [
     (512, 1100, 264, 0.12, "bf16", "g2k4"),
     (256, 4112, 72, 0.1, "bf16", "g2k8"),
     (256, 1056, 384, 0.1, "f16", "g2k4"),
-    (512, 1100, 30728, 0.12, "f16", "w"),
+    (512, 1100, 16648, 0.12, "f16", "g2"),
 ]
 
 
