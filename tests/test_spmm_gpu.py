@@ -238,6 +238,27 @@ def test_reorder_modes_agree_and_slabs_are_independent(oracle_c):
     m1.close()
 
 
+def test_random_shapes_and_options(oracle_c):
+    # seeded sweep over shapes, densities, dtypes, leading dimensions and option combinations:
+    # whichever kernels the library picks, C must match the oracle
+    rng = np.random.default_rng(20240811)
+    for case in range(48):
+        M = int(rng.integers(1, 700))
+        K = int(rng.integers(1, 900))
+        N = int(rng.choice([1, 2, 5, 8, 16, 24, 40, 64, 72, 100, 128, 136, 200, 264]))
+        density = float(rng.choice([0.001, 0.01, 0.05, 0.2, 0.6]))
+        dtype = "bf16" if rng.random() < 0.5 else "f16"
+        w = random_csr(M, K, N, density, seed=1000 + case, dtype=dtype, b_dist="normal")
+        pad_b, pad_c = int(rng.choice([0, 8, 3])), int(rng.choice([0, 4, 1]))
+        try:
+            m, _ = _run(w, oracle_c, reorder=int(rng.integers(0, 2)), tau=int(rng.choice([300, 700, 1000])),
+                        ldb=N + pad_b, ldc=N + pad_c, dense_tiles=int(rng.integers(-1, 2)))
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: M={M} K={K} N={N} density={density} {dtype} "
+                                 f"kernel={S.smat_last_kernel()}: {e}") from e
+        m.close()
+
+
 def test_graph_capture_and_replay(oracle_c):
     # smat_spmm only enqueues kernels (no allocation, no memset, no synchronisation), so it can be
     # captured in a HIP graph; every replay must give the eager result, also on the path that
