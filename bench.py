@@ -62,6 +62,8 @@ def main():
     ap.add_argument("--config", default="uniform", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--dense-tiles", type=int, default=0, choices=[-1, 0, 1],
+                    help="block-dense tile kernel: 0 automatic (default), 1 wherever it applies, -1 never")
     ap.add_argument("--cold", action="store_true", help="also time launches with the caches flushed in between")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (known traffic, scales the profiler's byte counters)")
@@ -80,7 +82,7 @@ def main():
     w = make_config(args.config, seed=args.seed)
 
     t0 = time.perf_counter()
-    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=args.dense_tiles)
     t_pre = time.perf_counter() - t0
     info = S.smat_get_info(h)
     layout = S.smat_get_layout_info(h)

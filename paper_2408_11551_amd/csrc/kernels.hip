@@ -167,6 +167,16 @@ __device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
         return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
 }
 
+// 16-byte store with the non-temporal hint.  The pointer passes through an empty asm so that
+// the compiler cannot merge this store with the plain one on the other side of a branch (it
+// would drop the hint when it does).
+__device__ __forceinline__ void store_streaming(float* dst, f32x4 v)
+{
+    asm volatile("" : "+v"(dst));
+    typedef __attribute__((address_space(1))) f32x4 global_f32x4;       // C is device memory: a global, not a flat store
+    __builtin_nontemporal_store(v, (global_f32x4*)dst);
+}
+
 // Everything a wave needs to walk its share of a block row.
 struct RowWalk {
     const uint32_t* slots;      // slot table of the row's first pack
@@ -412,7 +422,8 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     }
     w.ldb_bytes = ldb_bytes;
     w.no_row = static_cast<uint32_t>(d.K);
-    w.stream = stream_hint != 0;
+    w.stream = (stream_hint & 1) != 0;
+    const bool c_stream = (stream_hint & 2) != 0;  // C is stored with the non-temporal hint
 
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
@@ -442,9 +453,11 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
                 if constexpr (NT >= 4) {
                     if (vec_store) {
 #pragma unroll
-                        for (int t = 0; t < NT; t += 4)
-                            *reinterpret_cast<f32x4*>(dst + t) =
-                                f32x4{acc[c * NT + t][r], acc[c * NT + t + 1][r], acc[c * NT + t + 2][r], acc[c * NT + t + 3][r]};
+                        for (int t = 0; t < NT; t += 4) {
+                            const f32x4 v = f32x4{acc[c * NT + t][r], acc[c * NT + t + 1][r], acc[c * NT + t + 2][r], acc[c * NT + t + 3][r]};
+                            if (c_stream) store_streaming(dst + t, v);
+                            else *reinterpret_cast<f32x4*>(dst + t) = v;
+                        }
                         continue;
                     }
                 }
@@ -487,7 +500,8 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
                 if (out_row < 0 || col >= N) continue;
                 float* dst = C + out_row * ldc + col;
                 if (vec_store) {
-                    *reinterpret_cast<f32x4*>(dst) = v;
+                    if (c_stream) store_streaming(dst, v);
+                    else *reinterpret_cast<f32x4*>(dst) = v;
                 } else {
                     dst[0] = v[0]; dst[1] = v[1]; dst[2] = v[2]; dst[3] = v[3];
                 }
@@ -519,7 +533,11 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, float
     // Block values that are read once per launch (a single group per block row) and are too many
     // to stay in the 256 MB Infinity Cache between launches are streamed past the L2, which
     // then keeps the rows of B.
-    const int stream_hint = (grid.y == 1 && SW == 1 && static_cast<double>(d.stream_bytes) > 200e6) ? 1 : 0;
+    int stream_hint = (grid.y == 1 && SW == 1 && static_cast<double>(d.stream_bytes) > 200e6) ? 1 : 0;
+    // A B of about the size of the L2s stays there between its uses only if the write of C does
+    // not push it out: then C is stored past the cache (measured: -7 % where B is 4 MiB, no gain
+    // or a loss where B is 16 MiB and more).
+    if (static_cast<double>(d.K) * static_cast<double>(N) * 2.0 <= 8.0e6) stream_hint |= 2;
     hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, BF16>), grid, dim3(KW * SW * 64), 0, stream,
                        d, B, b_bytes, static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());
