@@ -54,6 +54,44 @@ def bcsr_format_bytes(n_e, nbr, M, K, N):
     return n_e * (512 + 4) + (nbr + 1) * 4 + M * 4 + K * N * 2 + M * N * 4
 
 
+def run_probes(S, torch, dev, stream):
+    """Measured ceilings: streaming read of 2 GiB (HBM) and of 128 MiB (Infinity Cache resident),
+    random gather of 128- and 256-byte rows from tables of 4 / 16 / 32 MiB, register-resident MFMA loop."""
+    sink = torch.zeros(4, dtype=torch.int32, device=dev)
+
+    def timed(fn, reps=10):
+        for _ in range(2):
+            fn()
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        for _ in range(reps):
+            fn()
+        b.record(stream)
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / reps * 1e-3
+
+    out = {}
+    for label, nbytes in (("read_2GiB_gbs", 2 << 30), ("read_128MiB_gbs", 128 << 20)):
+        buf = torch.ones(nbytes // 4, dtype=torch.int32, device=dev)
+        out[label] = nbytes / timed(lambda: S.smat_probe_read(buf, sink, stream)) / 1e9
+        del buf
+    g = torch.Generator(device="cpu").manual_seed(1)
+    waves, packs = 16384, 9
+    for row_bytes, lane_bytes in ((128, 8), (256, 16)):
+        for table_mib in (4, 16, 32):
+            rows = (table_mib << 20) // row_bytes
+            table = torch.ones((table_mib << 20) // 4, dtype=torch.int32, device=dev)
+            idx = torch.randint(0, rows, (waves * packs * 32,), generator=g, dtype=torch.int32).to(dev)
+            sec = timed(lambda: S.smat_probe_gather(table, row_bytes, idx, waves, packs, lane_bytes, sink, stream))
+            out[f"gather_{row_bytes}B_rows_{table_mib}MiB_table_gbs"] = waves * packs * 32 * row_bytes / sec / 1e9
+            del table, idx
+    wgs, iters = 2048, 1000
+    sec = timed(lambda: S.smat_probe_mfma(wgs, iters, sink, stream), reps=5)
+    out["mfma_16x16x32_f16_tflops"] = wgs * 4 * iters * 16 * 2.0 * 16 * 16 * 32 / sec / 1e12
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -66,6 +104,9 @@ def main():
                     help="block-dense tile kernel: 0 automatic (default), 1 wherever it applies, -1 never")
     ap.add_argument("--no-cold", dest="cold", action="store_false",
                     help="skip the second timing with the caches flushed between launches")
+    ap.add_argument("--probes", action="store_true",
+                    help="also time the library's probe kernels (streaming read, row gather, MFMA loop): what this GPU "
+                         "delivers for the access patterns the SpMM kernels are made of")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (known traffic, scales the profiler's byte counters)")
     args = ap.parse_args()
@@ -166,6 +207,9 @@ def main():
                          "hbm_frac": bytes_alg / (float(cold.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS,
                          "useful_tflops": useful_flop / (float(cold.mean()) * 1e-3) / 1e12}
         del flush
+
+    if args.probes:
+        extra["probes"] = run_probes(S, torch, dev, stream)
 
     cpu = None
     if not args.no_cpu_baseline:

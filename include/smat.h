@@ -171,6 +171,25 @@ const char *smat_last_error(void);
  * (for profiles and logs). */
 const char *smat_last_kernel(void);
 
+/*
+ * Probes: three kernels that measure what the device delivers for the access patterns the SpMM
+ * kernels are made of (bench.py --probes times them and prints the rates next to the
+ * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.
+ *
+ *   smat_probe_read    reads `bytes` (a multiple of 8 KiB is read) from dev_buf once, streaming
+ *   smat_probe_gather  `waves` wavefronts each fetch `packs` groups of 32 rows named by dev_idx
+ *                      (uint32[waves * packs * 32], row numbers into a table of row_bytes-byte
+ *                      rows): 16 lanes x bytes_per_lane (8 or 16) bytes from the start of
+ *                      every row, eight row loads in flight per lane as in the SpMM kernel
+ *   smat_probe_mfma    workgroups x 4 waves issue iters x 16 MFMA 16x16x32 (fp16) each on
+ *                      register operands: 2 * 16*16*32 flop per instruction and wave
+ *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
+ */
+smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
+smat_status_t smat_probe_gather(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
+                                int packs, int bytes_per_lane, void *dev_sink, void *stream);
+smat_status_t smat_probe_mfma(int workgroups, int iters, void *dev_sink, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

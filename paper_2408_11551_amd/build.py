@@ -17,6 +17,7 @@ SOURCES = {
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "probes.hip": [],
 }
 HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", os.path.join("..", "..", "include", "smat.h")]
 

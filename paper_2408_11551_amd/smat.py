@@ -48,6 +48,12 @@ def _load():
     lib.smat_preprocess.restype = ctypes.c_int
     lib.smat_preprocess.argtypes = [i64, i64, vp, vp, vp, ctypes.c_int, ctypes.POINTER(_Options),
                                     ctypes.POINTER(vp)]
+    lib.smat_probe_read.restype = ctypes.c_int
+    lib.smat_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.smat_probe_gather.restype = ctypes.c_int
+    lib.smat_probe_gather.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.smat_probe_mfma.restype = ctypes.c_int
+    lib.smat_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_get_layout_info.restype = ctypes.c_int
     lib.smat_get_layout_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 4
     lib.smat_get_info.restype = ctypes.c_int
@@ -189,6 +195,22 @@ def smat_spmm(h, B, C, N=None, stream=None):
     _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
                           ctypes.c_void_p(C.data_ptr()), C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N),
                           N, _stream_ptr(stream)))
+
+
+def smat_probe_read(buf, sink, stream=None):
+    """buf: device tensor read once end to end; sink: device tensor of >= 4 bytes."""
+    _check(_lib.smat_probe_read(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
+
+
+def smat_probe_gather(table, row_bytes, idx, waves, packs, bytes_per_lane, sink, stream=None):
+    """table: device bytes of rows; idx: device int32/uint32 tensor [waves * packs * 32] of row numbers."""
+    _check(_lib.smat_probe_gather(ctypes.c_void_p(table.data_ptr()), row_bytes, ctypes.c_void_p(idx.data_ptr()),
+                                  waves, packs, bytes_per_lane, ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
+
+
+def smat_probe_mfma(workgroups, iters, sink, stream=None):
+    _check(_lib.smat_probe_mfma(workgroups, iters, ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
 
 
 def smat_destroy(h):
