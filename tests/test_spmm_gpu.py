@@ -296,6 +296,24 @@ def test_graph_capture_and_replay(oracle_c):
         m.close()
 
 
+def test_probe_kernels_run():
+    # the measurement probes only have to launch, stay in bounds and reject bad arguments
+    sink = torch.zeros(4, dtype=torch.int32, device="cuda")
+    buf = torch.ones(1 << 20, dtype=torch.int32, device="cuda")
+    S.smat_probe_read(buf, sink)
+    rows = (buf.numel() * 4) // 256
+    idx = torch.randint(0, rows, (64 * 3 * 32,), dtype=torch.int32).cuda()
+    S.smat_probe_gather(buf, 256, idx, 64, 3, 16, sink)
+    S.smat_probe_gather(buf, 256, idx, 64, 3, 8, sink)
+    S.smat_probe_mfma(8, 10, sink)
+    torch.cuda.synchronize()
+    assert int(sink[0]) == 0
+    with pytest.raises(S.SmatError):
+        S.smat_probe_gather(buf, 64, idx, 64, 3, 16, sink)        # rows shorter than 16 lanes x 16 bytes
+    with pytest.raises(S.SmatError):
+        S.smat_probe_mfma(0, 10, sink)
+
+
 def test_empty_and_degenerate_inputs(oracle_c):
     z = Workload("zero", "f16", 40, 50, 12, np.zeros(41, np.int64), np.zeros(0, np.int32), np.zeros(0, np.uint16),
                  np.ones((50, 12), np.uint16))
