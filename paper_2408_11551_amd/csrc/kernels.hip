@@ -428,6 +428,22 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     const __amdgpu_buffer_rsrc_t rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
 
+    // Where this thread's output rows go is read now, not after the loop: the epilogue then
+    // starts with the addresses in registers instead of with one more trip to memory.
+    constexpr int Q = NT >= 4 ? WC / 4 : WC;       // epilogue items per tile row (quads, or single columns)
+    constexpr int EP = KW == 1 ? 4 : (SW * 16 * Q + WAVES * 64 - 1) / (WAVES * 64);
+    int out_rows[EP];
+    if constexpr (KW == 1) {
+#pragma unroll
+        for (int r = 0; r < 4; ++r) out_rows[r] = d.perm[br * 16 + 4 * g + r];
+    } else {
+#pragma unroll
+        for (int k = 0; k < EP; ++k) {
+            const int e = static_cast<int>(threadIdx.x) + k * WAVES * 64;
+            out_rows[k] = e < SW * 16 * Q ? d.perm[br * 16 + (e / Q) % 16] : -1;
+        }
+    }
+
     f32x4 acc[NCH * NT];
 #pragma unroll
     for (int t = 0; t < NCH * NT; ++t) acc[t] = f32x4{0.f, 0.f, 0.f, 0.f};
@@ -447,7 +463,7 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
             if (col0[c] >= N) continue;
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
-                const int64_t out_row = d.perm[br * 16 + 4 * g + r];
+                const int64_t out_row = out_rows[r];
                 if (out_row < 0) continue;
                 float* dst = C + out_row * ldc + col0[c];
                 if constexpr (NT >= 4) {
@@ -488,14 +504,16 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
         const int nbase = blockIdx.y * SW * WC;
         if constexpr (NT >= 4) {
             // each thread sums and stores four consecutive columns
-            constexpr int Q = WC / 4;              // quads per row of one wave's slab
-            for (int e = threadIdx.x; e < SW * 16 * Q; e += WAVES * 64) {
+#pragma unroll
+            for (int k = 0; k < EP; ++k) {
+                const int e = static_cast<int>(threadIdx.x) + k * WAVES * 64;
+                if (e >= SW * 16 * Q) break;
                 const int s = e / (16 * Q), row = (e / Q) % 16, c = (e % Q) * 4;
                 const float* src = red + (s * KW) * 16 * LD + row * LD + c;
                 f32x4 v = *reinterpret_cast<const f32x4*>(src);
 #pragma unroll
                 for (int x = 1; x < KW; ++x) v += *reinterpret_cast<const f32x4*>(src + x * 16 * LD);
-                const int64_t out_row = d.perm[br * 16 + row];
+                const int64_t out_row = out_rows[k];
                 const int col = nbase + s * WC + c;
                 if (out_row < 0 || col >= N) continue;
                 float* dst = C + out_row * ldc + col;
@@ -507,13 +525,16 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
                 }
             }
         } else {
-            for (int e = threadIdx.x; e < SW * 16 * WC; e += WAVES * 64) {
+#pragma unroll
+            for (int k = 0; k < EP; ++k) {
+                const int e = static_cast<int>(threadIdx.x) + k * WAVES * 64;
+                if (e >= SW * 16 * WC) break;
                 const int s = e / (16 * WC), row = (e / WC) % 16, c = e % WC;
                 const float* src = red + (s * KW) * 16 * LD + row * LD + c;
                 float v = src[0];
 #pragma unroll
                 for (int x = 1; x < KW; ++x) v += src[x * 16 * LD];
-                const int64_t out_row = d.perm[br * 16 + row];
+                const int64_t out_row = out_rows[k];
                 const int col = nbase + s * WC + c;
                 if (out_row >= 0 && col < N) C[out_row * ldc + col] = v;
             }
