@@ -67,6 +67,50 @@ def decode16(bits, dtype: str) -> np.ndarray:
 
 
 # ---------------------------------------------------------------------------
+# 8-bit decoding: the other operand types of the matrix units (the paper's list of
+# contributions claims every precision the matrix units accept; the Background section
+# names the 8-bit integer and floating-point forms next to fp16 / bf16)
+# ---------------------------------------------------------------------------
+def decode8(bits, dtype: str) -> np.ndarray:
+    """Exact float64 value of 8-bit operand bit patterns.
+
+    "e4m3": sign, 4 exponent bits (bias 7), 3 mantissa bits; no infinities, the one pattern
+            S.1111.111 is NaN, so the largest finite value is 1.75 * 2^8 = 448.
+    "e5m2": sign, 5 exponent bits (bias 15), 2 mantissa bits; exponent 11111 is inf (mantissa
+            0) or NaN, as in IEEE-754; the largest finite value is 1.75 * 2^15 = 57344.
+    "i8":   two's complement integer, -128 .. 127.
+    (The two floating-point layouts are those of the OCP 8-bit floating point specification,
+    which is what the gfx950 matrix units decode.)"""
+    b = np.asarray(bits).astype(np.int64) & 0xFF
+    if dtype == "i8":
+        return np.where(b >= 128, b - 256, b).astype(np.float64)
+    if dtype == "e4m3":
+        ebits, mbits, bias = 4, 3, 7
+    elif dtype == "e5m2":
+        ebits, mbits, bias = 5, 2, 15
+    else:
+        raise ValueError(dtype)
+    sign = np.where((b >> 7) & 1, -1.0, 1.0)
+    e = (b >> mbits) & ((1 << ebits) - 1)
+    m = (b & ((1 << mbits) - 1)).astype(np.float64)
+    emax = (1 << ebits) - 1
+    normal = np.ldexp(1.0 + m / (1 << mbits), (e - bias).astype(np.int64))
+    subnormal = np.ldexp(m / (1 << mbits), 1 - bias)
+    val = np.where(e == 0, subnormal, normal)
+    if dtype == "e4m3":
+        val = np.where((e == emax) & (m == (1 << mbits) - 1), np.nan, val)
+    else:
+        val = np.where((e == emax) & (m == 0), np.inf, val)
+        val = np.where((e == emax) & (m != 0), np.nan, val)
+    return sign * val
+
+
+def decode_bits(bits, dtype: str) -> np.ndarray:
+    """decode16 or decode8 by the name of the storage type."""
+    return decode16(bits, dtype) if dtype in ("f16", "bf16") else decode8(bits, dtype)
+
+
+# ---------------------------------------------------------------------------
 # O1: the product
 # ---------------------------------------------------------------------------
 def spmm_ref(M, K, N, row_ptr, col_idx, a_val, b):
@@ -123,7 +167,7 @@ def count_blocks_bruteforce(dense_nonzero: np.ndarray, h=H, w=W) -> int:
 
 def bcsr_from_csr(M, K, row_ptr, col_idx, a_bits, perm, h=H, w=W):
     """BCSR of A' = P.A (perm[new] = old).  Returns (rowPtr int32[nbr+1], col int32[n_e],
-    val uint16[n_e, h, w]); blocks of a block row in ascending block-column order, each
+    val [n_e, h, w] of the storage type of a_bits); blocks of a block row in ascending block-column order, each
     block row-major and zero filled (section "Data Structures")."""
     nbr = -(-M // h)
     rowPtr = np.zeros(nbr + 1, dtype=np.int32)
@@ -132,7 +176,7 @@ def bcsr_from_csr(M, K, row_ptr, col_idx, a_bits, perm, h=H, w=W):
         rows = [int(perm[i]) for i in range(I * h, min(I * h + h, M))]
         present = sorted({int(c) // w for r in rows for c in col_idx[int(row_ptr[r]):int(row_ptr[r + 1])]})
         slot = {J: n for n, J in enumerate(present)}
-        blk = np.zeros((len(present), h, w), dtype=np.uint16)
+        blk = np.zeros((len(present), h, w), dtype=np.asarray(a_bits).dtype)
         for local, r in enumerate(rows):
             for p in range(int(row_ptr[r]), int(row_ptr[r + 1])):
                 c = int(col_idx[p])
@@ -141,7 +185,7 @@ def bcsr_from_csr(M, K, row_ptr, col_idx, a_bits, perm, h=H, w=W):
         vals_out.append(blk)
         rowPtr[I + 1] = rowPtr[I] + len(present)
     col = np.asarray(cols_out, dtype=np.int32)
-    val = np.concatenate(vals_out, axis=0) if vals_out else np.zeros((0, h, w), np.uint16)
+    val = np.concatenate(vals_out, axis=0) if vals_out else np.zeros((0, h, w), np.asarray(a_bits).dtype)
     return rowPtr, col, val
 
 
@@ -163,8 +207,9 @@ def bcsr_from_csr_fast(M, K, row_ptr, col_idx, a_bits, perm, h=H, w=W):
     rowPtr = np.zeros(nbr + 1, dtype=np.int64)
     np.cumsum(np.bincount(uniq // nbc, minlength=nbr), out=rowPtr[1:])
     col = (uniq % nbc).astype(np.int32)
-    val = np.zeros((n_e, h, w), dtype=np.uint16)
-    val[inv, new_row % h, c % w] = np.asarray(a_bits, dtype=np.uint16)
+    a_bits = np.asarray(a_bits)
+    val = np.zeros((n_e, h, w), dtype=a_bits.dtype)
+    val[inv, new_row % h, c % w] = a_bits
     return rowPtr.astype(np.int32), col, val
 
 

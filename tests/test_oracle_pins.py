@@ -21,7 +21,7 @@ GOLDEN = os.path.join(os.path.dirname(__file__), "golden")
 
 
 def _vals(w):
-    return R.decode16(w.a_bits, w.dtype), R.decode16(w.b_bits, w.dtype)
+    return R.decode_bits(w.a_bits, w.dtype), R.decode_bits(w.b_bits, w.dtype)
 
 
 # ------------------------------------------------------------------ decode
@@ -39,6 +39,59 @@ def test_decode16_matches_generator_encoding_on_all_finite_patterns(dtype):
         assert R.decode16([0x3C00, 0xC000, 0x0001, 0x7BFF], dtype).tolist() == [1.0, -2.0, 2.0 ** -24, 65504.0]
     else:
         assert R.decode16([0x3F80, 0xC000, 0x3F00], dtype).tolist() == [1.0, -2.0, 0.5]
+
+
+@pytest.mark.parametrize("dtype", ["e4m3", "e5m2", "i8"])
+def test_decode8_on_all_patterns(dtype):
+    """Every one of the 256 codes against PyTorch's CPU casts (an independent implementation
+    of the same published formats), plus the values the format definitions give by hand."""
+    bits = np.arange(256, dtype=np.uint8)
+    got = R.decode8(bits, dtype)
+    want = from_bits(bits, dtype)
+    finite = np.isfinite(want)
+    assert np.array_equal(got[finite], want[finite])
+    assert np.array_equal(np.isnan(got), np.isnan(want))
+    assert np.array_equal(np.isinf(got), np.isinf(want))
+    if dtype == "e4m3":
+        # 1.0 = 0.0111.000; largest finite 0.1111.110 = 1.75 * 2^8; smallest subnormal 2^-6 / 8; one NaN per sign
+        assert R.decode8([0x38, 0xC0, 0x7E, 0x01, 0x08, 0x80], dtype).tolist() == [1.0, -2.0, 448.0, 2.0 ** -9, 2.0 ** -6, -0.0]
+        assert np.isnan(R.decode8([0x7F, 0xFF], dtype)).all() and np.isfinite(got).sum() == 254
+    elif dtype == "e5m2":
+        # 1.0 = 0.01111.00; largest finite 0.11110.11 = 1.75 * 2^15; smallest subnormal 2^-14 / 4; inf at 0.11111.00
+        assert R.decode8([0x3C, 0xC0, 0x7B, 0x01, 0x04], dtype).tolist() == [1.0, -2.0, 57344.0, 2.0 ** -16, 2.0 ** -14]
+        assert np.isinf(R.decode8([0x7C, 0xFC], dtype)).all() and np.isnan(R.decode8([0x7D, 0x7E, 0x7F, 0xFF], dtype)).all()
+        # an e5m2 code is the high byte of the fp16 code of the same value
+        assert np.array_equal(got[finite], R.decode16(bits.astype(np.uint16) << 8, "f16")[finite])
+    else:
+        assert R.decode8([0x00, 0x01, 0x7F, 0x80, 0xFF], dtype).tolist() == [0.0, 1.0, 127.0, -128.0, -1.0]
+        assert np.array_equal(np.sort(got), np.arange(-128, 128, dtype=np.float64))
+
+
+@pytest.mark.parametrize("dtype", ["e4m3", "e5m2", "i8"])
+def test_8bit_generator_round_trip_and_product(dtype):
+    """Encoding then decoding is the identity on representable values, ties go to even, and the
+    product oracle on 8-bit operands equals the dense product of the decoded matrices (exactly
+    for i8, where every partial sum is an integer far below 2^53)."""
+    if dtype == "i8":
+        assert from_bits(to_bits(np.array([2.5, 3.5, -2.5, 300.0, -300.0]), dtype), dtype).tolist() == [2.0, 4.0, -2.0, 127.0, -127.0]
+    elif dtype == "e4m3":
+        # between 1.0 and 1.125: tie -> 1.0 (even mantissa); between 1.125 and 1.25: tie -> 1.25; clamp at 448
+        assert from_bits(to_bits(np.array([1.0625, 1.1875, 1e6]), dtype), dtype).tolist() == [1.0, 1.25, 448.0]
+    else:
+        assert from_bits(to_bits(np.array([1.125, 1.375, 1e9]), dtype), dtype).tolist() == [1.0, 1.5, 57344.0]
+    from workloads import recast
+    w = recast(random_csr(40, 56, 9, 0.2, seed=5), dtype, a_scale=127.0 if dtype == "i8" else 1.0,
+               b_scale=127.0 if dtype == "i8" else 1.0)
+    assert w.a_bits.dtype == np.uint8 and w.b_bits.dtype == np.uint8
+    a, b = _vals(w)
+    assert np.array_equal(a, from_bits(w.a_bits, dtype)) and np.isfinite(a).all() and np.isfinite(b).all()
+    c, s = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, w.col_idx, a, b)
+    ad = dense_from_bits(w)
+    if dtype == "i8":
+        assert np.array_equal(c, ad @ b) and np.array_equal(c, np.rint(c)) and np.abs(a).max() > 64
+    else:
+        np.testing.assert_allclose(c, ad @ b, rtol=1e-13, atol=1e-15)
+    np.testing.assert_allclose(s, np.abs(ad) @ np.abs(b), rtol=1e-13, atol=1e-15)
 
 
 def test_rounding_is_nearest_even():

@@ -1,7 +1,7 @@
 """Seeded synthetic inputs (CSR A, dense B) shared by the tests, the bench and the oracle checks.
 
 This package holds no arithmetic of the SpMM method itself: it only draws
-random sparsity patterns and values, rounds them to 16-bit storage and hands
+random sparsity patterns and values, rounds them to their storage type and hands
 the same bits to whoever asks.
 """
 from .configs import (  # noqa: F401
@@ -16,4 +16,7 @@ from .configs import (  # noqa: F401
     dense_from_bits,
     to_bits,
     from_bits,
+    recast,
+    storage_dtype,
+    DTYPES_8BIT,
 )

@@ -1,10 +1,11 @@
 """Seeded generators for the synthetic SpMM workloads.
 
 Every workload is a CSR matrix A (int64 row_ptr, int32 col_idx with strictly
-ascending columns inside a row, 16-bit value bit patterns) and a dense
-row-major B (16-bit bit patterns).  Values are drawn in float64 and rounded
-once, round-to-nearest-even, to the storage type; both the CPU oracle and the
-GPU library receive exactly these bits.
+ascending columns inside a row, value bit patterns) and a dense row-major B
+(bit patterns of the same storage type: fp16 or bf16, and for the 8-bit operand
+types of the matrix units e4m3, e5m2 or i8).  Values are drawn in float64 and
+rounded once, round-to-nearest-even, to the storage type; both the CPU oracle
+and the GPU library receive exactly these bits.
 
 The shapes stand in for the workloads the paper measures on (SuiteSparse
 matrices with 36K-140K rows and 0.77M-10.4M nonzeros, Table I; and the
@@ -19,13 +20,30 @@ import numpy as np
 
 F16 = "f16"
 BF16 = "bf16"
+E4M3 = "e4m3"
+E5M2 = "e5m2"
+I8 = "i8"
+DTYPES_8BIT = (E4M3, E5M2, I8)
+
+
+def storage_dtype(dtype: str):
+    """numpy type that carries the bit patterns of `dtype`."""
+    return np.uint8 if dtype in DTYPES_8BIT else np.uint16
 
 
 # --------------------------------------------------------------------------
-# 16-bit storage encodings (format conversion only)
+# storage encodings (format conversion only)
 # --------------------------------------------------------------------------
+def _fp8_torch(dtype: str):
+    import torch
+    return torch.float8_e4m3fn if dtype == E4M3 else torch.float8_e5m2
+
+
 def to_bits(x: np.ndarray, dtype: str) -> np.ndarray:
-    """Round float64 values to fp16 / bf16 (RNE) and return the uint16 bit patterns."""
+    """Round float64 values to the storage type (round to nearest even) and return the bit
+    patterns: uint16 for fp16 / bf16, uint8 for the 8-bit types.  The 8-bit floating-point
+    types go through PyTorch's CPU casts (values beyond the largest finite one are clamped to
+    it first, so no NaN or infinity is ever produced); i8 rounds and clamps to -127 .. 127."""
     x = np.asarray(x, dtype=np.float64)
     if dtype == F16:
         return x.astype(np.float16).view(np.uint16)
@@ -33,16 +51,28 @@ def to_bits(x: np.ndarray, dtype: str) -> np.ndarray:
         u = x.astype(np.float32).view(np.uint32)
         rounded = (u + np.uint32(0x7FFF) + ((u >> np.uint32(16)) & np.uint32(1))) >> np.uint32(16)
         return rounded.astype(np.uint16)
+    if dtype in (E4M3, E5M2):
+        import torch
+        top = 448.0 if dtype == E4M3 else 57344.0
+        t = torch.from_numpy(np.clip(x, -top, top).astype(np.float32))
+        return t.to(_fp8_torch(dtype)).view(torch.uint8).numpy().copy()
+    if dtype == I8:
+        return np.clip(np.rint(x), -127, 127).astype(np.int8).view(np.uint8)
     raise ValueError(f"unknown dtype {dtype!r}")
 
 
 def from_bits(bits: np.ndarray, dtype: str) -> np.ndarray:
-    """Exact float64 value of fp16 / bf16 bit patterns."""
-    bits = np.asarray(bits, dtype=np.uint16)
+    """Exact float64 value of the bit patterns."""
     if dtype == F16:
-        return bits.view(np.float16).astype(np.float64)
+        return np.asarray(bits, dtype=np.uint16).view(np.float16).astype(np.float64)
     if dtype == BF16:
-        return (bits.astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+        return (np.asarray(bits, dtype=np.uint16).astype(np.uint32) << np.uint32(16)).view(np.float32).astype(np.float64)
+    if dtype in (E4M3, E5M2):
+        import torch
+        t = torch.from_numpy(np.ascontiguousarray(bits, dtype=np.uint8))
+        return t.view(_fp8_torch(dtype)).to(torch.float64).numpy()
+    if dtype == I8:
+        return np.asarray(bits, dtype=np.uint8).view(np.int8).astype(np.float64)
     raise ValueError(f"unknown dtype {dtype!r}")
 
 
@@ -52,14 +82,14 @@ def from_bits(bits: np.ndarray, dtype: str) -> np.ndarray:
 @dataclass
 class Workload:
     name: str
-    dtype: str                 # "f16" | "bf16"
+    dtype: str                 # "f16" | "bf16" | "e4m3" | "e5m2" | "i8"
     M: int
     K: int
     N: int
     row_ptr: np.ndarray        # int64 [M+1]
     col_idx: np.ndarray        # int32 [nnz], strictly ascending inside a row
-    a_bits: np.ndarray         # uint16 [nnz]
-    b_bits: np.ndarray         # uint16 [K, N] row-major
+    a_bits: np.ndarray         # uint16 (uint8 for the 8-bit types) [nnz]
+    b_bits: np.ndarray         # same type, [K, N] row-major
     meta: dict = field(default_factory=dict)
 
     @property
@@ -332,6 +362,15 @@ _BUILDERS = {
 def make_config(name: str, seed: int = 0, **kw) -> Workload:
     """Build one of the benchmark configurations (CONFIG_NAMES) for a seed."""
     return _BUILDERS[name](seed, **kw)
+
+
+def recast(w: Workload, dtype: str, a_scale: float = 1.0, b_scale: float = 1.0) -> Workload:
+    """The same pattern with the values of A and B scaled and rounded once more to another
+    storage type (scale 127 turns U(-1,1) into the full range of i8)."""
+    a = to_bits(from_bits(w.a_bits, w.dtype) * a_scale, dtype)
+    b = to_bits(from_bits(w.b_bits.reshape(-1), w.dtype) * b_scale, dtype).reshape(w.b_bits.shape)
+    return Workload(f"{w.name}_{dtype}", dtype, w.M, w.K, w.N, w.row_ptr, w.col_idx, a, np.ascontiguousarray(b),
+                    dict(w.meta))
 
 
 def dense_from_bits(w: Workload) -> np.ndarray:
