@@ -45,7 +45,13 @@ typedef enum {
     SMAT_ERR_HIP = 6            /* a HIP runtime call failed; text in smat_last_error   */
 } smat_status_t;
 
-typedef enum { SMAT_F16 = 0, SMAT_BF16 = 1 } smat_dtype_t;   /* storage type of A and B */
+/* Storage type of A and B: the operand types of the gfx950 matrix units (the paper's
+ * Introduction claims every precision the matrix units accept).  fp16 and bf16 take two
+ * bytes per value; SMAT_E4M3 and SMAT_E5M2 are the OCP 8-bit floating-point formats (1-4-3
+ * bits, bias 7, no infinities; 1-5-2 bits, bias 15) and SMAT_I8 is a two's complement byte.
+ * C is fp32 (fp32 accumulation) for the floating-point types and int32 (int32 accumulation,
+ * wrapping on overflow) for SMAT_I8. */
+typedef enum { SMAT_F16 = 0, SMAT_BF16 = 1, SMAT_E4M3 = 2, SMAT_E5M2 = 3, SMAT_I8 = 4 } smat_dtype_t;
 
 typedef struct {
     int block_h;        /* block height; only 16 is accepted                            */
@@ -58,7 +64,8 @@ typedef struct {
     int dense_tiles;    /* block-dense regions (sixteen block rows sharing most of their
                            block columns) have a kernel of their own that stages panels of
                            B in LDS: 0 = take it where an estimate says it is faster,
-                           1 = take it wherever it applies, -1 = never                    */
+                           1 = take it wherever it applies, -1 = never.  fp16 / bf16 only:
+                           with an 8-bit dtype 1 is refused and 0 means -1                */
 } smat_options_t;
 
 /* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0. */
@@ -71,8 +78,9 @@ void smat_default_options(smat_options_t *opt);
  *   M, K      rows / columns of A, 0 <= M < 2^31 - 16, 0 <= K < 2^24
  *   row_ptr   HOST int64[M+1], row_ptr[0] == 0, non-decreasing
  *   col_idx   HOST int32[nnz], strictly ascending inside each row, 0 <= col < K
- *   vals      HOST 16-bit values [nnz] (fp16 or bf16 bit patterns per dtype);
- *             a stored value of 0 still counts as a nonzero of the pattern
+ *   vals      HOST values [nnz], bit patterns of dtype: two bytes each for fp16 / bf16,
+ *             one byte each for the 8-bit types; a stored value of 0 still counts as a
+ *             nonzero of the pattern
  *   opt       may be NULL (defaults)
  *   out       receives a new handle; release it with smat_destroy
  *
@@ -99,7 +107,8 @@ smat_status_t smat_export_perm(const smat_handle_t *h, int32_t *perm);
 /* Canonical BCSR of A' (Data Structures section), all HOST, caller allocated:
  *   row_ptr int32[n_block_rows+1]  offsets into col_idx per block row
  *   col_idx int32[n_blocks]        block column of each block, ascending per block row
- *   vals    16-bit [n_blocks*256]  one 16x16 block after the other, row-major, zero filled
+ *   vals    [n_blocks*256] values of the handle's dtype (2 or 1 bytes each), one 16x16
+ *           block after the other, row-major, zero filled
  * vals may be NULL to export the structure only. */
 smat_status_t smat_export_bcsr(const smat_handle_t *h, int32_t *row_ptr, int32_t *col_idx, void *vals);
 
@@ -135,19 +144,19 @@ smat_status_t smat_get_layout_info(const smat_handle_t *h, int64_t *n_packs, int
 smat_status_t smat_bind_device(smat_handle_t *h, void *dev_workspace, size_t bytes, void *stream);
 
 /* Reads the device-side block values back and returns them in the canonical
- * layout of smat_export_bcsr (vals: HOST 16-bit [n_blocks*256]); used to verify
+ * layout of smat_export_bcsr (vals: HOST [n_blocks*256] values of the handle's dtype); used to verify
  * the device-side conversion.  Synchronises the stream. */
 smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *stream);
 
 /*
  * C = A * B on the device (Implementation section, Alg. 1: per output tile, loop
  * over the stored blocks of the block row, multiply-accumulate on the matrix
- * units), fp32 accumulation, rows of C in the ORIGINAL row order of A.
+ * units), fp32 accumulation (int32 for SMAT_I8), rows of C in the ORIGINAL row order of A.
  *
  *   dB   DEVICE, K x N row-major, element type = dtype of the handle, leading
  *        dimension ldb >= N (in elements)
- *   dC   DEVICE, M x N row-major fp32, leading dimension ldc >= N; every element
- *        of the M x N window is overwritten (rows of A without entries give 0)
+ *   dC   DEVICE, M x N row-major fp32 (int32 for SMAT_I8), leading dimension ldc >= N; every
+ *        element of the M x N window is overwritten (rows of A without entries give 0)
  *   N    >= 1 (N = 0 is a no-op); any value, any alignment: wide vector loads
  *        are used when N, ldb and the base address allow it
  *   stream  hipStream_t; the call only enqueues work (no synchronisation)
@@ -155,7 +164,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
  * Calls on DIFFERENT handles may run concurrently on different streams.  Two calls on the
  * same handle must not overlap in time: the handle's workspace holds the scratch area in
  * which a launch with few block-dense tiles keeps partial tiles.
- * Limits: the bytes of B that are addressed, ((K-1)*ldb + N)*2, must stay below 2 GiB;
+ * Limits: the bytes of B that are addressed, ((K-1)*ldb + N) * bytes per value, must stay below 2 GiB;
  * ldb < 2^23; N <= 1048560.
  */
 smat_status_t smat_spmm(const smat_handle_t *h, const void *dB, int64_t ldb,

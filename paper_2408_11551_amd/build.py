@@ -14,12 +14,13 @@ SOURCES = {
     "api.cpp": [],
     "preprocess.cpp": [],
     "kernels.hip": [],
+    "kernels_8bit.hip": [],
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "probes.hip": [],
 }
-HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", os.path.join("..", "..", "include", "smat.h")]
+HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h")]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
@@ -50,7 +51,7 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return OUT
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=4) as pool:
+    with ThreadPoolExecutor(max_workers=6) as pool:
         objs = list(pool.map(_compile, SOURCES.items()))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
     if verbose:

@@ -23,6 +23,7 @@ struct smat_handle {
     smat::Csr csr;
     smat::Bcsr bcsr;
     smat_dtype_t dtype = SMAT_F16;
+    int elem_bytes = 2;                  // bytes per stored value of A and B: 2, or 1 for the 8-bit types
     int dense_mode = 0;                  // option dense_tiles
     bool bound = false;
     // Packs (pack_layout.h): every block row is cut, from the left, into runs of consecutive
@@ -37,6 +38,8 @@ struct smat_handle {
     // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2.  The slot table of a
     // row takes 16 * L bytes per pack and its values 128 * L bytes; slots_off counts 32-byte
     // units of the former, which are 256-byte units of the latter.
+    // (Values: 128 * L bytes per pack for the 16-bit types, 64 * L for the 8-bit ones -- a unit
+    // is 128 values either way.)
     std::vector<int8_t> row_class;       // [nbr]
     std::vector<uint32_t> slots_off;     // [nbr+1]
     uint64_t slots_units = 0;
@@ -97,7 +100,7 @@ Layout make_layout(const smat_handle& h)
     l.work = take(nbr * 16);
     l.work_rest = take(nbr * 16);
     l.slots = take(static_cast<size_t>(h.slots_units) * 32);
-    l.vals = take(static_cast<size_t>(h.slots_units) * 256);
+    l.vals = take(static_cast<size_t>(h.slots_units) * 128 * static_cast<size_t>(h.elem_bytes));
     l.pack_ptr = take((nbr + 1) * sizeof(int32_t));
     l.slots_off = take((nbr + 1) * sizeof(uint32_t));
     l.blk_ptr = take((nbr + 1) * sizeof(int32_t));
@@ -223,7 +226,7 @@ void row_stats(const smat_handle& h, bool skip_dense, smat::DeviceBcsr& d)
     }
     d.n_order = rows;
     d.n_packs = packs;
-    d.stream_bytes = units * (256 + 32);
+    d.stream_bytes = units * (128 * h.elem_bytes + 32);
     d.max_row_packs = longest;
     d.mean_row_packs = rows ? static_cast<double>(packs) / static_cast<double>(rows) : 0.0;
     d.max_class = cls;
@@ -254,11 +257,14 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (!out) return fail(SMAT_ERR_INVALID_ARG, "out is NULL");
         if (M < 0 || K < 0) return fail(SMAT_ERR_INVALID_ARG, "negative matrix size");
         if (!row_ptr) return fail(SMAT_ERR_INVALID_ARG, "row_ptr is NULL");
-        if (dtype != SMAT_F16 && dtype != SMAT_BF16) return fail(SMAT_ERR_INVALID_ARG, "unknown dtype");
+        if (dtype < SMAT_F16 || dtype > SMAT_I8) return fail(SMAT_ERR_INVALID_ARG, "unknown dtype");
+        const bool narrow = dtype >= SMAT_E4M3;
         if (o.block_h != 16 || o.block_w != 16) return fail(SMAT_ERR_UNSUPPORTED, "only 16x16 blocks are supported");
         if (o.reorder != 0 && o.reorder != 1) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0 or 1");
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (o.dense_tiles < -1 || o.dense_tiles > 1) return fail(SMAT_ERR_INVALID_ARG, "dense_tiles must be -1, 0 or 1");
+        if (narrow && o.dense_tiles == 1)
+            return fail(SMAT_ERR_UNSUPPORTED, "the dense-tile kernel handles fp16 and bf16 only");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
         if ((M + 15) / 16 >= (int64_t{1} << 28)) return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
@@ -273,12 +279,16 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
 
         std::unique_ptr<smat_handle> h(new smat_handle());      // freed if anything below throws
         h->dtype = dtype;
-        h->dense_mode = o.dense_tiles;
+        h->elem_bytes = narrow ? 1 : 2;
+        h->dense_mode = narrow ? -1 : o.dense_tiles;
         h->csr.M = M;
         h->csr.K = K;
         h->csr.row_ptr.assign(row_ptr, row_ptr + M + 1);
         h->csr.col_idx.assign(col_idx, col_idx + nnz);
-        h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
+        if (narrow)      // kept as 16-bit words, value in the low byte
+            h->csr.vals.assign(static_cast<const uint8_t*>(vals), static_cast<const uint8_t*>(vals) + nnz);
+        else
+            h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
         smat::build_bcsr(h->csr, o.reorder != 0, o.tau_permille, h->bcsr);
         try {
             plan_packs(*h);
@@ -311,7 +321,7 @@ smat_status_t smat_get_layout_info(const smat_handle_t* h, int64_t* n_packs, int
 {
     if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
     if (n_packs) *n_packs = static_cast<int64_t>(h->pack_first.size()) - 1;
-    if (value_bytes) *value_bytes = static_cast<int64_t>(h->slots_units) * 256;
+    if (value_bytes) *value_bytes = static_cast<int64_t>(h->slots_units) * 128 * h->elem_bytes;
     if (table_bytes) *table_bytes = static_cast<int64_t>(h->slots_units) * 32 + h->bcsr.nbr * (16 + 16 * 4);
     if (n_columns) {
         int64_t cols = 0;
@@ -336,7 +346,12 @@ smat_status_t smat_export_bcsr(const smat_handle_t* h, int32_t* row_ptr, int32_t
         std::memcpy(row_ptr, h->bcsr.row_ptr.data(), sizeof(int32_t) * h->bcsr.row_ptr.size());
         if (h->bcsr.n_blocks > 0)
             std::memcpy(col_idx, h->bcsr.col_idx.data(), sizeof(int32_t) * h->bcsr.col_idx.size());
-        if (vals) smat::fill_canonical_vals(h->csr, h->bcsr, static_cast<uint16_t*>(vals));
+        if (vals && h->elem_bytes == 2) smat::fill_canonical_vals(h->csr, h->bcsr, static_cast<uint16_t*>(vals));
+        if (vals && h->elem_bytes == 1) {
+            std::vector<uint16_t> wide(static_cast<size_t>(h->bcsr.n_blocks) * 256);
+            smat::fill_canonical_vals(h->csr, h->bcsr, wide.data());
+            std::copy(wide.begin(), wide.end(), static_cast<uint8_t*>(vals));       // low bytes
+        }
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
         return fail(SMAT_ERR_ALLOC, "out of host memory in smat_export_bcsr");
@@ -424,7 +439,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         d.perm = reinterpret_cast<const int32_t*>(base + l.perm);
         d.work = reinterpret_cast<const int32_t*>(base + l.work);
         d.slots = reinterpret_cast<const uint32_t*>(base + l.slots);
-        d.vals = reinterpret_cast<const uint16_t*>(base + l.vals);
+        d.vals = base + l.vals;
         d.pack_ptr = reinterpret_cast<const int32_t*>(base + l.pack_ptr);
         d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
         d.blk_ptr = reinterpret_cast<const int32_t*>(base + l.blk_ptr);
@@ -453,9 +468,9 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
 
-        if ((e = smat::launch_fill_zero(base + l.vals, static_cast<size_t>(h->slots_units) * 16, s))) return hip_fail("zero block values", e);
-        if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
-                                        reinterpret_cast<uint16_t*>(base + l.vals), s)))
+        if ((e = smat::launch_fill_zero(base + l.vals, static_cast<size_t>(h->slots_units) * 8 * static_cast<size_t>(h->elem_bytes), s)))
+            return hip_fail("zero block values", e);
+        if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.vals, h->elem_bytes, s)))
             return hip_fail("fill block values", e);
         if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 64, s))) return hip_fail("zero tile values", e);
         if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
@@ -480,37 +495,45 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
     if (n_e == 0) return SMAT_OK;
     if (!vals) return fail(SMAT_ERR_INVALID_ARG, "vals is NULL");
     try {
-        std::vector<uint16_t> raw(static_cast<size_t>(h->slots_units) * 128);
+        const size_t es = static_cast<size_t>(h->elem_bytes);
+        std::vector<uint8_t> raw(static_cast<size_t>(h->slots_units) * 128 * es);
         hipStream_t s = static_cast<hipStream_t>(stream);
-        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, raw.size() * 2, hipMemcpyDeviceToHost, s));
+        int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, raw.size(), hipMemcpyDeviceToHost, s));
         if (e) return hip_fail("read block values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("read block values", e);
-        uint16_t* out = static_cast<uint16_t*>(vals);
-        std::memset(out, 0, n_e * 512);
+        // value number `at` of the device copy / of the canonical output, whatever the element size
+        auto get = [&](size_t at) -> uint16_t {
+            return es == 2 ? reinterpret_cast<const uint16_t*>(raw.data())[at] : raw[at];
+        };
+        auto put = [&](size_t at, uint16_t v) {
+            if (es == 2) static_cast<uint16_t*>(vals)[at] = v;
+            else static_cast<uint8_t*>(vals)[at] = static_cast<uint8_t>(v);
+        };
+        std::memset(vals, 0, n_e * 256 * es);
         for (size_t br = 0; br < static_cast<size_t>(h->bcsr.nbr); ++br) {
             const int L = 2 << h->row_class[br];
-            const int halves = smat::pack_halves(L);
-            const uint16_t* src = raw.data() + static_cast<size_t>(h->slots_off[br]) * 128;
-            for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, src += halves) {
+            const int elems = smat::pack_elems(L);
+            size_t src = static_cast<size_t>(h->slots_off[br]) * 128;
+            for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, src += static_cast<size_t>(elems)) {
                 uint8_t used[512];
                 std::memset(used, 0, sizeof(used));
                 int rank = 0;
-                for (int32_t s = h->pack_first[static_cast<size_t>(pk)]; s < h->pack_first[static_cast<size_t>(pk) + 1]; ++s) {
-                    uint16_t* blk = out + static_cast<size_t>(s) * 256;
+                for (int32_t sb = h->pack_first[static_cast<size_t>(pk)]; sb < h->pack_first[static_cast<size_t>(pk) + 1]; ++sb) {
                     for (int c = 0; c < 16; ++c) {
-                        if (!(h->bcsr.col_mask[s] >> c & 1u)) continue;
+                        if (!(h->bcsr.col_mask[sb] >> c & 1u)) continue;
                         const int g = smat::slot_group(rank), kk = smat::slot_pos(rank);
                         ++rank;
                         for (int r = 0; r < 16; ++r) {
-                            const int at = smat::pack_half_index(L, r, g, kk);
-                            blk[r * 16 + c] = src[at];
+                            const int at = smat::pack_elem_index(L, r, g, kk);
+                            put(static_cast<size_t>(sb) * 256 + static_cast<size_t>(r * 16 + c), get(src + static_cast<size_t>(at)));
                             used[at] = 1;
                         }
                     }
                 }
                 // every slot that holds no occupied column must have stayed zero
-                for (int q = 0; q < halves; ++q)
-                    if (!used[q] && src[q] != 0) return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
+                for (int q = 0; q < elems; ++q)
+                    if (!used[q] && get(src + static_cast<size_t>(q)) != 0)
+                        return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
             }
         }
         return SMAT_OK;
@@ -530,7 +553,7 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (ldb < N || ldc < N) return fail(SMAT_ERR_INVALID_ARG, "leading dimension smaller than N");
     if (N > 16 * 65535) return fail(SMAT_ERR_UNSUPPORTED, "N above 1048560");
     const int64_t K = h->csr.K;
-    if (K > 0 && ((K - 1) * ldb + N) * 2 >= (int64_t{1} << 31))
+    if (K > 0 && ((K - 1) * ldb + N) * h->elem_bytes >= (int64_t{1} << 31))
         return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
     if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
     // The dense path needs 16-byte rows of B at 8-column granularity; otherwise every block row
@@ -540,7 +563,7 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     // spreads that over all compute units (about 10 TB/s of L1 fills).  Both estimates are
     // measured rates; the faster path is taken.
     const bool bf16 = h->dtype == SMAT_BF16;
-    bool use_tiles = h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
+    bool use_tiles = h->elem_bytes == 2 && h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
     if (h->dense_mode < 0) use_tiles = false;
     if (use_tiles && h->dense_mode == 0) {
         const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
@@ -555,13 +578,13 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     int e = 0;
     if (use_tiles) {
         if (h->dev_rest.n_order > 0)
-            e = smat::launch_spmm(h->dev_rest, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);
+            e = smat::launch_spmm(h->dev_rest, h->dtype, dB, ldb, dC, ldc, N, stream, &variant);
         const char* dense_variant = "";
         if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &dense_variant);
         name = std::string(dense_variant) + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
         g_kernel = name.c_str();
     } else {
-        e = smat::launch_spmm(h->dev, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &variant);
+        e = smat::launch_spmm(h->dev, h->dtype, dB, ldb, dC, ldc, N, stream, &variant);
         g_kernel = variant;
     }
     if (e) return hip_fail("launch spmm", e);

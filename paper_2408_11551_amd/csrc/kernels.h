@@ -13,11 +13,11 @@ struct DeviceBcsr {
     const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
     // Launch table, one record of four words per workgroup of the per-row kernel, in launch
     // order: block row | row class << 28, number of packs, start of the row's slot table in
-    // 32-byte units (its values start at the same count of 256-byte units), 0.
+    // 32-byte units (its values start at the same count of 128-element units), 0.
     const int32_t* work = nullptr;       // [4 * n_order]
     int64_t n_order = 0;                 // rows the per-row kernel is launched for
     const uint32_t* slots = nullptr;     // slot tables: per pack 4 groups x L entries (L by row class)
-    const uint16_t* vals = nullptr;      // block values: per pack 64 L halves
+    const void* vals = nullptr;          // block values: per pack 64 L elements of 2 bytes (fp16, bf16) or 1 byte
     // bind-time value scatter only
     const int32_t* pack_ptr = nullptr;   // [nbr+1] pack offsets per block row
     const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table, 32-byte units
@@ -55,13 +55,18 @@ struct DenseTiles {
 int launch_fill_zero(void* dst, size_t n16, void* stream);
 
 // Scatters the CSR values into the device block layout.  csr_* are device copies of the
-// caller's CSR; vals must have been zeroed.
+// caller's CSR (values as 16-bit words, 8-bit types in the low byte); vals_out holds elements
+// of elem_bytes (1 or 2) and must have been zeroed.
 int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int32_t* csr_col_idx,
-                     const uint16_t* csr_vals, uint16_t* vals_out, void* stream);
+                     const uint16_t* csr_vals, void* vals_out, int elem_bytes, void* stream);
 
-// C = A * B.  Returns a hipError_t as int; *variant receives a static string naming the kernel.
-int launch_spmm(const DeviceBcsr& d, bool bf16, const void* B, int64_t ldb, float* C, int64_t ldc,
+// C = A * B.  dtype is a smat_dtype_t; C holds fp32, or int32 for the integer type.  Returns
+// a hipError_t as int; *variant receives a static string naming the kernel.
+int launch_spmm(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
                 int64_t N, void* stream, const char** variant);
+// the 8-bit types (their kernels are compiled in a translation unit of their own)
+int launch_spmm_8bit(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
+                     int64_t N, void* stream, const char** variant);
 
 // Scatters the CSR values of the dense super rows into the tile layout (vals zeroed before).
 int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,

@@ -17,11 +17,12 @@
 // ceil(n / 4) B-row loads per lane instead of 8, and only ceil(n / 8) of the four operand
 // dwords carry data.
 //
-// Block values: 64 L halves per pack, L = 2, 4 or 8 by the class of the block row (its fullest
-// pack has at most 4 L occupied columns, so positions L .. 7 of every lane group are empty in
-// the whole row and are not stored).  Lane l = 16 g + i of the wavefront owns halves
-// [L l, L l + L): row i of the block row, k slots 8 g .. 8 g + L - 1.  A row of class 8 stores
-// 1 KiB per pack, a row of class 2 a quarter of that.
+// Block values: 64 L elements per pack (2 bytes each for fp16 / bf16, 1 byte for the 8-bit
+// types), L = 2, 4 or 8 by the class of the block row (its fullest pack has at most 4 L occupied
+// columns, so positions L .. 7 of every lane group are empty in the whole row and are not
+// stored).  Lane l = 16 g + i of the wavefront owns elements [L l, L l + L): row i of the block
+// row, k slots 8 g .. 8 g + L - 1.  A 16-bit row of class 8 stores 1 KiB per pack, a row of
+// class 2 a quarter of that.
 //
 // Slot table: for every pack, 4 lane groups x L entries of 32 bits; entry [g][kk] is the row
 // of B that slot (g, kk) multiplies, or K (one past the last row) for an empty slot.  A lane
@@ -44,11 +45,11 @@ namespace smat {
 
 constexpr int kPackColumns = 32;     // k extent of the instruction
 
-// halves of block values stored per pack in a row of class L
-SMAT_HD inline int pack_halves(int L) { return 64 * L; }
+// block values stored per pack in a row of class L
+SMAT_HD inline int pack_elems(int L) { return 64 * L; }
 
-// half index, inside the pack, of row i in slot (g, kk), kk < L
-SMAT_HD inline int pack_half_index(int L, int i, int g, int kk) { return (16 * g + i) * L + kk; }
+// index, inside the pack, of the value of row i in slot (g, kk), kk < L
+SMAT_HD inline int pack_elem_index(int L, int i, int g, int kk) { return (16 * g + i) * L + kk; }
 
 // slot of the occupied column with rank j (number of occupied columns of the pack before it)
 SMAT_HD inline int slot_group(int j) { return j & 3; }

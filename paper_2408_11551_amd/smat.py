@@ -1,7 +1,8 @@
 """ctypes binding of libsmat.so: argument marshalling only, one Python function per C entry point.
 
 Host arrays are numpy arrays, device arrays are torch tensors on a HIP device (torch is used
-for device memory and streams, nothing else).  There is no fallback: if the shared library is
+for device memory and streams, nothing else; it is imported before the library is loaded so
+that both share one HIP runtime).  There is no fallback: if the shared library is
 missing and cannot be built, importing this module fails.
 """
 from __future__ import annotations
@@ -13,9 +14,23 @@ import numpy as np
 
 from . import build as _build
 
-SMAT_F16 = 0
-SMAT_BF16 = 1
-_DTYPES = {"f16": SMAT_F16, "bf16": SMAT_BF16, SMAT_F16: SMAT_F16, SMAT_BF16: SMAT_BF16}
+SMAT_F16, SMAT_BF16, SMAT_E4M3, SMAT_E5M2, SMAT_I8 = 0, 1, 2, 3, 4
+_DTYPES = {"f16": SMAT_F16, "bf16": SMAT_BF16, "e4m3": SMAT_E4M3, "e5m2": SMAT_E5M2, "i8": SMAT_I8}
+
+
+def _dtype_code(dtype) -> int:
+    """Name -> smat_dtype_t; numbers pass through (the library rejects unknown ones)."""
+    if isinstance(dtype, str):
+        if dtype not in _DTYPES:
+            raise ValueError(f"unknown dtype {dtype!r}")
+        return _DTYPES[dtype]
+    return int(dtype)
+
+
+def _elem_type(dtype):
+    """numpy type carrying one value of A or B."""
+    return np.uint8 if _dtype_code(dtype) in (SMAT_E4M3, SMAT_E5M2, SMAT_I8) else np.uint16
+
 
 _STATUS = {0: "SMAT_OK", 1: "SMAT_ERR_INVALID_ARG", 2: "SMAT_ERR_BAD_CSR", 3: "SMAT_ERR_UNSUPPORTED",
            4: "SMAT_ERR_ALLOC", 5: "SMAT_ERR_NOT_BOUND", 6: "SMAT_ERR_HIP"}
@@ -38,6 +53,11 @@ def lib_path() -> str:
 
 
 def _load():
+    # PyTorch ships its own copy of the HIP runtime.  It has to be in the process before
+    # libsmat.so is, so that the library binds to that same copy: device pointers and streams
+    # that torch hands over then belong to the runtime the library calls.  (Loaded the other way
+    # round, the process holds two runtimes, and the library's may not even find the device.)
+    import torch  # noqa: F401
     path = lib_path()
     if not os.path.exists(path):
         _build.build()                      # raises if hipcc is missing or the build fails
@@ -119,10 +139,14 @@ def smat_default_options() -> dict:
 
 def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
                     block_h=16, block_w=16, dense_tiles=0) -> int:
-    """row_ptr int64[M+1], col_idx int32[nnz], vals_bits uint16[nnz] (HOST) -> opaque handle."""
+    """row_ptr int64[M+1], col_idx int32[nnz], vals_bits uint16[nnz] (uint8 for the 8-bit types)
+    (HOST) -> opaque handle."""
     rp, rp_p = _host(row_ptr, np.int64)
     ci, ci_p = _host(col_idx, np.int32)
-    vb, vb_p = _host(vals_bits, np.uint16)
+    vals_bits = np.asarray(vals_bits)
+    if vals_bits.dtype.itemsize != np.dtype(_elem_type(dtype)).itemsize:
+        raise ValueError(f"vals_bits must hold {np.dtype(_elem_type(dtype)).itemsize}-byte values for dtype {dtype!r}")
+    vb, vb_p = _host(vals_bits, _elem_type(dtype))
     if rp.size != M + 1:
         raise ValueError("row_ptr must have M+1 entries")
     nnz = int(rp[-1]) if rp.size else 0
@@ -130,7 +154,7 @@ def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_
         raise ValueError("col_idx / vals shorter than row_ptr[M]")
     opt = _Options(block_h, block_w, reorder, tau_permille, dense_tiles)
     out = ctypes.c_void_p()
-    _check(_lib.smat_preprocess(M, K, rp_p, ci_p, vb_p, _DTYPES.get(dtype, dtype), ctypes.byref(opt), ctypes.byref(out)))
+    _check(_lib.smat_preprocess(M, K, rp_p, ci_p, vb_p, _dtype_code(dtype), ctypes.byref(opt), ctypes.byref(out)))
     return out.value
 
 
@@ -154,11 +178,12 @@ def smat_export_perm(h, M) -> np.ndarray:
     return perm
 
 
-def smat_export_bcsr(h, with_vals=True):
+def smat_export_bcsr(h, with_vals=True, dtype="f16"):
+    """dtype: the handle's dtype (decides the element size of vals)."""
     info = smat_get_info(h)
     row_ptr = np.empty(info["n_block_rows"] + 1, dtype=np.int32)
     col_idx = np.empty(info["n_blocks"], dtype=np.int32)
-    vals = np.empty((info["n_blocks"], 16, 16), dtype=np.uint16) if with_vals else None
+    vals = np.empty((info["n_blocks"], 16, 16), dtype=_elem_type(dtype)) if with_vals else None
     _check(_lib.smat_export_bcsr(h, row_ptr.ctypes.data_as(ctypes.c_void_p),
                                  col_idx.ctypes.data_as(ctypes.c_void_p),
                                  vals.ctypes.data_as(ctypes.c_void_p) if with_vals else None))
@@ -177,19 +202,21 @@ def smat_bind_device(h, workspace, stream=None):
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
-def smat_export_device_vals(h, stream=None) -> np.ndarray:
+def smat_export_device_vals(h, stream=None, dtype="f16") -> np.ndarray:
     n_e = smat_get_info(h)["n_blocks"]
-    vals = np.empty((n_e, 16, 16), dtype=np.uint16)
+    vals = np.empty((n_e, 16, 16), dtype=_elem_type(dtype))
     _check(_lib.smat_export_device_vals(h, vals.ctypes.data_as(ctypes.c_void_p), _stream_ptr(stream)))
     return vals
 
 
 def smat_spmm(h, B, C, N=None, stream=None):
-    """B: device tensor [K, >=N] of 16-bit elements, C: device float32 tensor [M, >=N]; rows contiguous."""
+    """B: device tensor [K, >=N] of the handle's element size (2 bytes, or 1 for the 8-bit
+    types; the library does not know the tensor's type, the caller must match the handle);
+    C: device tensor [M, >=N] of 4-byte elements (float32, int32 for "i8"); rows contiguous."""
     if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
         raise ValueError("B and C must be 2-D with unit column stride")
-    if B.element_size() != 2 or C.element_size() != 4:
-        raise ValueError("B must hold 16-bit elements and C 32-bit floats")
+    if B.element_size() not in (1, 2) or C.element_size() != 4:
+        raise ValueError("B must hold 1- or 2-byte elements and C 4-byte elements")
     if N is None:
         N = B.shape[1]
     _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
@@ -243,8 +270,11 @@ class SmatMatrix:
         import torch
         if N is None:
             N = B.shape[1]
+        if B.element_size() != np.dtype(_elem_type(self.dtype)).itemsize:
+            raise ValueError(f"B must hold {np.dtype(_elem_type(self.dtype)).itemsize}-byte elements for dtype {self.dtype!r}")
         if C is None:
-            C = torch.empty((self.M, N), dtype=torch.float32, device=B.device)
+            C = torch.empty((self.M, N), dtype=torch.int32 if _dtype_code(self.dtype) == SMAT_I8 else torch.float32,
+                            device=B.device)
         smat_spmm(self.handle, B, C, N)
         return C
 

@@ -9,7 +9,7 @@ import pytest
 
 import paper_2408_11551_amd as S
 from oracle import smat_ref as R
-from workloads import OCCUPANCY_SPEC, occupancy_csr, random_csr, band_csr, make_config
+from workloads import OCCUPANCY_SPEC, occupancy_csr, random_csr, band_csr, make_config, recast
 
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
@@ -115,6 +115,33 @@ def test_bad_input_becomes_status_codes():
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", reorder=2))
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, 7))
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(-1, 4, np.zeros(0, np.int64), ci, v, "f16"))
+
+
+@pytest.mark.parametrize("dtype", ["e4m3", "e5m2", "i8"])
+def test_8bit_types_preprocess_like_the_16bit_ones(dtype):
+    """The structure does not depend on the storage type; the exported block values are the
+    caller's bytes; the device copy of the values takes half the bytes of the fp16 one."""
+    w16 = random_csr(130, 333, 1, 0.05, seed=4)
+    w = recast(w16, dtype, a_scale=127.0 if dtype == "i8" else 1.0)
+    h, h16 = (S.smat_preprocess(x.M, x.K, x.row_ptr, x.col_idx, x.a_bits, x.dtype) for x in (w, w16))
+    try:
+        perm, n_e, n_id, used, (rp, ci, v) = _oracle_structure(w, 700)
+        assert v.dtype == np.uint8 and S.smat_get_info(h) == S.smat_get_info(h16)
+        assert np.array_equal(S.smat_export_perm(h, w.M), perm)
+        grp, gci, gv = S.smat_export_bcsr(h, dtype=dtype)
+        assert gv.dtype == np.uint8
+        assert np.array_equal(grp, rp) and np.array_equal(gci, ci) and np.array_equal(gv, v)
+        a, b = S.smat_get_layout_info(h), S.smat_get_layout_info(h16)
+        assert a["n_packs"] == b["n_packs"] and a["table_bytes"] == b["table_bytes"] and a["n_columns"] == b["n_columns"]
+        assert 2 * a["value_bytes"] == b["value_bytes"]
+        assert S.smat_device_bytes(h) < S.smat_device_bytes(h16)
+    finally:
+        S.smat_destroy(h)
+        S.smat_destroy(h16)
+    # the dense-tile kernel is 16-bit only: asking for it is refused, the automatic choice never takes it
+    _expect("SMAT_ERR_UNSUPPORTED", lambda: S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, dtype, dense_tiles=1))
+    with pytest.raises(ValueError):
+        S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w16.a_bits, dtype)       # 2-byte values for a 1-byte type
 
 
 def test_spmm_without_bind_is_an_error_not_a_fallback():

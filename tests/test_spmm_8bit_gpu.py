@@ -1,0 +1,204 @@
+"""GPU parity tests for the 8-bit operand types (e4m3, e5m2, i8), through the C ABI against the
+CPU oracle.
+
+Bars: structure, permutation and device block values bit-exact; C bit-exact for i8 (int32
+accumulation of integers -- the inputs keep every sum far below 2^31); for the two 8-bit
+floating-point types |err| <= 1e-2 * (|A||B|) as for the 16-bit types, and the tighter 2e-4
+that follows from the arithmetic (a product of two such values has at most 8 significant bits
+and is exact in fp32, so only the fp32 additions round).
+"""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+torch = pytest.importorskip("torch")
+
+import paper_2408_11551_amd as S            # noqa: E402
+from oracle import smat_ref as R            # noqa: E402
+from workloads import random_csr, occupancy_csr, OCCUPANCY_SPEC, make_config, recast  # noqa: E402
+
+DT8 = ["e4m3", "e5m2", "i8"]
+REL_BAR = 1e-2
+REL_TIGHT = 2e-4
+UNTOUCHED = 0x5A5A5A5A        # C is filled with this word before a launch
+
+
+def _to8(w, dtype, b_scale=None):
+    """A workload drawn for fp16 re-rounded to an 8-bit type; i8 stretches U(-1,1) to -127..127."""
+    if dtype == "i8":
+        return recast(w, dtype, a_scale=127.0, b_scale=b_scale if b_scale is not None else 40.0)
+    return recast(w, dtype)
+
+
+def _dev_b(w, ldb=None, shift=0):
+    """B on the device; with ldb > N the padding holds 0x7F (NaN in both float formats, 127 in
+    i8: never to be used); shift > 0 moves the base address off its alignment by that many bytes."""
+    ldb = ldb or w.N
+    flat = torch.full((w.K * ldb + shift,), 0x7F, dtype=torch.uint8)
+    rows = flat[shift:].view(w.K, ldb) if w.K else flat[shift:].view(0, ldb)
+    rows[:, :w.N] = torch.from_numpy(w.b_bits.reshape(w.K, w.N))
+    dev = flat.cuda()
+    return dev[shift:].view(w.K, ldb)[:, :w.N]
+
+
+def _oracle_c(oracle_c, w):
+    return oracle_c.spmm_ref_c(w.M, w.K, w.N, w.row_ptr, w.col_idx, R.decode8(w.a_bits, w.dtype), R.decode8(w.b_bits, w.dtype))
+
+
+def _spmm(m, w, b, ldc=None):
+    ldc = ldc or w.N
+    cfull = torch.full((w.M, ldc), UNTOUCHED, dtype=torch.int32, device="cuda")
+    if w.dtype != "i8":
+        cfull = cfull.view(torch.float32)
+    S.smat_spmm(m.handle, b, cfull[:, :w.N], w.N)
+    torch.cuda.synchronize()
+    if ldc > w.N:
+        assert (cfull[:, w.N:].view(torch.int32) == UNTOUCHED).all()       # nothing written beyond column N
+    return cfull[:, :w.N].cpu().numpy()
+
+
+def _check(got, c_ref, s_ref, w):
+    if w.dtype == "i8":
+        assert got.dtype == np.int32
+        assert np.abs(c_ref).max() < 2.0 ** 31
+        assert np.array_equal(got.astype(np.float64), c_ref)
+    else:
+        err = np.abs(got.astype(np.float64) - c_ref)
+        assert np.all(err <= REL_BAR * s_ref), f"max err/S = {np.max(err / np.maximum(s_ref, 1e-300)):.3e}"
+        assert np.all(err <= REL_TIGHT * s_ref + 1e-30), f"tight: {np.max(err / np.maximum(s_ref, 1e-300)):.3e}"
+    empty = np.diff(w.row_ptr) == 0
+    assert np.all(got[empty] == 0)
+
+
+def _run(w, oracle_c, reorder=1, ldb=None, ldc=None, shift=0):
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder)
+    try:
+        got = _spmm(m, w, _dev_b(w, ldb, shift), ldc)
+        c_ref, s_ref = _oracle_c(oracle_c, w)
+        _check(got, c_ref, s_ref, w)
+        return m, got
+    except Exception:
+        m.close()
+        raise
+
+
+SHAPES = [
+    # M, K, N, density
+    (16, 16, 16, 1.0),
+    (1, 1, 1, 1.0),
+    (15, 17, 3, 0.5),
+    (64, 64, 64, 0.1),
+    (100, 200, 8, 0.05),
+    (130, 70, 24, 0.2),
+    (257, 129, 100, 0.03),
+    (300, 300, 130, 0.02),
+    (48, 1024, 256, 0.3),
+    (90, 300, 120, 0.1),
+    (40, 600, 272, 0.2),
+    (72, 90, 528, 0.1),
+    (33, 40, 7, 0.0),
+]
+
+
+@pytest.mark.parametrize("dtype", DT8)
+def test_small_shapes_all_load_widths(dtype, oracle_c):
+    widths = set()
+    for M, K, N, density in SHAPES:
+        w = _to8(random_csr(M, K, N, density, seed=M + K + N, b_dist="normal"), dtype)
+        m, _ = _run(w, oracle_c)
+        if w.nnz:
+            name = S.smat_last_kernel()
+            assert name.startswith(f"spmm_{dtype}_n"), name
+            widths.add(int(name.split("_n")[1].split("k")[0]))
+        # structure and device-side block values, bit-exact
+        pats = R.block_pattern(M, w.row_ptr, w.col_idx)
+        perm, n_e, n_id, used = R.choose_perm(pats, 700)
+        rp, ci, v = R.bcsr_from_csr(M, K, w.row_ptr, w.col_idx, w.a_bits, perm)
+        assert v.dtype == np.uint8
+        assert np.array_equal(S.smat_export_perm(m.handle, M), perm)
+        grp, gci, gv = S.smat_export_bcsr(m.handle, dtype=dtype)
+        assert np.array_equal(grp, rp) and np.array_equal(gci, ci) and np.array_equal(gv, v)
+        assert np.array_equal(S.smat_export_device_vals(m.handle, dtype=dtype), v)
+        m.close()
+    assert widths == {1, 2, 4, 8, 16}, widths        # every load width of the 8-bit kernels ran
+
+
+@pytest.mark.parametrize("N", [8, 40, 128, 272])
+@pytest.mark.parametrize("dtype", DT8)
+def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
+    # the prescribed-occupancy rows (pack boundaries, one row per class, an empty row, a ragged
+    # last block column): all three loops of the kernel in one launch; small integers, exact in
+    # every one of the three types
+    w = recast(occupancy_csr(OCCUPANCY_SPEC, K=16 * 64 + 5, N=N, seed=11 + N), dtype)
+    for reorder in (0, 1):
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder)
+        got = _spmm(m, w, _dev_b(w))
+        c_ref, _ = _oracle_c(oracle_c, w)
+        assert np.array_equal(got.astype(np.float64), c_ref)
+        assert S.smat_last_kernel().endswith("_l8")
+        perm = S.smat_export_perm(m.handle, w.M)
+        _, _, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+        assert np.array_equal(S.smat_export_device_vals(m.handle, dtype=dtype), v)
+        m.close()
+    sparse_rows = [OCCUPANCY_SPEC[4], OCCUPANCY_SPEC[5], [], OCCUPANCY_SPEC[7], [(2, 3), (9, 5)]]
+    for spec, suffix in ((sparse_rows, "_l4"), ([sparse_rows[0], [], sparse_rows[3]], "_l2")):
+        w2 = recast(occupancy_csr(spec, K=16 * 64 + 5, N=N, seed=5 + N), dtype)
+        m = S.SmatMatrix(w2.M, w2.K, w2.row_ptr, w2.col_idx, w2.a_bits, w2.dtype, reorder=0)
+        got = _spmm(m, w2, _dev_b(w2))
+        c_ref, _ = _oracle_c(oracle_c, w2)
+        assert np.array_equal(got.astype(np.float64), c_ref)
+        assert S.smat_last_kernel().endswith(suffix), S.smat_last_kernel()
+        m.close()
+
+
+@pytest.mark.parametrize("dtype", DT8)
+def test_long_rows_are_split_over_waves(dtype, oracle_c):
+    # few block rows with hundreds of packs each: several waves share a row and their partial
+    # tiles are summed through LDS (integer sums for i8)
+    for M, K, N, density in ((64, 8192, 64, 0.3), (48, 6000, 272, 0.05), (32, 4096, 24, 0.5)):
+        w = _to8(random_csr(M, K, N, density, seed=K + N, b_dist="uniform"), dtype, b_scale=100.0)
+        m, _ = _run(w, oracle_c)
+        name = S.smat_last_kernel()
+        assert int(name.split("k")[1].split("s")[0]) > 1, name
+        m.close()
+
+
+@pytest.mark.parametrize("dtype", DT8)
+def test_leading_dimensions_and_misaligned_base(dtype, oracle_c):
+    base = random_csr(150, 170, 64, 0.08, seed=21, b_dist="normal")
+    w = _to8(base, dtype)
+    for ldb, ldc, shift in ((64, 64, 0), (80, 68, 0), (67, 65, 0), (64, 64, 1), (72, 64, 4), (96, 72, 8)):
+        m, _ = _run(w, oracle_c, ldb=ldb, ldc=ldc, shift=shift)
+        nt = int(S.smat_last_kernel().split("_n")[1].split("k")[0])
+        assert ldb % nt == 0 and shift % nt == 0, (S.smat_last_kernel(), ldb, shift)
+        m.close()
+
+
+@pytest.mark.parametrize("dtype", DT8)
+def test_uniform_full_size(dtype, oracle_c):
+    # the bench workload (16384^2, 1e-3 dense, N = 128) in the 8-bit types, every element checked
+    w = _to8(make_config("uniform"), dtype)
+    m, _ = _run(w, oracle_c)
+    assert S.smat_last_kernel().startswith(f"spmm_{dtype}_n8"), S.smat_last_kernel()
+    info = S.smat_get_layout_info(m.handle)
+    m16 = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, make_config("uniform").a_bits, "f16", bind=False)
+    info16 = S.smat_get_layout_info(m16.handle)
+    assert info["n_packs"] == info16["n_packs"] and info["value_bytes"] * 2 == info16["value_bytes"]
+    assert info["table_bytes"] == info16["table_bytes"]
+    m.close()
+    m16.close()
+
+
+def test_hidden_blocks_i8_bit_exact_at_scale(oracle_c):
+    # 21 M stored entries in dense hidden blocks, rows of C summing 650 products each: int32, exact
+    w = recast(make_config("hidden_blocks"), "i8", a_scale=127.0, b_scale=127.0)
+    m, _ = _run(w, oracle_c)
+    m.close()
+
+
+def test_dense_tiles_are_refused_for_8bit():
+    w = _to8(random_csr(256, 128, 64, 0.5, seed=1), "e4m3")
+    with pytest.raises(S.SmatError) as e:
+        S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1, bind=False)
+    assert e.value.status_name == "SMAT_ERR_UNSUPPORTED"
