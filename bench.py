@@ -24,6 +24,7 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 matrix peak
+MFMA_PEAK_TFLOPS_8BIT = 5000.0 # dense fp8 / int8 matrix peak (reached by the K=64/128 forms; the path uses K=32)
 
 WORKLOAD_TEXT = {
     "tiny": "tiny unstructured 1024x1024 1% fp16, B 1024x64",
@@ -40,18 +41,18 @@ MEASURED_TRAFFIC_BYTES = {"uniform": 48.2e6, "banded": 139.0e6, "powerlaw": 708.
                           "hidden_blocks": 467.6e6, "pruned_weight": 201.6e6}
 
 
-def algorithmic_bytes(layout, K, N, M):
+def algorithmic_bytes(layout, K, N, M, es=2):
     """What one launch must move: the device copy of A (values of every pack, tables) read
     once, B read once, C written once.  Rows of B gathered again and again come from the
     caches and are reported separately."""
-    return layout["value_bytes"] + layout["table_bytes"] + K * N * 2 + M * N * 4
+    return layout["value_bytes"] + layout["table_bytes"] + K * N * es + M * N * 4
 
 
-def bcsr_format_bytes(n_e, nbr, M, K, N):
+def bcsr_format_bytes(n_e, nbr, M, K, N, es=2):
     """The same count for the paper's BCSR as it stands (512 B of values and a 4-byte column
     per stored block, rowPtr, perm), for comparison: the packs leave out the columns of a block
     that hold nothing."""
-    return n_e * (512 + 4) + (nbr + 1) * 4 + M * 4 + K * N * 2 + M * N * 4
+    return n_e * (256 * es + 4) + (nbr + 1) * 4 + M * 4 + K * N * es + M * N * 4
 
 
 def run_probes(S, torch, dev, stream):
@@ -99,6 +100,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--config", default="uniform", choices=list(WORKLOAD_TEXT))
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--dtype", default=None, choices=["f16", "bf16", "e4m3", "e5m2", "i8"],
+                    help="re-round the workload's values to another operand type of the matrix units "
+                         "(default: the type the workload is defined in; i8 scales A by 127 and B by 40)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--dense-tiles", type=int, default=0, choices=[-1, 0, 1],
                     help="block-dense tile kernel: 0 automatic (default), 1 wherever it applies, -1 never")
@@ -117,11 +121,16 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the SpMM path has no CPU fallback")
     import paper_2408_11551_amd as S
-    from workloads import make_config
+    from workloads import make_config, recast
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     w = make_config(args.config, seed=args.seed)
+    recast_to = args.dtype if args.dtype and args.dtype != w.dtype else None
+    if recast_to:
+        w = recast(w, recast_to, a_scale=127.0 if recast_to == "i8" else 1.0, b_scale=40.0 if recast_to == "i8" else 1.0)
+    es = w.b_bits.dtype.itemsize                   # bytes per value of A and B
+    mfma_peak = MFMA_PEAK_TFLOPS if es == 2 else MFMA_PEAK_TFLOPS_8BIT
 
     t0 = time.perf_counter()
     h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=args.dense_tiles)
@@ -134,8 +143,8 @@ def main():
     S.smat_bind_device(h, ws)
     t_bind = time.perf_counter() - t0
 
-    B = torch.from_numpy(w.b_bits.view(np.int16).reshape(w.K, w.N)).to(dev)
-    C = torch.empty((w.M, w.N), dtype=torch.float32, device=dev)
+    B = torch.from_numpy(w.b_bits.view(np.int16 if es == 2 else np.uint8).reshape(w.K, w.N)).to(dev)
+    C = torch.empty((w.M, w.N), dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
@@ -166,12 +175,13 @@ def main():
     useful_flop = 2.0 * w.nnz * w.N
     stored_flop = 2.0 * info["n_blocks"] * 256 * w.N
     issued_flop = 2.0 * layout["n_packs"] * 16 * 32 * (-(-w.N // 16) * 16)      # one MFMA 16x16x32 per pack and 16 columns
-    bytes_alg = algorithmic_bytes(layout, w.K, w.N, w.M)
-    bytes_bcsr = bcsr_format_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N)
+    bytes_alg = algorithmic_bytes(layout, w.K, w.N, w.M, es)
+    bytes_bcsr = bcsr_format_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N, es)
     achieved_gbs = bytes_alg / (kernel_ms * 1e-3) / 1e9
     issued_tflops = issued_flop / (kernel_ms * 1e-3) / 1e12
     # the roofline that binds: time at peak for the bytes against time at peak for the flops
-    mfma_bound = issued_flop / (MFMA_PEAK_TFLOPS * 1e12) > bytes_alg / (HBM_PEAK_GBS * 1e9)
+    mfma_bound = issued_flop / (mfma_peak * 1e12) > bytes_alg / (HBM_PEAK_GBS * 1e9)
+    traffic = None if recast_to else MEASURED_TRAFFIC_BYTES.get(args.config)     # counters were read on the default types
 
     # the paper's protocol (Methodology): one warm-up, ten timed launches, each between its own events
     evs = []
@@ -214,8 +224,8 @@ def main():
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import cref, smat_ref
-        a64 = smat_ref.decode16(w.a_bits, w.dtype)
-        b64 = smat_ref.decode16(w.b_bits, w.dtype)
+        a64 = smat_ref.decode_bits(w.a_bits, w.dtype)
+        b64 = smat_ref.decode_bits(w.b_bits, w.dtype)
         # bounded sample: leading rows of A holding at most ~4e9 multiply-adds (whole matrix if smaller)
         budget = 4e9
         rows = int(np.searchsorted(w.row_ptr * float(w.N), budget, side="right")) - 1
@@ -245,7 +255,8 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": WORKLOAD_TEXT[args.config], "name": args.config, "seed": args.seed,
+            "workload": WORKLOAD_TEXT[args.config] + (f", values re-rounded to {recast_to}" if recast_to else ""),
+            "name": args.config, "seed": args.seed,
             "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
             "n_blocks": info["n_blocks"], "n_blocks_identity": info["n_blocks_identity"],
             "used_identity": info["used_identity"],
@@ -259,18 +270,18 @@ def main():
         "single_launch_ms": {"mean": float(single.mean()), "median": float(np.median(single)),
                              "min": float(single.min()), "cv": float(single.std() / single.mean())},
         "roofline": ({
-            "bound": "mfma", "achieved": issued_tflops, "peak": MFMA_PEAK_TFLOPS, "unit": "TFLOP/s",
-            "frac": issued_tflops / MFMA_PEAK_TFLOPS, "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "bound": "mfma", "achieved": issued_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
+            "frac": issued_tflops / mfma_peak, "traffic": traffic,
             "flops_issued": issued_flop, "kernel": kernel_name,
         } if mfma_bound else {
             "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC_BYTES.get(args.config),
+            "traffic": traffic,
             "bytes_algorithmic": bytes_alg, "kernel": kernel_name,
         }),
         "layout": {"n_packs": layout["n_packs"], "value_bytes": layout["value_bytes"],
                    "table_bytes": layout["table_bytes"], "occupied_columns": layout["n_columns"],
-                   "b_gather_bytes": layout["n_columns"] * w.N * 2,
+                   "b_gather_bytes": layout["n_columns"] * w.N * es,
                    "mfma_issued_tflops": issued_tflops, "hbm_gbs": achieved_gbs,
                    "bcsr_format_bytes": bytes_bcsr, "bcsr_format_gbs": bytes_bcsr / (kernel_ms * 1e-3) / 1e9},
         "cpu_baseline": cpu,

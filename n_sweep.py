@@ -22,6 +22,8 @@ def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--configs", nargs="+", default=["uniform", "powerlaw", "hidden_blocks"])
     ap.add_argument("--n", type=int, nargs="+", default=[1, 2, 4, 8, 16, 32, 64, 128, 256, 512, 1000])
+    ap.add_argument("--dtype", default=None, choices=["f16", "bf16", "e4m3", "e5m2", "i8"],
+                    help="re-round the workloads to another operand type (i8 scales A by 127 and B by 40)")
     ap.add_argument("--reps", type=int, default=30)
     ap.add_argument("--check-rows", type=int, default=48)
     ap.add_argument("--out", default=None)
@@ -31,7 +33,7 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("n_sweep.py: no GPU visible; the SpMM path has no CPU fallback")
     import paper_2408_11551_amd as S
-    from workloads import make_config, to_bits, from_bits
+    from workloads import make_config, to_bits, from_bits, recast
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
@@ -48,6 +50,10 @@ def main():
 
     for name in args.configs:
         w = make_config(name)
+        if args.dtype and args.dtype != w.dtype:
+            w = recast(w, args.dtype, a_scale=127.0 if args.dtype == "i8" else 1.0)
+        es = w.a_bits.dtype.itemsize
+        b_scale = 40.0 if w.dtype == "i8" else 1.0
         h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
         ws = torch.empty(S.smat_device_bytes(h), dtype=torch.uint8, device=dev)
         S.smat_bind_device(h, ws)
@@ -55,9 +61,9 @@ def main():
         rng = np.random.default_rng([7, len(name)])
         sample = np.sort(rng.choice(w.M, size=min(args.check_rows, w.M), replace=False))
         for N in args.n:
-            b_bits = to_bits(rng.standard_normal((w.K, N)), w.dtype)
-            B = torch.from_numpy(b_bits.view(np.int16)).to(dev)
-            C = torch.empty((w.M, N), dtype=torch.float32, device=dev)
+            b_bits = to_bits(rng.standard_normal((w.K, N)) * b_scale, w.dtype)
+            B = torch.from_numpy(b_bits.view(np.int16 if es == 2 else np.uint8)).to(dev)
+            C = torch.empty((w.M, N), dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=dev)
             for _ in range(3):
                 S.smat_spmm(h, B, C, N, stream)
             torch.cuda.synchronize()
@@ -79,10 +85,10 @@ def main():
                 err = np.abs(got[k] - ref)
                 assert np.all(err <= 1e-2 * bound + 1e-30), f"parity failed: {name} N={N} row {r}"
                 worst = max(worst, float(np.max(err / np.maximum(bound, 1e-300))))
-            moved = layout["value_bytes"] + layout["table_bytes"] + w.K * N * 2 + w.M * N * 4
-            rec = {"config": name, "N": N, "seconds": sec, "kernel": S.smat_last_kernel(),
+            moved = layout["value_bytes"] + layout["table_bytes"] + w.K * N * es + w.M * N * 4
+            rec = {"config": name, "dtype": w.dtype, "N": N, "seconds": sec, "kernel": S.smat_last_kernel(),
                    "useful_tflops": 2.0 * w.nnz * N / sec / 1e12, "bytes_alg": moved, "hbm_gbs": moved / sec / 1e9,
-                   "b_gather_bytes": layout["n_columns"] * N * 2, "max_err_over_bound": worst}
+                   "b_gather_bytes": layout["n_columns"] * N * es, "max_err_over_bound": worst}
             emit(rec)
             table.setdefault(name, []).append(rec)
             del B, C
