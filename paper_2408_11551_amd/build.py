@@ -9,16 +9,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libsmat.so")
-# source -> extra flags
-SOURCES = {
-    "api.cpp": [],
-    "preprocess.cpp": [],
-    "kernels.hip": [],
-    "kernels_8bit.hip": [],
+# object name -> (source, extra flags)
+UNITS = {
+    "api": ("api.cpp", []),
+    "preprocess": ("preprocess.cpp", []),
+    "kernels": ("kernels.hip", []),
+    # the per-row kernel for the 8-bit operand types: one object per type, built side by side
+    "kernels_e4m3": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=2"]),
+    "kernels_e5m2": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=3"]),
+    "kernels_i8": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=4"]),
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
-    "kernels_dense.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "probes.hip": [],
+    "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
+    "probes": ("probes.hip", []),
 }
 HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h")]
 
@@ -35,13 +38,13 @@ def is_stale() -> bool:
     if not os.path.exists(OUT):
         return True
     built = os.path.getmtime(OUT)
-    deps = [os.path.join(CSRC, f) for f in list(SOURCES) + HEADERS] + [os.path.abspath(__file__)]
+    deps = [os.path.join(CSRC, f) for f in sorted({src for src, _ in UNITS.values()}) + HEADERS] + [os.path.abspath(__file__)]
     return any(os.path.getmtime(d) > built for d in deps)
 
 
 def _compile(item):
-    src, extra = item
-    obj = os.path.join(OBJ, src + ".o")
+    name, (src, extra) = item
+    obj = os.path.join(OBJ, name + ".o")
     cmd = [HIPCC, *FLAGS, *extra, "-x", "hip", "-c", os.path.join(CSRC, src), "-o", obj]
     subprocess.run(cmd, check=True)
     return obj
@@ -51,8 +54,8 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if not force and not is_stale():
         return OUT
     os.makedirs(OBJ, exist_ok=True)
-    with ThreadPoolExecutor(max_workers=6) as pool:
-        objs = list(pool.map(_compile, SOURCES.items()))
+    with ThreadPoolExecutor(max_workers=8) as pool:
+        objs = list(pool.map(_compile, UNITS.items()))
     cmd = [HIPCC, "--offload-arch=gfx950", "-shared", "-fPIC", *objs, "-o", OUT]
     if verbose:
         print(" ".join(cmd), flush=True)

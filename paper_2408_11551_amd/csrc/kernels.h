@@ -64,9 +64,13 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // a hipError_t as int; *variant receives a static string naming the kernel.
 int launch_spmm(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
                 int64_t N, void* stream, const char** variant);
-// the 8-bit types (their kernels are compiled in a translation unit of their own)
-int launch_spmm_8bit(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
+// the 8-bit types (kernels_8bit.hip, compiled once per type)
+int launch_spmm_e4m3(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
                      int64_t N, void* stream, const char** variant);
+int launch_spmm_e5m2(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
+                     int64_t N, void* stream, const char** variant);
+int launch_spmm_i8(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
+                   int64_t N, void* stream, const char** variant);
 
 // Scatters the CSR values of the dense super rows into the tile layout (vals zeroed before).
 int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,

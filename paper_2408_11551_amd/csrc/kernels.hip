@@ -86,7 +86,10 @@ int launch_spmm(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void
     switch (dtype) {
     case kF16: return launch_dtype<kF16>(d, B, ldb, C, ldc, N, s, variant);
     case kBF16: return launch_dtype<kBF16>(d, B, ldb, C, ldc, N, s, variant);
-    default: return launch_spmm_8bit(d, dtype, B, ldb, C, ldc, N, stream, variant);
+    case kE4M3: return launch_spmm_e4m3(d, B, ldb, C, ldc, N, stream, variant);
+    case kE5M2: return launch_spmm_e5m2(d, B, ldb, C, ldc, N, stream, variant);
+    case kI8: return launch_spmm_i8(d, B, ldb, C, ldc, N, stream, variant);
+    default: return static_cast<int>(hipErrorInvalidValue);
     }
 }
 
