@@ -38,7 +38,8 @@ WORKLOAD_TEXT = {
 # HBM-side bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after a 256 MiB calibration copy), or None
 MEASURED_TRAFFIC_BYTES = {"uniform": 48.2e6, "banded": 139.0e6, "powerlaw": 708.4e6,
-                          "hidden_blocks": 467.6e6, "pruned_weight": 201.6e6}
+                          "hidden_blocks": 467.6e6, "pruned_weight": 201.6e6,
+                          "uniform:e4m3": 29.1e6}
 
 
 def algorithmic_bytes(layout, K, N, M, es=2):
@@ -181,7 +182,7 @@ def main():
     issued_tflops = issued_flop / (kernel_ms * 1e-3) / 1e12
     # the roofline that binds: time at peak for the bytes against time at peak for the flops
     mfma_bound = issued_flop / (mfma_peak * 1e12) > bytes_alg / (HBM_PEAK_GBS * 1e9)
-    traffic = None if recast_to else MEASURED_TRAFFIC_BYTES.get(args.config)     # counters were read on the default types
+    traffic = MEASURED_TRAFFIC_BYTES.get(f"{args.config}:{recast_to}" if recast_to else args.config)
 
     # the paper's protocol (Methodology): one warm-up, ten timed launches, each between its own events
     evs = []
