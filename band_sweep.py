@@ -53,6 +53,9 @@ def main():
     ap.add_argument("--fit-max", type=int, default=4096)
     ap.add_argument("--reps", type=int, default=20)
     ap.add_argument("--check-rows", type=int, default=64)
+    ap.add_argument("--ablation", action="store_true",
+                    help="also time the three reduced kernels (block-grid walk, BCSR iteration, BCSR iteration + one "
+                         "MFMA per block) on the canonical BCSR, as in the paper's figure of optimisation steps")
     ap.add_argument("--out", default=None)
     args = ap.parse_args()
 
@@ -98,6 +101,10 @@ def main():
         info, layout = S.smat_get_info(h), S.smat_get_layout_info(h)
         ws = torch.empty(S.smat_device_bytes(h), dtype=torch.uint8, device=dev)
         S.smat_bind_device(h, ws)
+        area = None
+        if args.ablation:
+            area = torch.empty(S.smat_ablation_bytes(h), dtype=torch.uint8, device=dev)
+            S.smat_ablation_bind(h, area)
         for N in args.n:
             bb = np.ascontiguousarray(w.b_bits.reshape(w.K, w.N)[:, :N])
             B = torch.from_numpy(bb.view(np.int16)).to(dev)
@@ -105,19 +112,23 @@ def main():
             sec = time_launches(lambda: S.smat_spmm(h, B, C, N, stream), stream, torch, args.reps)
             kernel = S.smat_last_kernel()
             # self-check on a sample of rows: the definition in fp64, bar 1e-2 * |A||B|
-            got = C.cpu().numpy().astype(np.float64)
             sample = np.sort(rng.choice(M, size=min(args.check_rows, M), replace=False))
             b64 = from_bits(bb.reshape(-1), w.dtype).reshape(w.K, N)
-            worst = 0.0
+            refs, bounds = [], []
             for r in sample:
                 lo, hi = int(w.row_ptr[r]), int(w.row_ptr[r + 1])
                 av = from_bits(w.a_bits[lo:hi], w.dtype)
                 rows = b64[w.col_idx[lo:hi]]
-                ref = av @ rows
-                bound = np.abs(av) @ np.abs(rows)
-                err = np.abs(got[r] - ref)
-                assert np.all(err <= 1e-2 * bound + 1e-30), f"parity failed at b={b} N={N} row {r}"
-                worst = max(worst, float(np.max(err / np.maximum(bound, 1e-300))))
+                refs.append(av @ rows)
+                bounds.append(np.abs(av) @ np.abs(rows))
+            refs, bounds = np.stack(refs), np.stack(bounds)
+
+            def check(c_dev, what):
+                err = np.abs(c_dev[torch.from_numpy(sample).to(dev)].cpu().numpy().astype(np.float64) - refs)
+                assert np.all(err <= 1e-2 * bounds + 1e-30), f"parity failed: {what} at b={b} N={N}"
+                return float(np.max(err / np.maximum(bounds, 1e-300)))
+
+            worst = check(C, "library kernel")
             nnz = w.nnz
             rec = {"what": "spmm", "b": b, "N": N, "nnz": nnz, "sparsity": 1.0 - nnz / float(M) / M,
                    "n_blocks": info["n_blocks"], "n_packs": layout["n_packs"], "seconds": sec, "kernel": kernel,
@@ -125,6 +136,14 @@ def main():
                    "dense_effective_tflops": 2.0 * nnz * N / dense_s[N] / 1e12,
                    "speedup_over_dense": dense_s[N] / sec, "max_err_over_bound": worst,
                    "gen_s": t_gen, "preprocess_s": t_pre}
+            if args.ablation:
+                # the reduced kernels, each checked on the same sample of rows
+                for level, label in ((0, "grid_walk"), (1, "bcsr"), (2, "bcsr_mfma")):
+                    C2 = torch.empty_like(C)
+                    reps = max(2, min(args.reps, int(0.2 / max(sec, 1e-6) / 50)))          # the slow levels get fewer launches
+                    rec[f"ablation_{label}_s"] = time_launches(lambda: S.smat_ablation_spmm(h, level, B, C2, N, stream), stream, torch, reps)
+                    check(C2, f"ablation kernel {label}")
+                    del C2
             emit(rec)
             rows_out.append(rec)
             del B, C
@@ -139,6 +158,20 @@ def main():
         first = next(iter(rs.values()))
         cells = [f"{rs[N]['seconds']*1e6:.1f}, {rs[N]['useful_tflops']:.1f}, {rs[N]['speedup_over_dense']:.2f}" for N in args.n]
         print(f"| {b} | {100*first['sparsity']:.2f} % | {first['n_blocks']} | {first['n_packs']} | " + " | ".join(cells) + " |")
+    if args.ablation:
+        labels = ("grid_walk", "bcsr", "bcsr_mfma")
+        for N in args.n:
+            print(f"\nN = {N}: time in us (and ns per stored block)\n| b | blocks | grid walk | BCSR iteration | + MFMA per block | library kernel |\n|---|---|---|---|---|---|")
+            for b in args.bands:
+                r = next(x for x in rows_out if x["b"] == b and x["N"] == N)
+                cells = [f"{r[f'ablation_{k}_s']*1e6:.1f} ({r[f'ablation_{k}_s']*1e9/r['n_blocks']:.2f})" for k in labels]
+                print(f"| {b} | {r['n_blocks']} | " + " | ".join(cells) + f" | {r['seconds']*1e6:.1f} ({r['seconds']*1e9/r['n_blocks']:.3f}) |")
+            for k in labels:
+                pts = [r for r in rows_out if r["N"] == N and r["b"] <= args.fit_max]
+                if len(pts) >= 3:
+                    slope, icpt, r2 = fit_line([p["n_blocks"] for p in pts], [p[f"ablation_{k}_s"] for p in pts])
+                    emit({"what": "fit", "kernel": k, "N": N, "unit": "n_blocks", "T_e_ns": slope * 1e9, "T_init_us": icpt * 1e6,
+                          "r2": r2, "points": len(pts), "fit_max_b": args.fit_max})
     for N in args.n:
         pts = [r for r in rows_out if r["N"] == N and r["b"] <= args.fit_max]
         if len(pts) >= 3:

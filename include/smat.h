@@ -181,6 +181,29 @@ const char *smat_last_error(void);
 const char *smat_last_kernel(void);
 
 /*
+ * Ablation (Performance model section, figure of measured against modelled time; Implementation
+ * section, optimisation steps B and T): the same product from the canonical BCSR arrays of the
+ * handle (rowPtr, col, 256 values per block) with fewer of the optimisations, to be timed next
+ * to smat_spmm.  fp16 / bf16 handles only; one wavefront per (block row, 16 columns of C), no
+ * pipelining.
+ *   level 0   every block of the grid is visited and its presence looked up in a dense block
+ *             map (no BCSR iteration), scalar multiply-adds in fp32
+ *   level 1   "B": iteration over the stored blocks through rowPtr / col, scalar multiply-adds
+ *   level 2   "B + T": the same iteration, one MFMA 16x16x16 per stored block
+ * smat_ablation_bytes   bytes of DEVICE memory smat_ablation_bind needs (the block values in
+ *                       canonical layout, 512 bytes per stored block, plus the block map when
+ *                       the block grid has at most 2^26 entries; without it level 0 is refused)
+ * smat_ablation_bind    fills that area (256-byte aligned, caller-owned, alive until
+ *                       smat_destroy); the handle must already be bound with smat_bind_device,
+ *                       whose rowPtr / col / permutation copies the kernels share; synchronises
+ * smat_ablation_spmm    arguments as smat_spmm; only enqueues
+ */
+smat_status_t smat_ablation_bytes(const smat_handle_t *h, size_t *bytes);
+smat_status_t smat_ablation_bind(smat_handle_t *h, void *dev_area, size_t bytes, void *stream);
+smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *dB, int64_t ldb,
+                                 void *dC, int64_t ldc, int64_t N, void *stream);
+
+/*
  * Probes: three kernels that measure what the device delivers for the access patterns the SpMM
  * kernels are made of (bench.py --probes times them and prints the rates next to the
  * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.

@@ -22,6 +22,7 @@ UNITS = {
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
     "probes": ("probes.hip", []),
+    "ablation": ("ablation.hip", []),
 }
 HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h")]
 

@@ -58,6 +58,9 @@ struct smat_handle {
     const int64_t* d_csr_row_ptr = nullptr;
     const int32_t* d_csr_col_idx = nullptr;
     const uint16_t* d_csr_vals = nullptr;
+    // canonical BCSR on the device, for the ablation kernels (smat_ablation_bind)
+    smat::CanonicalBcsr ablation;
+    bool ablation_bound = false;
 };
 
 namespace {
@@ -588,6 +591,84 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
         g_kernel = variant;
     }
     if (e) return hip_fail("launch spmm", e);
+    return SMAT_OK;
+}
+
+// Largest block grid for which the ablation keeps a dense block map (level 0).
+static constexpr int64_t kAblationMapEntries = int64_t{1} << 26;
+
+static size_t ablation_vals_bytes(const smat_handle* h) { return align_up(static_cast<size_t>(h->bcsr.n_blocks) * 512); }
+static bool ablation_has_map(const smat_handle* h) { return h->bcsr.nbr * h->bcsr.nbc <= kAblationMapEntries; }
+
+smat_status_t smat_ablation_bytes(const smat_handle_t* h, size_t* bytes)
+{
+    if (!h || !bytes) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    if (h->elem_bytes != 2) return fail(SMAT_ERR_UNSUPPORTED, "the ablation kernels handle fp16 and bf16 only");
+    size_t n = ablation_vals_bytes(h);
+    if (ablation_has_map(h)) n += align_up(static_cast<size_t>(h->bcsr.nbr * h->bcsr.nbc) * sizeof(int32_t));
+    *bytes = n ? n : kAlign;
+    return SMAT_OK;
+}
+
+smat_status_t smat_ablation_bind(smat_handle_t* h, void* dev_area, size_t bytes, void* stream)
+{
+    if (!h || !dev_area) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "smat_ablation_bind needs a handle bound with smat_bind_device");
+    if (reinterpret_cast<uintptr_t>(dev_area) % kAlign != 0) return fail(SMAT_ERR_INVALID_ARG, "dev_area must be 256-byte aligned");
+    size_t need = 0;
+    const smat_status_t st = smat_ablation_bytes(h, &need);
+    if (st != SMAT_OK) return st;
+    if (bytes < need) return fail(SMAT_ERR_INVALID_ARG, "dev_area too small: need " + std::to_string(need) + " bytes");
+    try {
+        hipStream_t s = static_cast<hipStream_t>(stream);
+        char* base = static_cast<char*>(dev_area);
+        const smat::Bcsr& b = h->bcsr;
+        std::vector<uint16_t> vals(static_cast<size_t>(b.n_blocks) * 256);
+        smat::fill_canonical_vals(h->csr, b, vals.data());
+        std::vector<int32_t> map;
+        if (ablation_has_map(h)) {
+            map.assign(static_cast<size_t>(b.nbr * b.nbc), -1);
+            for (int64_t br = 0; br < b.nbr; ++br)
+                for (int32_t k = b.row_ptr[br]; k < b.row_ptr[br + 1]; ++k)
+                    map[static_cast<size_t>(br * b.nbc + b.col_idx[k])] = k;
+        }
+        int e;
+        if (!vals.empty() && (e = static_cast<int>(hipMemcpyAsync(base, vals.data(), vals.size() * 2, hipMemcpyHostToDevice, s))))
+            return hip_fail("copy canonical block values", e);
+        if (!map.empty() && (e = static_cast<int>(hipMemcpyAsync(base + ablation_vals_bytes(h), map.data(), map.size() * 4, hipMemcpyHostToDevice, s))))
+            return hip_fail("copy block map", e);
+        if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("ablation bind synchronize", e);
+        smat::CanonicalBcsr& m = h->ablation;
+        m.row_ptr = h->dev.blk_ptr;
+        m.col_idx = h->dev.blk_col;
+        m.perm = h->dev.perm;
+        m.vals = reinterpret_cast<const uint16_t*>(base);
+        m.block_map = map.empty() ? nullptr : reinterpret_cast<const int32_t*>(base + ablation_vals_bytes(h));
+        m.M = h->csr.M;
+        m.K = h->csr.K;
+        m.nbr = b.nbr;
+        m.nbc = b.nbc;
+        h->ablation_bound = true;
+        return SMAT_OK;
+    } catch (const std::bad_alloc&) {
+        return fail(SMAT_ERR_ALLOC, "out of host memory in smat_ablation_bind");
+    }
+}
+
+smat_status_t smat_ablation_spmm(const smat_handle_t* h, int level, const void* dB, int64_t ldb, void* dC,
+                                 int64_t ldc, int64_t N, void* stream)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->ablation_bound) return fail(SMAT_ERR_NOT_BOUND, "smat_ablation_spmm called before smat_ablation_bind");
+    if (level < 0 || level > 2) return fail(SMAT_ERR_INVALID_ARG, "level must be 0, 1 or 2");
+    if (level == 0 && !h->ablation.block_map) return fail(SMAT_ERR_UNSUPPORTED, "level 0 keeps a dense block map: block grid above 2^26 entries");
+    if (N < 0) return fail(SMAT_ERR_INVALID_ARG, "N is negative");
+    if (N == 0 || h->csr.M == 0) return SMAT_OK;
+    if (!dC || (!dB && h->csr.K > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL matrix pointer");
+    if (ldb < N || ldc < N) return fail(SMAT_ERR_INVALID_ARG, "leading dimension smaller than N");
+    if (N > 16 * 65535) return fail(SMAT_ERR_UNSUPPORTED, "N above 1048560");
+    const int e = smat::launch_ablation(h->ablation, level, h->dtype == SMAT_BF16, dB, ldb, static_cast<float*>(dC), ldc, N, stream);
+    if (e) return hip_fail("launch ablation kernel", e);
     return SMAT_OK;
 }
 

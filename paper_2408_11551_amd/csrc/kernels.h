@@ -83,4 +83,21 @@ int dense_split(const DenseTiles& t, int64_t N);
 int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
                       float* C, int64_t ldc, int64_t N, void* stream, const char** variant);
 
+// The canonical BCSR of the paper on the device (Data Structures section), for the ablation
+// kernels only (ablation.hip).
+struct CanonicalBcsr {
+    const int32_t* row_ptr = nullptr;    // [nbr+1]
+    const int32_t* col_idx = nullptr;    // [n_blocks]
+    const uint16_t* vals = nullptr;      // [n_blocks * 256] row-major 16x16 blocks
+    const int32_t* block_map = nullptr;  // [nbr * nbc] index of the stored block or -1 (level 0 only)
+    const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
+    int64_t M = 0, K = 0, nbr = 0, nbc = 0;
+};
+
+// level 0: every block of the grid is visited and looked up in block_map, scalar multiply-adds;
+// level 1: rowPtr / col iteration, scalar multiply-adds; level 2: rowPtr / col iteration and
+// one MFMA 16x16x16 per stored block.  fp16 / bf16, C fp32.
+int launch_ablation(const CanonicalBcsr& m, int level, bool bf16, const void* B, int64_t ldb, float* C,
+                    int64_t ldc, int64_t N, void* stream);
+
 }  // namespace smat

@@ -91,6 +91,12 @@ def _load():
     lib.smat_export_device_vals.argtypes = [vp, vp, vp]
     lib.smat_spmm.restype = ctypes.c_int
     lib.smat_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
+    lib.smat_ablation_bytes.restype = ctypes.c_int
+    lib.smat_ablation_bytes.argtypes = [vp, ctypes.POINTER(sz)]
+    lib.smat_ablation_bind.restype = ctypes.c_int
+    lib.smat_ablation_bind.argtypes = [vp, vp, sz, vp]
+    lib.smat_ablation_spmm.restype = ctypes.c_int
+    lib.smat_ablation_spmm.argtypes = [vp, ctypes.c_int, vp, i64, vp, i64, i64, vp]
     lib.smat_destroy.restype = None
     lib.smat_destroy.argtypes = [vp]
     lib.smat_last_error.restype = ctypes.c_char_p
@@ -222,6 +228,32 @@ def smat_spmm(h, B, C, N=None, stream=None):
     _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
                           ctypes.c_void_p(C.data_ptr()), C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N),
                           N, _stream_ptr(stream)))
+
+
+def smat_ablation_bytes(h) -> int:
+    n = ctypes.c_size_t()
+    _check(_lib.smat_ablation_bytes(h, ctypes.byref(n)))
+    return n.value
+
+
+def smat_ablation_bind(h, area, stream=None):
+    """area: torch uint8 tensor on the device, at least smat_ablation_bytes(h) bytes, 256-byte aligned."""
+    _check(_lib.smat_ablation_bind(h, ctypes.c_void_p(area.data_ptr()), area.numel() * area.element_size(),
+                                   _stream_ptr(stream)))
+
+
+def smat_ablation_spmm(h, level, B, C, N=None, stream=None):
+    """As smat_spmm, through the ablation kernel of the given level (0, 1 or 2)."""
+    if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
+        raise ValueError("B and C must be 2-D with unit column stride")
+    if B.element_size() != 2 or C.element_size() != 4:
+        raise ValueError("B must hold 2-byte elements and C 4-byte elements")
+    if N is None:
+        N = B.shape[1]
+    _check(_lib.smat_ablation_spmm(h, level, ctypes.c_void_p(B.data_ptr()),
+                                   B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
+                                   ctypes.c_void_p(C.data_ptr()),
+                                   C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N), N, _stream_ptr(stream)))
 
 
 def smat_probe_read(buf, sink, stream=None):

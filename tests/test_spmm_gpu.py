@@ -426,3 +426,36 @@ def test_config_powerlaw_full_parity(oracle_c):
         if nxt < w.M:                         # and the next cluster starts where this one ends
             assert perm[nxt] == int(np.flatnonzero(state == 0)[0])
     m.close()
+
+
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_ablation_kernels_compute_the_same_product(dtype, oracle_c):
+    # the three reduced kernels (block-grid walk, BCSR iteration, BCSR iteration + one MFMA 16x16x16
+    # per block) on ragged shapes, through the C ABI, against the oracle and the library's own kernel
+    for M, K, N, density in ((16, 16, 16, 1.0), (130, 70, 24, 0.2), (257, 129, 100, 0.03), (300, 333, 7, 0.1), (33, 40, 5, 0.0)):
+        w = random_csr(M, K, N, density, seed=M + N, dtype=dtype, b_dist="normal")
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+        area = torch.empty(S.smat_ablation_bytes(m.handle), dtype=torch.uint8, device="cuda")
+        S.smat_ablation_bind(m.handle, area)
+        b = _dev_b(w, ldb=N + 3)
+        c_ref, s_ref = _oracle_c(oracle_c, w)
+        for level in (0, 1, 2):
+            cfull = torch.full((w.M, N + 2), float("nan"), dtype=torch.float32, device="cuda")
+            S.smat_ablation_spmm(m.handle, level, b, cfull[:, :N], N)
+            torch.cuda.synchronize()
+            assert torch.isnan(cfull[:, N:]).all()
+            _check_c(cfull[:, :N].cpu().numpy(), c_ref, s_ref, w)
+        m.close()
+    # unbound, wrong level, 8-bit handle
+    w = random_csr(64, 64, 8, 0.1, seed=1, dtype=dtype)
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    b, c = _dev_b(w), torch.empty((w.M, w.N), dtype=torch.float32, device="cuda")
+    with pytest.raises(S.SmatError) as e:
+        S.smat_ablation_spmm(m.handle, 1, b, c)
+    assert e.value.status_name == "SMAT_ERR_NOT_BOUND"
+    area = torch.empty(S.smat_ablation_bytes(m.handle), dtype=torch.uint8, device="cuda")
+    S.smat_ablation_bind(m.handle, area)
+    with pytest.raises(S.SmatError) as e:
+        S.smat_ablation_spmm(m.handle, 3, b, c)
+    assert e.value.status_name == "SMAT_ERR_INVALID_ARG"
+    m.close()
