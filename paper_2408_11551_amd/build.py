@@ -9,15 +9,19 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libsmat.so")
+# The per-row kernel starts with a chain of dependent loads (launch record -> slot table -> rows
+# of B); having the dispatcher place its leading arguments in scalar registers takes the load of
+# the arguments themselves off the front of that chain.
+PRELOAD = ["-mllvm", "-amdgpu-kernarg-preload-count=16"]
 # object name -> (source, extra flags)
 UNITS = {
     "api": ("api.cpp", []),
     "preprocess": ("preprocess.cpp", []),
-    "kernels": ("kernels.hip", []),
+    "kernels": ("kernels.hip", PRELOAD),
     # the per-row kernel for the 8-bit operand types: one object per type, built side by side
-    "kernels_e4m3": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=2"]),
-    "kernels_e5m2": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=3"]),
-    "kernels_i8": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=4"]),
+    "kernels_e4m3": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=2", *PRELOAD]),
+    "kernels_e5m2": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=3", *PRELOAD]),
+    "kernels_i8": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=4", *PRELOAD]),
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),

@@ -372,9 +372,13 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
 
 template <int NT, int KW, int SW, int NCH, int LMAX, int DT>
 __global__ __launch_bounds__(KW * SW * 64)
-void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
-                 typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store, int stream_hint)
+void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ slots, const void* __restrict__ vals,
+                 const int32_t* __restrict__ perm, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
+                 uint32_t K, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store, int stream_hint)
 {
+    // The arguments are plain words, the ones needed first in front: the compiler is asked
+    // (build flag) to have the dispatcher place the leading ones in scalar registers, so that the
+    // first load of the kernel does not have to wait for a load of its own arguments.
     using Acc = typename Elem<DT>::Acc;
     using Out = typename Elem<DT>::Out;
     constexpr int ES = Elem<DT>::ES;
@@ -386,14 +390,14 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     const int ks = wave % KW;                      // which share of the block row
     const int sl = wave / KW;                      // which column slab of the group
     const int i = lane & 15, g = lane >> 4;
-    const i32x4 rec = reinterpret_cast<const i32x4*>(d.work)[blockIdx.x];   // one record of the launch table
+    const i32x4 rec = reinterpret_cast<const i32x4*>(work)[blockIdx.x];     // one record of the launch table
     const int br = rec[0] & 0x0FFFFFFF;
     const int cls = rec[0] >> 28;                  // 0: L = 2, 1: L = 4, 2: L = 8
     const int n0 = (blockIdx.y * SW + sl) * WC;
 
     RowWalk w;
-    w.slots = d.slots + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * 8;      // 32 bytes of slot table per unit
-    w.vals = static_cast<const uint8_t*>(d.vals) + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * (128 * ES);   // 128 values per unit
+    w.slots = slots + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * 8;        // 32 bytes of slot table per unit
+    w.vals = static_cast<const uint8_t*>(vals) + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * (128 * ES);     // 128 values per unit
     w.npacks = n0 < N ? rec[1] : 0;
     w.ks = ks;
     w.g = g;
@@ -407,7 +411,7 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
         w.lane_off[c] = col0[c] < N ? static_cast<uint32_t>(col0[c]) * ES : kOutOfRange;
     }
     w.ldb_bytes = ldb_bytes;
-    w.no_row = static_cast<uint32_t>(d.K);
+    w.no_row = K;
     w.stream = (stream_hint & 1) != 0;
     const bool c_stream = (stream_hint & 2) != 0;  // C is stored with the non-temporal hint
 
@@ -421,12 +425,12 @@ void spmm_kernel(DeviceBcsr d, const void* __restrict__ B, uint32_t b_bytes, uin
     int out_rows[EP];
     if constexpr (KW == 1) {
 #pragma unroll
-        for (int r = 0; r < 4; ++r) out_rows[r] = d.perm[br * 16 + 4 * g + r];
+        for (int r = 0; r < 4; ++r) out_rows[r] = perm[br * 16 + 4 * g + r];
     } else {
 #pragma unroll
         for (int k = 0; k < EP; ++k) {
             const int e = static_cast<int>(threadIdx.x) + k * WAVES * 64;
-            out_rows[k] = e < SW * 16 * Q ? d.perm[br * 16 + (e / Q) % 16] : -1;
+            out_rows[k] = e < SW * 16 * Q ? perm[br * 16 + (e / Q) % 16] : -1;
         }
     }
 
@@ -547,8 +551,8 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, void*
     // or a loss where B is 16 MiB and more).
     if (static_cast<double>(d.K) * static_cast<double>(N) * ES <= 8.0e6) stream_hint |= 2;
     hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, DT>), grid, dim3(KW * SW * 64), 0, stream,
-                       d, B, b_bytes, static_cast<uint32_t>(ldb * ES), static_cast<typename Elem<DT>::Out*>(C), ldc,
-                       static_cast<int>(N), vec_store, stream_hint);
+                       d.work, d.slots, d.vals, d.perm, B, b_bytes, static_cast<uint32_t>(ldb * ES), static_cast<uint32_t>(d.K),
+                       static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());
 }
 
