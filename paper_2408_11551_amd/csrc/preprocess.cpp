@@ -106,9 +106,15 @@ private:
 
 }  // namespace
 
-int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr,
-                        const std::vector<int32_t>& pat_idx, int tau_permille,
-                        std::vector<int32_t>& order)
+// kLazy chooses how rows become candidates of the open cluster (the result is the same):
+// false: every row ahead of the scan that shares a column with the union is visited; right
+// where a row shares many columns with the union (the visits are few next to the counting);
+// true: a row is visited only once its count could pass the merge test; right where most
+// rows share a single column (one visit per count otherwise).
+template <bool kLazy>
+static int64_t cluster_rows(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr,
+                            const std::vector<int32_t>& pat_idx, int tau_permille,
+                            std::vector<int32_t>& order)
 {
     order.clear();
     order.reserve(M);
@@ -127,17 +133,35 @@ int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_
     for (int64_t c = 0; c < nbc; ++c) inv_len[c] = inv_ptr[c + 1] - inv_ptr[c];
 
     std::vector<uint8_t> clustered(M, 0);
-    std::vector<int32_t> shared(M, 0);        // |row n union| for the candidates of the open cluster
+    // per row ahead of the scan: |row n union of the open cluster|; kLazy: twice that, + 1 if the
+    // row is in the candidate set
+    std::vector<int32_t> shared(M, 0);
+    std::vector<int32_t> touched;             // rows with shared != 0, to be cleared when the cluster closes
     std::vector<int64_t> in_union(nbc, -1);   // id of the cluster whose union holds the column
+    std::vector<int32_t> row_len(M);
+    for (int64_t r = 0; r < M; ++r) row_len[r] = static_cast<int32_t>(pat_ptr[r + 1] - pat_ptr[r]);
+    int64_t shortest = 0;                     // shortest non-empty pattern
+    for (int64_t r = 0; r < M; ++r)
+        if (row_len[r] > 0 && (shortest == 0 || row_len[r] < shortest)) shortest = row_len[r];
     AscendingSet candidates(M);
     int64_t n_clusters = 0;
     const int64_t keep = 1000 - tau_permille;
 
-    // a column enters the union while the scan stands at row `pos`
+    // A column enters the union while the scan stands at row `pos`: every row ahead of the scan
+    // that has the column shares one more column with the union.  kLazy: a row is only worth a visit
+    // once it could pass the merge test at all.  The test at the visit, with the union U' >= U of
+    // that later moment and the row's count n' of then, is 1000 n' > keep (|w| + U' - n'), which
+    // implies (1000 + keep) n' > keep (|w| + U); n' is reached at the row's last increment, where
+    // the same inequality with the U of that moment (smaller still) therefore holds.  So a row
+    // enters the candidate set at the first increment that satisfies it, and no row that would be
+    // merged is left out; the exact test is still taken at the visit.  The same bound with the
+    // shortest pattern of the matrix in place of |w| comes first, so that most increments read
+    // nothing but the counter.
     auto add_column = [&](int32_t c, int64_t pos, int64_t cluster, int64_t& union_size) {
         if (in_union[c] == cluster) return;
         in_union[c] = cluster;
         ++union_size;
+        const int64_t least = keep * (shortest + union_size) / (1000 + keep);   // a count must exceed this to matter for any row
         int32_t* rows = inv_rows.data() + inv_ptr[c];
         int64_t kept = 0;
         for (int64_t k = 0; k < inv_len[c]; ++k) {
@@ -145,7 +169,17 @@ int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_
             if (clustered[r]) continue;                  // drop rows that are gone for good
             rows[kept++] = r;
             if (r > pos) {
-                if (shared[r]++ == 0) candidates.insert(r);
+                if constexpr (kLazy) {
+                    const int32_t word = (shared[r] += 2);
+                    if (word == 2) touched.push_back(r);
+                    const int64_t n = word >> 1;
+                    if (!(word & 1) && n > least && (1000 + keep) * n > keep * (row_len[r] + union_size)) {
+                        candidates.insert(r);
+                        shared[r] = word | 1;
+                    }
+                } else {
+                    if (shared[r]++ == 0) candidates.insert(r);
+                }
             }
         }
         inv_len[c] = kept;
@@ -174,17 +208,31 @@ int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_
             if (w < 0) break;
             candidates.erase(w);
             pos = w;
-            const int64_t inter = shared[w];
-            shared[w] = 0;
-            const int64_t uni = (pat_ptr[w + 1] - pat_ptr[w]) + union_size - inter;
+            const int64_t inter = kLazy ? shared[w] >> 1 : shared[w];
+            if constexpr (!kLazy) shared[w] = 0;        // every row with a count is visited, so this clears them all
+            const int64_t uni = row_len[w] + union_size - inter;
             if (1000 * inter > keep * uni) {             // 1 - inter/uni < tau/1000
                 clustered[w] = 1;
                 order.push_back(static_cast<int32_t>(w));
                 for (int64_t q = pat_ptr[w]; q < pat_ptr[w + 1]; ++q) add_column(pat_idx[q], w, cluster, union_size);
             }
         }
+        for (int32_t r : touched) shared[r] = 0;
+        touched.clear();
     }
     return n_clusters;
+}
+
+int64_t jaccard_cluster(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr,
+                        const std::vector<int32_t>& pat_idx, int tau_permille,
+                        std::vector<int32_t>& order)
+{
+    // A row of mean length l meets a union of about l columns in l * l / nbc of them on average:
+    // below a few, most rows ahead of the scan share one column and would be visited for it.
+    const double mean_len = M > 0 ? static_cast<double>(pat_idx.size()) / static_cast<double>(M) : 0.0;
+    const bool lazy = nbc > 0 && mean_len * mean_len < 4.0 * static_cast<double>(nbc);
+    return lazy ? cluster_rows<true>(M, nbc, pat_ptr, pat_idx, tau_permille, order)
+                : cluster_rows<false>(M, nbc, pat_ptr, pat_idx, tau_permille, order);
 }
 
 int64_t count_blocks(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr,

@@ -144,6 +144,36 @@ def test_8bit_types_preprocess_like_the_16bit_ones(dtype):
         S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w16.a_bits, dtype)       # 2-byte values for a 1-byte type
 
 
+@pytest.mark.parametrize("tau", [300, 700, 900])
+def test_both_candidate_strategies_of_the_clustering_match_the_oracle(tau, oracle_c):
+    """The library keeps candidates of the open cluster in one of two ways, by how many columns a
+    row shares with a union on average (short patterns: a row is visited only once its count could
+    pass the merge test; long patterns: every row with a count is visited).  Both must give the
+    oracle's permutation: a power-law matrix with ~15 block columns per row out of 128, where
+    clusters of several rows form, and one with ~90 out of 128."""
+    from workloads.configs import zipf_truncated_pmf, _csr_from_keys
+    rng = np.random.default_rng(5)
+    M, K = 6000, 2048
+    dvals, pmf = zipf_truncated_pmf(1.2, 16.0)
+    for scale in (1, 12):                                  # mean pattern length ~15 and ~90
+        deg = rng.choice(dvals, size=M, p=pmf) * scale
+        rows = np.repeat(np.arange(M, dtype=np.int64), deg)
+        cols = rng.integers(0, K, size=rows.size, dtype=np.int64)
+        keys = np.unique(rows * K + cols)
+        rp, ci = _csr_from_keys(keys, M, K)
+        h = S.smat_preprocess(M, K, rp, ci, np.ones(ci.size, np.uint16), "f16", tau_permille=tau)
+        try:
+            pp, pi = oracle_c.block_pattern_csr(M, K, rp, ci)
+            mean_len = pi.size / M
+            assert (mean_len ** 2 < 4 * 128) == (scale == 1)            # the two cases fall on both sides of the library's rule
+            perm, n_e, n_id, used = oracle_c.choose_perm_c(M, pp, pi, K // 16, tau)
+            assert np.array_equal(S.smat_export_perm(h, M), perm)
+            info = S.smat_get_info(h)
+            assert (info["n_blocks"], info["n_blocks_identity"], info["used_identity"]) == (n_e, n_id, used)
+        finally:
+            S.smat_destroy(h)
+
+
 def test_spmm_without_bind_is_an_error_not_a_fallback():
     rp = np.array([0, 1], np.int64)
     h = S.smat_preprocess(1, 1, rp, np.array([0], np.int32), np.array([0x3C00], np.uint16), "f16")
