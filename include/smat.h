@@ -64,8 +64,7 @@ typedef struct {
     int dense_tiles;    /* block-dense regions (sixteen block rows sharing most of their
                            block columns) have a kernel of their own that stages panels of
                            B in LDS: 0 = take it where an estimate says it is faster,
-                           1 = take it wherever it applies, -1 = never.  fp16 / bf16 only:
-                           with an 8-bit dtype 1 is refused and 0 means -1                */
+                           1 = take it wherever it applies, -1 = never                    */
 } smat_options_t;
 
 /* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0. */

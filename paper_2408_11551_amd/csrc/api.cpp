@@ -118,7 +118,7 @@ Layout make_layout(const smat_handle& h)
     l.t_cols = take(h.step_cols.size() * sizeof(int32_t));
     l.t_rows = take(h.step_rows.size() * sizeof(uint32_t));
     l.t_base = take(h.step_base.size() * sizeof(uint32_t));
-    l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
+    l.t_vals = take(static_cast<size_t>(h.dense_slots) * 512 * static_cast<size_t>(h.elem_bytes));
     l.t_scratch = take(h.dense_super.empty() ? 0 : kTileScratchBytes);
     l.total = off ? off : kAlign;
     return l;
@@ -266,8 +266,6 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (o.reorder != 0 && o.reorder != 1) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0 or 1");
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (o.dense_tiles < -1 || o.dense_tiles > 1) return fail(SMAT_ERR_INVALID_ARG, "dense_tiles must be -1, 0 or 1");
-        if (narrow && o.dense_tiles == 1)
-            return fail(SMAT_ERR_UNSUPPORTED, "the dense-tile kernel handles fp16 and bf16 only");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
         if ((M + 15) / 16 >= (int64_t{1} << 28)) return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
@@ -283,7 +281,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         std::unique_ptr<smat_handle> h(new smat_handle());      // freed if anything below throws
         h->dtype = dtype;
         h->elem_bytes = narrow ? 1 : 2;
-        h->dense_mode = narrow ? -1 : o.dense_tiles;
+        h->dense_mode = o.dense_tiles;
         h->csr.M = M;
         h->csr.K = K;
         h->csr.row_ptr.assign(row_ptr, row_ptr + M + 1);
@@ -462,8 +460,8 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.step_cols = reinterpret_cast<const int32_t*>(base + l.t_cols);
         tiles.step_rows = reinterpret_cast<const uint32_t*>(base + l.t_rows);
         tiles.step_base = reinterpret_cast<const uint32_t*>(base + l.t_base);
-        tiles.vals = reinterpret_cast<const uint16_t*>(base + l.t_vals);
-        tiles.scratch = h->dense_super.empty() ? nullptr : reinterpret_cast<float*>(base + l.t_scratch);
+        tiles.vals = base + l.t_vals;
+        tiles.scratch = h->dense_super.empty() ? nullptr : base + l.t_scratch;
         tiles.scratch_bytes = h->dense_super.empty() ? 0 : kTileScratchBytes;
         tiles.n = static_cast<int32_t>(h->dense_super.size());
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
@@ -475,9 +473,9 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
             return hip_fail("zero block values", e);
         if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.vals, h->elem_bytes, s)))
             return hip_fail("fill block values", e);
-        if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 64, s))) return hip_fail("zero tile values", e);
-        if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals,
-                                         reinterpret_cast<uint16_t*>(base + l.t_vals), s)))
+        if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 32 * static_cast<size_t>(h->elem_bytes), s)))
+            return hip_fail("zero tile values", e);
+        if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.t_vals, h->elem_bytes, s)))
             return hip_fail("fill tile values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("bind synchronize", e);
         h->dev = d;
@@ -559,21 +557,21 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (K > 0 && ((K - 1) * ldb + N) * h->elem_bytes >= (int64_t{1} << 31))
         return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
     if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
-    // The dense path needs 16-byte rows of B at 8-column granularity; otherwise every block row
-    // goes through the per-row kernel.  It also has to pay: a tile walks its steps at about
+    // The dense path fetches B in 16-byte pieces (8 columns, or 16 for the 8-bit types) that must lie
+    // wholly inside or outside the N columns; otherwise every block row goes through the per-row kernel.  It also has to pay: a tile walks its steps at about
     // 0.7 us each with little to overlap them, so few tiles leave most of the chip idle, while
     // the per-row kernel fetches every occupied column's row of B again for every block row but
     // spreads that over all compute units (about 10 TB/s of L1 fills).  Both estimates are
     // measured rates; the faster path is taken.
-    const bool bf16 = h->dtype == SMAT_BF16;
-    bool use_tiles = h->elem_bytes == 2 && h->tiles.n > 0 && N % 8 == 0 && ldb % 8 == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
+    const int piece = 16 / h->elem_bytes;           // columns of B in 16 bytes
+    bool use_tiles = h->tiles.n > 0 && N % piece == 0 && ldb % piece == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
     if (h->dense_mode < 0) use_tiles = false;
     if (use_tiles && h->dense_mode == 0) {
         const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
         const int ks = smat::dense_split(h->tiles, N);
         double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * 0.7 + 4.0);
         if (ks > 1) t_tiles += 3.0 + tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
-        const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
+        const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * h->elem_bytes / 10.0e6 + 4.0;
         use_tiles = t_tiles <= t_rows;
     }
     const char* variant = "";
@@ -583,7 +581,7 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
         if (h->dev_rest.n_order > 0)
             e = smat::launch_spmm(h->dev_rest, h->dtype, dB, ldb, dC, ldc, N, stream, &variant);
         const char* dense_variant = "";
-        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, bf16, dB, ldb, static_cast<float*>(dC), ldc, N, stream, &dense_variant);
+        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, h->dtype, dB, ldb, dC, ldc, N, stream, &dense_variant);
         name = std::string(dense_variant) + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
         g_kernel = name.c_str();
     } else {

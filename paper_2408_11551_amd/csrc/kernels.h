@@ -35,17 +35,17 @@ struct DeviceBcsr {
 
 // Block-dense parts of the matrix: "super rows" of sixteen consecutive block rows whose block
 // columns overlap enough to be walked together (kernels_dense.hip).  The union of a super
-// row's block columns, ascending, is cut into steps of two block columns; step q stores 1 KiB
-// for every block row that has one of its two columns (bit j of step_rows), back to back
-// from slot step_base[q].
+// row's block columns, ascending, is cut into steps of two block columns; step q stores 512
+// values (1 KiB for the 16-bit types) for every block row that has one of its two columns (bit j
+// of step_rows), back to back from slot step_base[q].
 struct DenseTiles {
     const int32_t* super_rows = nullptr;   // [n] super row index s: block rows 16 s .. 16 s + 15
     const int32_t* step_ptr = nullptr;     // [n+1] offsets into the step arrays
     const int32_t* step_cols = nullptr;    // [2 * steps] block columns of a step (INT_MAX: none)
     const uint32_t* step_rows = nullptr;   // [steps] 16-bit mask of block rows present in the step
-    const uint32_t* step_base = nullptr;   // [steps] first 1 KiB slot of the step
-    const uint16_t* vals = nullptr;        // [512 * slots]
-    float* scratch = nullptr;              // partial tiles of launches that split the steps of a tile
+    const uint32_t* step_base = nullptr;   // [steps] first slot of the step
+    const void* vals = nullptr;            // [512 * slots] values of 2 bytes or 1
+    void* scratch = nullptr;               // partial tiles (fp32, or int32 for the integer type) of launches that split the steps of a tile
     size_t scratch_bytes = 0;
     int32_t n = 0;
     double mean_steps = 0;                 // steps per super row, on average
@@ -74,14 +74,15 @@ int launch_spmm_i8(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int
 
 // Scatters the CSR values of the dense super rows into the tile layout (vals zeroed before).
 int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,
-                      const int32_t* csr_col_idx, const uint16_t* csr_vals, uint16_t* vals_out, void* stream);
+                      const int32_t* csr_col_idx, const uint16_t* csr_vals, void* vals_out, int elem_bytes, void* stream);
 
 // Workgroups per 128-column tile the dense launch would use for this N (1: no split).
 int dense_split(const DenseTiles& t, int64_t N);
 
-// C rows of the dense super rows.  Needs N, ldb multiples of 8 and B aligned to 16 bytes.
-int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
-                      float* C, int64_t ldc, int64_t N, void* stream, const char** variant);
+// C rows of the dense super rows.  dtype is a smat_dtype_t.  Needs N and ldb multiples of the
+// elements in 16 bytes (8, or 16 for the 8-bit types) and B aligned to 16 bytes.
+int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, int dtype, const void* B, int64_t ldb,
+                      void* C, int64_t ldc, int64_t N, void* stream, const char** variant);
 
 // The canonical BCSR of the paper on the device (Data Structures section), for the ablation
 // kernels only (ablation.hip).

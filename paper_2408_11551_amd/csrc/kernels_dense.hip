@@ -19,14 +19,9 @@
 #include <hip/hip_runtime.h>
 
 #include "kernels.h"
+#include "mfma_types.h"
 
 namespace smat {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
 
 namespace {
 
@@ -39,13 +34,10 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
     return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), static_cast<uint32_t>(v[2]), static_cast<uint32_t>(v[3])};
 }
 
-template <bool BF16>
-__device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
+__device__ __forceinline__ u32x4 buf_load8(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
-    if constexpr (BF16)
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    else
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
+    const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
+    return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), 0u, 0u};
 }
 
 }  // namespace
@@ -70,25 +62,34 @@ __device__ __forceinline__ f32x4 mfma_pack(u32x4 a, u32x4 b, f32x4 c)
 // compute unit gets only one tile.  (A 256-column tile with 256 accumulators per lane in the
 // accumulation registers was built as well: 9 % faster than one group at N = 4096, slower than
 // two groups, and removed.)
-template <bool BF16, int RING, int KG>
+//
+// DT is the operand type.  The 8-bit types run the same walk with elements of one byte: a step
+// is still two block columns = the 32 k slots of their MFMA 16x16x32 forms, a block row's values
+// for a step are 512 bytes (eight per lane), the panel of B is 32 rows of 128 bytes, staged by
+// one 16-byte piece per thread, and the operand of MFMA x is byte x of the lane's eight rows.
+template <int DT, int RING, int KG>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
 void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, uint32_t b_bytes,
-                       uint32_t ldb_bytes, float* __restrict__ C, int64_t ldc, int N, int vec_store)
+                       uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store)
 {
     static_assert(RING == 2 || RING == 3, "at most 256 registers per lane");
+    using Acc = typename Elem<DT>::Acc;
+    using Out = typename Elem<DT>::Out;
+    constexpr int ES = Elem<DT>::ES;               // bytes per element of A and B
     constexpr int NT = 8;                          // columns per lane; 16 lanes cover a 128-column chunk
     constexpr int RM = 4;                          // block rows per wave
     constexpr int NCH = 1;                         // 128-column chunks per workgroup
-    constexpr int NS = 2 * NCH;                    // 16-byte pieces of the panel a thread stages per step
+    constexpr int NS = ES * NCH;                   // 16-byte pieces of the panel a thread stages per step
+    constexpr int PW = 8 * ES * NCH;               // 16-byte pieces per panel row (128 * NCH elements)
     constexpr int NBUF = RING == 3 ? 3 : 2;        // panel buffers; the loop body of RING steps keeps their indices constant
-    __shared__ u32x4 panel_all[KG][NBUF][32][16 * NCH];   // per wave group, buffers of 32 B rows x (128 * NCH) halves
+    __shared__ u32x4 panel_all[KG][NBUF][32][PW];  // per wave group, buffers of 32 B rows x (128 * NCH) elements
 
     const int tid = threadIdx.x & 255;             // thread inside its wave group
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
     const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
-    u32x4 (*panel)[32][16 * NCH] = panel_all[kg];
+    u32x4 (*panel)[32][PW] = panel_all[kg];
     const int i = lane & 15, g = lane >> 4;
     const int sidx = blockIdx.x;
     const int super = t.super_rows[sidx];
@@ -106,16 +107,19 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
     const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        const_cast<uint16_t*>(t.vals) + static_cast<size_t>(first_slot) * 512, 0,
-        static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
+        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * (512 * ES), 0,
+        static_cast<int>((end_slot - first_slot) * (512u * ES)), kRsrcFlags);
 
-    // staging of the B panel: thread tid copies, per chunk, 16 bytes of rows (tid >> 4) and 16 + (tid >> 4)
-    const int st_row = tid >> 4, st_chunk = tid & 15;
+    // staging of the B panel, 16 bytes per piece.  16-bit types: thread tid copies, per chunk, the
+    // pieces of rows (tid >> 4) and 16 + (tid >> 4) at column 8 * (tid & 15); 8-bit types: the one
+    // piece of row (tid >> 3) at column 16 * (tid & 7).  (N is a multiple of the columns of a piece
+    // on this path, so a piece is all inside or all outside.)
+    const int st_row = ES == 2 ? tid >> 4 : tid >> 3, st_chunk = ES == 2 ? tid & 15 : tid & 7;
     uint32_t st_off[NCH];
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
-        const int st_col = n0 + 128 * c + NT * st_chunk;
-        st_off[c] = st_col < N ? static_cast<uint32_t>(st_col) * 2u : kOutOfRange;
+        const int st_col = n0 + 128 * c + (16 / ES) * st_chunk;
+        st_off[c] = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
     }
     const uint32_t no_row = static_cast<uint32_t>(d.K);
     const int nbc = static_cast<int>((d.K + 15) >> 4);
@@ -135,22 +139,35 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     auto load_panel = [&](const StepMeta& m, u32x4 (&stage)[NS]) {
         const int c0 = m.c0, c1 = m.c1;
         // rows past K (ragged last block column, or no second column) are out of range: zeros
-        uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
-        uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
-        row0 = row0 < no_row ? row0 : no_row;
-        row1 = row1 < no_row ? row1 : no_row;
-        const uint32_t off0 = __umul24(row0, ldb_bytes), off1 = __umul24(row1, ldb_bytes);
+        if constexpr (ES == 2) {
+            uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
+            uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
+            row0 = row0 < no_row ? row0 : no_row;
+            row1 = row1 < no_row ? row1 : no_row;
+            const uint32_t off0 = __umul24(row0, ldb_bytes), off1 = __umul24(row1, ldb_bytes);
 #pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            stage[2 * c] = buf_load16(b_rsrc, off0 + st_off[c], 0u);
-            stage[2 * c + 1] = buf_load16(b_rsrc, off1 + st_off[c], 0u);
+            for (int c = 0; c < NCH; ++c) {
+                stage[2 * c] = buf_load16(b_rsrc, off0 + st_off[c], 0u);
+                stage[2 * c + 1] = buf_load16(b_rsrc, off1 + st_off[c], 0u);
+            }
+        } else {
+            const int col = st_row < 16 ? c0 : c1;
+            uint32_t row = col < nbc ? static_cast<uint32_t>(col) * 16u + (st_row & 15) : no_row;
+            row = row < no_row ? row : no_row;
+            const uint32_t off = __umul24(row, ldb_bytes);
+#pragma unroll
+            for (int c = 0; c < NCH; ++c) stage[c] = buf_load16(b_rsrc, off + st_off[c], 0u);
         }
     };
     auto store_panel = [&](int buf, const u32x4 (&stage)[NS]) {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
-            panel[buf][st_row][16 * c + st_chunk] = stage[2 * c];
-            panel[buf][16 + st_row][16 * c + st_chunk] = stage[2 * c + 1];
+            if constexpr (ES == 2) {
+                panel[buf][st_row][16 * c + st_chunk] = stage[2 * c];
+                panel[buf][16 + st_row][16 * c + st_chunk] = stage[2 * c + 1];
+            } else {
+                panel[buf][st_row][8 * c + st_chunk] = stage[c];
+            }
         }
     };
     // Values of the wave's four block rows for step q.  A block row without data in the step
@@ -164,15 +181,16 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
             const int j = RM * wave + r;
             const uint32_t slot = base + __popc(rows & ((1u << j) - 1u));
             const uint32_t absent = (live && (rows >> j & 1u)) ? 0u : kOutOfRange;      // wave-uniform
-            a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
+            if constexpr (ES == 2) a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
+            else a[r] = buf_load8(a_rsrc, (static_cast<uint32_t>(lane) * 8u) | absent, slot * 512u);
         }
     };
 
-    f32x4 acc[RM][NCH * NT];
+    Acc acc[RM][NCH * NT];
 #pragma unroll
     for (int r = 0; r < RM; ++r)
 #pragma unroll
-        for (int x = 0; x < NCH * NT; ++x) acc[r][x] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int x = 0; x < NCH * NT; ++x) acc[r][x] = Acc{0, 0, 0, 0};
 
     // Software pipeline with register rings of RING slots (no copies; the loop body is RING steps
     // without an exit; steps past the last one read zeros as block values).  While step s is
@@ -208,20 +226,43 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) {
                     // B rows of this lane's k range: row 8g + kk, columns 128c + 8i .. 128c + 8i+7
-                    u32x4 R[8];
+                    if constexpr (ES == 2) {
+                        u32x4 R[8];
 #pragma unroll
-                    for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][16 * c + i];
-                    __builtin_amdgcn_sched_barrier(0);
+                        for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][16 * c + i];
+                        __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                    for (int x = 0; x < NT; ++x) {
-                        const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
-                        u32x4 b;
+                        for (int x = 0; x < NT; ++x) {
+                            const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
+                            u32x4 b;
 #pragma unroll
-                        for (int qd = 0; qd < 4; ++qd)
-                            b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
+                            for (int qd = 0; qd < 4; ++qd)
+                                b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
 #pragma unroll
-                        for (int r = 0; r < RM; ++r)
-                            acc[r][c * NT + x] = mfma_pack<BF16>(a[u][r], b, acc[r][c * NT + x]);
+                            for (int r = 0; r < RM; ++r)
+                                acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
+                        }
+                    } else {
+                        // eight bytes per row: the lane's eight columns; operand dword = byte x of four rows
+                        u32x2 R[8];
+#pragma unroll
+                        for (int kk = 0; kk < 8; ++kk)
+                            R[kk] = reinterpret_cast<const u32x2*>(&panel[buf][8 * g + kk][8 * c])[i];
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int x = 0; x < NT; ++x) {
+                            const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
+                            u32x4 b = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                            for (int qd = 0; qd < 2; ++qd) {
+                                const uint32_t lo = __builtin_amdgcn_perm(R[4 * qd + 1][x >> 2], R[4 * qd][x >> 2], pair);
+                                const uint32_t hi = __builtin_amdgcn_perm(R[4 * qd + 3][x >> 2], R[4 * qd + 2][x >> 2], pair);
+                                b[qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                            }
+#pragma unroll
+                            for (int r = 0; r < RM; ++r)
+                                acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
+                        }
                     }
                     __builtin_amdgcn_sched_barrier(0);
                 }
@@ -234,7 +275,7 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 
     if constexpr (KG == 2) {
         // group 1 hands its accumulators to group 0, two block rows per wave at a time (64 KiB)
-        __shared__ float handover[4 * 2 * NT * 4 * 64];
+        __shared__ Out handover[4 * 2 * NT * 4 * 64];
 #pragma unroll
         for (int half = 0; half < 2; ++half) {
             if (kg == 1) {
@@ -266,14 +307,14 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
         if (ks > 1) {
             // partial tile, row-major 256 x 128 floats, at [(tile * ks + z)]
             const size_t tile = static_cast<size_t>(sidx) * gridDim.y + blockIdx.y;
-            float* part = t.scratch + (tile * ks + blockIdx.z) * (256 * 128);
+            Out* part = static_cast<Out*>(t.scratch) + (tile * ks + blockIdx.z) * (256 * 128);
 #pragma unroll
             for (int r = 0; r < RM; ++r)
 #pragma unroll
                 for (int y = 0; y < 4; ++y) {
-                    float* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
-                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
-                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
+                    Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
+                    *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
+                    *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
                 }
             return;
         }
@@ -289,10 +330,10 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
             for (int y = 0; y < 4; ++y) {
                 const int64_t out_row = d.perm[br * 16 + 4 * g + y];
                 if (out_row < 0) continue;
-                float* dst = C + out_row * ldc + col0;
+                Out* dst = C + out_row * ldc + col0;
                 if (vec_store) {
-                    *reinterpret_cast<f32x4*>(dst) = f32x4{acc[r][c * NT][y], acc[r][c * NT + 1][y], acc[r][c * NT + 2][y], acc[r][c * NT + 3][y]};
-                    *reinterpret_cast<f32x4*>(dst + 4) = f32x4{acc[r][c * NT + 4][y], acc[r][c * NT + 5][y], acc[r][c * NT + 6][y], acc[r][c * NT + 7][y]};
+                    *reinterpret_cast<Acc*>(dst) = Acc{acc[r][c * NT][y], acc[r][c * NT + 1][y], acc[r][c * NT + 2][y], acc[r][c * NT + 3][y]};
+                    *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][c * NT + 4][y], acc[r][c * NT + 5][y], acc[r][c * NT + 6][y], acc[r][c * NT + 7][y]};
                 } else {
 #pragma unroll
                     for (int x = 0; x < NT; ++x) dst[x] = acc[r][c * NT + x][y];
@@ -302,23 +343,26 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     }
 }
 
-template <bool BF16, int RING, int KG>
+template <int DT, int RING, int KG>
 static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
-                              float* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
+                              void* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
 {
     dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_dense_kernel<BF16, RING, KG>), grid, dim3(256 * KG), 0, s, d, t, B, b_bytes,
-                       static_cast<uint32_t>(ldb * 2), C, ldc, static_cast<int>(N), vec_store);
+    hipLaunchKernelGGL((spmm_dense_kernel<DT, RING, KG>), grid, dim3(256 * KG), 0, s, d, t, B, b_bytes,
+                       static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc,
+                       static_cast<int>(N), vec_store);
 }
 
 
 // Scatter of the CSR values into the tile layout: one thread per row of a dense super row.
 // A tile step q holds, for every block row of the super row that has one of the step's two
-// block columns, 1 KiB: lane l = 16 g + i owns halves [8 l, 8 l + 8) = row i, columns 8g..8g+7 of
-// the 32 columns of the step (first block column: 0..15, second: 16..31).
+// block columns, 512 values: lane l = 16 g + i owns values [8 l, 8 l + 8) = row i, columns 8g..8g+7
+// of the 32 columns of the step (first block column: 0..15, second: 16..31).  T is the stored
+// element (the 8-bit types keep the low byte of the 16-bit words the CSR values arrive in).
+template <typename T>
 __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __restrict__ csr_row_ptr,
                                   const int32_t* __restrict__ csr_col_idx, const uint16_t* __restrict__ csr_vals,
-                                  uint16_t* __restrict__ vals_out)
+                                  T* __restrict__ vals_out)
 {
     const int sidx = blockIdx.x;                       // which dense super row
     const int rr = threadIdx.x;                        // row inside the super row, 0..255
@@ -343,40 +387,46 @@ __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __r
         const uint32_t rows = t.step_rows[q];
         const size_t slot = static_cast<size_t>(t.step_base[q]) + __popc(rows & ((1u << j) - 1u));
         const int pc = (lo & 1) * 16 + (c & 15);
-        vals_out[slot * 512 + static_cast<size_t>((16 * (pc >> 3) + ii) * 8 + (pc & 7))] = csr_vals[p];
+        vals_out[slot * 512 + static_cast<size_t>((16 * (pc >> 3) + ii) * 8 + (pc & 7))] = static_cast<T>(csr_vals[p]);
     }
 }
 
 int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* csr_row_ptr,
-                      const int32_t* csr_col_idx, const uint16_t* csr_vals, uint16_t* vals_out, void* stream)
+                      const int32_t* csr_col_idx, const uint16_t* csr_vals, void* vals_out, int elem_bytes, void* stream)
 {
     if (t.n == 0) return 0;
-    hipLaunchKernelGGL(dense_fill_kernel, dim3(static_cast<unsigned>(t.n)), dim3(256), 0,
-                       static_cast<hipStream_t>(stream), d, t, csr_row_ptr, csr_col_idx, csr_vals, vals_out);
+    if (elem_bytes == 1)
+        hipLaunchKernelGGL(dense_fill_kernel<uint8_t>, dim3(static_cast<unsigned>(t.n)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), d, t, csr_row_ptr, csr_col_idx, csr_vals, static_cast<uint8_t*>(vals_out));
+    else
+        hipLaunchKernelGGL(dense_fill_kernel<uint16_t>, dim3(static_cast<unsigned>(t.n)), dim3(256), 0,
+                           static_cast<hipStream_t>(stream), d, t, csr_row_ptr, csr_col_idx, csr_vals, static_cast<uint16_t*>(vals_out));
     return static_cast<int>(hipGetLastError());
 }
 
 // Adds the ks partial tiles of every (super row, 128-column slab) in the order 0 .. ks-1 and
 // writes the rows to C.  Eight workgroups per tile (32 rows each); a thread sums four groups of
 // four columns and has all its loads in flight at once.
+// V is the vector of four elements of C: f32x4, or i32x4 for the integer type.
+template <typename V, typename Out>
 __global__ __launch_bounds__(256)
-void dense_reduce_kernel(DeviceBcsr d, DenseTiles t, int ks, float* __restrict__ C, int64_t ldc, int N, int vec_store)
+void dense_reduce_kernel(DeviceBcsr d, DenseTiles t, int ks, Out* __restrict__ C, int64_t ldc, int N, int vec_store)
 {
     const int super = t.super_rows[blockIdx.x];
     const int n0 = blockIdx.y * 128;
     const size_t tile = static_cast<size_t>(blockIdx.x) * gridDim.y + blockIdx.y;
-    const float* part = t.scratch + tile * ks * (256 * 128);
-    f32x4 v[4];
+    const Out* part = static_cast<const Out*>(t.scratch) + tile * ks * (256 * 128);
+    V v[4];
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
         const int e = static_cast<int>(blockIdx.z) * 1024 + j * 256 + static_cast<int>(threadIdx.x);
-        v[j] = *reinterpret_cast<const f32x4*>(part + e * 4);
+        v[j] = *reinterpret_cast<const V*>(part + e * 4);
     }
     for (int z = 1; z < ks; ++z)
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int e = static_cast<int>(blockIdx.z) * 1024 + j * 256 + static_cast<int>(threadIdx.x);
-            v[j] += *reinterpret_cast<const f32x4*>(part + static_cast<size_t>(z) * (256 * 128) + e * 4);
+            v[j] += *reinterpret_cast<const V*>(part + static_cast<size_t>(z) * (256 * 128) + e * 4);
         }
 #pragma unroll
     for (int j = 0; j < 4; ++j) {
@@ -384,9 +434,9 @@ void dense_reduce_kernel(DeviceBcsr d, DenseTiles t, int ks, float* __restrict__
         const int row = e >> 5, c = (e & 31) * 4;
         const int64_t out_row = d.perm[static_cast<int64_t>(super) * 256 + row];
         if (out_row < 0 || n0 + c >= N) continue;             // N is a multiple of 8 on this path
-        float* dst = C + out_row * ldc + n0 + c;
+        Out* dst = C + out_row * ldc + n0 + c;
         if (vec_store) {
-            *reinterpret_cast<f32x4*>(dst) = v[j];
+            *reinterpret_cast<V*>(dst) = v[j];
         } else {
             dst[0] = v[j][0]; dst[1] = v[j][1]; dst[2] = v[j][2]; dst[3] = v[j][3];
         }
@@ -406,31 +456,43 @@ int dense_split(const DenseTiles& t, int64_t N)
     return ks < 2 ? 1 : static_cast<int>(ks);
 }
 
-int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, bool bf16, const void* B, int64_t ldb,
-                      float* C, int64_t ldc, int64_t N, void* stream, const char** variant)
+template <int DT>
+static int launch_dense_dtype(const DeviceBcsr& d, const DenseTiles& t, const void* B, int64_t ldb, void* C, int64_t ldc,
+                              int64_t N, hipStream_t s, const char** variant)
 {
-    if (t.n == 0) return 0;
-    const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * 2) : 0u;
+    using Out = typename Elem<DT>::Out;
+    using Acc = typename Elem<DT>::Acc;
+    const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * Elem<DT>::ES) : 0u;
     const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
-    hipStream_t s = static_cast<hipStream_t>(stream);
     // long super rows: two wave groups per workgroup; short ones: one group, two workgroups per CU
     const bool deep = t.mean_steps >= 32.0;
     const int ks = dense_split(t, N);
     static thread_local char name[40];
-    if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", bf16 ? "bf16" : "f16", deep ? 2 : 1, ks);
-    else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", bf16 ? "bf16" : "f16", deep ? 2 : 1);
+    const char* type = DT == kF16 ? "f16" : DT == kBF16 ? "bf16" : DT == kE4M3 ? "e4m3" : DT == kE5M2 ? "e5m2" : "i8";
+    if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", type, deep ? 2 : 1, ks);
+    else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", type, deep ? 2 : 1);
     *variant = name;
-    if (bf16) {
-        if (deep) launch_dense_tile<true, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<true, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    } else {
-        if (deep) launch_dense_tile<false, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<false, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    }
+    if (deep) launch_dense_tile<DT, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    else launch_dense_tile<DT, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
     if (ks > 1)
-        hipLaunchKernelGGL(dense_reduce_kernel, dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8), dim3(256), 0, s,
-                           d, t, ks, C, ldc, static_cast<int>(N), vec_store);
+        hipLaunchKernelGGL((dense_reduce_kernel<Acc, Out>), dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8),
+                           dim3(256), 0, s, d, t, ks, static_cast<Out*>(C), ldc, static_cast<int>(N), vec_store);
     return static_cast<int>(hipGetLastError());
+}
+
+int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, int dtype, const void* B, int64_t ldb,
+                      void* C, int64_t ldc, int64_t N, void* stream, const char** variant)
+{
+    if (t.n == 0) return 0;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    switch (dtype) {
+    case kF16: return launch_dense_dtype<kF16>(d, t, B, ldb, C, ldc, N, s, variant);
+    case kBF16: return launch_dense_dtype<kBF16>(d, t, B, ldb, C, ldc, N, s, variant);
+    case kE4M3: return launch_dense_dtype<kE4M3>(d, t, B, ldb, C, ldc, N, s, variant);
+    case kE5M2: return launch_dense_dtype<kE5M2>(d, t, B, ldb, C, ldc, N, s, variant);
+    case kI8: return launch_dense_dtype<kI8>(d, t, B, ldb, C, ldc, N, s, variant);
+    default: return static_cast<int>(hipErrorInvalidValue);
+    }
 }
 
 }  // namespace smat

@@ -11,27 +11,10 @@
 #include <type_traits>
 
 #include "kernels.h"
+#include "mfma_types.h"
 #include "pack_layout.h"
 
 namespace smat {
-
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x2 __attribute__((ext_vector_type(2)));
-typedef int i32x3 __attribute__((ext_vector_type(3)));
-
-// Operand types.  The numbers are those of smat_dtype_t in the public header.
-enum : int { kF16 = 0, kBF16 = 1, kE4M3 = 2, kE5M2 = 3, kI8 = 4 };
-
-template <int DT> struct Elem {
-    static constexpr int ES = DT <= kBF16 ? 2 : 1;                                  // bytes per element of A and B
-    using Acc = typename std::conditional<DT == kI8, i32x4, f32x4>::type;           // one 16x16 output tile, per lane
-    using Out = typename std::conditional<DT == kI8, int32_t, float>::type;         // element of C
-};
 
 // Work split: one workgroup per (block row, group of SW column slabs of 16*NT columns).  The
 // group has KW*SW wavefronts: wave (ks, sl) takes packs ks, ks+KW, ... of the block row
@@ -109,24 +92,6 @@ template <> struct SLoad<16> {
     static __device__ __forceinline__ void ld(uint32_t* r, __amdgpu_buffer_rsrc_t s, uint32_t off, uint32_t soff)
     { i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(s, off, soff, 2); r[0] = v[0]; r[1] = v[1]; r[2] = v[2]; r[3] = v[3]; }
 };
-
-// One matrix instruction: a 16 x 32 piece of A' times 32 x 16 of B.  The 8-bit forms take the
-// first two dwords of a and b.
-template <int DT>
-__device__ __forceinline__ typename Elem<DT>::Acc mfma_pack(u32x4 a, u32x4 b, typename Elem<DT>::Acc c)
-{
-    if constexpr (DT == kBF16) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), c, 0, 0, 0);
-    } else if constexpr (DT == kF16) {
-        return __builtin_amdgcn_mfma_f32_16x16x32_f16(__builtin_bit_cast(f16x8, a), __builtin_bit_cast(f16x8, b), c, 0, 0, 0);
-    } else {
-        const long a8 = __builtin_bit_cast(long, u32x2{a[0], a[1]});
-        const long b8 = __builtin_bit_cast(long, u32x2{b[0], b[1]});
-        if constexpr (DT == kE4M3) return __builtin_amdgcn_mfma_f32_16x16x32_fp8_fp8(a8, b8, c, 0, 0, 0);
-        else if constexpr (DT == kE5M2) return __builtin_amdgcn_mfma_f32_16x16x32_bf8_bf8(a8, b8, c, 0, 0, 0);
-        else return __builtin_amdgcn_mfma_i32_16x16x32_i8(a8, b8, c, 0, 0, 0);
-    }
-}
 
 // 16-byte store with the non-temporal hint.  The pointer passes through an empty asm so that
 // the compiler cannot merge this store with the plain one on the other side of a branch (it

@@ -138,8 +138,6 @@ def test_8bit_types_preprocess_like_the_16bit_ones(dtype):
     finally:
         S.smat_destroy(h)
         S.smat_destroy(h16)
-    # the dense-tile kernel is 16-bit only: asking for it is refused, the automatic choice never takes it
-    _expect("SMAT_ERR_UNSUPPORTED", lambda: S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, dtype, dense_tiles=1))
     with pytest.raises(ValueError):
         S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w16.a_bits, dtype)       # 2-byte values for a 1-byte type
 

@@ -197,8 +197,60 @@ def test_hidden_blocks_i8_bit_exact_at_scale(oracle_c):
     m.close()
 
 
-def test_dense_tiles_are_refused_for_8bit():
-    w = _to8(random_csr(256, 128, 64, 0.5, seed=1), "e4m3")
-    with pytest.raises(S.SmatError) as e:
-        S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1, bind=False)
-    assert e.value.status_name == "SMAT_ERR_UNSUPPORTED"
+DENSE_SHAPES = [
+    # M, K, N, density, variant of the dense-tile kernel (as in the 16-bit tests; N a multiple of 16)
+    (256, 128, 128, 0.5, "g1"),
+    (512, 256, 144, 0.15, "g1"),
+    (272, 130, 16, 0.3, "g1"),
+    (1024, 512, 272, 0.12, "g1k2"),
+    (300, 700, 64, 0.2, "g1k2"),
+    (256, 1040, 144, 0.1, "g2k4"),
+    (256, 4112, 80, 0.1, "g2k8"),
+    (512, 1100, 16656, 0.12, "g2"),
+]
+
+
+@pytest.mark.parametrize("shape", DENSE_SHAPES, ids=lambda s: "x".join(map(str, s)))
+@pytest.mark.parametrize("dtype", DT8)
+def test_block_dense_path(dtype, shape, oracle_c):
+    M, K, N, density, kind = shape
+    w = _to8(random_csr(M, K, N, density, seed=M + K + N, b_dist="normal"), dtype)
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1)
+    got = _spmm(m, w, _dev_b(w, ldb=N + 16), ldc=N + 4)
+    assert S.smat_last_kernel().split("+")[0] == f"spmm_dense_{dtype}_{kind}", S.smat_last_kernel()
+    c_ref, s_ref = _oracle_c(oracle_c, w)
+    _check(got, c_ref, s_ref, w)
+    # device copy of the tile values is not exported; the per-row copy of the same handle is, and must match
+    perm = S.smat_export_perm(m.handle, M)
+    _, _, v = R.bcsr_from_csr(M, K, w.row_ptr, w.col_idx, w.a_bits, perm)
+    assert np.array_equal(S.smat_export_device_vals(m.handle, dtype=dtype), v)
+    # small integers: exact in all three types, so a misplaced value or B row cannot hide in the tolerance
+    wi = recast(random_csr(M, K, N, density, seed=M + K + N, values="smallint", b_dist="smallint"), dtype)
+    mi = S.SmatMatrix(wi.M, wi.K, wi.row_ptr, wi.col_idx, wi.a_bits, wi.dtype, dense_tiles=1)
+    goti = _spmm(mi, wi, _dev_b(wi))
+    assert S.smat_last_kernel().startswith("spmm_dense")
+    ci_ref, _ = _oracle_c(oracle_c, wi)
+    assert np.array_equal(goti.astype(np.float64), ci_ref)
+    # a width the dense path does not take (N not a multiple of 16) goes through the per-row kernel
+    w2 = _to8(random_csr(M, K, 24, density, seed=M + K, b_dist="normal"), dtype)
+    m2, _ = _run(w2, oracle_c)
+    assert not S.smat_last_kernel().startswith("spmm_dense")
+    # switched off / automatic choice: either way the result
+    m3 = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=-1)
+    _check(_spmm(m3, w, _dev_b(w)), c_ref, s_ref, w)
+    assert not S.smat_last_kernel().startswith("spmm_dense")
+    m4 = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=0)
+    _check(_spmm(m4, w, _dev_b(w)), c_ref, s_ref, w)
+    for x in (m, mi, m2, m3, m4):
+        x.close()
+
+
+@pytest.mark.parametrize("dtype", DT8)
+def test_pruned_weight_full_size(dtype, oracle_c):
+    # the block-dense workload (4096^2, 10 % dense, N = 2048) in the 8-bit types: the automatic choice
+    # must take the tile kernel, every element checked
+    base = make_config("pruned_weight")
+    w = recast(base, dtype, a_scale=127.0 / 0.08 if dtype == "i8" else 16.0, b_scale=30.0 if dtype == "i8" else 1.0)
+    m, _ = _run(w, oracle_c)
+    assert S.smat_last_kernel() == f"spmm_dense_{dtype}_g2", S.smat_last_kernel()
+    m.close()
