@@ -571,7 +571,9 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
         const int ks = smat::dense_split(h->tiles, N);
         double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * 0.7 + 4.0);
         if (ks > 1) t_tiles += 3.0 + tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
-        const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * h->elem_bytes / 10.0e6 + 4.0;
+        // (two bytes per value also for the 8-bit types: on block-dense rows the per-row kernel did not
+        // get faster with them -- 35.6 us against 35 on the band workload -- while the tile kernel did)
+        const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
         use_tiles = t_tiles <= t_rows;
     }
     const char* variant = "";

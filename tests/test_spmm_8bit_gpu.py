@@ -245,6 +245,15 @@ def test_block_dense_path(dtype, shape, oracle_c):
         x.close()
 
 
+@pytest.mark.parametrize("dtype", ["e4m3", "i8"])
+def test_banded_full_size(dtype, oracle_c):
+    # the band workload (65536^2, N = 256): short super rows, the one-group tile kernel, chosen automatically
+    w = _to8(make_config("banded"), dtype, b_scale=100.0)
+    m, _ = _run(w, oracle_c)
+    assert S.smat_last_kernel() == f"spmm_dense_{dtype}_g1", S.smat_last_kernel()
+    m.close()
+
+
 @pytest.mark.parametrize("dtype", DT8)
 def test_pruned_weight_full_size(dtype, oracle_c):
     # the block-dense workload (4096^2, 10 % dense, N = 2048) in the 8-bit types: the automatic choice
