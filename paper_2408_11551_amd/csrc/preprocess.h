@@ -15,7 +15,7 @@ struct Csr {
     int64_t M = 0, K = 0;
     std::vector<int64_t> row_ptr;   // [M+1]
     std::vector<int32_t> col_idx;   // [nnz]
-    std::vector<uint16_t> vals;     // [nnz]
+    std::vector<uint16_t> vals;     // [nnz] bit patterns (an 8-bit type sits in the low byte)
 };
 
 struct Bcsr {
