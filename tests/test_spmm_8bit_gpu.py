@@ -16,7 +16,7 @@ torch = pytest.importorskip("torch")
 
 import paper_2408_11551_amd as S            # noqa: E402
 from oracle import smat_ref as R            # noqa: E402
-from workloads import random_csr, occupancy_csr, OCCUPANCY_SPEC, make_config, recast  # noqa: E402
+from workloads import random_csr, band_csr, occupancy_csr, OCCUPANCY_SPEC, make_config, recast  # noqa: E402
 
 DT8 = ["e4m3", "e5m2", "i8"]
 REL_BAR = 1e-2
@@ -263,3 +263,38 @@ def test_pruned_weight_full_size(dtype, oracle_c):
     m, _ = _run(w, oracle_c)
     assert S.smat_last_kernel() == f"spmm_dense_{dtype}_g2", S.smat_last_kernel()
     m.close()
+
+
+def test_seeded_sweep_of_random_shapes_and_options(oracle_c):
+    # 90 seeded cases over the three types: ragged and block-dense shapes, bands, all options of the
+    # preprocessing, leading dimensions with poisoned padding; every element of C against the oracle
+    rng = np.random.default_rng(2024)
+    for case in range(90):
+        dtype = DT8[case % 3]
+        kind = int(rng.integers(5))
+        N = int(rng.choice([1, 2, 3, 4, 7, 8, 12, 16, 24, 32, 48, 64, 100, 128, 144, 200, 256, 272, 400]))
+        if kind == 4:       # block-dense: complete super rows, N in whole 16-byte pieces
+            M, K = int(rng.choice([256, 272, 512, 700])), int(rng.integers(100, 2200))
+            N = int(rng.choice([16, 48, 128, 144, 272]))
+            base = random_csr(M, K, N, float(rng.choice([0.08, 0.15, 0.3, 0.6])), seed=case, b_dist="normal")
+        elif kind == 3:
+            M = int(rng.integers(64, 1500))
+            base = band_csr(M, int(rng.integers(1, 80)), N, seed=case, p=float(rng.choice([0.3, 1.0])), b_dist="normal")
+        else:
+            M, K = int(rng.integers(1, 700)), int(rng.integers(1, 900))
+            if kind == 2:
+                M, K = int(rng.integers(16, 300)), int(rng.integers(900, 5000))
+            base = random_csr(M, K, N, float(rng.choice([0.0, 0.002, 0.01, 0.05, 0.2, 0.5, 1.0])), seed=case, b_dist="normal")
+        w = _to8(base, dtype)
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=int(rng.integers(2)),
+                         tau_permille=int(rng.choice([0, 300, 700, 1000])), dense_tiles=int(rng.integers(-1, 2)))
+        ldb = w.N + int(rng.choice([0, 0, 1, 2, 4, 8, 16]))
+        ldc = w.N + int(rng.choice([0, 0, 1, 3, 4]))
+        got = _spmm(m, w, _dev_b(w, ldb), ldc)
+        c_ref, s_ref = _oracle_c(oracle_c, w)
+        try:
+            _check(got, c_ref, s_ref, w)
+        except AssertionError as e:
+            raise AssertionError(f"case {case}: {dtype} {w.M}x{w.K}x{w.N} nnz={w.nnz} ldb={ldb} ldc={ldc} "
+                                 f"kernel={S.smat_last_kernel()}: {e}") from None
+        m.close()
