@@ -112,6 +112,11 @@ def main():
     ap.add_argument("--probes", action="store_true",
                     help="also time the library's probe kernels (streaming read, row gather, MFMA loop): what this GPU "
                          "delivers for the access patterns the SpMM kernels are made of")
+    ap.add_argument("--reorder", type=int, default=1, choices=[0, 1],
+                    help="row reordering of the preprocessing: 1 Jaccard clustering with the identity guard (default), 0 none")
+    ap.add_argument("--vendor", action="store_true",
+                    help="also time the vendor's CSR SpMM on the same matrix (hipSPARSE through torch.sparse.mm, "
+                         "fp32: it offers no 16-bit CSR SpMM here)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (known traffic, scales the profiler's byte counters)")
     args = ap.parse_args()
@@ -134,7 +139,8 @@ def main():
     mfma_peak = MFMA_PEAK_TFLOPS if es == 2 else MFMA_PEAK_TFLOPS_8BIT
 
     t0 = time.perf_counter()
-    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=args.dense_tiles)
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=args.dense_tiles,
+                          reorder=args.reorder)
     t_pre = time.perf_counter() - t0
     info = S.smat_get_info(h)
     layout = S.smat_get_layout_info(h)
@@ -222,6 +228,29 @@ def main():
     if args.probes:
         extra["probes"] = run_probes(S, torch, dev, stream)
 
+    if args.vendor:
+        # the same product through the vendor's sparse library; values widened to fp32 (exact)
+        from workloads import from_bits
+        a32 = torch.from_numpy(from_bits(w.a_bits, w.dtype)).to(torch.float32)
+        A_csr = torch.sparse_csr_tensor(torch.from_numpy(w.row_ptr), torch.from_numpy(w.col_idx.astype(np.int64)), a32,
+                                        size=(w.M, w.K), device=dev)
+        B32 = torch.from_numpy(from_bits(w.b_bits.reshape(-1), w.dtype).reshape(w.K, w.N)).to(torch.float32).to(dev)
+        for _ in range(3):
+            torch.sparse.mm(A_csr, B32)
+        torch.cuda.synchronize()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        reps = 20
+        a.record(stream)
+        for _ in range(reps):
+            torch.sparse.mm(A_csr, B32)
+        b.record(stream)
+        torch.cuda.synchronize()
+        vendor_ms = a.elapsed_time(b) / reps
+        extra["vendor_csr_spmm"] = {"library": "hipSPARSE CSR SpMM through torch.sparse.mm", "dtype": "f32", "ms": vendor_ms,
+                                    "useful_tflops": useful_flop / (vendor_ms * 1e-3) / 1e12,
+                                    "times_slower_than_this_library": vendor_ms / kernel_ms}
+        del A_csr, B32
+
     cpu = None
     if not args.no_cpu_baseline:
         from oracle import cref, smat_ref
@@ -264,6 +293,7 @@ def main():
             "blocks_per_row_mean": float(per_row.mean()) if per_row.size else 0.0,
             "blocks_per_row_std": float(per_row.std()) if per_row.size else 0.0,
             "blocks_per_row_max": int(per_row.max()) if per_row.size else 0,
+            "reorder": args.reorder,
             "preprocess_s": t_pre, "bind_s": t_bind, "kernel": kernel_name, "cache": "hot (back-to-back launches)",
         },
         "stored_block_tflops": stored_flop / (kernel_ms * 1e-3) / 1e12,
