@@ -9,6 +9,10 @@ HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 OBJ = os.path.join(HERE, "_build")
 OUT = os.path.join(HERE, "libsmat.so")
+# a plain-C program that uses the library through include/smat.h alone (no Python in the process)
+EXAMPLE_SRC = os.path.join(HERE, "..", "examples", "c_abi_example.c")
+EXAMPLE_OUT = os.path.join(HERE, "c_abi_example")
+ROCM = os.environ.get("ROCM_PATH", "/opt/rocm")
 # The per-row kernel starts with a chain of dependent loads (launch record -> slot table -> rows
 # of B); having the dispatcher place its leading arguments in scalar registers takes the load of
 # the arguments themselves off the front of that chain.
@@ -65,6 +69,14 @@ def build(force: bool = True, verbose: bool = False) -> str:
     if verbose:
         print(" ".join(cmd), flush=True)
     subprocess.run(cmd, check=True)
+    if os.path.exists(EXAMPLE_SRC):
+        cmd = [os.environ.get("CC", "gcc"), "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__", EXAMPLE_SRC,
+               "-I" + os.path.join(HERE, "..", "include"), "-I" + os.path.join(ROCM, "include"),
+               "-L" + HERE, "-lsmat", "-L" + os.path.join(ROCM, "lib"), "-lamdhip64",
+               "-Wl,-rpath,$ORIGIN", "-Wl,-rpath," + os.path.join(ROCM, "lib"), "-o", EXAMPLE_OUT]
+        if verbose:
+            print(" ".join(cmd), flush=True)
+        subprocess.run(cmd, check=True)
     return OUT
 
 

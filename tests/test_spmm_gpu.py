@@ -459,3 +459,16 @@ def test_ablation_kernels_compute_the_same_product(dtype, oracle_c):
         S.smat_ablation_spmm(m.handle, 3, b, c)
     assert e.value.status_name == "SMAT_ERR_INVALID_ARG"
     m.close()
+
+
+def test_plain_c_program_through_the_abi():
+    # examples/c_abi_example.c: no Python, no PyTorch in the process; device memory from hipMalloc,
+    # every element of C compared with an integer loop on the host.  Built by build.py.
+    import os
+    import subprocess
+    exe = os.path.join(os.path.dirname(S.lib_path()), "c_abi_example")
+    if not os.path.exists(exe):
+        pytest.skip("c_abi_example has not been built (paper_2408_11551_amd/build.py builds it)")
+    for args in (["1000", "777", "40", "9"], ["4096", "4096", "128", "33"], ["300", "64", "256", "40"], ["17", "20", "1", "3"]):
+        out = subprocess.run([exe, *args], capture_output=True, text=True, timeout=120)
+        assert out.returncode == 0 and out.stdout.strip().endswith("OK"), (args, out.stdout, out.stderr)
