@@ -118,7 +118,7 @@ Layout make_layout(const smat_handle& h)
     l.t_cols = take(h.step_cols.size() * sizeof(int32_t));
     l.t_rows = take(h.step_rows.size() * sizeof(uint32_t));
     l.t_base = take(h.step_base.size() * sizeof(uint32_t));
-    l.t_vals = take(static_cast<size_t>(h.dense_slots) * 512 * static_cast<size_t>(h.elem_bytes));
+    l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
     l.t_scratch = take(h.dense_super.empty() ? 0 : kTileScratchBytes);
     l.total = off ? off : kAlign;
     return l;
@@ -138,6 +138,10 @@ void plan_dense_tiles(smat_handle& h)
     h.step_ptr.assign(1, 0);
     if (h.dense_mode < 0) return;
     std::vector<int32_t> uni;
+    // block columns per step: the 32 k slots of a 16-bit MFMA are two block columns; the 8-bit types
+    // take four per step (two MFMA 16x16x32 per output tile between barriers), so that a step moves
+    // the same bytes and a tile has half as many of them
+    const int64_t cps = h.elem_bytes == 1 ? 4 : 2;
     for (int64_t s = 0; (s + 1) * 16 <= nbr; ++s) {
         const int32_t lo = b.row_ptr[s * 16], hi = b.row_ptr[s * 16 + 16];
         if (hi - lo < 64) continue;
@@ -148,21 +152,22 @@ void plan_dense_tiles(smat_handle& h)
         for (int32_t k = lo; k < hi; ++k) occupied += __builtin_popcount(b.col_mask[k]);
         const int64_t n_uni = static_cast<int64_t>(uni.size()), n_blk = hi - lo;
         if (n_uni < 8 || n_blk * 20 < 7 * 16 * n_uni || occupied < 8 * n_blk) continue;
-        const int64_t steps = (n_uni + 1) / 2;
+        const int64_t steps = (n_uni + cps - 1) / cps;
         if (steps * 16 >= (int64_t{1} << 21) || h.dense_slots + static_cast<uint64_t>(steps) * 16 >= (uint64_t{1} << 31)) continue;
         h.dense_super.push_back(static_cast<int32_t>(s));
         h.dense_columns += occupied;
         for (int j = 0; j < 16; ++j) h.row_dense[static_cast<size_t>(s * 16 + j)] = 1;
         for (int64_t q = 0; q < steps; ++q) {
-            const int32_t c0 = uni[2 * q], c1 = 2 * q + 1 < n_uni ? uni[2 * q + 1] : 0x7FFFFFFF;
+            int32_t cols[4];
+            for (int64_t e = 0; e < cps; ++e) cols[e] = cps * q + e < n_uni ? uni[cps * q + e] : 0x7FFFFFFF;
             uint32_t rows = 0;
             for (int j = 0; j < 16; ++j) {
                 const int32_t* first = b.col_idx.data() + b.row_ptr[s * 16 + j];
                 const int32_t* last = b.col_idx.data() + b.row_ptr[s * 16 + j + 1];
-                if (std::binary_search(first, last, c0) || std::binary_search(first, last, c1)) rows |= 1u << j;
+                for (int64_t e = 0; e < cps; ++e)
+                    if (std::binary_search(first, last, cols[e])) rows |= 1u << j;
             }
-            h.step_cols.push_back(c0);
-            h.step_cols.push_back(c1);
+            for (int64_t e = 0; e < cps; ++e) h.step_cols.push_back(cols[e]);
             h.step_rows.push_back(rows);
             h.step_base.push_back(static_cast<uint32_t>(h.dense_slots));
             h.dense_slots += static_cast<uint64_t>(__builtin_popcount(rows));
@@ -465,6 +470,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.scratch_bytes = h->dense_super.empty() ? 0 : kTileScratchBytes;
         tiles.n = static_cast<int32_t>(h->dense_super.size());
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
+        tiles.cols_per_step = h->elem_bytes == 1 ? 4 : 2;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
@@ -473,7 +479,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
             return hip_fail("zero block values", e);
         if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.vals, h->elem_bytes, s)))
             return hip_fail("fill block values", e);
-        if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 32 * static_cast<size_t>(h->elem_bytes), s)))
+        if ((e = smat::launch_fill_zero(base + l.t_vals, static_cast<size_t>(h->dense_slots) * 64, s)))
             return hip_fail("zero tile values", e);
         if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.t_vals, h->elem_bytes, s)))
             return hip_fail("fill tile values", e);
@@ -569,7 +575,8 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     if (use_tiles && h->dense_mode == 0) {
         const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
         const int ks = smat::dense_split(h->tiles, N);
-        double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * 0.7 + 4.0);
+        const double step_us = h->elem_bytes == 1 ? 1.0 : 0.7;     // an 8-bit step covers twice the block columns
+        double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * step_us + 4.0);
         if (ks > 1) t_tiles += 3.0 + tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
         // (two bytes per value also for the 8-bit types: on block-dense rows the per-row kernel did not
         // get faster with them -- 35.6 us against 35 on the band workload -- while the tile kernel did)

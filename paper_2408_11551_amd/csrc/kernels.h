@@ -35,20 +35,22 @@ struct DeviceBcsr {
 
 // Block-dense parts of the matrix: "super rows" of sixteen consecutive block rows whose block
 // columns overlap enough to be walked together (kernels_dense.hip).  The union of a super
-// row's block columns, ascending, is cut into steps of two block columns; step q stores 512
-// values (1 KiB for the 16-bit types) for every block row that has one of its two columns (bit j
-// of step_rows), back to back from slot step_base[q].
+// row's block columns, ascending, is cut into steps of cols_per_step block columns (two for the
+// 16-bit types = the 32 k slots of one MFMA; four for the 8-bit types = two MFMAs); step q stores
+// 1 KiB for every block row that has one of its columns (bit j of step_rows), back to back from
+// slot step_base[q].
 struct DenseTiles {
     const int32_t* super_rows = nullptr;   // [n] super row index s: block rows 16 s .. 16 s + 15
     const int32_t* step_ptr = nullptr;     // [n+1] offsets into the step arrays
-    const int32_t* step_cols = nullptr;    // [2 * steps] block columns of a step (INT_MAX: none)
+    const int32_t* step_cols = nullptr;    // [cols_per_step * steps] block columns of a step (INT_MAX: none)
     const uint32_t* step_rows = nullptr;   // [steps] 16-bit mask of block rows present in the step
     const uint32_t* step_base = nullptr;   // [steps] first slot of the step
-    const void* vals = nullptr;            // [512 * slots] values of 2 bytes or 1
+    const void* vals = nullptr;            // [1024 bytes * slots]
     void* scratch = nullptr;               // partial tiles (fp32, or int32 for the integer type) of launches that split the steps of a tile
     size_t scratch_bytes = 0;
     int32_t n = 0;
     double mean_steps = 0;                 // steps per super row, on average
+    int cols_per_step = 2;
 };
 
 // Sets n16 16-byte words at dst to zero.

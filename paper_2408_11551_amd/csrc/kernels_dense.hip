@@ -34,12 +34,6 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
     return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), static_cast<uint32_t>(v[2]), static_cast<uint32_t>(v[3])};
 }
 
-__device__ __forceinline__ u32x4 buf_load8(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
-{
-    const i32x2 v = __builtin_amdgcn_raw_buffer_load_b64(r, voff, soff, 0);
-    return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), 0u, 0u};
-}
-
 }  // namespace
 
 // C rows of the dense super rows, 128 columns per workgroup; 4 waves, wave w owns block rows
@@ -63,10 +57,12 @@ __device__ __forceinline__ u32x4 buf_load8(__amdgpu_buffer_rsrc_t r, uint32_t vo
 // accumulation registers was built as well: 9 % faster than one group at N = 4096, slower than
 // two groups, and removed.)
 //
-// DT is the operand type.  The 8-bit types run the same walk with elements of one byte: a step
-// is still two block columns = the 32 k slots of their MFMA 16x16x32 forms, a block row's values
-// for a step are 512 bytes (eight per lane), the panel of B is 32 rows of 128 bytes, staged by
-// one 16-byte piece per thread, and the operand of MFMA x is byte x of the lane's eight rows.
+// DT is the operand type.  The 8-bit types run the same walk with elements of one byte and
+// steps of four block columns (KS = 2 sub-steps of 32 k slots, i.e. two MFMA 16x16x32 per output
+// tile between barriers): a block row's values for a step are again 1 KiB (sixteen bytes per
+// lane, eight per sub-step), the panel of B is 64 rows of 128 bytes, staged in two 16-byte
+// pieces per thread, and the operand of MFMA x is byte x of the lane's eight rows of a sub-step.
+// A step thus moves the same bytes as a 16-bit one and a tile has half as many steps.
 template <int DT, int RING, int KG>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -80,16 +76,17 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     constexpr int NT = 8;                          // columns per lane; 16 lanes cover a 128-column chunk
     constexpr int RM = 4;                          // block rows per wave
     constexpr int NCH = 1;                         // 128-column chunks per workgroup
-    constexpr int NS = ES * NCH;                   // 16-byte pieces of the panel a thread stages per step
+    constexpr int KS = ES == 1 ? 2 : 1;            // sub-steps of 32 k slots (two block columns) per step
+    constexpr int NS = 2 * NCH;                    // 16-byte pieces of the panel a thread stages per step
     constexpr int PW = 8 * ES * NCH;               // 16-byte pieces per panel row (128 * NCH elements)
     constexpr int NBUF = RING == 3 ? 3 : 2;        // panel buffers; the loop body of RING steps keeps their indices constant
-    __shared__ u32x4 panel_all[KG][NBUF][32][PW];  // per wave group, buffers of 32 B rows x (128 * NCH) elements
+    __shared__ u32x4 panel_all[KG][NBUF][32 * KS][PW];  // per wave group, buffers of 32 KS rows of B x (128 * NCH) elements
 
     const int tid = threadIdx.x & 255;             // thread inside its wave group
     const int lane = tid & 63;
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
     const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
-    u32x4 (*panel)[32][PW] = panel_all[kg];
+    u32x4 (*panel)[32 * KS][PW] = panel_all[kg];
     const int i = lane & 15, g = lane >> 4;
     const int sidx = blockIdx.x;
     const int super = t.super_rows[sidx];
@@ -107,13 +104,13 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
     const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * (512 * ES), 0,
-        static_cast<int>((end_slot - first_slot) * (512u * ES)), kRsrcFlags);
+        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
+        static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
 
     // staging of the B panel, 16 bytes per piece.  16-bit types: thread tid copies, per chunk, the
-    // pieces of rows (tid >> 4) and 16 + (tid >> 4) at column 8 * (tid & 15); 8-bit types: the one
-    // piece of row (tid >> 3) at column 16 * (tid & 7).  (N is a multiple of the columns of a piece
-    // on this path, so a piece is all inside or all outside.)
+    // pieces of rows (tid >> 4) and 16 + (tid >> 4) at column 8 * (tid & 15); 8-bit types: the
+    // pieces of rows (tid >> 3) and 32 + (tid >> 3) at column 16 * (tid & 7).  (N is a multiple of
+    // the columns of a piece on this path, so a piece is all inside or all outside.)
     const int st_row = ES == 2 ? tid >> 4 : tid >> 3, st_chunk = ES == 2 ? tid & 15 : tid & 7;
     uint32_t st_off[NCH];
 #pragma unroll
@@ -127,19 +124,19 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     // What a step's loads need to know, fetched with scalar loads one step before it is used:
     // a scalar load that is waited for right away costs a few hundred cycles in which the wave,
     // alone on its SIMD, does nothing.
-    struct StepMeta { int c0, c1; uint32_t rows, base; };
+    struct StepMeta { int c[2 * KS]; uint32_t rows, base; };
     auto fetch_meta = [&](int q) {
         StepMeta m;
-        m.c0 = t.step_cols[2 * static_cast<size_t>(q)];
-        m.c1 = t.step_cols[2 * static_cast<size_t>(q) + 1];
+#pragma unroll
+        for (int e = 0; e < 2 * KS; ++e) m.c[e] = t.step_cols[(2 * KS) * static_cast<size_t>(q) + e];
         m.rows = t.step_rows[q];
         m.base = t.step_base[q];
         return m;
     };
     auto load_panel = [&](const StepMeta& m, u32x4 (&stage)[NS]) {
-        const int c0 = m.c0, c1 = m.c1;
-        // rows past K (ragged last block column, or no second column) are out of range: zeros
+        // rows past K (ragged last block column, or no such column) are out of range: zeros
         if constexpr (ES == 2) {
+            const int c0 = m.c[0], c1 = m.c[1];
             uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
             uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
             row0 = row0 < no_row ? row0 : no_row;
@@ -151,12 +148,15 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                 stage[2 * c + 1] = buf_load16(b_rsrc, off1 + st_off[c], 0u);
             }
         } else {
-            const int col = st_row < 16 ? c0 : c1;
-            uint32_t row = col < nbc ? static_cast<uint32_t>(col) * 16u + (st_row & 15) : no_row;
-            row = row < no_row ? row : no_row;
-            const uint32_t off = __umul24(row, ldb_bytes);
 #pragma unroll
-            for (int c = 0; c < NCH; ++c) stage[c] = buf_load16(b_rsrc, off + st_off[c], 0u);
+            for (int j = 0; j < KS; ++j) {
+                const int col = st_row < 16 ? m.c[2 * j] : m.c[2 * j + 1];
+                uint32_t row = col < nbc ? static_cast<uint32_t>(col) * 16u + (st_row & 15) : no_row;
+                row = row < no_row ? row : no_row;
+                const uint32_t off = __umul24(row, ldb_bytes);
+#pragma unroll
+                for (int c = 0; c < NCH; ++c) stage[KS * c + j] = buf_load16(b_rsrc, off + st_off[c], 0u);
+            }
         }
     };
     auto store_panel = [&](int buf, const u32x4 (&stage)[NS]) {
@@ -166,7 +166,8 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                 panel[buf][st_row][16 * c + st_chunk] = stage[2 * c];
                 panel[buf][16 + st_row][16 * c + st_chunk] = stage[2 * c + 1];
             } else {
-                panel[buf][st_row][8 * c + st_chunk] = stage[c];
+#pragma unroll
+                for (int j = 0; j < KS; ++j) panel[buf][32 * j + st_row][8 * c + st_chunk] = stage[KS * c + j];
             }
         }
     };
@@ -181,8 +182,7 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
             const int j = RM * wave + r;
             const uint32_t slot = base + __popc(rows & ((1u << j) - 1u));
             const uint32_t absent = (live && (rows >> j & 1u)) ? 0u : kOutOfRange;      // wave-uniform
-            if constexpr (ES == 2) a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
-            else a[r] = buf_load8(a_rsrc, (static_cast<uint32_t>(lane) * 8u) | absent, slot * 512u);
+            a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
         }
     };
 
@@ -243,25 +243,32 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                                 acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
                         }
                     } else {
-                        // eight bytes per row: the lane's eight columns; operand dword = byte x of four rows
-                        u32x2 R[8];
+                        // per sub-step, eight bytes per row: the lane's eight columns; operand dword =
+                        // byte x of four rows.  The lane's block values of sub-step j are dwords 2j, 2j+1.
 #pragma unroll
-                        for (int kk = 0; kk < 8; ++kk)
-                            R[kk] = reinterpret_cast<const u32x2*>(&panel[buf][8 * g + kk][8 * c])[i];
-                        __builtin_amdgcn_sched_barrier(0);
+                        for (int j = 0; j < KS; ++j) {
+                            u32x2 R[8];
 #pragma unroll
-                        for (int x = 0; x < NT; ++x) {
-                            const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
-                            u32x4 b = u32x4{0u, 0u, 0u, 0u};
+                            for (int kk = 0; kk < 8; ++kk)
+                                R[kk] = reinterpret_cast<const u32x2*>(&panel[buf][32 * j + 8 * g + kk][8 * c])[i];
+                            __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-                            for (int qd = 0; qd < 2; ++qd) {
-                                const uint32_t lo = __builtin_amdgcn_perm(R[4 * qd + 1][x >> 2], R[4 * qd][x >> 2], pair);
-                                const uint32_t hi = __builtin_amdgcn_perm(R[4 * qd + 3][x >> 2], R[4 * qd + 2][x >> 2], pair);
-                                b[qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                            for (int x = 0; x < NT; ++x) {
+                                const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
+                                u32x4 b = u32x4{0u, 0u, 0u, 0u};
+#pragma unroll
+                                for (int qd = 0; qd < 2; ++qd) {
+                                    const uint32_t lo = __builtin_amdgcn_perm(R[4 * qd + 1][x >> 2], R[4 * qd][x >> 2], pair);
+                                    const uint32_t hi = __builtin_amdgcn_perm(R[4 * qd + 3][x >> 2], R[4 * qd + 2][x >> 2], pair);
+                                    b[qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                                }
+#pragma unroll
+                                for (int r = 0; r < RM; ++r) {
+                                    const u32x4 aj = u32x4{a[u][r][2 * j], a[u][r][2 * j + 1], 0u, 0u};
+                                    acc[r][c * NT + x] = mfma_pack<DT>(aj, b, acc[r][c * NT + x]);
+                                }
                             }
-#pragma unroll
-                            for (int r = 0; r < RM; ++r)
-                                acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
+                            __builtin_amdgcn_sched_barrier(0);
                         }
                     }
                     __builtin_amdgcn_sched_barrier(0);
@@ -356,9 +363,11 @@ static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, 
 
 // Scatter of the CSR values into the tile layout: one thread per row of a dense super row.
 // A tile step q holds, for every block row of the super row that has one of the step's two
-// block columns, 512 values: lane l = 16 g + i owns values [8 l, 8 l + 8) = row i, columns 8g..8g+7
-// of the 32 columns of the step (first block column: 0..15, second: 16..31).  T is the stored
-// element (the 8-bit types keep the low byte of the 16-bit words the CSR values arrive in).
+// block columns, 1 KiB.  16-bit types (two block columns per step): lane l = 16 g + i owns values
+// [8 l, 8 l + 8) = row i, columns 8g..8g+7 of the 32 columns of the step.  8-bit types (four block
+// columns per step, two sub-steps of 32 columns): lane l owns bytes [16 l, 16 l + 16): eight of
+// sub-step 0, then eight of sub-step 1, each row i, columns 8g..8g+7 of the sub-step.  T is the
+// stored element (the 8-bit types keep the low byte of the 16-bit words the CSR values arrive in).
 template <typename T>
 __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __restrict__ csr_row_ptr,
                                   const int32_t* __restrict__ csr_col_idx, const uint16_t* __restrict__ csr_vals,
@@ -371,8 +380,9 @@ __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __r
     const int64_t r = d.perm[i];
     const int j = rr >> 4, ii = rr & 15;
     const int q0 = t.step_ptr[sidx], q1 = t.step_ptr[sidx + 1];
-    const int32_t* cols = t.step_cols + 2 * static_cast<size_t>(q0);   // ascending; a missing last column is INT_MAX
-    const int ncols = 2 * (q1 - q0);
+    const int cps = t.cols_per_step, ksub = cps / 2;
+    const int32_t* cols = t.step_cols + static_cast<size_t>(cps) * static_cast<size_t>(q0);   // ascending; a missing last column is INT_MAX
+    const int ncols = cps * (q1 - q0);
     int hint = 0;
     for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
         const int c = csr_col_idx[p];
@@ -383,11 +393,12 @@ __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __r
             if (cols[mid] < bc) lo = mid + 1; else hi = mid;
         }
         hint = lo;
-        const size_t q = static_cast<size_t>(q0 + (lo >> 1));
+        const size_t q = static_cast<size_t>(q0 + lo / cps);
         const uint32_t rows = t.step_rows[q];
         const size_t slot = static_cast<size_t>(t.step_base[q]) + __popc(rows & ((1u << j) - 1u));
-        const int pc = (lo & 1) * 16 + (c & 15);
-        vals_out[slot * 512 + static_cast<size_t>((16 * (pc >> 3) + ii) * 8 + (pc & 7))] = static_cast<T>(csr_vals[p]);
+        const int pc = (lo % cps) * 16 + (c & 15);                 // column inside the step
+        const int sub = pc >> 5, g = (pc & 31) >> 3;               // sub-step, lane group
+        vals_out[slot * (1024 / sizeof(T)) + static_cast<size_t>(((16 * g + ii) * ksub + sub) * 8 + (pc & 7))] = static_cast<T>(csr_vals[p]);
     }
 }
 

@@ -198,15 +198,17 @@ def test_hidden_blocks_i8_bit_exact_at_scale(oracle_c):
 
 
 DENSE_SHAPES = [
-    # M, K, N, density, variant of the dense-tile kernel (as in the 16-bit tests; N a multiple of 16)
+    # M, K, N, density, variant of the dense-tile kernel (N a multiple of 16).  A step of the 8-bit
+    # types covers four block columns, so "long super rows" (two wave groups, g2) start at K ~ 2000
     (256, 128, 128, 0.5, "g1"),
     (512, 256, 144, 0.15, "g1"),
     (272, 130, 16, 0.3, "g1"),
-    (1024, 512, 272, 0.12, "g1k2"),
-    (300, 700, 64, 0.2, "g1k2"),
-    (256, 1040, 144, 0.1, "g2k4"),
+    (1024, 512, 272, 0.12, "g1"),
+    (300, 700, 64, 0.2, "g1"),
+    (256, 1040, 144, 0.1, "g1k2"),
+    (256, 2100, 144, 0.1, "g2k4"),
     (256, 4112, 80, 0.1, "g2k8"),
-    (512, 1100, 16656, 0.12, "g2"),
+    (512, 2100, 8336, 0.1, "g2"),
 ]
 
 
