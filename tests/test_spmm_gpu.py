@@ -472,3 +472,48 @@ def test_plain_c_program_through_the_abi():
     for args in (["1000", "777", "40", "9"], ["4096", "4096", "128", "33"], ["300", "64", "256", "40"], ["17", "20", "1", "3"]):
         out = subprocess.run([exe, *args], capture_output=True, text=True, timeout=120)
         assert out.returncode == 0 and out.stdout.strip().endswith("OK"), (args, out.stdout, out.stderr)
+
+
+def test_two_handles_on_two_streams_and_rebinding(oracle_c):
+    # calls on different handles may overlap on different streams; a handle may be bound again to
+    # another workspace (the old one is then free to go)
+    w1 = random_csr(700, 900, 136, 0.05, seed=31, dtype="f16", b_dist="normal")
+    w2 = random_csr(512, 1100, 264, 0.12, seed=32, dtype="bf16", b_dist="normal")       # block-dense: tile kernel with split tiles
+    m1 = S.SmatMatrix(w1.M, w1.K, w1.row_ptr, w1.col_idx, w1.a_bits, w1.dtype)
+    m2 = S.SmatMatrix(w2.M, w2.K, w2.row_ptr, w2.col_idx, w2.a_bits, w2.dtype, dense_tiles=1)
+    b1, b2 = _dev_b(w1), _dev_b(w2)
+    c1 = torch.empty((w1.M, w1.N), dtype=torch.float32, device="cuda")
+    c2 = torch.empty((w2.M, w2.N), dtype=torch.float32, device="cuda")
+    s1, s2 = torch.cuda.Stream(), torch.cuda.Stream()
+    torch.cuda.synchronize()
+    for _ in range(20):
+        S.smat_spmm(m1.handle, b1, c1, w1.N, s1)
+        S.smat_spmm(m2.handle, b2, c2, w2.N, s2)
+    torch.cuda.synchronize()
+    r1, r2 = _oracle_c(oracle_c, w1), _oracle_c(oracle_c, w2)
+    _check_c(c1.cpu().numpy(), r1[0], r1[1], w1)
+    _check_c(c2.cpu().numpy(), r2[0], r2[1], w2)
+    # bind both again, to fresh workspaces; the old ones are overwritten before the next launch
+    old1, old2 = m1.workspace, m2.workspace
+    m1.bind()
+    m2.bind()
+    old1.fill_(0xFF)
+    old2.fill_(0xFF)
+    c1.fill_(float("nan"))
+    c2.fill_(float("nan"))
+    S.smat_spmm(m1.handle, b1, c1, w1.N)
+    S.smat_spmm(m2.handle, b2, c2, w2.N)
+    torch.cuda.synchronize()
+    _check_c(c1.cpu().numpy(), r1[0], r1[1], w1)
+    _check_c(c2.cpu().numpy(), r2[0], r2[1], w2)
+    m1.close()
+    m2.close()
+
+
+def test_wide_and_odd_output_widths(oracle_c):
+    # thousands of columns that are no multiple of anything: many column slabs per block row, the
+    # narrowest loads, a leading dimension far larger than N
+    for N, ldb, dtype in ((5001, 5001, "f16"), (4098, 6000, "bf16"), (3000, 3000, "f16")):
+        w = random_csr(90, 300, N, 0.06, seed=N, dtype=dtype, b_dist="normal")
+        m, _ = _run(w, oracle_c, ldb=ldb, ldc=N + 1)
+        m.close()
