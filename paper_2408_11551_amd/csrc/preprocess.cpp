@@ -106,6 +106,62 @@ private:
 
 }  // namespace
 
+// Rows with the same pattern (the sixteen rows of a dense block row, the degrees of freedom of
+// one mesh node) have the same intersection with any union, so the counting is done once per
+// distinct pattern ("class"), not once per row: the inverted index lists classes, and a class
+// whose count makes it a candidate puts all its unclustered rows ahead of the scan into the
+// candidate set.
+struct PatternClasses {
+    std::vector<int32_t> class_of;     // [M]
+    std::vector<int32_t> first_row;    // [n] a row that carries the class's pattern
+    std::vector<int64_t> member_ptr;   // [n+1]
+    std::vector<int32_t> members;      // rows of every class, ascending
+};
+
+PatternClasses group_equal_patterns(int64_t M, const std::vector<int64_t>& pat_ptr, const std::vector<int32_t>& pat_idx)
+{
+    std::vector<uint64_t> hash(M);
+    for (int64_t r = 0; r < M; ++r) {
+        uint64_t x = 0x9E3779B97F4A7C15ull ^ static_cast<uint64_t>(pat_ptr[r + 1] - pat_ptr[r]);
+        for (int64_t q = pat_ptr[r]; q < pat_ptr[r + 1]; ++q) {
+            x ^= static_cast<uint64_t>(static_cast<uint32_t>(pat_idx[q])) + 0x9E3779B97F4A7C15ull + (x << 6) + (x >> 2);
+            x *= 0xFF51AFD7ED558CCDull;
+        }
+        hash[r] = x;
+    }
+    auto same = [&](int32_t a, int32_t b) {
+        const int64_t la = pat_ptr[a + 1] - pat_ptr[a];
+        return la == pat_ptr[b + 1] - pat_ptr[b] &&
+               std::equal(pat_idx.begin() + pat_ptr[a], pat_idx.begin() + pat_ptr[a + 1], pat_idx.begin() + pat_ptr[b]);
+    };
+    auto less = [&](int32_t a, int32_t b) {            // a total order in which equal patterns are neighbours
+        if (hash[a] != hash[b]) return hash[a] < hash[b];
+        const auto a0 = pat_idx.begin() + pat_ptr[a], a1 = pat_idx.begin() + pat_ptr[a + 1];
+        const auto b0 = pat_idx.begin() + pat_ptr[b], b1 = pat_idx.begin() + pat_ptr[b + 1];
+        if (std::lexicographical_compare(a0, a1, b0, b1)) return true;
+        if (std::lexicographical_compare(b0, b1, a0, a1)) return false;
+        return a < b;                                   // same pattern: by row, so that members ascend
+    };
+    std::vector<int32_t> by_pattern(M);
+    std::iota(by_pattern.begin(), by_pattern.end(), 0);
+    std::sort(by_pattern.begin(), by_pattern.end(), less);
+    PatternClasses pc;
+    pc.class_of.assign(M, 0);
+    pc.member_ptr.push_back(0);
+    for (int64_t k = 0; k < M; ++k) {
+        const int32_t r = by_pattern[k];
+        if (k == 0 || !same(by_pattern[k - 1], r)) {
+            if (k > 0) pc.member_ptr.push_back(static_cast<int64_t>(pc.members.size()));
+            pc.first_row.push_back(r);
+        }
+        pc.class_of[r] = static_cast<int32_t>(pc.first_row.size()) - 1;
+        pc.members.push_back(r);                        // ascending inside a class: ties are ordered by row
+    }
+    pc.member_ptr.push_back(static_cast<int64_t>(pc.members.size()));
+    if (M == 0) pc.member_ptr.assign(1, 0);
+    return pc;
+}
+
 // kLazy chooses how rows become candidates of the open cluster (the result is the same):
 // false: every row ahead of the scan that shares a column with the union is visited; right
 // where a row shares many columns with the union (the visits are few next to the counting);
@@ -118,68 +174,73 @@ static int64_t cluster_rows(int64_t M, int64_t nbc, const std::vector<int64_t>& 
 {
     order.clear();
     order.reserve(M);
-    // inverted index: rows of every block column, ascending
+    const PatternClasses pc = group_equal_patterns(M, pat_ptr, pat_idx);
+    const int64_t n_classes = static_cast<int64_t>(pc.first_row.size());
+    auto class_begin = [&](int64_t k) { return pat_ptr[pc.first_row[k]]; };
+    auto class_end = [&](int64_t k) { return pat_ptr[pc.first_row[k] + 1]; };
+    // inverted index: classes of every block column
     std::vector<int64_t> inv_ptr(nbc + 1, 0);
-    for (int32_t c : pat_idx) ++inv_ptr[c + 1];
+    for (int64_t k = 0; k < n_classes; ++k)
+        for (int64_t q = class_begin(k); q < class_end(k); ++q) ++inv_ptr[pat_idx[q] + 1];
     for (int64_t c = 0; c < nbc; ++c) inv_ptr[c + 1] += inv_ptr[c];
-    std::vector<int32_t> inv_rows(pat_idx.size());
+    std::vector<int32_t> inv_classes(static_cast<size_t>(inv_ptr[nbc]));
     {
         std::vector<int64_t> fill(inv_ptr.begin(), inv_ptr.end() - 1);
-        for (int64_t r = 0; r < M; ++r)
-            for (int64_t q = pat_ptr[r]; q < pat_ptr[r + 1]; ++q)
-                inv_rows[fill[pat_idx[q]]++] = static_cast<int32_t>(r);
+        for (int64_t k = 0; k < n_classes; ++k)
+            for (int64_t q = class_begin(k); q < class_end(k); ++q)
+                inv_classes[fill[pat_idx[q]]++] = static_cast<int32_t>(k);
     }
     std::vector<int64_t> inv_len(nbc);
     for (int64_t c = 0; c < nbc; ++c) inv_len[c] = inv_ptr[c + 1] - inv_ptr[c];
 
     std::vector<uint8_t> clustered(M, 0);
-    // per row ahead of the scan: |row n union of the open cluster|; kLazy: twice that, + 1 if the
-    // row is in the candidate set
-    std::vector<int32_t> shared(M, 0);
-    std::vector<int32_t> touched;             // rows with shared != 0, to be cleared when the cluster closes
+    std::vector<int32_t> alive(n_classes);    // unclustered rows of the class
+    for (int64_t k = 0; k < n_classes; ++k) alive[k] = static_cast<int32_t>(pc.member_ptr[k + 1] - pc.member_ptr[k]);
+    // per class: 2 * |pattern n union of the open cluster| + (1 if its rows are in the candidate set)
+    std::vector<int32_t> shared(n_classes, 0);
+    std::vector<int32_t> touched;             // classes with shared != 0, cleared when the cluster closes
     std::vector<int64_t> in_union(nbc, -1);   // id of the cluster whose union holds the column
-    std::vector<int32_t> row_len(M);
-    for (int64_t r = 0; r < M; ++r) row_len[r] = static_cast<int32_t>(pat_ptr[r + 1] - pat_ptr[r]);
+    std::vector<int32_t> class_len(n_classes);
     int64_t shortest = 0;                     // shortest non-empty pattern
-    for (int64_t r = 0; r < M; ++r)
-        if (row_len[r] > 0 && (shortest == 0 || row_len[r] < shortest)) shortest = row_len[r];
+    for (int64_t k = 0; k < n_classes; ++k) {
+        class_len[k] = static_cast<int32_t>(class_end(k) - class_begin(k));
+        if (class_len[k] > 0 && (shortest == 0 || class_len[k] < shortest)) shortest = class_len[k];
+    }
     AscendingSet candidates(M);
     int64_t n_clusters = 0;
     const int64_t keep = 1000 - tau_permille;
 
-    // A column enters the union while the scan stands at row `pos`: every row ahead of the scan
-    // that has the column shares one more column with the union.  kLazy: a row is only worth a visit
-    // once it could pass the merge test at all.  The test at the visit, with the union U' >= U of
-    // that later moment and the row's count n' of then, is 1000 n' > keep (|w| + U' - n'), which
-    // implies (1000 + keep) n' > keep (|w| + U); n' is reached at the row's last increment, where
-    // the same inequality with the U of that moment (smaller still) therefore holds.  So a row
-    // enters the candidate set at the first increment that satisfies it, and no row that would be
-    // merged is left out; the exact test is still taken at the visit.  The same bound with the
-    // shortest pattern of the matrix in place of |w| comes first, so that most increments read
-    // nothing but the counter.
+    // A column enters the union while the scan stands at row `pos`: every class that has the
+    // column shares one more column with the union, and so does each of its rows.  Only rows
+    // ahead of the scan can still be visited; their count when the scan reaches them is the
+    // class's.  kLazy: a row is only worth a visit once it could pass the merge test at all.  The
+    // test at the visit, with the union U' >= U of that later moment and the count n' of then, is
+    // 1000 n' > keep (|w| + U' - n'), which implies (1000 + keep) n' > keep (|w| + U); n' is
+    // reached at the last increment, where the same inequality with the U of that moment (smaller
+    // still) therefore holds.  So the rows of a class enter the candidate set at the first
+    // increment that satisfies it, and no row that would be merged is left out; the exact test is
+    // still taken at the visit.  The same bound with the shortest pattern of the matrix in place
+    // of |w| comes first, so that most increments read nothing but the counter.
     auto add_column = [&](int32_t c, int64_t pos, int64_t cluster, int64_t& union_size) {
         if (in_union[c] == cluster) return;
         in_union[c] = cluster;
         ++union_size;
         const int64_t least = keep * (shortest + union_size) / (1000 + keep);   // a count must exceed this to matter for any row
-        int32_t* rows = inv_rows.data() + inv_ptr[c];
+        int32_t* classes = inv_classes.data() + inv_ptr[c];
         int64_t kept = 0;
-        for (int64_t k = 0; k < inv_len[c]; ++k) {
-            const int32_t r = rows[k];
-            if (clustered[r]) continue;                  // drop rows that are gone for good
-            rows[kept++] = r;
-            if (r > pos) {
-                if constexpr (kLazy) {
-                    const int32_t word = (shared[r] += 2);
-                    if (word == 2) touched.push_back(r);
-                    const int64_t n = word >> 1;
-                    if (!(word & 1) && n > least && (1000 + keep) * n > keep * (row_len[r] + union_size)) {
-                        candidates.insert(r);
-                        shared[r] = word | 1;
-                    }
-                } else {
-                    if (shared[r]++ == 0) candidates.insert(r);
-                }
+        for (int64_t x = 0; x < inv_len[c]; ++x) {
+            const int32_t k = classes[x];
+            if (alive[k] == 0) continue;                 // drop classes that are gone for good
+            classes[kept++] = k;
+            const int32_t word = (shared[k] += 2);
+            if (word == 2) touched.push_back(k);
+            if (word & 1) continue;                      // its rows are candidates already
+            const int64_t n = word >> 1;
+            if (kLazy && !(n > least && (1000 + keep) * n > keep * (class_len[k] + union_size))) continue;
+            shared[k] = word | 1;
+            for (int64_t y = pc.member_ptr[k]; y < pc.member_ptr[k + 1]; ++y) {
+                const int32_t r = pc.members[y];
+                if (r > pos && !clustered[r]) candidates.insert(r);
             }
         }
         inv_len[c] = kept;
@@ -189,6 +250,7 @@ static int64_t cluster_rows(int64_t M, int64_t nbc, const std::vector<int64_t>& 
         if (clustered[v]) continue;
         const int64_t cluster = n_clusters++;
         clustered[v] = 1;
+        --alive[pc.class_of[v]];
         order.push_back(static_cast<int32_t>(v));
         if (pat_ptr[v] == pat_ptr[v + 1]) {
             // empty seed: distance 0 to other empty rows, 1 to everything else
@@ -196,6 +258,7 @@ static int64_t cluster_rows(int64_t M, int64_t nbc, const std::vector<int64_t>& 
                 for (int64_t w = v + 1; w < M; ++w)
                     if (!clustered[w] && pat_ptr[w] == pat_ptr[w + 1]) {
                         clustered[w] = 1;
+                        --alive[pc.class_of[w]];
                         order.push_back(static_cast<int32_t>(w));
                     }
             continue;
@@ -208,16 +271,18 @@ static int64_t cluster_rows(int64_t M, int64_t nbc, const std::vector<int64_t>& 
             if (w < 0) break;
             candidates.erase(w);
             pos = w;
-            const int64_t inter = kLazy ? shared[w] >> 1 : shared[w];
-            if constexpr (!kLazy) shared[w] = 0;        // every row with a count is visited, so this clears them all
-            const int64_t uni = row_len[w] + union_size - inter;
+            const int32_t k = pc.class_of[w];
+            const int64_t inter = shared[k] >> 1;
+            const int64_t uni = class_len[k] + union_size - inter;
             if (1000 * inter > keep * uni) {             // 1 - inter/uni < tau/1000
                 clustered[w] = 1;
+                --alive[k];
                 order.push_back(static_cast<int32_t>(w));
-                for (int64_t q = pat_ptr[w]; q < pat_ptr[w + 1]; ++q) add_column(pat_idx[q], w, cluster, union_size);
+                if (inter < class_len[k])                // otherwise every column of the row is in the union already
+                    for (int64_t q = pat_ptr[w]; q < pat_ptr[w + 1]; ++q) add_column(pat_idx[q], w, cluster, union_size);
             }
         }
-        for (int32_t r : touched) shared[r] = 0;
+        for (int32_t k : touched) shared[k] = 0;
         touched.clear();
     }
     return n_clusters;
