@@ -11,7 +11,8 @@
 // goes up by one.  The counter a row carries when the scan reaches it is then
 // exactly |row n union|, and rows that never became candidates have an empty
 // intersection and could not have merged.  The result is the same permutation
-// the row-by-row scan gives.
+// the row-by-row scan gives.  (The index and the counters are kept per distinct
+// row pattern, not per row: rows with the same pattern have the same counter.)
 #include "preprocess.h"
 
 #include <algorithm>
