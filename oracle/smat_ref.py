@@ -274,3 +274,52 @@ def choose_perm(patterns, tau_permille, reorder=True, h=H):
     if n_c < n_id:
         return cand, n_c, n_id, False
     return ident, n_id, n_id, True
+
+
+# ---------------------------------------------------------------------------
+# O4: row + column reordering (the variant the paper tried next to the row-only one,
+# section "Preprocessing": columns are permuted as well, at the price of permuting B)
+# ---------------------------------------------------------------------------
+def column_patterns(M, K, row_ptr, col_idx, perm, h=H):
+    """pattern[c] = ascending list of block ROWS floor(i / h) of A' = P.A that column c
+    touches (i = new row index, perm[new] = old): the transposed view of block_pattern."""
+    new_of_old = np.empty(M, dtype=np.int64)
+    new_of_old[np.asarray(perm, dtype=np.int64)] = np.arange(M, dtype=np.int64)
+    pats = [set() for _ in range(K)]
+    for r in range(M):
+        br = int(new_of_old[r]) // h
+        for p in range(int(row_ptr[r]), int(row_ptr[r + 1])):
+            pats[int(col_idx[p])].add(br)
+    return [sorted(x) for x in pats]
+
+
+def permute_columns(M, K, row_ptr, col_idx, a_bits, col_perm):
+    """CSR of A.Q with col_perm[new] = old: entry (r, c) moves to column new_of_old[c];
+    columns are sorted again inside every row."""
+    new_of_old = np.empty(K, dtype=np.int64)
+    new_of_old[np.asarray(col_perm, dtype=np.int64)] = np.arange(K, dtype=np.int64)
+    out_idx = np.empty_like(np.asarray(col_idx))
+    out_val = np.empty_like(np.asarray(a_bits))
+    for r in range(M):
+        lo, hi = int(row_ptr[r]), int(row_ptr[r + 1])
+        cols = new_of_old[np.asarray(col_idx[lo:hi], dtype=np.int64)]
+        order = np.argsort(cols, kind="stable")
+        out_idx[lo:hi] = cols[order]
+        out_val[lo:hi] = np.asarray(a_bits[lo:hi])[order]
+    return out_idx, out_val
+
+
+def choose_row_and_col_perm(M, K, row_ptr, col_idx, tau_permille, h=H, w=W):
+    """Rows first, exactly as choose_perm.  Then the same greedy clustering on the columns of
+    A' = P.A, a column's pattern being the set of block rows it touches; the column order is
+    kept only if it lowers the number of blocks of A' further (same guard as for the rows).
+    Returns (perm, col_perm, n_e, n_e_rows_only, n_e_identity, cols_identity)."""
+    perm, n_rows, n_id, _ = choose_perm(block_pattern(M, row_ptr, col_idx, w), tau_permille, True, h)
+    cpats = column_patterns(M, K, row_ptr, col_idx, perm, h)
+    ident = np.arange(K, dtype=np.int32)
+    cand = jaccard_reorder(cpats, tau_permille)
+    n_cand = count_blocks(cpats, cand, w)       # blocks of (P.A.Q)^T on the w-column grid = blocks of P.A.Q
+    if n_cand < n_rows:
+        return perm, cand, n_cand, n_rows, n_id, False
+    return perm, ident, n_rows, n_rows, n_id, True
+

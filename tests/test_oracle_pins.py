@@ -377,3 +377,62 @@ def test_band_keeps_identity_and_guard_never_worse():
             assert used_identity == (perm.tolist() == list(range(96))) or n_e == n_id
     perm, n_e, n_id, used_identity = R.choose_perm(pats, 700, reorder=False)
     assert used_identity and n_e == n_id
+
+
+# ------------------------------------------------------------------ O4 rows + columns
+def _planted_blocks(n_grid, p_block, seed):
+    """Dense 16x16 blocks on a grid, rows and columns scrambled; returns the workload and the planted count."""
+    w = make_config("hidden_blocks", seed=seed, n_grid=n_grid, p_block=p_block, N=4)
+    return w, w.nnz // 256
+
+
+def test_row_and_column_reordering_against_brute_force_and_guards():
+    for n_grid, p_block, seed in ((16, 0.15, 0), (48, 0.05, 1), (64, 0.04, 2)):
+        w, planted = _planted_blocks(n_grid, p_block, seed)
+        perm, q, n_e, n_rows, n_id, cols_identity = R.choose_row_and_col_perm(w.M, w.K, w.row_ptr, w.col_idx, 700)
+        assert sorted(perm.tolist()) == list(range(w.M)) and sorted(q.tolist()) == list(range(w.K))
+        dense = dense_from_bits(w) != 0
+        assert R.count_blocks_bruteforce(dense[perm]) == n_rows              # rows only
+        assert R.count_blocks_bruteforce(dense[perm][:, q]) == n_e           # rows and columns
+        assert planted <= n_e <= n_rows <= n_id                              # each guard can only lower the count
+        assert cols_identity == (n_e == n_rows and np.array_equal(q, np.arange(w.K)))
+        # the permuted CSR is the permuted matrix, and its BCSR has n_e blocks
+        ci, av = R.permute_columns(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, q)
+        a = np.zeros((w.M, w.K))
+        a[np.repeat(np.arange(w.M), np.diff(w.row_ptr)), ci] = from_bits(av, w.dtype)
+        assert np.array_equal(a, dense_from_bits(w)[:, q])
+        rp, cc, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, ci, av, perm)
+        assert cc.size == n_e
+        # (A Q) (Q^T B) == A B: the product oracle on the permuted CSR with the rows of B permuted alike
+        b = from_bits(w.b_bits.reshape(-1), w.dtype).reshape(w.K, w.N)
+        c0, _ = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, w.col_idx, from_bits(w.a_bits, w.dtype), b)
+        c1, _ = R.spmm_ref(w.M, w.K, w.N, w.row_ptr, ci, from_bits(av, w.dtype), b[q])
+        np.testing.assert_allclose(c1, c0, rtol=1e-12, atol=1e-14)
+
+
+def test_row_and_column_reordering_recovers_a_scrambled_block_diagonal():
+    # one dense 16x16 block per block row and per block column (a scrambled block-permutation
+    # matrix): rows of a block have the same pattern and share nothing with other rows, so the row
+    # clustering regroups them (16 blocks per planted block, its columns being scattered), and the
+    # columns of a block then have the same block-row pattern, so the column clustering brings the
+    # count down to the planted one -- by hand: n blocks, 16 n after rows only
+    n = 40
+    rng = np.random.default_rng(9)
+    where = rng.permutation(n)                       # planted block i sits at block column where[i]
+    row_of = rng.permutation(16 * n)                 # scrambled position of every original row / column
+    col_of = rng.permutation(16 * n)
+    keys = []
+    for i in range(n):
+        for a in range(16):
+            for b in range(16):
+                keys.append(int(row_of[16 * i + a]) * 16 * n + int(col_of[16 * where[i] + b]))
+    keys = np.sort(np.asarray(keys, dtype=np.int64))
+    M = K = 16 * n
+    rows, cols = keys // K, (keys % K).astype(np.int32)
+    row_ptr = np.zeros(M + 1, np.int64)
+    np.cumsum(np.bincount(rows, minlength=M), out=row_ptr[1:])
+    perm, q, n_e, n_rows, n_id, cols_identity = R.choose_row_and_col_perm(M, K, row_ptr, cols, 700)
+    assert (n_e, n_rows, cols_identity) == (n, 16 * n, False) and n_id > n_rows
+    dense = np.zeros((M, K), bool)
+    dense[rows, cols] = True
+    assert R.count_blocks_bruteforce(dense[perm][:, q]) == n
