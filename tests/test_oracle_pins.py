@@ -411,28 +411,31 @@ def test_row_and_column_reordering_against_brute_force_and_guards():
 
 
 def test_row_and_column_reordering_recovers_a_scrambled_block_diagonal():
-    # one dense 16x16 block per block row and per block column (a scrambled block-permutation
-    # matrix): rows of a block have the same pattern and share nothing with other rows, so the row
-    # clustering regroups them (16 blocks per planted block, its columns being scattered), and the
-    # columns of a block then have the same block-row pattern, so the column clustering brings the
-    # count down to the planted one -- by hand: n blocks, 16 n after rows only
-    n = 40
+    # Blocks of 4x4 (the oracle takes the block size), one dense block per block row and per block
+    # column.  Column b of planted block j is sent to block column (j + d_b) mod n, slot b, with
+    # d = (0, 1, 4, 6): all differences d_b - d_b' are distinct and below n / 2, so two different
+    # planted blocks meet in at most ONE block column.  Unrelated rows are then at Jaccard distance
+    # >= 1 - 1/7 > 0.7 and never merge; the four rows of a block have the same pattern and always
+    # do.  By hand: the row clustering puts every block into one block row, where its four
+    # scattered columns make 4 blocks (4 n in all); after that the columns of a block all have the
+    # pattern {its block row}, columns of different blocks are at distance 1, and the column
+    # clustering brings the count down to n.
+    n, hw, d = 29, 4, (0, 1, 4, 6)
     rng = np.random.default_rng(9)
-    where = rng.permutation(n)                       # planted block i sits at block column where[i]
-    row_of = rng.permutation(16 * n)                 # scrambled position of every original row / column
-    col_of = rng.permutation(16 * n)
+    row_of = rng.permutation(hw * n)                 # scrambled position of every original row
     keys = []
-    for i in range(n):
-        for a in range(16):
-            for b in range(16):
-                keys.append(int(row_of[16 * i + a]) * 16 * n + int(col_of[16 * where[i] + b]))
+    for j in range(n):
+        for a in range(hw):
+            for b in range(hw):
+                keys.append(int(row_of[hw * j + a]) * hw * n + hw * ((j + d[b]) % n) + b)
     keys = np.sort(np.asarray(keys, dtype=np.int64))
-    M = K = 16 * n
+    M = K = hw * n
     rows, cols = keys // K, (keys % K).astype(np.int32)
     row_ptr = np.zeros(M + 1, np.int64)
     np.cumsum(np.bincount(rows, minlength=M), out=row_ptr[1:])
-    perm, q, n_e, n_rows, n_id, cols_identity = R.choose_row_and_col_perm(M, K, row_ptr, cols, 700)
-    assert (n_e, n_rows, cols_identity) == (n, 16 * n, False) and n_id > n_rows
+    perm, q, n_e, n_rows, n_id, cols_identity = R.choose_row_and_col_perm(M, K, row_ptr, cols, 700, h=hw, w=hw)
+    assert (n_e, n_rows, cols_identity) == (n, 4 * n, False) and n_id > n_rows
     dense = np.zeros((M, K), bool)
     dense[rows, cols] = True
-    assert R.count_blocks_bruteforce(dense[perm][:, q]) == n
+    assert R.count_blocks_bruteforce(dense[perm][:, q], hw, hw) == n
+    assert R.count_blocks_bruteforce(dense[perm], hw, hw) == 4 * n
