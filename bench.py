@@ -112,8 +112,9 @@ def main():
     ap.add_argument("--probes", action="store_true",
                     help="also time the library's probe kernels (streaming read, row gather, MFMA loop): what this GPU "
                          "delivers for the access patterns the SpMM kernels are made of")
-    ap.add_argument("--reorder", type=int, default=1, choices=[0, 1],
-                    help="row reordering of the preprocessing: 1 Jaccard clustering with the identity guard (default), 0 none")
+    ap.add_argument("--reorder", type=int, default=1, choices=[0, 1, 2],
+                    help="reordering of the preprocessing: 1 Jaccard clustering of the rows with the identity guard (default), "
+                         "0 none, 2 rows and then columns (the variant the paper set aside)")
     ap.add_argument("--vendor", action="store_true",
                     help="also time the vendor's CSR SpMM on the same matrix (hipSPARSE through torch.sparse.mm, "
                          "fp32: it offers no 16-bit CSR SpMM here)")

@@ -57,7 +57,13 @@ typedef struct {
     int block_h;        /* block height; only 16 is accepted                            */
     int block_w;        /* block width;  only 16 is accepted                            */
     int reorder;        /* 0: keep the row order (P = I); 1: Jaccard clustering, kept
-                           only if it yields strictly fewer blocks than the identity    */
+                           only if it yields strictly fewer blocks than the identity;
+                           2: the same, then the columns of P A are clustered in the same
+                           way (a column's pattern being the block rows it touches) and
+                           that column order Q is kept only if P A Q has strictly fewer
+                           blocks still -- the variant the paper tried and set aside
+                           (Preprocessing section); B is not moved: the kernel fetches
+                           its rows through Q                                            */
     int tau_permille;   /* merge threshold of the clustering in 1/1000, 0..1000: a row w
                            joins a cluster with column union pc iff
                            1 - |w n pc| / |w u pc| < tau_permille / 1000                 */
@@ -102,6 +108,12 @@ smat_status_t smat_get_info(const smat_handle_t *h, int64_t *n_block_rows, int64
 
 /* perm: HOST int32[M], perm[new_row] = old_row (A' = P A, Overview section). */
 smat_status_t smat_export_perm(const smat_handle_t *h, int32_t *perm);
+
+/* Column order of the row + column variant (reorder = 2): HOST int32[K], col_perm[new] = old;
+ * the identity when no column order was kept.  With one, the block structure and the values of
+ * smat_export_bcsr are those of P A Q.  n_blocks_rows_only (may be NULL) receives the number of
+ * blocks of P A. */
+smat_status_t smat_export_col_perm(const smat_handle_t *h, int32_t *col_perm, int64_t *n_blocks_rows_only);
 
 /* Canonical BCSR of A' (Data Structures section), all HOST, caller allocated:
  *   row_ptr int32[n_block_rows+1]  offsets into col_idx per block row

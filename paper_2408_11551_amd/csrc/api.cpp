@@ -26,6 +26,7 @@ struct smat_handle {
     int elem_bytes = 2;                  // bytes per stored value of A and B: 2, or 1 for the 8-bit types
     int dense_mode = 0;                  // option dense_tiles
     bool bound = false;
+    bool cols_permuted = false;          // row + column reordering took a column order: csr and bcsr are those of P A Q
     // Packs (pack_layout.h): every block row is cut, from the left, into runs of consecutive
     // blocks that hold at most 32 occupied columns together; a pack is what one matrix
     // instruction multiplies.
@@ -268,7 +269,9 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         if (dtype < SMAT_F16 || dtype > SMAT_I8) return fail(SMAT_ERR_INVALID_ARG, "unknown dtype");
         const bool narrow = dtype >= SMAT_E4M3;
         if (o.block_h != 16 || o.block_w != 16) return fail(SMAT_ERR_UNSUPPORTED, "only 16x16 blocks are supported");
-        if (o.reorder != 0 && o.reorder != 1) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0 or 1");
+        if (o.reorder < 0 || o.reorder > 2) return fail(SMAT_ERR_INVALID_ARG, "reorder must be 0, 1 or 2");
+        if (o.reorder == 2 && o.dense_tiles == 1)
+            return fail(SMAT_ERR_UNSUPPORTED, "the dense-tile kernel reads B in whole block columns: not with a column permutation");
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (o.dense_tiles < -1 || o.dense_tiles > 1) return fail(SMAT_ERR_INVALID_ARG, "dense_tiles must be -1, 0 or 1");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
@@ -296,6 +299,10 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         else
             h->csr.vals.assign(static_cast<const uint16_t*>(vals), static_cast<const uint16_t*>(vals) + nnz);
         smat::build_bcsr(h->csr, o.reorder != 0, o.tau_permille, h->bcsr);
+        if (o.reorder == 2) {
+            h->cols_permuted = smat::reorder_columns(h->csr, o.tau_permille, h->bcsr);
+            if (h->cols_permuted) h->dense_mode = -1;
+        }
         try {
             plan_packs(*h);
         } catch (const std::length_error& e) {
@@ -341,6 +348,15 @@ smat_status_t smat_export_perm(const smat_handle_t* h, int32_t* perm)
 {
     if (!h || (!perm && h->csr.M > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
     if (h->csr.M > 0) std::memcpy(perm, h->bcsr.perm.data(), sizeof(int32_t) * static_cast<size_t>(h->csr.M));
+    return SMAT_OK;
+}
+
+smat_status_t smat_export_col_perm(const smat_handle_t* h, int32_t* col_perm, int64_t* n_blocks_rows_only)
+{
+    if (!h || (!col_perm && h->csr.K > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
+    for (int64_t c = 0; c < h->csr.K; ++c)
+        col_perm[c] = h->cols_permuted ? h->bcsr.col_perm[static_cast<size_t>(c)] : static_cast<int32_t>(c);
+    if (n_blocks_rows_only) *n_blocks_rows_only = h->cols_permuted ? h->bcsr.n_blocks_rows_only : h->bcsr.n_blocks;
     return SMAT_OK;
 }
 
@@ -397,8 +413,10 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
                 for (int32_t s = h->pack_first[static_cast<size_t>(pk)]; s < h->pack_first[static_cast<size_t>(pk) + 1]; ++s)
                     for (int c = 0; c < 16; ++c) {
                         if (!(b.col_mask[s] >> c & 1u)) continue;
+                        // the row of B is the ORIGINAL column: through Q when the columns were permuted
+                        const size_t col = static_cast<size_t>(b.col_idx[s]) * 16u + static_cast<size_t>(c);
                         table[smat::slot_group(rank) * L + smat::slot_pos(rank)] =
-                            static_cast<uint32_t>(b.col_idx[s]) * 16u + static_cast<uint32_t>(c);
+                            h->cols_permuted ? static_cast<uint32_t>(b.col_perm[col]) : static_cast<uint32_t>(col);
                         ++rank;
                     }
             }
@@ -611,6 +629,7 @@ smat_status_t smat_ablation_bytes(const smat_handle_t* h, size_t* bytes)
 {
     if (!h || !bytes) return fail(SMAT_ERR_INVALID_ARG, "NULL argument");
     if (h->elem_bytes != 2) return fail(SMAT_ERR_UNSUPPORTED, "the ablation kernels handle fp16 and bf16 only");
+    if (h->cols_permuted) return fail(SMAT_ERR_UNSUPPORTED, "the ablation kernels read B in whole block columns: not with a column permutation");
     size_t n = ablation_vals_bytes(h);
     if (ablation_has_map(h)) n += align_up(static_cast<size_t>(h->bcsr.nbr * h->bcsr.nbc) * sizeof(int32_t));
     *bytes = n ? n : kAlign;

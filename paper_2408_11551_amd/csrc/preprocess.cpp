@@ -314,6 +314,8 @@ int64_t count_blocks(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr
     return n;
 }
 
+static void build_structure(const Csr& a, const std::vector<int64_t>& pat_ptr, const std::vector<int32_t>& pat_idx, Bcsr& out);
+
 void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out)
 {
     const int64_t M = a.M;
@@ -341,6 +343,14 @@ void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out)
         }
     }
 
+    build_structure(a, pat_ptr, pat_idx, out);
+}
+
+// Row pointer, block columns and column masks of the BCSR of A' = P A for the permutation
+// already in out.perm.
+static void build_structure(const Csr& a, const std::vector<int64_t>& pat_ptr, const std::vector<int32_t>& pat_idx, Bcsr& out)
+{
+    const int64_t M = a.M;
     // structure: per block row the ascending union of its rows' patterns
     out.row_ptr.assign(out.nbr + 1, 0);
     out.col_idx.clear();
@@ -374,6 +384,60 @@ void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out)
         }
     }
 
+}
+
+bool reorder_columns(Csr& a, int tau_permille, Bcsr& b)
+{
+    const int64_t M = a.M, K = a.K;
+    b.col_perm.resize(static_cast<size_t>(K));
+    std::iota(b.col_perm.begin(), b.col_perm.end(), 0);
+    b.n_blocks_rows_only = b.n_blocks;
+    if (K == 0 || M == 0) return false;
+    // column patterns: ascending block rows of A' = P A per column (rows are walked in their new order)
+    std::vector<int64_t> cpat_ptr(K + 1, 0);
+    std::vector<int32_t> last(K, -1);
+    for (int64_t i = 0; i < M; ++i) {
+        const int64_t r = b.perm[i];
+        const int32_t br = static_cast<int32_t>(i / kBlock);
+        for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p)
+            if (last[a.col_idx[p]] != br) { last[a.col_idx[p]] = br; ++cpat_ptr[a.col_idx[p] + 1]; }
+    }
+    for (int64_t c = 0; c < K; ++c) cpat_ptr[c + 1] += cpat_ptr[c];
+    std::vector<int32_t> cpat_idx(static_cast<size_t>(cpat_ptr[K]));
+    {
+        std::vector<int64_t> fill(cpat_ptr.begin(), cpat_ptr.end() - 1);
+        std::fill(last.begin(), last.end(), -1);
+        for (int64_t i = 0; i < M; ++i) {
+            const int64_t r = b.perm[i];
+            const int32_t br = static_cast<int32_t>(i / kBlock);
+            for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p)
+                if (last[a.col_idx[p]] != br) { last[a.col_idx[p]] = br; cpat_idx[fill[a.col_idx[p]]++] = br; }
+        }
+    }
+    std::vector<int32_t> cand;
+    jaccard_cluster(K, b.nbr, cpat_ptr, cpat_idx, tau_permille, cand);
+    const int64_t n_cand = count_blocks(K, b.nbr, cpat_ptr, cpat_idx, cand.data());     // blocks of the transpose = blocks of P A Q
+    if (n_cand >= b.n_blocks) return false;              // strictly fewer, else keep Q = I
+    b.col_perm.swap(cand);
+    // A <- A Q: entry (r, c) moves to the new index of column c; columns ascend again inside every row
+    std::vector<int32_t> new_of_old(static_cast<size_t>(K));
+    for (int64_t c = 0; c < K; ++c) new_of_old[b.col_perm[c]] = static_cast<int32_t>(c);
+    std::vector<std::pair<int32_t, uint16_t>> row;
+    for (int64_t r = 0; r < M; ++r) {
+        row.clear();
+        for (int64_t p = a.row_ptr[r]; p < a.row_ptr[r + 1]; ++p) row.emplace_back(new_of_old[a.col_idx[p]], a.vals[p]);
+        std::sort(row.begin(), row.end());
+        for (size_t x = 0; x < row.size(); ++x) {
+            a.col_idx[a.row_ptr[r] + static_cast<int64_t>(x)] = row[x].first;
+            a.vals[a.row_ptr[r] + static_cast<int64_t>(x)] = row[x].second;
+        }
+    }
+    std::vector<int64_t> pat_ptr;
+    std::vector<int32_t> pat_idx;
+    block_patterns(a, pat_ptr, pat_idx);
+    b.n_blocks = n_cand;
+    build_structure(a, pat_ptr, pat_idx, b);
+    return true;
 }
 
 void work_order(const std::vector<int32_t>& cost_ptr, std::vector<int32_t>& order)

@@ -26,6 +26,9 @@ struct Bcsr {
     std::vector<uint16_t> col_mask;  // [n_e] bit c set iff column c of the block holds a stored entry
     int64_t n_blocks = 0, n_blocks_identity = 0;
     bool used_identity = true;
+    // row + column reordering only (reorder_columns): new column -> old column, identity if unused
+    std::vector<int32_t> col_perm;
+    int64_t n_blocks_rows_only = 0;
     int64_t n_clusters = 0;
 };
 
@@ -46,6 +49,14 @@ int64_t count_blocks(int64_t M, int64_t nbc, const std::vector<int64_t>& pat_ptr
 
 // Full pipeline: patterns -> (optional) clustering -> guard -> BCSR structure and column masks.
 void build_bcsr(const Csr& a, bool reorder, int tau_permille, Bcsr& out);
+
+// Row + column variant (the one the paper tried next to the row-only reordering, Preprocessing
+// section): after build_bcsr, clusters the columns of A' = P A with the same greedy procedure, a
+// column's pattern being the block rows it touches, and keeps the column order Q only if P A Q
+// has strictly fewer blocks.  If it does, `a` becomes A Q (columns renumbered, ascending inside
+// every row), b.col_perm holds Q (new -> old) and the structure of b is rebuilt; returns whether
+// it did.
+bool reorder_columns(Csr& a, int tau_permille, Bcsr& b);
 
 // Launch order of the block rows, given their cost as a row_ptr-like prefix array
 // (cost of row br = cost_ptr[br+1] - cost_ptr[br]).

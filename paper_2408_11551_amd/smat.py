@@ -81,6 +81,8 @@ def _load():
                                   ctypes.POINTER(ctypes.c_int)]
     lib.smat_export_perm.restype = ctypes.c_int
     lib.smat_export_perm.argtypes = [vp, vp]
+    lib.smat_export_col_perm.restype = ctypes.c_int
+    lib.smat_export_col_perm.argtypes = [vp, vp, ctypes.POINTER(i64)]
     lib.smat_export_bcsr.restype = ctypes.c_int
     lib.smat_export_bcsr.argtypes = [vp, vp, vp, vp]
     lib.smat_device_bytes.restype = ctypes.c_int
@@ -182,6 +184,14 @@ def smat_export_perm(h, M) -> np.ndarray:
     perm = np.empty(M, dtype=np.int32)
     _check(_lib.smat_export_perm(h, perm.ctypes.data_as(ctypes.c_void_p)))
     return perm
+
+
+def smat_export_col_perm(h, K):
+    """(col_perm int32[K] with col_perm[new] = old, number of blocks after the row permutation alone)."""
+    q = np.empty(K, dtype=np.int32)
+    n_rows = ctypes.c_int64()
+    _check(_lib.smat_export_col_perm(h, q.ctypes.data_as(ctypes.c_void_p), ctypes.byref(n_rows)))
+    return q, n_rows.value
 
 
 def smat_export_bcsr(h, with_vals=True, dtype="f16"):

@@ -112,7 +112,7 @@ def test_bad_input_becomes_status_codes():
     _expect("SMAT_ERR_BAD_CSR", lambda: S.smat_preprocess(2, 4, np.array([1, 2, 3], np.int64), ci, v, "f16"))
     _expect("SMAT_ERR_UNSUPPORTED", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", block_w=8))
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", tau_permille=1001))
-    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", reorder=2))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, "f16", reorder=3))
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(2, 4, rp, ci, v, 7))
     _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(-1, 4, np.zeros(0, np.int64), ci, v, "f16"))
 
@@ -170,6 +170,32 @@ def test_both_candidate_strategies_of_the_clustering_match_the_oracle(tau, oracl
             assert (info["n_blocks"], info["n_blocks_identity"], info["used_identity"]) == (n_e, n_id, used)
         finally:
             S.smat_destroy(h)
+
+
+@pytest.mark.parametrize("tau", [300, 700, 950])
+def test_row_and_column_reordering_matches_oracle(tau):
+    """reorder = 2: row permutation, column permutation, block counts, and the BCSR of P A Q (structure and
+    values) bit-exact against the oracle, on scrambled planted blocks and on random matrices."""
+    cases = [make_config("hidden_blocks", n_grid=16, p_block=0.15, N=4), make_config("hidden_blocks", n_grid=64, p_block=0.04, N=4),
+             random_csr(130, 333, 1, 0.05, seed=8), random_csr(64, 40, 1, 0.3, seed=9, dtype="bf16"), random_csr(17, 16, 1, 0.0, seed=1)]
+    for w in cases:
+        h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=2, tau_permille=tau)
+        try:
+            perm, q, n_e, n_rows, n_id, cols_identity = R.choose_row_and_col_perm(w.M, w.K, w.row_ptr, w.col_idx, tau)
+            assert np.array_equal(S.smat_export_perm(h, w.M), perm)
+            gq, g_rows = S.smat_export_col_perm(h, w.K)
+            assert np.array_equal(gq, q) and g_rows == n_rows
+            info = S.smat_get_info(h)
+            assert (info["n_blocks"], info["n_blocks_identity"]) == (n_e, n_id)
+            ci, av = R.permute_columns(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, q)
+            rp, cc, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, ci, av, perm)
+            grp, gci, gv = S.smat_export_bcsr(h)
+            assert np.array_equal(grp, rp) and np.array_equal(gci, cc) and np.array_equal(gv, v)
+        finally:
+            S.smat_destroy(h)
+    w = cases[0]
+    _expect("SMAT_ERR_UNSUPPORTED", lambda: S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=2, dense_tiles=1))
+    _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=3))
 
 
 def test_spmm_without_bind_is_an_error_not_a_fallback():

@@ -517,3 +517,42 @@ def test_wide_and_odd_output_widths(oracle_c):
         w = random_csr(90, 300, N, 0.06, seed=N, dtype=dtype, b_dist="normal")
         m, _ = _run(w, oracle_c, ldb=ldb, ldc=N + 1)
         m.close()
+
+
+def test_row_and_column_reordering_gives_the_same_product(oracle_c):
+    # reorder = 2 renumbers the columns of A inside the library; B is not moved, C is the same product
+    cases = [make_config("hidden_blocks", n_grid=64, p_block=0.04, N=48), random_csr(300, 500, 40, 0.03, seed=12, b_dist="normal"),
+             random_csr(257, 129, 100, 0.2, seed=13, dtype="bf16", b_dist="normal")]
+    for w in cases:
+        m, _ = _run(w, oracle_c, reorder=2, ldb=w.N + 2, ldc=w.N + 1)
+        q, n_rows = S.smat_export_col_perm(m.handle, w.K)
+        assert sorted(q.tolist()) == list(range(w.K)) and S.smat_get_info(m.handle)["n_blocks"] <= n_rows
+        # device block values against the oracle's BCSR of P A Q
+        perm = S.smat_export_perm(m.handle, w.M)
+        ci, av = R.permute_columns(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, q)
+        _, _, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, ci, av, perm)
+        assert np.array_equal(S.smat_export_device_vals(m.handle), v)
+        m.close()
+
+
+def test_hidden_blocks_full_size_with_column_reordering(oracle_c):
+    # 32768^2: rows first, then the columns of P A clustered by the C oracle on their block-row
+    # patterns; the library's column order, block count and product must be the oracle's
+    w = make_config("hidden_blocks")
+    m, _ = _run(w, oracle_c, reorder=2)
+    perm = S.smat_export_perm(m.handle, w.M)
+    q, n_rows = S.smat_export_col_perm(m.handle, w.K)
+    info = S.smat_get_info(m.handle)
+    # column patterns of P A, as the oracle defines them, built with numpy for speed
+    new_of_old = np.empty(w.M, np.int64)
+    new_of_old[perm] = np.arange(w.M)
+    rows = np.repeat(new_of_old, np.diff(w.row_ptr)) // 16
+    key = np.unique(w.col_idx.astype(np.int64) * (w.M // 16 + 1) + rows)
+    cols, brs = key // (w.M // 16 + 1), (key % (w.M // 16 + 1)).astype(np.int32)
+    cp = np.zeros(w.K + 1, np.int64)
+    np.cumsum(np.bincount(cols, minlength=w.K), out=cp[1:])
+    oq, _ = oracle_c.jaccard_reorder_c(w.K, cp, brs, -(-w.M // 16), 700)
+    n_q = oracle_c.count_blocks_c(w.K, cp, brs, -(-w.M // 16), oq)
+    assert n_q < n_rows and np.array_equal(q, oq) and info["n_blocks"] == n_q
+    assert info["n_blocks"] == w.nnz // 256            # every planted block is one block again
+    m.close()
