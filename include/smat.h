@@ -70,7 +70,9 @@ typedef struct {
     int dense_tiles;    /* block-dense regions (sixteen block rows sharing most of their
                            block columns) have a kernel of their own that stages panels of
                            B in LDS: 0 = take it where an estimate says it is faster,
-                           1 = take it wherever it applies, -1 = never                    */
+                           1 = take it wherever it applies, -1 = never.  It reads B in
+                           whole block columns, so it is not used once reorder = 2 has
+                           kept a column order, and 1 together with reorder = 2 is refused */
 } smat_options_t;
 
 /* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0. */
