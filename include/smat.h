@@ -134,12 +134,16 @@ smat_status_t smat_device_bytes(const smat_handle_t *h, size_t *bytes);
  * column of a block is occupied when it holds a stored entry); one matrix
  * instruction per 16 output columns multiplies a pack, and columns that hold
  * nothing are neither stored nor fetched from B.  Two full blocks make a pack.
+ * A block row whose occupied columns hold hardly more than one stored entry each (at most
+ * 17/16 on average) is kept by entry instead: packs of 32 stored entries, one value and one
+ * named row of B per entry, expanded into the instruction's operand in registers.
  *   n_packs       packs of the whole matrix
  *   value_bytes   bytes of block values over all packs
  *   table_bytes   bytes of the per-pack tables naming the rows of B, plus the
  *                 launch table and the row permutation
- *   n_columns     occupied columns over all stored blocks (each needs one row
- *                 of B per output tile)
+ *   n_columns     rows of B named by the tables: the occupied columns over all stored
+ *                 blocks (the stored entries, in block rows kept by entry); each is
+ *                 fetched once per output tile
  * Any out pointer may be NULL. */
 smat_status_t smat_get_layout_info(const smat_handle_t *h, int64_t *n_packs, int64_t *value_bytes,
                                    int64_t *table_bytes, int64_t *n_columns);

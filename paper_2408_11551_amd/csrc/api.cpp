@@ -36,8 +36,9 @@ struct smat_handle {
     std::vector<uint32_t> blk_meta;      // [n_blocks] column mask | occupied columns of the pack before the block << 16
     std::vector<int32_t> order;          // [nbr] block rows in launch order
     // Row class: how many B-row loads per lane a pack of the block row needs at most (occupied
-    // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2.  The slot table of a
-    // row takes 16 * L bytes per pack and its values 128 * L bytes; slots_off counts 32-byte
+    // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2; class 3 is an entry row
+    // (pack_layout.h), laid out like class 2 with only the first 32 values of a pack in use.  The
+    // slot table of a row takes 16 * L bytes per pack and its values 128 * L bytes; slots_off counts 32-byte
     // units of the former, which are 256-byte units of the latter.
     // (Values: 128 * L bytes per pack for the 16-bit types, 64 * L for the 8-bit ones -- a unit
     // is 128 values either way.)
@@ -45,6 +46,9 @@ struct smat_handle {
     std::vector<uint32_t> slots_off;     // [nbr+1]
     uint64_t slots_units = 0;
     int max_class = 0;
+    int64_t value_bytes = 0;             // bytes of block values a launch over every block row reads
+    int64_t b_rows = 0;                  // slots that name a row of B, over all packs
+    std::vector<int32_t> row_b_rows;     // [nbr] the same per block row
     // Dense path (kernels.h, DenseTiles): complete super rows of sixteen block rows whose block
     // columns overlap enough.  row_dense marks the block rows it covers.
     std::vector<int32_t> dense_super, step_ptr, step_cols;
@@ -88,7 +92,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
-    size_t perm, work, work_rest, slots, vals, pack_ptr, slots_off, blk_ptr, blk_col, blk_pack, blk_meta;
+    size_t perm, work, work_rest, slots, vals, pack_ptr, slots_off, row_class, blk_ptr, blk_col, blk_pack, blk_meta;
     size_t csr_row_ptr, csr_col_idx, csr_vals;
     size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, t_scratch, total;
 };
@@ -107,6 +111,7 @@ Layout make_layout(const smat_handle& h)
     l.vals = take(static_cast<size_t>(h.slots_units) * 128 * static_cast<size_t>(h.elem_bytes));
     l.pack_ptr = take((nbr + 1) * sizeof(int32_t));
     l.slots_off = take((nbr + 1) * sizeof(uint32_t));
+    l.row_class = take(nbr);
     l.blk_ptr = take((nbr + 1) * sizeof(int32_t));
     l.blk_col = take(n_e * sizeof(int32_t));
     l.blk_pack = take(n_e * sizeof(int32_t));
@@ -177,6 +182,30 @@ void plan_dense_tiles(smat_handle& h)
     }
 }
 
+// Stored entries of block row br of A' (rows perm[16 br] ...).
+int64_t block_row_nnz(const smat_handle& h, size_t br)
+{
+    int64_t nnz = 0;
+    for (int64_t i = static_cast<int64_t>(br) * 16; i < static_cast<int64_t>(br) * 16 + 16 && i < h.csr.M; ++i) {
+        const size_t r = static_cast<size_t>(h.bcsr.perm[static_cast<size_t>(i)]);
+        nnz += h.csr.row_ptr[r + 1] - h.csr.row_ptr[r];
+    }
+    return nnz;
+}
+
+// Stored entries of block row br in the order of an entry row's slots (pack_layout.h): by
+// column, then by row of the block row.  An item is column << 4 | row.
+void entry_order(const smat_handle& h, size_t br, std::vector<uint64_t>& items)
+{
+    items.clear();
+    for (size_t rr = 0; rr < 16 && br * 16 + rr < static_cast<size_t>(h.csr.M); ++rr) {
+        const size_t r = static_cast<size_t>(h.bcsr.perm[br * 16 + rr]);
+        for (int64_t p = h.csr.row_ptr[r]; p < h.csr.row_ptr[r + 1]; ++p)
+            items.push_back(static_cast<uint64_t>(h.csr.col_idx[static_cast<size_t>(p)]) << 4 | static_cast<uint64_t>(rr));
+    }
+    std::sort(items.begin(), items.end());
+}
+
 // Cuts every block row into packs and derives the row classes (pack_layout.h).
 void plan_packs(smat_handle& h)
 {
@@ -189,10 +218,14 @@ void plan_packs(smat_handle& h)
     h.row_class.assign(nbr, 0);
     h.slots_off.assign(nbr + 1, 0);
     h.max_class = 0;
+    h.value_bytes = 0;
+    h.b_rows = 0;
+    h.row_b_rows.assign(nbr, 0);
     uint64_t units = 0;
     for (size_t br = 0; br < nbr; ++br) {
         const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
         int in_pack = 0, worst = 0, pack = -1;
+        int64_t occupied = 0;
         for (int32_t s = s0; s < s1; ++s) {
             const int cols = __builtin_popcount(b.col_mask[s]);
             if (pack < 0 || in_pack + cols > smat::kPackColumns) {
@@ -203,13 +236,31 @@ void plan_packs(smat_handle& h)
             h.blk_pack[static_cast<size_t>(s)] = pack;
             h.blk_meta[static_cast<size_t>(s)] = static_cast<uint32_t>(b.col_mask[s]) | static_cast<uint32_t>(in_pack) << 16;
             in_pack += cols;
+            occupied += cols;
             worst = std::max(worst, in_pack);
         }
-        const int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
+        int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
+        int64_t n_packs = pack + 1;
+        const int64_t nnz = block_row_nnz(h, br);
+        if (cls == 2 && nnz * 16 <= occupied * 17) {
+            // entry row: packs of 32 stored entries; the per-block records above are not used for it
+            cls = smat::kEntryClass;
+            const int64_t by_entry = (nnz + 31) / 32;
+            for (int64_t x = n_packs; x < by_entry; ++x) h.pack_first.push_back(s1);
+            for (int64_t x = by_entry; x < n_packs; ++x) h.pack_first.pop_back();
+            n_packs = by_entry;
+            h.value_bytes += n_packs * 32 * h.elem_bytes;
+            h.b_rows += nnz;
+            h.row_b_rows[br] = static_cast<int32_t>(nnz);
+        } else {
+            h.value_bytes += (n_packs * 64 * h.elem_bytes) << (cls + 1);
+            h.b_rows += occupied;
+            h.row_b_rows[br] = static_cast<int32_t>(occupied);
+        }
         h.row_class[br] = static_cast<int8_t>(cls);
         h.max_class = std::max(h.max_class, cls);
         h.slots_off[br] = static_cast<uint32_t>(units);
-        units += static_cast<uint64_t>(pack + 1) << cls;                  // 1, 2 or 4 units per pack
+        units += static_cast<uint64_t>(n_packs) * static_cast<uint64_t>(smat::pack_units(cls));
         if (units >= (uint64_t{1} << 32)) throw std::length_error("slot table too large");
         h.pack_ptr[br + 1] = static_cast<int32_t>(h.pack_first.size());
     }
@@ -222,20 +273,23 @@ void plan_packs(smat_handle& h)
 // Launch statistics over a subset of block rows.
 void row_stats(const smat_handle& h, bool skip_dense, smat::DeviceBcsr& d)
 {
-    int64_t longest = 0, packs = 0, rows = 0, units = 0;
+    int64_t longest = 0, packs = 0, rows = 0, bytes = 0, b_rows = 0;
     int cls = 0;
     for (int64_t br = 0; br < h.bcsr.nbr; ++br) {
         if (skip_dense && h.row_dense[static_cast<size_t>(br)]) continue;
         const int64_t len = h.pack_ptr[static_cast<size_t>(br) + 1] - h.pack_ptr[static_cast<size_t>(br)];
         longest = std::max(longest, len);
         packs += len;
-        units += len << h.row_class[static_cast<size_t>(br)];
-        cls = std::max<int>(cls, h.row_class[static_cast<size_t>(br)]);
+        const int rc = h.row_class[static_cast<size_t>(br)];
+        bytes += len * (rc == smat::kEntryClass ? 32 * h.elem_bytes + 128 : smat::pack_units(rc) * (128 * h.elem_bytes + 32));
+        cls = std::max<int>(cls, rc);
+        b_rows += h.row_b_rows[static_cast<size_t>(br)];
         ++rows;
     }
     d.n_order = rows;
     d.n_packs = packs;
-    d.stream_bytes = units * (128 * h.elem_bytes + 32);
+    d.stream_bytes = bytes;
+    d.b_rows = b_rows;
     d.max_row_packs = longest;
     d.mean_row_packs = rows ? static_cast<double>(packs) / static_cast<double>(rows) : 0.0;
     d.max_class = cls;
@@ -334,13 +388,9 @@ smat_status_t smat_get_layout_info(const smat_handle_t* h, int64_t* n_packs, int
 {
     if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
     if (n_packs) *n_packs = static_cast<int64_t>(h->pack_first.size()) - 1;
-    if (value_bytes) *value_bytes = static_cast<int64_t>(h->slots_units) * 128 * h->elem_bytes;
+    if (value_bytes) *value_bytes = h->value_bytes;
     if (table_bytes) *table_bytes = static_cast<int64_t>(h->slots_units) * 32 + h->bcsr.nbr * (16 + 16 * 4);
-    if (n_columns) {
-        int64_t cols = 0;
-        for (uint16_t m : h->bcsr.col_mask) cols += __builtin_popcount(m);
-        *n_columns = cols;
-    }
+    if (n_columns) *n_columns = h->b_rows;
     return SMAT_OK;
 }
 
@@ -405,9 +455,25 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         std::memcpy(perm_padded.data(), b.perm.data(), sizeof(int32_t) * M);
         // slot tables (pack_layout.h): the B row of every occupied column of every pack
         std::vector<uint32_t> slots(static_cast<size_t>(h->slots_units) * 8, static_cast<uint32_t>(h->csr.K));
+        std::vector<uint64_t> items;
         for (size_t br = 0; br < nbr; ++br) {
-            const int L = 2 << h->row_class[br];
             uint32_t* table = slots.data() + static_cast<size_t>(h->slots_off[br]) * 8;
+            if (h->row_class[br] == smat::kEntryClass) {
+                // entry row: one slot per stored entry; the entries' row numbers go into the top
+                // bytes of the group's first four slots
+                entry_order(*h, br, items);
+                for (size_t e = 0; e < items.size(); ++e) {
+                    const size_t col = static_cast<size_t>(items[e] >> 4);
+                    const uint32_t rr = static_cast<uint32_t>(items[e] & 15u);
+                    const int rank = static_cast<int>(e & 31), g = smat::slot_group(rank), kk = smat::slot_pos(rank);
+                    uint32_t* group = table + (e >> 5) * 32 + g * 8;
+                    group[kk] = (group[kk] & 0xFF000000u) |
+                                (h->cols_permuted ? static_cast<uint32_t>(b.col_perm[col]) : static_cast<uint32_t>(col));
+                    group[kk >> 1] |= rr << (24 + 4 * (kk & 1));
+                }
+                continue;
+            }
+            const int L = 2 << h->row_class[br];
             for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, table += 4 * L) {
                 int rank = 0;
                 for (int32_t s = h->pack_first[static_cast<size_t>(pk)]; s < h->pack_first[static_cast<size_t>(pk) + 1]; ++s)
@@ -450,6 +516,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         if ((e = up(l.slots, slots.data(), slots.size() * 4))) return hip_fail("copy slot tables", e);
         if ((e = up(l.pack_ptr, h->pack_ptr.data(), h->pack_ptr.size() * 4))) return hip_fail("copy pack offsets", e);
         if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
+        if ((e = up(l.row_class, h->row_class.data(), h->row_class.size()))) return hip_fail("copy row classes", e);
         if ((e = up(l.blk_ptr, b.row_ptr.data(), b.row_ptr.size() * 4))) return hip_fail("copy block offsets", e);
         if ((e = up(l.blk_col, b.col_idx.data(), n_e * 4))) return hip_fail("copy block columns", e);
         if ((e = up(l.blk_pack, h->blk_pack.data(), n_e * 4))) return hip_fail("copy block packs", e);
@@ -466,6 +533,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         d.vals = base + l.vals;
         d.pack_ptr = reinterpret_cast<const int32_t*>(base + l.pack_ptr);
         d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
+        d.row_class = reinterpret_cast<const int8_t*>(base + l.row_class);
         d.blk_ptr = reinterpret_cast<const int32_t*>(base + l.blk_ptr);
         d.blk_col = reinterpret_cast<const int32_t*>(base + l.blk_col);
         d.blk_pack = reinterpret_cast<const int32_t*>(base + l.blk_pack);
@@ -535,7 +603,33 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
             else static_cast<uint8_t*>(vals)[at] = static_cast<uint8_t>(v);
         };
         std::memset(vals, 0, n_e * 256 * es);
+        std::vector<uint64_t> items;
         for (size_t br = 0; br < static_cast<size_t>(h->bcsr.nbr); ++br) {
+            if (h->row_class[br] == smat::kEntryClass) {
+                // entry row: the values of the stored entries in the order of the slot tables
+                const size_t src0 = static_cast<size_t>(h->slots_off[br]) * 128;
+                const int32_t* bc0 = h->bcsr.col_idx.data() + h->bcsr.row_ptr[br];
+                const int32_t* bc1 = h->bcsr.col_idx.data() + h->bcsr.row_ptr[br + 1];
+                entry_order(*h, br, items);
+                const int64_t e = static_cast<int64_t>(items.size());
+                for (int64_t x = 0; x < e; ++x) {
+                    const int32_t col = static_cast<int32_t>(items[static_cast<size_t>(x)] >> 4);
+                    const size_t rr = static_cast<size_t>(items[static_cast<size_t>(x)] & 15u);
+                    const size_t sb = static_cast<size_t>(std::lower_bound(bc0, bc1, col >> 4) - h->bcsr.col_idx.data());
+                    const int rank = static_cast<int>(x & 31);
+                    const size_t at = src0 + static_cast<size_t>(x >> 5) * 512 +
+                                      static_cast<size_t>(smat::entry_elem_index(smat::slot_group(rank), smat::slot_pos(rank)));
+                    put(sb * 256 + rr * 16 + static_cast<size_t>(col & 15), get(at));
+                }
+                // the rest of the last pack's 32 values must have stayed zero
+                for (int64_t x = e; x < (e + 31) / 32 * 32; ++x) {
+                    const int rank = static_cast<int>(x & 31);
+                    if (get(src0 + static_cast<size_t>(x >> 5) * 512 +
+                            static_cast<size_t>(smat::entry_elem_index(smat::slot_group(rank), smat::slot_pos(rank)))) != 0)
+                        return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
+                }
+                continue;
+            }
             const int L = 2 << h->row_class[br];
             const int elems = smat::pack_elems(L);
             size_t src = static_cast<size_t>(h->slots_off[br]) * 128;

@@ -21,6 +21,7 @@ struct DeviceBcsr {
     // bind-time value scatter only
     const int32_t* pack_ptr = nullptr;   // [nbr+1] pack offsets per block row
     const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table, 32-byte units
+    const int8_t* row_class = nullptr;   // [nbr] 0..2: packs of occupied columns with L = 2, 4, 8; 3: entry row
     const int32_t* blk_ptr = nullptr;    // [nbr+1] stored-block offsets per block row
     const int32_t* blk_col = nullptr;    // [n_blocks] block column, ascending inside a block row
     const int32_t* blk_pack = nullptr;   // [n_blocks] pack of the block, counted inside its block row
@@ -28,9 +29,10 @@ struct DeviceBcsr {
     int64_t M = 0, K = 0, nbr = 0;
     int64_t n_packs = 0;                 // packs of the rows in the launch table
     int64_t stream_bytes = 0;            // values + slot tables of those rows
+    int64_t b_rows = 0;                  // slots of those rows that name a row of B (each fetched once per column slab)
     int64_t max_row_packs = 0;           // longest block row
     double mean_row_packs = 0;
-    int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pack)
+    int max_class = 0;                   // highest row class present (0: <=8, 1: <=16, 2: <=32 occupied columns per pack, 3: entry rows)
 };
 
 // Block-dense parts of the matrix: "super rows" of sixteen consecutive block rows whose block

@@ -28,8 +28,9 @@ int launch_fill_zero(void* dst, size_t n16, void* stream)
 
 // One thread per row of A' = P A: walks the row's CSR entries, finds each entry's block in
 // the block row by binary search over the ascending block columns and stores the value at
-// its slot in the block's pack (pack_layout.h).  The CSR values arrive as 16-bit words; T is
-// the stored element (the 8-bit types keep the low byte).
+// its slot in the block's pack (pack_layout.h); in an entry row the value goes to the slot with
+// the entry's number instead.  The CSR values arrive as 16-bit words; T is the stored element
+// (the 8-bit types keep the low byte).
 template <typename T>
 __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_row_ptr,
                                  const int32_t* __restrict__ csr_col_idx,
@@ -43,10 +44,34 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
     const int lo0 = d.blk_ptr[br], hi0 = d.blk_ptr[br + 1];
     const int npacks = d.pack_ptr[br + 1] - d.pack_ptr[br];
     if (npacks == 0) return;
-    // class of the block row from the size of its slot table: 1, 2 or 4 units per pack
     const uint32_t unit0 = d.slots_off[br];
-    const int L = 2 * static_cast<int>((d.slots_off[br + 1] - unit0) / static_cast<uint32_t>(npacks));
+    const int cls = d.row_class[br];
     T* row_vals = vals_out + static_cast<size_t>(unit0) * 128;
+    if (cls == kEntryClass) {
+        // entry row: the entries of the block row are numbered by column, then by row; an
+        // entry's number is the count of those before it, row by row of the block row
+        const int64_t j0 = br << 4, j1 = (j0 + 16 < d.M) ? j0 + 16 : d.M;
+        for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
+            const int c = csr_col_idx[p];
+            int64_t e = 0;
+            for (int64_t j = j0; j < j1; ++j) {
+                const int64_t rj = d.perm[j];
+                const int64_t first = csr_row_ptr[rj];
+                const int below = j < i ? c + 1 : c;       // columns that come before (c, this row) in row j
+                int64_t lo = first, hi = csr_row_ptr[rj + 1];
+                while (lo < hi) {
+                    const int64_t mid = (lo + hi) >> 1;
+                    if (csr_col_idx[mid] < below) lo = mid + 1; else hi = mid;
+                }
+                e += lo - first;
+            }
+            const int rank = static_cast<int>(e & 31);
+            row_vals[static_cast<size_t>(e >> 5) * pack_elems(8) + entry_elem_index(slot_group(rank), slot_pos(rank))] =
+                static_cast<T>(csr_vals[p]);
+        }
+        return;
+    }
+    const int L = 2 << cls;
     int hint = lo0;
     for (int64_t p = csr_row_ptr[r]; p < csr_row_ptr[r + 1]; ++p) {
         const int c = csr_col_idx[p];

@@ -28,7 +28,21 @@
 // of B that slot (g, kk) multiplies, or K (one past the last row) for an empty slot.  A lane
 // reads its group's L entries with one or two loads.
 //
-// Per stored block, for the bind-time value scatter only: its block column, its pack (counted
+// Entry rows.  A block row whose occupied columns hold hardly more than one stored entry each
+// (nnz <= 17/16 of the occupied columns; graphs, uniformly random matrices) would store sixteen
+// values per column, fifteen of them zero.  Such a row is kept by ENTRY instead (row class 3):
+// its stored entries, row by row of the block row and by ascending column inside a row, are
+// cut into packs of 32; entry number j of a pack takes slot (j mod 4, j div 4) like an occupied
+// column would.  The pack's slot table names the B row of every entry (a column with two
+// entries is named twice) and carries, in the otherwise unused top byte of entries 0..3 of
+// every lane group, the eight 4-bit row numbers of the group's entries (entry kk in bits
+// 4 kk .. 4 kk + 3 of the 32 bits formed by those four bytes, lowest entry's byte first).  Its
+// values are the 32 entry values alone, group by group (8 g + kk), at the start of the area a
+// class-8 pack would fill: 64 bytes instead of 1 KiB for the 16-bit types.  The kernel expands
+// them into the left operand in registers: lane (g, i) keeps value kk where the row number of
+// entry (g, kk) is i and puts zero elsewhere.
+//
+// Per stored block, for the bind-time value scatter only (not for entry rows): its block column, its pack (counted
 // inside the block row) and a word holding its 16-bit column occupancy mask (low half) and the
 // number of occupied columns of the pack that come before it (high half).
 #pragma once
@@ -44,6 +58,14 @@
 namespace smat {
 
 constexpr int kPackColumns = 32;     // k extent of the instruction
+constexpr int kEntryClass = 3;       // row class of an entry row (classes 0..2: L = 2, 4, 8)
+
+// slot-table units (32 bytes; 128 values) one pack of a row of class cls takes
+SMAT_HD inline int pack_units(int cls) { return cls == kEntryClass ? 4 : 1 << cls; }
+// row loads per lane and pack
+SMAT_HD inline int class_loads(int cls) { return cls == kEntryClass ? 8 : 2 << cls; }
+// index, inside the pack's value area, of the value of entry (g, kk) of an entry row
+SMAT_HD inline int entry_elem_index(int g, int kk) { return 8 * g + kk; }
 
 // block values stored per pack in a row of class L
 SMAT_HD inline int pack_elems(int L) { return 64 * L; }

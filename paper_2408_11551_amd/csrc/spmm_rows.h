@@ -118,22 +118,26 @@ struct RowWalk {
 };
 
 // Per-class pieces shared by the two pipelines below.
-template <int NT, int L, int NCH, int DT>
+template <int NT, int L, int NCH, int DT, bool ENTRY = false>
 struct PackOps {
     using Acc = typename Elem<DT>::Acc;
     static constexpr int ES = Elem<DT>::ES;
     static constexpr int LB = NT * ES;                    // bytes per B row load
+    static_assert(!ENTRY || L == 8, "an entry pack has eight slots per lane group");
     static constexpr int AB = L * ES;                     // bytes of block values per lane and pack
+    static constexpr int EB = 8 * ES;                     // entry rows: bytes of a lane group's eight entry values
     static constexpr int ND = LB >= 4 ? LB / 4 : 1;       // dwords per B row load
     static constexpr int NQ = (AB + 3) / 4;               // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
-    uint32_t slots_voff, vals_voff, lane_off[NCH], ldb_bytes, no_row;
+    uint32_t slots_voff, vals_voff, lane_off[NCH], ldb_bytes, no_row, row_match;
     int last;
     bool stream;
 
     __device__ __forceinline__ PackOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
-        : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L), vals_voff(static_cast<uint32_t>(w.lane) * AB),
-          ldb_bytes(w.ldb_bytes), no_row(w.no_row), last(w.npacks - 1), stream(w.stream)
+        : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L),
+          vals_voff(ENTRY ? static_cast<uint32_t>(w.g) * EB : static_cast<uint32_t>(w.lane) * AB),
+          ldb_bytes(w.ldb_bytes), no_row(w.no_row), row_match(static_cast<uint32_t>(w.lane & 15) * 0x11111111u),
+          last(w.npacks - 1), stream(w.stream)
     {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
@@ -163,21 +167,31 @@ struct PackOps {
     // zero); `live` false (a step past the wave's last pack) reads zeros instead
     __device__ __forceinline__ u32x4 load_a(int p, bool live) const
     {
+        // an entry pack lies where a pack of class 8 would and uses its first 32 values: the
+        // lane group's eight, to be expanded by multiply()
+        constexpr int W = ENTRY ? EB : AB;
         uint32_t r[4] = {0u, 0u, 0u, 0u};
-        if (!live) BLoad<AB>::ld(r, none_rsrc, vals_voff, 0u);
-        else if (stream) SLoad<AB>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
-        else BLoad<AB>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
+        if (!live) BLoad<W>::ld(r, none_rsrc, vals_voff, 0u);
+        else if (stream) SLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
+        else BLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
         return u32x4{r[0], r[1], r[2], r[3]};
     }
     // Occupied columns fill the slots group by group, so position kk is empty in every group
     // as soon as it is empty in group 0 (lane 0).  In the sparse classes a pack therefore has
     // a wave-uniform "level": the number of leading positions that hold anything, rounded up
     // to 1, 2 or 4; only that many B rows are requested, and the multiply permutes only the
-    // operand dwords they feed.  Returns the level.
+    // operand dwords they feed.  Returns the level; for an entry pack, the row numbers of the
+    // lane group's entries instead (4 bits each), which multiply() needs.
     __device__ __forceinline__ int issue_b(const uint32_t (&m)[L], uint32_t (&R)[L][NCH][ND]) const
     {
         int level = L;
-        if constexpr (L == 2) {
+        if constexpr (ENTRY) {
+            // the eight row numbers of the group's entries, from the top bytes of its first four
+            // slots (the address arithmetic below only takes the low 24 bits of a slot)
+            const uint32_t lo = __builtin_amdgcn_perm(m[1], m[0], 0x0C0C0703u);
+            const uint32_t hi = __builtin_amdgcn_perm(m[3], m[2], 0x0C0C0703u);
+            level = static_cast<int>(__builtin_amdgcn_perm(hi, lo, 0x05040100u));
+        } else if constexpr (L == 2) {
             level = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(m[1])) == no_row ? 1 : 2;
         } else if constexpr (L == 4) {
             level = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(m[1])) == no_row ? 1
@@ -185,7 +199,7 @@ struct PackOps {
         }
 #pragma unroll
         for (int kk = 0; kk < L; ++kk)
-            if (kk < level) {
+            if (ENTRY || kk < level) {
                 const uint32_t row_off = __umul24(m[kk], ldb_bytes);
 #pragma unroll
                 for (int c = 0; c < NCH; ++c) BLoad<LB>::ld(R[kk][c], b_rsrc, row_off + lane_off[c], 0u);
@@ -194,8 +208,25 @@ struct PackOps {
     }
     // Rows above the pack's level were not requested: their registers hold stale data and are
     // replaced by zeros (a select on a wave-uniform condition) before the permutes.
-    __device__ __forceinline__ void multiply(const u32x4& a, const uint32_t (&R)[L][NCH][ND], int level, Acc (&acc)[NCH * NT]) const
+    __device__ __forceinline__ void multiply(const u32x4& a_in, const uint32_t (&R)[L][NCH][ND], int level, Acc (&acc)[NCH * NT]) const
     {
+        u32x4 a = a_in;
+        if constexpr (ENTRY) {
+            // left operand of lane (g, i): entry value kk where the entry's row is i, else zero.
+            // `miss` has a zero nibble kk exactly there.
+            const uint32_t miss = static_cast<uint32_t>(level) ^ row_match;
+            constexpr int PER = 4 / ES;                    // entries per operand dword
+#pragma unroll
+            for (int q = 0; q < 4; ++q) {
+                uint32_t keep = 0u;
+                if (q < 8 / PER) {
+#pragma unroll
+                    for (int e = 0; e < PER; ++e)
+                        if (((miss >> (4 * (PER * q + e))) & 15u) == 0u) keep |= (ES == 2 ? 0xFFFFu : 0xFFu) << (8 * ES * e);
+                }
+                a[q] = a_in[q] & keep;
+            }
+        }
 #pragma unroll
         for (int c = 0; c < NCH; ++c) {
             uint32_t S[L][ND];
@@ -240,10 +271,10 @@ struct PackOps {
 // handles two packs and has no exit in the middle (an odd tail multiplies zeros).  The
 // scheduling barriers keep every load ahead of the multiply that precedes its use, and the
 // prologue issues its loads in the order the loop body leaves them in flight.
-template <int NT, int KW, int L, int NCH, int DT>
+template <int NT, int KW, int L, int NCH, int DT, bool ENTRY = false>
 __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_t rsrc, typename Elem<DT>::Acc (&acc)[NCH * NT])
 {
-    using Ops = PackOps<NT, L, NCH, DT>;
+    using Ops = PackOps<NT, L, NCH, DT, ENTRY>;
     if (w.ks >= w.npacks) return;
     const Ops ops(w, rsrc);
     const int count = (w.npacks - w.ks + KW - 1) / KW;     // packs of this wave
@@ -255,21 +286,21 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
     __builtin_amdgcn_sched_barrier(0);
     ops.load_slots(p + KW, m1);
     u32x4 a0 = ops.load_a(p, true);
-    ops.issue_b(m0, R0);
+    int l0 = ops.issue_b(m0, R0), l1;                      // level of the pack (entry rows: its row numbers)
     __builtin_amdgcn_sched_barrier(0);
     u32x4 a1 = ops.load_a(p + KW, count > 1);
     for (int it = 0; it < iters; ++it) {
         const int h = 2 * it;                              // pack of this wave multiplied first
         ops.load_slots(p + 2 * KW, m0);
-        ops.issue_b(m1, R1);
+        l1 = ops.issue_b(m1, R1);
         __builtin_amdgcn_sched_barrier(0);
-        ops.multiply(a0, R0, L, acc);
+        ops.multiply(a0, R0, l0, acc);
         __builtin_amdgcn_sched_barrier(0);
         a0 = ops.load_a(p + 2 * KW, h + 2 < count);
         ops.load_slots(p + 3 * KW, m1);
-        ops.issue_b(m0, R0);
+        l0 = ops.issue_b(m0, R0);
         __builtin_amdgcn_sched_barrier(0);
-        ops.multiply(a1, R1, L, acc);
+        ops.multiply(a1, R1, l1, acc);
         __builtin_amdgcn_sched_barrier(0);
         a1 = ops.load_a(p + 3 * KW, h + 3 < count);
         p += 2 * KW;
@@ -357,7 +388,7 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
     const int i = lane & 15, g = lane >> 4;
     const i32x4 rec = reinterpret_cast<const i32x4*>(work)[blockIdx.x];     // one record of the launch table
     const int br = rec[0] & 0x0FFFFFFF;
-    const int cls = rec[0] >> 28;                  // 0: L = 2, 1: L = 4, 2: L = 8
+    const int cls = rec[0] >> 28;                  // 0: L = 2, 1: L = 4, 2: L = 8, 3: entry row
     const int n0 = (blockIdx.y * SW + sl) * WC;
 
     RowWalk w;
@@ -405,6 +436,7 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
 
     if constexpr (LMAX >= 8) {
         if (cls == 2) walk_row<NT, KW, 8, NCH, DT>(w, rsrc, acc);
+        if (cls == kEntryClass) walk_row<NT, KW, 8, NCH, DT, true>(w, rsrc, acc);
     }
     if constexpr (LMAX >= 4) {
         if (cls == 1) walk_row_deep<NT, KW, 4, NCH, DT>(w, rsrc, acc);
@@ -540,7 +572,7 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     // per group; KW waves share one block row (partial tiles summed through LDS).  Splitting a
     // row costs a pipeline fill and a reduction per extra wave, so KW is the smallest split for
     // which (a) the longest row, walked at about 0.25 us per pack and wave, stays below half of
-    // what the launch needs at ~5 TB/s, and (b) the launch has at least two waves for every
+    // what the launch needs (its streams at ~5 TB/s plus the gather of B), and (b) the launch has at least two waves for every
     // SIMD of the chip.
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
     // two chunks per wave: 16-bit types only (the 8-bit types reach the same 256 bytes per row
@@ -552,10 +584,16 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     const int64_t groups = d.n_order * ((wave_slabs + sw - 1) / sw);
     const double stream_us = (static_cast<double>(d.stream_bytes) + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * ES) / 5.0e6;
+    // every named row of B is fetched once per slab, 16*NT elements of it (no less than a
+    // 64-byte piece).  The compute units take in about 10 TB/s of such fills together; the
+    // gather enters at twice that rate, which is where the measured choices (three workloads,
+    // N = 1 ... 1000) change over.
+    const double piece = 16.0 * NT * ES < 64.0 ? 64.0 : 16.0 * NT * ES;
+    const double gather_us = static_cast<double>(d.b_rows) * static_cast<double>(slabs) * piece / 20.0e6;
     const double longest_us = static_cast<double>(d.max_row_packs) * 0.25;
     int kw = 1;
     while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
-           (longest_us / kw > 0.5 * stream_us || groups * sw * kw < 2048)) kw *= 2;
+           (longest_us / kw > 0.5 * (stream_us + gather_us) || groups * sw * kw < 2048)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \

@@ -217,12 +217,15 @@ def test_default_options():
 def _greedy_packs(w, perm):
     """Packs per block row, written out from the definition: walk the stored blocks of a block
     row from the left and close a pack when the next block's occupied columns would not fit
-    32 any more.  Returns (n_packs, value_bytes, n_columns)."""
+    32 any more; a row of the densest class whose stored entries number at most 17/16 of its
+    occupied columns is cut into packs of 32 entries instead and stores one value per entry.
+    Returns (n_packs, value_bytes, slot_table_bytes, rows_of_B_named)."""
     inv = np.empty(w.M, dtype=np.int64)
     inv[perm] = np.arange(w.M)
     rows_new = inv[np.repeat(np.arange(w.M), np.diff(w.row_ptr))]
     key = np.unique((rows_new // 16) * w.K + w.col_idx)               # occupied (block row, column)
-    n_packs = value_bytes = 0
+    nnz_of = np.bincount(rows_new // 16, minlength=-(-w.M // 16))
+    n_packs = value_bytes = slot_bytes = b_rows = 0
     for br in range(-(-w.M // 16)):
         cols = key[(key >= br * w.K) & (key < (br + 1) * w.K)] - br * w.K
         per_block = np.unique(cols // 16, return_counts=True)[1]
@@ -233,28 +236,42 @@ def _greedy_packs(w, perm):
                 fill = 0
             fill += int(c)
             packs[-1] = fill
-        n_packs += len(packs)
-        if packs:
-            L = 2 if max(packs) <= 8 else 4 if max(packs) <= 16 else 8
+        if not packs:
+            continue
+        L = 2 if max(packs) <= 8 else 4 if max(packs) <= 16 else 8
+        if L == 8 and int(nnz_of[br]) * 16 <= cols.size * 17:
+            n = -(-int(nnz_of[br]) // 32)
+            n_packs += n
+            value_bytes += n * 64
+            slot_bytes += n * 128
+            b_rows += int(nnz_of[br])
+        else:
+            n_packs += len(packs)
             value_bytes += len(packs) * 128 * L
-    return n_packs, value_bytes, int(key.size)
+            slot_bytes += len(packs) * 16 * L
+            b_rows += cols.size
+    return n_packs, value_bytes, slot_bytes, b_rows
 
 
 def test_layout_info_matches_the_pack_definition():
     cases = [random_csr(100, 300, 1, 0.004, seed=1), random_csr(64, 64, 1, 0.5, seed=2),
              random_csr(130, 333, 1, 0.05, seed=3), band_csr(256, 8, 1, seed=4, p=0.5),
-             random_csr(48, 1000, 1, 0.02, seed=5), random_csr(33, 20, 1, 0.0, seed=6)]
+             random_csr(48, 1000, 1, 0.02, seed=5), random_csr(33, 20, 1, 0.0, seed=6),
+             random_csr(64, 4096, 1, 0.004, seed=7), random_csr(200, 8192, 1, 0.003, seed=8)]
+    kinds = set()
     for w in cases:
         h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
         try:
             perm = S.smat_export_perm(h, w.M)
             info = S.smat_get_layout_info(h)
-            n_packs, value_bytes, n_columns = _greedy_packs(w, perm)
-            assert (info["n_packs"], info["value_bytes"], info["n_columns"]) == (n_packs, value_bytes, n_columns)
-            assert info["table_bytes"] == value_bytes // 8 + 80 * -(-w.M // 16)
-            assert 32 * info["n_packs"] >= n_columns
+            n_packs, value_bytes, slot_bytes, b_rows = _greedy_packs(w, perm)
+            assert (info["n_packs"], info["value_bytes"], info["n_columns"]) == (n_packs, value_bytes, b_rows)
+            assert info["table_bytes"] == slot_bytes + 80 * -(-w.M // 16)
+            assert 32 * info["n_packs"] >= b_rows
+            kinds.add(value_bytes * 2 < slot_bytes * 8)              # entry rows dominate
         finally:
             S.smat_destroy(h)
+    assert kinds == {True, False}
 
 
 def test_layout_info_on_prescribed_occupancies():
@@ -264,7 +281,7 @@ def test_layout_info_on_prescribed_occupancies():
         perm = S.smat_export_perm(h, w.M)
         assert np.array_equal(perm, np.arange(w.M))
         info = S.smat_get_layout_info(h)
-        n_packs, value_bytes, n_columns = _greedy_packs(w, perm)
+        n_packs, value_bytes, _, n_columns = _greedy_packs(w, perm)
         assert (info["n_packs"], info["value_bytes"], info["n_columns"]) == (n_packs, value_bytes, n_columns)
         # by hand: 3 + 2 + 1 + 2 + 1 + 1 + 0 + 1 + 1 + 4 packs (row 1: 11+11 | 11+10+1; row 9: ten
         # blocks of three columns per pack); classes 8, 8, 8, 8, 2, 4, -, 2, 8, 8
