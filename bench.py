@@ -37,9 +37,9 @@ WORKLOAD_TEXT = {
 
 # HBM-side bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
 # profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after a 256 MiB calibration copy), or None
-MEASURED_TRAFFIC_BYTES = {"uniform": 48.2e6, "banded": 139.0e6, "powerlaw": 708.4e6,
-                          "hidden_blocks": 467.6e6, "pruned_weight": 201.6e6,
-                          "uniform:e4m3": 29.1e6}
+MEASURED_TRAFFIC_BYTES = {"uniform": 40.3e6, "banded": 139.0e6, "powerlaw": 576.7e6,
+                          "hidden_blocks": 377.4e6, "pruned_weight": 201.6e6,
+                          "uniform:e4m3": 25.6e6}
 
 
 def algorithmic_bytes(layout, K, N, M, es=2):
@@ -315,7 +315,7 @@ def main():
             "frac_at_bcsr_format_bytes": bytes_bcsr / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
         }),
         "layout": {"n_packs": layout["n_packs"], "value_bytes": layout["value_bytes"],
-                   "table_bytes": layout["table_bytes"], "occupied_columns": layout["n_columns"],
+                   "table_bytes": layout["table_bytes"], "rows_of_b_named": layout["n_columns"],
                    "b_gather_bytes": layout["n_columns"] * w.N * es,
                    "mfma_issued_tflops": issued_tflops, "hbm_gbs": achieved_gbs,
                    "bcsr_format_bytes": bytes_bcsr, "bcsr_format_gbs": bytes_bcsr / (kernel_ms * 1e-3) / 1e9},

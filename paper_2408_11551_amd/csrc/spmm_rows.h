@@ -572,15 +572,22 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     // per group; KW waves share one block row (partial tiles summed through LDS).  Splitting a
     // row costs a pipeline fill and a reduction per extra wave, so KW is the smallest split for
     // which (a) the longest row, walked at about 0.25 us per pack and wave, stays below half of
-    // what the launch needs (its streams at ~5 TB/s plus the gather of B), and (b) the launch has at least two waves for every
-    // SIMD of the chip.
+    // what the launch needs (its streams at ~5 TB/s plus the gather of B), and (b) the launch
+    // has at least two waves for every SIMD of the chip (four where the variant's registers
+    // allow six resident).
     const int64_t slabs = (N + 16 * NT - 1) / (16 * NT);
     // two chunks per wave: 16-bit types only (the 8-bit types reach the same 256 bytes per row
     // with NT = 16), and the dense class has no registers to spare
     constexpr bool kTwoChunks = NT == 8 && ES == 2 && LMAX < 8;
     const int nch = (kTwoChunks && slabs >= 2) ? 2 : 1;
     const int64_t wave_slabs = (slabs + nch - 1) / nch;
-    const int sw = wave_slabs >= 2 ? 2 : 1;
+    // Two waves of a group on neighbouring slabs read the block values once for both, but every
+    // phase of the launch then gathers from twice as many columns of B.  Measured (three
+    // workloads, N = 256 ... 1000, 16-bit and 8-bit): with full-width pieces of B (256 bytes per
+    // row and slab) that start on cache lines, one slab per group is 2-14 % faster; with
+    // misaligned rows (N = 1000) or narrow pieces the pair is.
+    const bool whole_lines = 16 * NT * ES >= 256 && (ldb * ES) % 128 == 0 && reinterpret_cast<uintptr_t>(B) % 128 == 0;
+    const int sw = (wave_slabs >= 2 && !whole_lines) ? 2 : 1;
     const int64_t groups = d.n_order * ((wave_slabs + sw - 1) / sw);
     const double stream_us = (static_cast<double>(d.stream_bytes) + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * ES) / 5.0e6;
@@ -591,9 +598,11 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     const double piece = 16.0 * NT * ES < 64.0 ? 64.0 : 16.0 * NT * ES;
     const double gather_us = static_cast<double>(d.b_rows) * static_cast<double>(slabs) * piece / 20.0e6;
     const double longest_us = static_cast<double>(d.max_row_packs) * 0.25;
+    // the narrow variants keep six waves per SIMD resident, the wide ones three
+    const int64_t wave_target = NT <= 2 ? 4096 : 2048;
     int kw = 1;
     while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
-           (longest_us / kw > 0.5 * (stream_us + gather_us) || groups * sw * kw < 2048)) kw *= 2;
+           (longest_us / kw > 0.5 * (stream_us + gather_us) || groups * sw * kw < wave_target)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \

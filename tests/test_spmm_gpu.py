@@ -17,7 +17,7 @@ torch = pytest.importorskip("torch")
 
 import paper_2408_11551_amd as S            # noqa: E402
 from oracle import smat_ref as R            # noqa: E402
-from workloads import random_csr, band_csr, occupancy_csr, OCCUPANCY_SPEC, make_config, Workload  # noqa: E402
+from workloads import random_csr, band_csr, occupancy_csr, column_entries_csr, OCCUPANCY_SPEC, make_config, Workload  # noqa: E402
 
 REL_BAR = 1e-2        # stated tolerance
 REL_TIGHT = 2e-4      # derived from fp32 accumulation, see module docstring
@@ -179,6 +179,37 @@ def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
         c_ref, _ = _oracle_c(oracle_c, w2)
         assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
         assert S.smat_last_kernel().endswith(suffix), S.smat_last_kernel()
+        m.close()
+
+
+# stored entries per occupied column, block row by block row: one entry each (kept by entry:
+# 40 entries in two packs); 68 entries in 64 columns (17/16 exactly: still by entry); 69 in 64
+# (by column, class 8); a sparse row; an empty one; 300 single entries (ten packs, the last one
+# short); a short last block row of single entries
+ENTRY_SPEC = [[1] * 40, [1] * 60 + [2] * 4, [1] * 59 + [2] * 5, [1] * 5 + [3], [], [1] * 300, [1] * 33]
+ENTRY_ROWS_OF_B = 40 + 68 + 64 + 6 + 0 + 300 + 33
+
+
+@pytest.mark.parametrize("N", [8, 40, 128, 272])
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_rows_kept_by_entry(N, dtype, oracle_c):
+    # integer values: the result is exact, an entry in the wrong slot or with the wrong row
+    # number cannot hide
+    w = column_entries_csr(ENTRY_SPEC, M=16 * 6 + 5, K=4000, N=N, seed=3 + N, dtype=dtype)
+    c_ref, _ = _oracle_c(oracle_c, w)
+    for reorder in (0, 2):
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=reorder)
+        c = m.spmm(_dev_b(w))
+        torch.cuda.synchronize()
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+        if reorder == 0:
+            info = S.smat_get_layout_info(m.handle)
+            assert info["n_columns"] == ENTRY_ROWS_OF_B
+            # 64 bytes per pack of entries; the row kept by column: two or three packs of 1 KiB
+            assert info["value_bytes"] - 64 * (2 + 3 + 10 + 2) - 256 in (2048, 3072)
+            perm = S.smat_export_perm(m.handle, w.M)
+            _, _, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+            assert np.array_equal(S.smat_export_device_vals(m.handle), v)
         m.close()
 
 

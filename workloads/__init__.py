@@ -12,6 +12,7 @@ from .configs import (  # noqa: F401
     band_csr,
     band_full_csr,
     occupancy_csr,
+    column_entries_csr,
     OCCUPANCY_SPEC,
     dense_from_bits,
     to_bits,

@@ -234,6 +234,30 @@ def occupancy_csr(spec, K: int, N: int, seed: int, dtype: str = F16, b_dist: str
                     to_bits(v, dtype), _dense_b(rng, K, N, b_dist, dtype))
 
 
+def column_entries_csr(spec, M: int, K: int, N: int, seed: int, dtype: str = F16, b_dist: str = "smallint",
+                       name: str | None = None) -> Workload:
+    """Matrix with a prescribed number of stored entries per occupied column.
+
+    spec[r] lists, for block row r (rows 16 r ... of the M rows; the last one may be short), the
+    number of stored entries of each of its occupied columns; the columns are drawn at random
+    from all of K, the rows of an entry at random inside the block row.  Values are small
+    integers.  Serves the tests of block rows that are nearly empty inside their blocks.
+    """
+    rng = np.random.default_rng([seed, 3100, len(spec), K])
+    keys = []
+    for r, counts in enumerate(spec):
+        height = min(16, M - 16 * r)
+        cols = rng.choice(K, size=len(counts), replace=False)
+        for c, n in zip(cols, counts):
+            rows = rng.choice(height, size=min(n, height), replace=False)
+            keys.extend((16 * r + rows).astype(np.int64) * K + int(c))
+    keys = np.unique(np.asarray(keys, dtype=np.int64))
+    row_ptr, col_idx = _csr_from_keys(keys, M, K)
+    v = rng.integers(1, 5, size=keys.size) * rng.choice([-1.0, 1.0], size=keys.size)
+    return Workload(name or f"column_entries_{M}x{K}", dtype, M, K, N, row_ptr, col_idx,
+                    to_bits(v, dtype), _dense_b(rng, K, N, b_dist, dtype))
+
+
 # --------------------------------------------------------------------------
 # the five benchmark configurations
 # --------------------------------------------------------------------------
