@@ -585,9 +585,12 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     // phase of the launch then gathers from twice as many columns of B.  Measured (three
     // workloads, N = 256 ... 1000, 16-bit and 8-bit): with full-width pieces of B (256 bytes per
     // row and slab) that start on cache lines, one slab per group is 2-14 % faster; with
-    // misaligned rows (N = 1000) or narrow pieces the pair is.
+    // misaligned rows (N = 1000) or narrow pieces the pair is, and so it is when the block values
+    // are too many to stay in the 256 MB Infinity Cache from one pass over the block rows to the
+    // next (712 MB: 683 against 744 us).
     const bool whole_lines = 16 * NT * ES >= 256 && (ldb * ES) % 128 == 0 && reinterpret_cast<uintptr_t>(B) % 128 == 0;
-    const int sw = (wave_slabs >= 2 && !whole_lines) ? 2 : 1;
+    const bool one_slab = whole_lines && static_cast<double>(d.stream_bytes) <= 128.0e6;
+    const int sw = (wave_slabs >= 2 && !one_slab) ? 2 : 1;
     const int64_t groups = d.n_order * ((wave_slabs + sw - 1) / sw);
     const double stream_us = (static_cast<double>(d.stream_bytes) + static_cast<double>(d.M) * N * 4.0 +
                               static_cast<double>(d.K) * N * ES) / 5.0e6;
