@@ -569,6 +569,45 @@ def test_row_and_column_reordering_gives_the_same_product(oracle_c):
         m.close()
 
 
+def test_rows_kept_by_entry_under_a_kept_column_order(oracle_c):
+    # columns in groups of sixteen that touch the same three block rows, one entry each, at
+    # scattered positions: the row clustering finds nothing, the column clustering brings every
+    # groups back together (a quarter fewer blocks), and every block row has one entry per column
+    rng = np.random.default_rng(77)
+    R_, G = 8, 400
+    M, K, N = 16 * R_, 16 * G, 24
+    place = rng.permutation(K)
+    keys = []
+    for g in range(G):
+        for br in rng.choice(R_, size=3, replace=False):
+            for c in place[16 * g:16 * g + 16]:
+                keys.append((16 * int(br) + int(rng.integers(16))) * K + int(c))
+    keys = np.unique(np.asarray(keys, dtype=np.int64))
+    rows = keys // K
+    row_ptr = np.zeros(M + 1, dtype=np.int64)
+    np.cumsum(np.bincount(rows, minlength=M), out=row_ptr[1:])
+    col_idx = (keys - rows * K).astype(np.int32)
+    from workloads import to_bits
+    vals = to_bits(rng.integers(1, 5, size=keys.size) * rng.choice([-1.0, 1.0], size=keys.size), "f16")
+    b = to_bits(rng.integers(-4, 5, size=K * N).astype(np.float64), "f16")
+    w = Workload("column_groups", "f16", M, K, N, row_ptr, col_idx, vals, b)
+    c_ref, _ = _oracle_c(oracle_c, w)
+    m = S.SmatMatrix(M, K, row_ptr, col_idx, vals, "f16", reorder=2)
+    c = m.spmm(_dev_b(w))
+    torch.cuda.synchronize()
+    assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+    q, n_rows = S.smat_export_col_perm(m.handle, K)
+    info = S.smat_get_info(m.handle)
+    assert info["n_blocks"] < n_rows and not np.array_equal(q, np.arange(K))          # the column order was kept
+    lay = S.smat_get_layout_info(m.handle)
+    assert lay["n_columns"] == keys.size and lay["value_bytes"] == 64 * lay["n_packs"]   # every block row by entry
+    perm = S.smat_export_perm(m.handle, M)
+    ci, av = R.permute_columns(M, K, row_ptr, col_idx, vals, q)
+    _, _, v = R.bcsr_from_csr(M, K, row_ptr, ci, av, perm)
+    assert np.array_equal(S.smat_export_device_vals(m.handle), v)
+    m.close()
+
+
 def test_hidden_blocks_full_size_with_column_reordering(oracle_c):
     # 32768^2: rows first, then the columns of P A clustered by the C oracle on their block-row
     # patterns; the library's column order, block count and product must be the oracle's
