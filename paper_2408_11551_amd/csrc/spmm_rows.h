@@ -402,9 +402,14 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
 #pragma unroll
     for (int c = 0; c < NCH; ++c) {
         col0[c] = n0 + c * NW + NT * i;
-        // a lane whose columns lie beyond N carries the out-of-range bit in its offset
-        // (N is a multiple of NT on this path, so a lane's columns are all in or all out)
-        w.lane_off[c] = col0[c] < N ? static_cast<uint32_t>(col0[c]) * ES : kOutOfRange;
+        // A lane whose columns lie beyond N carries the out-of-range bit in its offset (N is a
+        // multiple of NT on this path, so a lane's columns are all in or all out) -- unless one of
+        // the other three lanes of its quad is inside: the memory pipeline takes a quad of lanes
+        // with consecutive addresses at once and a quad with a hole lane by lane (N = 1, 2, 3, 6
+        // ran 1.6 x slower than N = 4, 8).  Such a lane reads what follows column N (the row's
+        // padding or the next row; past the end of B the range check returns zeros) into columns
+        // of the tile that are never stored.
+        w.lane_off[c] = col0[c] - NT * (i & 3) < N ? static_cast<uint32_t>(col0[c]) * ES : kOutOfRange;
     }
     w.ldb_bytes = ldb_bytes;
     w.no_row = K;
