@@ -171,7 +171,8 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
  * units), fp32 accumulation (int32 for SMAT_I8), rows of C in the ORIGINAL row order of A.
  *
  *   dB   DEVICE, K x N row-major, element type = dtype of the handle, leading
- *        dimension ldb >= N (in elements)
+ *        dimension ldb >= N (in elements); the padding between rows may be read (whatever it
+ *        holds never reaches C), nothing outside the ((K-1)*ldb + N) elements is touched
  *   dC   DEVICE, M x N row-major fp32 (int32 for SMAT_I8), leading dimension ldc >= N; every
  *        element of the M x N window is overwritten (rows of A without entries give 0)
  *   N    >= 1 (N = 0 is a no-op); any value, any alignment: wide vector loads
