@@ -44,6 +44,11 @@ namespace smat {
 // per step is fixed inside a loop on purpose: the in-order load counter then lets a multiply
 // wait for exactly the loads it needs while younger ones stay in flight.
 //
+// Entry rows (row class 3, pack_layout.h) run the L = 8 loop on packs of 32 stored entries:
+// the slot table names one B row per entry and carries the entries' row numbers, the pack's
+// values are the 32 entry values, and the left operand is built in registers -- lane (g, i)
+// keeps the value of entry (g, kk) where that entry's row number is i.
+//
 // All loads of the loop are buffer loads whose wave-uniform part of the address travels in
 // a scalar register, so a step spends vector ALU work only on what is per lane: one
 // multiply-add per B row address and one byte-permute per operand dword.
