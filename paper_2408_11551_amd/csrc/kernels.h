@@ -17,7 +17,8 @@ struct DeviceBcsr {
     const int32_t* work = nullptr;       // [4 * n_order]
     int64_t n_order = 0;                 // rows the per-row kernel is launched for
     const uint32_t* slots = nullptr;     // slot tables: per pack 4 groups x L entries (L by row class)
-    const void* vals = nullptr;          // block values: per pack 64 L elements of 2 bytes (fp16, bf16) or 1 byte
+    const void* vals = nullptr;          // block values: per pack 64 L elements of 2 bytes (fp16, bf16) or 1 byte;
+                                         // entry rows: the pack's 32 entry values at the start of a class-8 area
     // bind-time value scatter only
     const int32_t* pack_ptr = nullptr;   // [nbr+1] pack offsets per block row
     const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table, 32-byte units
