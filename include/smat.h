@@ -135,7 +135,8 @@ smat_status_t smat_device_bytes(const smat_handle_t *h, size_t *bytes);
  * instruction per 16 output columns multiplies a pack, and columns that hold
  * nothing are neither stored nor fetched from B.  Two full blocks make a pack.
  * A block row whose occupied columns hold hardly more than one stored entry each (at most
- * 17/16 on average) is kept by entry instead: packs of 32 stored entries, one value and one
+ * 9/8 on average; 3/2 when the values of the whole matrix kept by column would exceed 192 MB)
+ * is kept by entry instead: packs of 32 stored entries, one value and one
  * named row of B per entry, expanded into the instruction's operand in registers.
  *   n_packs       packs of the whole matrix
  *   value_bytes   bytes of block values over all packs

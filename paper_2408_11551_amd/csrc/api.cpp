@@ -6,6 +6,7 @@
 #include <hip/hip_runtime_api.h>
 
 #include <algorithm>
+#include <cstdlib>
 #include <cmath>
 #include <cstdio>
 #include <cstring>
@@ -221,28 +222,52 @@ void plan_packs(smat_handle& h)
     h.value_bytes = 0;
     h.b_rows = 0;
     h.row_b_rows.assign(nbr, 0);
-    uint64_t units = 0;
-    for (size_t br = 0; br < nbr; ++br) {
-        const int32_t s0 = b.row_ptr[br], s1 = b.row_ptr[br + 1];
-        int in_pack = 0, worst = 0, pack = -1;
-        int64_t occupied = 0;
-        for (int32_t s = s0; s < s1; ++s) {
+    // Cuts block row br into packs of occupied columns; with `record` the per-block records of
+    // the bind-time scatter are written.  Returns the number of packs.
+    struct Cut { int64_t packs, occupied; int worst; };
+    auto cut_row = [&](size_t br, bool record) {
+        int in_pack = 0, worst = 0;
+        int64_t pack = -1, occupied = 0;
+        for (int32_t s = b.row_ptr[br]; s < b.row_ptr[br + 1]; ++s) {
             const int cols = __builtin_popcount(b.col_mask[s]);
             if (pack < 0 || in_pack + cols > smat::kPackColumns) {
                 ++pack;
                 in_pack = 0;
-                h.pack_first.push_back(s);
+                if (record) h.pack_first.push_back(s);
             }
-            h.blk_pack[static_cast<size_t>(s)] = pack;
-            h.blk_meta[static_cast<size_t>(s)] = static_cast<uint32_t>(b.col_mask[s]) | static_cast<uint32_t>(in_pack) << 16;
+            if (record) {
+                h.blk_pack[static_cast<size_t>(s)] = static_cast<int32_t>(pack);
+                h.blk_meta[static_cast<size_t>(s)] = static_cast<uint32_t>(b.col_mask[s]) | static_cast<uint32_t>(in_pack) << 16;
+            }
             in_pack += cols;
             occupied += cols;
             worst = std::max(worst, in_pack);
         }
-        int cls = worst <= 8 ? 0 : (worst <= 16 ? 1 : 2);
-        int64_t n_packs = pack + 1;
+        return Cut{pack + 1, occupied, worst};
+    };
+    // How many stored entries per occupied column a block row of the densest class may have
+    // and still be kept by entry (pack_layout.h).  A row kept by entry gathers one row of B per
+    // entry instead of one per column but streams 2 bytes per entry instead of 32 per column.
+    // Measured on uniformly random matrices at N = 8 ... 256: while the values kept by column
+    // stay in the 256 MB Infinity Cache from launch to launch the two forms break even at about
+    // 1.15 entries per column (1.08: by entry up to 6 % faster, 1.33: 10-20 % slower); once they
+    // do not (290 MB), by entry is 11-22 % faster even at 1.33.
+    int64_t by_column_bytes = 0;
+    for (size_t br = 0; br < nbr; ++br) {
+        const Cut c = cut_row(br, false);
+        const int cls = c.worst <= 8 ? 0 : (c.worst <= 16 ? 1 : 2);
+        by_column_bytes += (c.packs * 64 * h.elem_bytes) << (cls + 1);
+    }
+    const int64_t entry_limit_16ths = by_column_bytes > 192000000 ? 24 : 18;      // 3/2 or 9/8
+    uint64_t units = 0;
+    for (size_t br = 0; br < nbr; ++br) {
+        const int32_t s1 = b.row_ptr[br + 1];
+        const Cut c = cut_row(br, true);
+        const int64_t occupied = c.occupied;
+        int cls = c.worst <= 8 ? 0 : (c.worst <= 16 ? 1 : 2);
+        int64_t n_packs = c.packs;
         const int64_t nnz = block_row_nnz(h, br);
-        if (cls == 2 && nnz * 16 <= occupied * 17) {
+        if (cls == 2 && nnz * 16 <= occupied * entry_limit_16ths) {
             // entry row: packs of 32 stored entries; the per-block records above are not used for it
             cls = smat::kEntryClass;
             const int64_t by_entry = (nnz + 31) / 32;

@@ -29,10 +29,10 @@
 // reads its group's L entries with one or two loads.
 //
 // Entry rows.  A block row whose occupied columns hold hardly more than one stored entry each
-// (nnz <= 17/16 of the occupied columns; graphs, uniformly random matrices) would store sixteen
-// values per column, fifteen of them zero.  Such a row is kept by ENTRY instead (row class 3):
-// its stored entries, row by row of the block row and by ascending column inside a row, are
-// cut into packs of 32; entry number j of a pack takes slot (j mod 4, j div 4) like an occupied
+// (nnz <= 9/8 of the occupied columns, or 3/2 for matrices too large to stay cached; graphs,
+// uniformly random matrices) would store sixteen values per column, fifteen of them zero.  Such
+// a row is kept by ENTRY instead (row class 3): its stored entries, by ascending column and, inside
+// a column, by row of the block row, are cut into packs of 32; entry number j of a pack takes slot (j mod 4, j div 4) like an occupied
 // column would.  The pack's slot table names the B row of every entry (a column with two
 // entries is named twice) and carries, in the otherwise unused top byte of entries 0..3 of
 // every lane group, the eight 4-bit row numbers of the group's entries (entry kk in bits

@@ -611,11 +611,14 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     const double piece = 16.0 * NT * ES < 64.0 ? 64.0 : 16.0 * NT * ES;
     const double gather_us = static_cast<double>(d.b_rows) * static_cast<double>(slabs) * piece / 20.0e6;
     const double longest_us = static_cast<double>(d.max_row_packs) * 0.25;
-    // the narrow variants keep six waves per SIMD resident, the wide ones three
-    const int64_t wave_target = NT <= 2 ? 4096 : 2048;
+    // the narrow variants (row loads of at most four bytes) keep six waves per SIMD resident,
+    // the wide ones three
+    const int64_t wave_target = NT * ES <= 4 ? 4096 : 2048;
+    // (a) is for rows that stand out; where all rows are about as long, (b) alone decides
+    const bool skewed = static_cast<double>(d.max_row_packs) > 2.0 * d.mean_row_packs;
     int kw = 1;
     while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
-           (longest_us / kw > 0.5 * (stream_us + gather_us) || groups * sw * kw < wave_target)) kw *= 2;
+           ((skewed && longest_us / kw > 0.5 * (stream_us + gather_us)) || groups * sw * kw < wave_target)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \

@@ -214,18 +214,19 @@ def test_default_options():
                                         "dense_tiles": 0}
 
 
-def _greedy_packs(w, perm):
+def _greedy_packs(w, perm, elem_bytes=2):
     """Packs per block row, written out from the definition: walk the stored blocks of a block
     row from the left and close a pack when the next block's occupied columns would not fit
-    32 any more; a row of the densest class whose stored entries number at most 17/16 of its
-    occupied columns is cut into packs of 32 entries instead and stores one value per entry.
+    32 any more; a row of the densest class whose stored entries number at most 9/8 of its
+    occupied columns (3/2 when the whole matrix kept by column would hold more than 192 MB of
+    values) is cut into packs of 32 entries instead and stores one value per entry.
     Returns (n_packs, value_bytes, slot_table_bytes, rows_of_B_named)."""
     inv = np.empty(w.M, dtype=np.int64)
     inv[perm] = np.arange(w.M)
     rows_new = inv[np.repeat(np.arange(w.M), np.diff(w.row_ptr))]
     key = np.unique((rows_new // 16) * w.K + w.col_idx)               # occupied (block row, column)
     nnz_of = np.bincount(rows_new // 16, minlength=-(-w.M // 16))
-    n_packs = value_bytes = slot_bytes = b_rows = 0
+    rows = []
     for br in range(-(-w.M // 16)):
         cols = key[(key >= br * w.K) & (key < (br + 1) * w.K)] - br * w.K
         per_block = np.unique(cols // 16, return_counts=True)[1]
@@ -236,20 +237,24 @@ def _greedy_packs(w, perm):
                 fill = 0
             fill += int(c)
             packs[-1] = fill
-        if not packs:
-            continue
-        L = 2 if max(packs) <= 8 else 4 if max(packs) <= 16 else 8
-        if L == 8 and int(nnz_of[br]) * 16 <= cols.size * 17:
-            n = -(-int(nnz_of[br]) // 32)
+        if packs:
+            L = 2 if max(packs) <= 8 else 4 if max(packs) <= 16 else 8
+            rows.append((len(packs), L, cols.size, int(nnz_of[br])))
+    by_column = sum(n * 64 * L * elem_bytes for n, L, _, _ in rows)
+    limit = 24 if by_column > 192_000_000 else 18
+    n_packs = value_bytes = slot_bytes = b_rows = 0
+    for n, L, occ, nnz in rows:
+        if L == 8 and nnz * 16 <= occ * limit:
+            n = -(-nnz // 32)
             n_packs += n
-            value_bytes += n * 64
+            value_bytes += n * 32 * elem_bytes
             slot_bytes += n * 128
-            b_rows += int(nnz_of[br])
+            b_rows += nnz
         else:
-            n_packs += len(packs)
-            value_bytes += len(packs) * 128 * L
-            slot_bytes += len(packs) * 16 * L
-            b_rows += cols.size
+            n_packs += n
+            value_bytes += n * 64 * L * elem_bytes
+            slot_bytes += n * 16 * L
+            b_rows += occ
     return n_packs, value_bytes, slot_bytes, b_rows
 
 

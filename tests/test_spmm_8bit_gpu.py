@@ -156,9 +156,9 @@ def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
 @pytest.mark.parametrize("dtype", DT8)
 def test_rows_kept_by_entry(N, dtype, oracle_c):
     # block rows with one stored entry per occupied column (kept by entry: 32 bytes of values per
-    # pack), at the 17/16 limit, just above it (kept by column), sparse, empty, long, and a short
+    # pack), at the 9/8 limit, just above it (kept by column), sparse, empty, long, and a short
     # last block row; small integers, exact in every one of the three types
-    spec = [[1] * 40, [1] * 60 + [2] * 4, [1] * 59 + [2] * 5, [1] * 5 + [3], [], [1] * 300, [1] * 33]
+    spec = [[1] * 40, [1] * 56 + [2] * 8, [1] * 55 + [2] * 9, [1] * 5 + [3], [], [1] * 300, [1] * 33]
     w = recast(column_entries_csr(spec, M=16 * 6 + 5, K=4000, N=N, seed=3 + N), dtype)
     c_ref, _ = _oracle_c(oracle_c, w)
     for reorder in (0, 2):
@@ -167,7 +167,7 @@ def test_rows_kept_by_entry(N, dtype, oracle_c):
         assert np.array_equal(got.astype(np.float64), c_ref)
         if reorder == 0:
             info = S.smat_get_layout_info(m.handle)
-            assert info["n_columns"] == 40 + 68 + 64 + 6 + 300 + 33
+            assert info["n_columns"] == 40 + 72 + 64 + 6 + 300 + 33
             assert info["value_bytes"] - 32 * (2 + 3 + 10 + 2) - 128 in (1024, 1536)
             perm = S.smat_export_perm(m.handle, w.M)
             _, _, v = R.bcsr_from_csr(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)

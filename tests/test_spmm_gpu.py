@@ -183,11 +183,11 @@ def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
 
 
 # stored entries per occupied column, block row by block row: one entry each (kept by entry:
-# 40 entries in two packs); 68 entries in 64 columns (17/16 exactly: still by entry); 69 in 64
+# 40 entries in two packs); 72 entries in 64 columns (9/8 exactly: still by entry); 73 in 64
 # (by column, class 8); a sparse row; an empty one; 300 single entries (ten packs, the last one
 # short); a short last block row of single entries
-ENTRY_SPEC = [[1] * 40, [1] * 60 + [2] * 4, [1] * 59 + [2] * 5, [1] * 5 + [3], [], [1] * 300, [1] * 33]
-ENTRY_ROWS_OF_B = 40 + 68 + 64 + 6 + 0 + 300 + 33
+ENTRY_SPEC = [[1] * 40, [1] * 56 + [2] * 8, [1] * 55 + [2] * 9, [1] * 5 + [3], [], [1] * 300, [1] * 33]
+ENTRY_ROWS_OF_B = 40 + 72 + 64 + 6 + 0 + 300 + 33
 
 
 @pytest.mark.parametrize("N", [8, 40, 128, 272])
