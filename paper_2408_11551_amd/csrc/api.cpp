@@ -38,14 +38,13 @@ struct smat_handle {
     std::vector<int32_t> order;          // [nbr] block rows in launch order
     // Row class: how many B-row loads per lane a pack of the block row needs at most (occupied
     // columns are dealt to four lane groups): 2, 4 or 8 -> class 0, 1, 2; class 3 is an entry row
-    // (pack_layout.h), laid out like class 2 with only the first 32 values of a pack in use.  The
-    // slot table of a row takes 16 * L bytes per pack and its values 128 * L bytes; slots_off counts 32-byte
-    // units of the former, which are 256-byte units of the latter.
-    // (Values: 128 * L bytes per pack for the 16-bit types, 64 * L for the 8-bit ones -- a unit
-    // is 128 values either way.)
+    // (pack_layout.h).  The slot table of a row takes 16 * L bytes per pack (128 for an entry row);
+    // slots_off counts 32-byte units of it.  Its values take 64 * L elements per pack (one 64-byte
+    // unit for an entry row); vals_off counts 64-byte units.
     std::vector<int8_t> row_class;       // [nbr]
     std::vector<uint32_t> slots_off;     // [nbr+1]
-    uint64_t slots_units = 0;
+    std::vector<uint32_t> vals_off;      // [nbr+1]
+    uint64_t slots_units = 0, vals_units = 0;
     int max_class = 0;
     int64_t value_bytes = 0;             // bytes of block values a launch over every block row reads
     int64_t b_rows = 0;                  // slots that name a row of B, over all packs
@@ -93,7 +92,7 @@ size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
 struct Layout {
-    size_t perm, work, work_rest, slots, vals, pack_ptr, slots_off, row_class, blk_ptr, blk_col, blk_pack, blk_meta;
+    size_t perm, work, work_rest, slots, vals, pack_ptr, vals_off, row_class, blk_ptr, blk_col, blk_pack, blk_meta;
     size_t csr_row_ptr, csr_col_idx, csr_vals;
     size_t t_super, t_ptr, t_cols, t_rows, t_base, t_vals, t_scratch, total;
 };
@@ -109,9 +108,9 @@ Layout make_layout(const smat_handle& h)
     l.work = take(nbr * 16);
     l.work_rest = take(nbr * 16);
     l.slots = take(static_cast<size_t>(h.slots_units) * 32);
-    l.vals = take(static_cast<size_t>(h.slots_units) * 128 * static_cast<size_t>(h.elem_bytes));
+    l.vals = take(static_cast<size_t>(h.vals_units) * 64);
     l.pack_ptr = take((nbr + 1) * sizeof(int32_t));
-    l.slots_off = take((nbr + 1) * sizeof(uint32_t));
+    l.vals_off = take((nbr + 1) * sizeof(uint32_t));
     l.row_class = take(nbr);
     l.blk_ptr = take((nbr + 1) * sizeof(int32_t));
     l.blk_col = take(n_e * sizeof(int32_t));
@@ -218,6 +217,7 @@ void plan_packs(smat_handle& h)
     h.blk_meta.assign(n_e, 0);
     h.row_class.assign(nbr, 0);
     h.slots_off.assign(nbr + 1, 0);
+    h.vals_off.assign(nbr + 1, 0);
     h.max_class = 0;
     h.value_bytes = 0;
     h.b_rows = 0;
@@ -259,7 +259,7 @@ void plan_packs(smat_handle& h)
         by_column_bytes += (c.packs * 64 * h.elem_bytes) << (cls + 1);
     }
     const int64_t entry_limit_16ths = by_column_bytes > 192000000 ? 24 : 18;      // 3/2 or 9/8
-    uint64_t units = 0;
+    uint64_t units = 0, vunits = 0;
     for (size_t br = 0; br < nbr; ++br) {
         const int32_t s1 = b.row_ptr[br + 1];
         const Cut c = cut_row(br, true);
@@ -285,13 +285,17 @@ void plan_packs(smat_handle& h)
         h.row_class[br] = static_cast<int8_t>(cls);
         h.max_class = std::max(h.max_class, cls);
         h.slots_off[br] = static_cast<uint32_t>(units);
+        h.vals_off[br] = static_cast<uint32_t>(vunits);
         units += static_cast<uint64_t>(n_packs) * static_cast<uint64_t>(smat::pack_units(cls));
-        if (units >= (uint64_t{1} << 32)) throw std::length_error("slot table too large");
+        vunits += static_cast<uint64_t>(n_packs) * static_cast<uint64_t>(smat::pack_value_units(cls, h.elem_bytes));
+        if (units >= (uint64_t{1} << 32) || vunits >= (uint64_t{1} << 32)) throw std::length_error("slot table too large");
         h.pack_ptr[br + 1] = static_cast<int32_t>(h.pack_first.size());
     }
     h.pack_first.push_back(static_cast<int32_t>(n_e));
     h.slots_off[nbr] = static_cast<uint32_t>(units);
+    h.vals_off[nbr] = static_cast<uint32_t>(vunits);
     h.slots_units = units;
+    h.vals_units = vunits;
     smat::work_order(h.pack_ptr, h.order);
 }
 
@@ -521,7 +525,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
             rec[0] = static_cast<int32_t>(br) | (static_cast<int32_t>(h->row_class[br]) << 28);
             rec[1] = h->pack_ptr[br + 1] - h->pack_ptr[br];
             rec[2] = static_cast<int32_t>(h->slots_off[br]);
-            rec[3] = 0;
+            rec[3] = static_cast<int32_t>(h->vals_off[br]);
             if (!h->row_dense[br]) work_rest.insert(work_rest.end(), rec, rec + 4);
         }
 
@@ -540,7 +544,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         if ((e = up(l.t_base, h->step_base.data(), h->step_base.size() * 4))) return hip_fail("copy tiles", e);
         if ((e = up(l.slots, slots.data(), slots.size() * 4))) return hip_fail("copy slot tables", e);
         if ((e = up(l.pack_ptr, h->pack_ptr.data(), h->pack_ptr.size() * 4))) return hip_fail("copy pack offsets", e);
-        if ((e = up(l.slots_off, h->slots_off.data(), h->slots_off.size() * 4))) return hip_fail("copy slot offsets", e);
+        if ((e = up(l.vals_off, h->vals_off.data(), h->vals_off.size() * 4))) return hip_fail("copy value offsets", e);
         if ((e = up(l.row_class, h->row_class.data(), h->row_class.size()))) return hip_fail("copy row classes", e);
         if ((e = up(l.blk_ptr, b.row_ptr.data(), b.row_ptr.size() * 4))) return hip_fail("copy block offsets", e);
         if ((e = up(l.blk_col, b.col_idx.data(), n_e * 4))) return hip_fail("copy block columns", e);
@@ -557,7 +561,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         d.slots = reinterpret_cast<const uint32_t*>(base + l.slots);
         d.vals = base + l.vals;
         d.pack_ptr = reinterpret_cast<const int32_t*>(base + l.pack_ptr);
-        d.slots_off = reinterpret_cast<const uint32_t*>(base + l.slots_off);
+        d.vals_off = reinterpret_cast<const uint32_t*>(base + l.vals_off);
         d.row_class = reinterpret_cast<const int8_t*>(base + l.row_class);
         d.blk_ptr = reinterpret_cast<const int32_t*>(base + l.blk_ptr);
         d.blk_col = reinterpret_cast<const int32_t*>(base + l.blk_col);
@@ -586,7 +590,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);
 
-        if ((e = smat::launch_fill_zero(base + l.vals, static_cast<size_t>(h->slots_units) * 8 * static_cast<size_t>(h->elem_bytes), s)))
+        if ((e = smat::launch_fill_zero(base + l.vals, static_cast<size_t>(h->vals_units) * 4, s)))
             return hip_fail("zero block values", e);
         if ((e = smat::launch_bcsr_fill(d, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.vals, h->elem_bytes, s)))
             return hip_fail("fill block values", e);
@@ -614,7 +618,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
     if (!vals) return fail(SMAT_ERR_INVALID_ARG, "vals is NULL");
     try {
         const size_t es = static_cast<size_t>(h->elem_bytes);
-        std::vector<uint8_t> raw(static_cast<size_t>(h->slots_units) * 128 * es);
+        std::vector<uint8_t> raw(static_cast<size_t>(h->vals_units) * 64);
         hipStream_t s = static_cast<hipStream_t>(stream);
         int e = static_cast<int>(hipMemcpyAsync(raw.data(), h->dev.vals, raw.size(), hipMemcpyDeviceToHost, s));
         if (e) return hip_fail("read block values", e);
@@ -632,7 +636,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
         for (size_t br = 0; br < static_cast<size_t>(h->bcsr.nbr); ++br) {
             if (h->row_class[br] == smat::kEntryClass) {
                 // entry row: the values of the stored entries in the order of the slot tables
-                const size_t src0 = static_cast<size_t>(h->slots_off[br]) * 128;
+                const size_t src0 = static_cast<size_t>(h->vals_off[br]) * (64 / es), stride = 64 / es;   // in elements
                 const int32_t* bc0 = h->bcsr.col_idx.data() + h->bcsr.row_ptr[br];
                 const int32_t* bc1 = h->bcsr.col_idx.data() + h->bcsr.row_ptr[br + 1];
                 entry_order(*h, br, items);
@@ -642,14 +646,14 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
                     const size_t rr = static_cast<size_t>(items[static_cast<size_t>(x)] & 15u);
                     const size_t sb = static_cast<size_t>(std::lower_bound(bc0, bc1, col >> 4) - h->bcsr.col_idx.data());
                     const int rank = static_cast<int>(x & 31);
-                    const size_t at = src0 + static_cast<size_t>(x >> 5) * 512 +
+                    const size_t at = src0 + static_cast<size_t>(x >> 5) * stride +
                                       static_cast<size_t>(smat::entry_elem_index(smat::slot_group(rank), smat::slot_pos(rank)));
                     put(sb * 256 + rr * 16 + static_cast<size_t>(col & 15), get(at));
                 }
                 // the rest of the last pack's 32 values must have stayed zero
                 for (int64_t x = e; x < (e + 31) / 32 * 32; ++x) {
                     const int rank = static_cast<int>(x & 31);
-                    if (get(src0 + static_cast<size_t>(x >> 5) * 512 +
+                    if (get(src0 + static_cast<size_t>(x >> 5) * stride +
                             static_cast<size_t>(smat::entry_elem_index(smat::slot_group(rank), smat::slot_pos(rank)))) != 0)
                         return fail(SMAT_ERR_HIP, "device block values: unoccupied slot is not zero");
                 }
@@ -657,7 +661,7 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
             }
             const int L = 2 << h->row_class[br];
             const int elems = smat::pack_elems(L);
-            size_t src = static_cast<size_t>(h->slots_off[br]) * 128;
+            size_t src = static_cast<size_t>(h->vals_off[br]) * (64 / es);
             for (int32_t pk = h->pack_ptr[br]; pk < h->pack_ptr[br + 1]; ++pk, src += static_cast<size_t>(elems)) {
                 uint8_t used[512];
                 std::memset(used, 0, sizeof(used));

@@ -13,15 +13,15 @@ struct DeviceBcsr {
     const int32_t* perm = nullptr;       // [nbr*16] new row -> old row, -1 beyond M
     // Launch table, one record of four words per workgroup of the per-row kernel, in launch
     // order: block row | row class << 28, number of packs, start of the row's slot table in
-    // 32-byte units (its values start at the same count of 128-element units), 0.
+    // 32-byte units, start of its values in 64-byte units.
     const int32_t* work = nullptr;       // [4 * n_order]
     int64_t n_order = 0;                 // rows the per-row kernel is launched for
     const uint32_t* slots = nullptr;     // slot tables: per pack 4 groups x L entries (L by row class)
     const void* vals = nullptr;          // block values: per pack 64 L elements of 2 bytes (fp16, bf16) or 1 byte;
-                                         // entry rows: the pack's 32 entry values at the start of a class-8 area
+                                         // entry rows: the pack's 32 entry values in one 64-byte unit
     // bind-time value scatter only
     const int32_t* pack_ptr = nullptr;   // [nbr+1] pack offsets per block row
-    const uint32_t* slots_off = nullptr; // [nbr+1] start of the row's slot table, 32-byte units
+    const uint32_t* vals_off = nullptr;  // [nbr+1] start of the row's values, 64-byte units
     const int8_t* row_class = nullptr;   // [nbr] 0..2: packs of occupied columns with L = 2, 4, 8; 3: entry row
     const int32_t* blk_ptr = nullptr;    // [nbr+1] stored-block offsets per block row
     const int32_t* blk_col = nullptr;    // [n_blocks] block column, ascending inside a block row

@@ -44,9 +44,8 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
     const int lo0 = d.blk_ptr[br], hi0 = d.blk_ptr[br + 1];
     const int npacks = d.pack_ptr[br + 1] - d.pack_ptr[br];
     if (npacks == 0) return;
-    const uint32_t unit0 = d.slots_off[br];
     const int cls = d.row_class[br];
-    T* row_vals = vals_out + static_cast<size_t>(unit0) * 128;
+    T* row_vals = vals_out + static_cast<size_t>(d.vals_off[br]) * (64 / sizeof(T));
     if (cls == kEntryClass) {
         // entry row: the entries of the block row are numbered by column, then by row; an
         // entry's number is the count of those before it, row by row of the block row
@@ -66,7 +65,7 @@ __global__ void bcsr_fill_kernel(DeviceBcsr d, const int64_t* __restrict__ csr_r
                 e += lo - first;
             }
             const int rank = static_cast<int>(e & 31);
-            row_vals[static_cast<size_t>(e >> 5) * pack_elems(8) + entry_elem_index(slot_group(rank), slot_pos(rank))] =
+            row_vals[static_cast<size_t>(e >> 5) * (64 / sizeof(T)) + entry_elem_index(slot_group(rank), slot_pos(rank))] =
                 static_cast<T>(csr_vals[p]);
         }
         return;

@@ -37,8 +37,8 @@
 // entries is named twice) and carries, in the otherwise unused top byte of entries 0..3 of
 // every lane group, the eight 4-bit row numbers of the group's entries (entry kk in bits
 // 4 kk .. 4 kk + 3 of the 32 bits formed by those four bytes, lowest entry's byte first).  Its
-// values are the 32 entry values alone, group by group (8 g + kk), at the start of the area a
-// class-8 pack would fill: 64 bytes instead of 1 KiB for the 16-bit types.  The kernel expands
+// values are the 32 entry values alone, group by group (8 g + kk), in one 64-byte unit (the
+// 8-bit types use half of it) instead of 1 KiB.  The kernel expands
 // them into the left operand in registers: lane (g, i) keeps value kk where the row number of
 // entry (g, kk) is i and puts zero elsewhere.
 //
@@ -64,6 +64,8 @@ constexpr int kEntryClass = 3;       // row class of an entry row (classes 0..2:
 SMAT_HD inline int pack_units(int cls) { return cls == kEntryClass ? 4 : 1 << cls; }
 // row loads per lane and pack
 SMAT_HD inline int class_loads(int cls) { return cls == kEntryClass ? 8 : 2 << cls; }
+// 64-byte units of block values one pack of a row of class cls takes (elements of es bytes)
+SMAT_HD inline int pack_value_units(int cls, int es) { return cls == kEntryClass ? 1 : (2 << cls) * es; }
 // index, inside the pack's value area, of the value of entry (g, kk) of an entry row
 SMAT_HD inline int entry_elem_index(int g, int kk) { return 8 * g + kk; }
 

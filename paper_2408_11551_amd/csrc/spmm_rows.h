@@ -131,6 +131,7 @@ struct PackOps {
     static_assert(!ENTRY || L == 8, "an entry pack has eight slots per lane group");
     static constexpr int AB = L * ES;                     // bytes of block values per lane and pack
     static constexpr int EB = 8 * ES;                     // entry rows: bytes of a lane group's eight entry values
+    static constexpr uint32_t PB = ENTRY ? 64u : 64u * AB; // bytes of block values per pack
     static constexpr int ND = LB >= 4 ? LB / 4 : 1;       // dwords per B row load
     static constexpr int NQ = (AB + 3) / 4;               // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
@@ -147,7 +148,7 @@ struct PackOps {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
         slots_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npacks * 16 * L, kRsrcFlags);
-        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(w.vals), 0, w.npacks * (64 * AB), kRsrcFlags);
+        vals_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(w.vals), 0, w.npacks * static_cast<int>(PB), kRsrcFlags);
         none_rsrc = __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(w.vals), 0, 0, kRsrcFlags);
     }
     // Loads of a pack are unconditional: a pack index past the row's end is clamped to the
@@ -172,13 +173,13 @@ struct PackOps {
     // zero); `live` false (a step past the wave's last pack) reads zeros instead
     __device__ __forceinline__ u32x4 load_a(int p, bool live) const
     {
-        // an entry pack lies where a pack of class 8 would and uses its first 32 values: the
-        // lane group's eight, to be expanded by multiply()
+        // an entry pack is its 32 entry values (one 64-byte unit): the lane group's eight, to be
+        // expanded by multiply()
         constexpr int W = ENTRY ? EB : AB;
         uint32_t r[4] = {0u, 0u, 0u, 0u};
         if (!live) BLoad<W>::ld(r, none_rsrc, vals_voff, 0u);
-        else if (stream) SLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
-        else BLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * (64u * AB));
+        else if (stream) SLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * PB);
+        else BLoad<W>::ld(r, vals_rsrc, vals_voff, clamp(p) * PB);
         return u32x4{r[0], r[1], r[2], r[3]};
     }
     // Occupied columns fill the slots group by group, so position kk is empty in every group
@@ -398,7 +399,7 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
 
     RowWalk w;
     w.slots = slots + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * 8;        // 32 bytes of slot table per unit
-    w.vals = static_cast<const uint8_t*>(vals) + static_cast<size_t>(static_cast<uint32_t>(rec[2])) * (128 * ES);     // 128 values per unit
+    w.vals = static_cast<const uint8_t*>(vals) + static_cast<size_t>(static_cast<uint32_t>(rec[3])) * 64;            // 64 bytes per unit
     w.npacks = n0 < N ? rec[1] : 0;
     w.ks = ks;
     w.g = g;
