@@ -62,7 +62,9 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
 // tile between barriers): a block row's values for a step are again 1 KiB (sixteen bytes per
 // lane, eight per sub-step), the panel of B is 64 rows of 128 bytes, staged in two 16-byte
 // pieces per thread, and the operand of MFMA x is byte x of the lane's eight rows of a sub-step.
-// A step thus moves the same bytes as a 16-bit one and a tile has half as many steps.
+// A step thus moves the same bytes as a 16-bit one and a tile has half as many steps.  int8 has
+// an instruction with k = 64 (16x16x64, sixteen bytes per lane and operand) that takes both
+// sub-steps at once at twice the rate; the floating-point 8-bit types have none of that shape.
 template <int DT, int RING, int KG>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
@@ -242,6 +244,33 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
                             for (int r = 0; r < RM; ++r)
                                 acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
                         }
+                    } else if constexpr (DT == kI8) {
+                        // int8: one MFMA 16x16x64 per output tile takes both sub-steps at once (the
+                        // lane's sixteen block values as they lie; operand dwords 2j, 2j+1 = byte x of
+                        // the eight rows of sub-step j)
+                        u32x2 R[KS][8];
+#pragma unroll
+                        for (int j = 0; j < KS; ++j)
+#pragma unroll
+                            for (int kk = 0; kk < 8; ++kk)
+                                R[j][kk] = reinterpret_cast<const u32x2*>(&panel[buf][32 * j + 8 * g + kk][8 * c])[i];
+                        __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+                        for (int x = 0; x < NT; ++x) {
+                            const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
+                            u32x4 b;
+#pragma unroll
+                            for (int j = 0; j < KS; ++j)
+#pragma unroll
+                                for (int qd = 0; qd < 2; ++qd) {
+                                    const uint32_t lo = __builtin_amdgcn_perm(R[j][4 * qd + 1][x >> 2], R[j][4 * qd][x >> 2], pair);
+                                    const uint32_t hi = __builtin_amdgcn_perm(R[j][4 * qd + 3][x >> 2], R[j][4 * qd + 2][x >> 2], pair);
+                                    b[2 * j + qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
+                                }
+#pragma unroll
+                            for (int r = 0; r < RM; ++r) acc[r][c * NT + x] = mfma_i8_k64(a[u][r], b, acc[r][c * NT + x]);
+                        }
+                        __builtin_amdgcn_sched_barrier(0);
                     } else {
                         // per sub-step, eight bytes per row: the lane's eight columns; operand dword =
                         // byte x of four rows.  The lane's block values of sub-step j are dwords 2j, 2j+1.

@@ -45,4 +45,11 @@ __device__ __forceinline__ typename Elem<DT>::Acc mfma_pack(u32x4 a, u32x4 b, ty
     }
 }
 
+// int8 with k = 64 (gfx950): a 16 x 64 piece of A' times 64 x 16 of B, sixteen bytes per lane and
+// operand; twice the rate of the k = 32 form.
+__device__ __forceinline__ i32x4 mfma_i8_k64(u32x4 a, u32x4 b, i32x4 c)
+{
+    return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b), c, 0, 0, 0);
+}
+
 }  // namespace smat
