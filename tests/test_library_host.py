@@ -172,6 +172,31 @@ def test_both_candidate_strategies_of_the_clustering_match_the_oracle(tau, oracl
             S.smat_destroy(h)
 
 
+@pytest.mark.parametrize("M,degree_scale,tau", [(16384, 1, 700), (16384, 1, 300), (8192, 12, 700)])
+def test_small_powerlaw_whole_permutation_matches_the_literal_oracle(M, degree_scale, tau, oracle_c):
+    """A matrix of the `powerlaw` workload's shape (the same truncated Zipf degrees, uniform columns,
+    shuffled rows) small enough for the literal row-by-row clustering to walk in full: the library's
+    WHOLE permutation, its block counts and its BCSR structure must equal the oracle's.  Degrees as in
+    the workload take the library's scan that visits a row only once its count could pass (short
+    patterns); degrees times twelve take the other one."""
+    w = make_config("powerlaw", M=M, degree_scale=degree_scale)
+    pp, pi = oracle_c.block_pattern_csr(w.M, w.K, w.row_ptr, w.col_idx)
+    nbc = w.K // 16
+    assert ((pi.size / M) ** 2 < 4 * nbc) == (degree_scale == 1)        # the two sides of the library's rule
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, tau_permille=tau)
+    try:
+        perm, n_e, n_id, used = oracle_c.choose_perm_c(w.M, pp, pi, nbc, tau)
+        assert not used and n_e < n_id                                   # the clustering does something here
+        assert np.array_equal(S.smat_export_perm(h, w.M), perm)
+        info = S.smat_get_info(h)
+        assert (info["n_blocks"], info["n_blocks_identity"], info["used_identity"]) == (n_e, n_id, used)
+        rp, ci, _ = R.bcsr_from_csr_fast(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, perm)
+        grp, gci, _ = S.smat_export_bcsr(h, with_vals=False)
+        assert np.array_equal(grp, rp) and np.array_equal(gci, ci)
+    finally:
+        S.smat_destroy(h)
+
+
 @pytest.mark.parametrize("tau", [300, 700, 950])
 def test_row_and_column_reordering_matches_oracle(tau):
     """reorder = 2: row permutation, column permutation, block counts, and the BCSR of P A Q (structure and

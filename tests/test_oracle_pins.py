@@ -379,6 +379,59 @@ def test_band_keeps_identity_and_guard_never_worse():
     assert used_identity and n_e == n_id
 
 
+def test_guard_of_the_c_twin_equals_python_and_keeps_identity_on_ties(oracle_c):
+    """choose_perm_c (the guard around the C clustering, which the full-size tests take their expected
+    permutation from) against smat_ref.choose_perm, and against what the guard means: the candidate is
+    kept only with STRICTLY fewer blocks.  By hand first: three rows with patterns {0}, {1}, {0} lie in
+    one block row; the clustering (any tau > 0) orders them 0, 2, 1, and both orders have 2 blocks -- a
+    tie with a candidate that is not the identity, so the identity must come back."""
+    pp = np.asarray([0, 1, 2, 3], np.int64)
+    pi = np.asarray([0, 1, 0], np.int32)
+    cand, _ = oracle_c.jaccard_reorder_c(3, pp, pi, 2, 700)
+    assert cand.tolist() == [0, 2, 1]
+    perm, n_e, n_id, used = oracle_c.choose_perm_c(3, pp, pi, 2, 700)
+    assert (perm.tolist(), n_e, n_id, used) == ([0, 1, 2], 2, 2, True)
+    # block height 1 on the same rows: identity {0},{1},{0} = 3 blocks, candidate also 3 (every row is a block row)
+    perm, n_e, n_id, used = oracle_c.choose_perm_c(3, pp, pi, 2, 700, h=1)
+    assert (perm.tolist(), n_e, n_id, used) == ([0, 1, 2], 3, 3, True)
+    # block height 2: identity {0,1},{0} = 3 blocks, candidate {0},{1} = 2: strictly fewer, kept
+    perm, n_e, n_id, used = oracle_c.choose_perm_c(3, pp, pi, 2, 700, h=2)
+    assert (perm.tolist(), n_e, n_id, used) == ([0, 2, 1], 2, 3, False)
+
+    ties = wins = losses = 0
+    for seed in range(240):
+        rng = np.random.default_rng([seed, 77])
+        M, K = int(rng.integers(3, 70)), 16 * int(rng.integers(1, 9))
+        h = int(rng.choice([2, 4, 16]))
+        w = random_csr(M, K, 1, float(rng.choice([0.01, 0.03, 0.1, 0.3])), seed=seed + 900)
+        pats = _patterns(w)
+        pp, pi = oracle_c.block_pattern_csr(M, K, w.row_ptr, w.col_idx)
+        for tau in (0, 300, 700, 1000):
+            want = R.choose_perm(pats, tau, h=h)
+            got = oracle_c.choose_perm_c(M, pp, pi, K // 16, tau, h=h)
+            assert np.array_equal(got[0], want[0]) and tuple(got[1:]) == tuple(want[1:]), (seed, tau, h)
+            cand = R.jaccard_reorder(pats, tau)
+            n_c, n_id = R.count_blocks(pats, cand, h), R.count_blocks(pats, np.arange(M), h)
+            moved = cand.tolist() != list(range(M))
+            ties += moved and n_c == n_id
+            wins += n_c < n_id
+            losses += n_c > n_id
+            # the guard, from the two counts alone
+            assert got[3] == (not n_c < n_id) and got[1] == min(n_c, n_id) and got[2] == n_id
+            if tau == 0:
+                assert got[3] and got[0].tolist() == list(range(M))
+        want = R.choose_perm(pats, 700, reorder=False, h=h)
+        got = oracle_c.choose_perm_c(M, pp, pi, K // 16, 700, reorder=False, h=h)
+        assert np.array_equal(got[0], want[0]) and tuple(got[1:]) == tuple(want[1:]) and got[3]
+    # all three outcomes of the comparison occur in the set, ties with a moved candidate among them
+    assert ties >= 50 and wins >= 50 and losses >= 5, (ties, wins, losses)
+    # a band keeps the identity (Preprocessing section)
+    w = band_csr(512, 64, 1, seed=3, p=0.3)
+    pp, pi = oracle_c.block_pattern_csr(512, 512, w.row_ptr, w.col_idx)
+    perm, n_e, n_id, used = oracle_c.choose_perm_c(512, pp, pi, 32, 700)
+    assert used and perm.tolist() == list(range(512)) and n_e == n_id
+
+
 # ------------------------------------------------------------------ O4 rows + columns
 def _planted_blocks(n_grid, p_block, seed):
     """Dense 16x16 blocks on a grid, rows and columns scrambled; returns the workload and the planted count."""

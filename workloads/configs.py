@@ -321,12 +321,14 @@ def zipf_truncated_pmf(alpha: float, target_mean: float):
         d_max += 1
 
 
-def _cfg_powerlaw(seed):
-    M = K = 262144
-    N = 64
-    rng = np.random.default_rng([seed, 4])
+def _cfg_powerlaw(seed, M=262144, N=64, degree_scale=1):
+    """M = 262144 is the benchmark configuration; smaller M (same degree law, same shuffling) gives
+    matrices of the same shape that a literal row-by-row clustering can still walk in full;
+    degree_scale multiplies every degree (longer patterns, same law)."""
+    K = M
+    rng = np.random.default_rng([seed, 4] if (M, degree_scale) == (262144, 1) else [seed, 4, M, degree_scale])
     dvals, pmf = zipf_truncated_pmf(1.2, 16.0)
-    deg = rng.choice(dvals, size=M, p=pmf)
+    deg = rng.choice(dvals, size=M, p=pmf) * degree_scale
     rows = np.repeat(np.arange(M, dtype=np.int64), deg)
     cols = rng.integers(0, K, size=rows.size, dtype=np.int64)
     shuffle = rng.permutation(M).astype(np.int64)      # "rows given in random order"
