@@ -1,16 +1,19 @@
 #!/usr/bin/env python3
 """Benchmark of the blocked SpMM hot path on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config uniform]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--config hidden_blocks]
 
 A step is one smat_spmm call (C = A.B on the preprocessed, device-resident matrix); the
 one-time preprocessing and the device bind are timed separately and reported in `config`,
 never folded into the step time (the paper also times the kernel only, section
-Methodology).  Prints ONE JSON line: useful TFLOP/s = 2*nnz*N / t, the roofline of the
-SpMM kernel (bytes one launch has to move between HBM and the chip / average launch
-duration from HIP events on the launch stream, against 8 TB/s; for a block-dense matrix
-the matrix-unit flops against 2.5 PFLOP/s instead) and the CPU oracle timed on the host
-cores.
+Methodology).  Prints ONE JSON line for the headline workload: useful TFLOP/s =
+2*nnz*N / t; the roofline of the dominant kernel (for a launch bound by memory: the bytes
+one launch has to move between HBM and the chip / its duration with L2 and Infinity Cache
+emptied before the launch, against 8 TB/s, the back-to-back figure beside it; for a
+block-dense matrix: the matrix-unit flops / its duration against 2.5 PFLOP/s); the same
+figures for every benchmark workload, measured in the same run (`all_configs`); what this
+GPU delivers for the access patterns the kernels are made of (`probes`); and the CPU
+oracle timed on the host cores (`cpu_baseline`).
 """
 from __future__ import annotations
 
@@ -24,7 +27,7 @@ import numpy as np
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_PEAK_TFLOPS = 2500.0      # dense fp16 / bf16 matrix peak
-MFMA_PEAK_TFLOPS_8BIT = 5000.0 # dense fp8 / int8 matrix peak (reached by the K=64/128 forms; the path uses K=32)
+MFMA_PEAK_TFLOPS_8BIT = 5000.0 # dense fp8 / int8 matrix peak (reached by the K=64/128 forms)
 
 WORKLOAD_TEXT = {
     "tiny": "tiny unstructured 1024x1024 1% fp16, B 1024x64",
@@ -34,12 +37,14 @@ WORKLOAD_TEXT = {
     "hidden_blocks": "hidden 16x16 blocks 32768x32768 2% fp16, B 32768x256",
     "pruned_weight": "pruned weight 4096x4096 90% sparse bf16, B 4096x2048",
 }
+# The headline is the largest workload that fits one GPU: most stored entries (21.3 M) and flops,
+# and the one the row reordering exists for.
+HEADLINE = "hidden_blocks"
 
-# HBM-side bytes per launch from the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs summarised under
-# profiles/ (FETCH_SIZE scaled by 2.0, WRITE_SIZE by 1.0 after a 256 MiB calibration copy), or None
-MEASURED_TRAFFIC_BYTES = {"uniform": 40.3e6, "banded": 139.0e6, "powerlaw": 576.7e6,
-                          "hidden_blocks": 377.4e6, "pruned_weight": 201.6e6,
-                          "uniform:e4m3": 25.6e6}
+# rocprofv3 summaries of the same command, one per workload: kernel trace, FETCH_SIZE / WRITE_SIZE
+# (HBM-side traffic) and matrix-unit counters.  The traffic figure of the line is read from there
+# by hand, never typed into this file: the line carries null and names the file.
+PROFILE_OF = {name: f"profiles/spmm_{name}.md" for name in WORKLOAD_TEXT if name != "tiny"}
 
 
 def algorithmic_bytes(layout, K, N, M, es=2):
@@ -94,12 +99,141 @@ def run_probes(S, torch, dev, stream):
     return out
 
 
+def gather_probe_for(probes, row_piece_bytes, b_bytes):
+    """The probe figure that matches a launch: pieces of 128 or 256 bytes per named row, table size next above B's."""
+    piece = 256 if row_piece_bytes >= 256 else 128
+    table = 4 if b_bytes <= 4.5e6 else (16 if b_bytes <= 17e6 else 32)
+    key = f"gather_{piece}B_rows_{table}MiB_table_gbs"
+    return key, probes[key]
+
+
+class Bound:
+    """One workload, preprocessed and bound to the device."""
+
+    def __init__(self, S, torch, dev, name, seed, dtype=None, reorder=1, dense_tiles=0):
+        from workloads import make_config, recast
+        w = make_config(name, seed=seed)
+        self.recast_to = dtype if dtype and dtype != w.dtype else None
+        if self.recast_to:
+            w = recast(w, self.recast_to, a_scale=127.0 if self.recast_to == "i8" else 1.0,
+                       b_scale=40.0 if self.recast_to == "i8" else 1.0)
+        self.S, self.torch, self.w, self.name = S, torch, w, name
+        self.es = w.b_bits.dtype.itemsize                   # bytes per value of A and B
+        t0 = time.perf_counter()
+        self.h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=dense_tiles, reorder=reorder)
+        self.t_pre = time.perf_counter() - t0
+        self.info = S.smat_get_info(self.h)
+        self.layout = S.smat_get_layout_info(self.h)
+        self.ws = torch.empty(S.smat_device_bytes(self.h), dtype=torch.uint8, device=dev)
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        S.smat_bind_device(self.h, self.ws)
+        self.t_bind = time.perf_counter() - t0
+        self.B = torch.from_numpy(w.b_bits.view(np.int16 if self.es == 2 else np.uint8).reshape(w.K, w.N)).to(dev)
+        self.C = torch.empty((w.M, w.N), dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=dev)
+
+    def step(self, stream):
+        self.S.smat_spmm(self.h, self.B, self.C, self.w.N, stream)
+
+    def close(self):
+        self.S.smat_destroy(self.h)
+        self.h = None
+        self.ws = self.B = self.C = None
+
+    # ---- figures that follow from the layout
+    def derived(self):
+        w, lay, info = self.w, self.layout, self.info
+        mfma_peak = MFMA_PEAK_TFLOPS if self.es == 2 else MFMA_PEAK_TFLOPS_8BIT
+        d = {
+            "useful_flop": 2.0 * w.nnz * w.N,
+            # one MFMA 16x16x32 per pack and 16 columns: on a block-dense matrix these are the flops of the stored blocks
+            "issued_flop": 2.0 * lay["n_packs"] * 16 * 32 * (-(-w.N // 16) * 16),
+            "bytes_alg": algorithmic_bytes(lay, w.K, w.N, w.M, self.es),
+            "bytes_bcsr": bcsr_format_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N, self.es),
+            "b_gather_bytes": lay["n_columns"] * w.N * self.es,
+            "mfma_peak": mfma_peak,
+        }
+        # the roofline that binds: time at peak for the flops against time at peak for the bytes
+        d["mfma_bound"] = d["issued_flop"] / (mfma_peak * 1e12) > d["bytes_alg"] / (HBM_PEAK_GBS * 1e9)
+        return d
+
+
+def timed_hot(torch, stream, bound, steps, warmup):
+    """W untimed steps, then exactly K steps between HIP events on the launch stream and a wall clock."""
+    for _ in range(warmup):
+        bound.step(stream)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(steps):
+        bound.step(stream)
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    return wall * 1e3 / steps, ev0.elapsed_time(ev1) / steps
+
+
+def timed_cold(torch, stream, bound, flush, reps):
+    """Each launch between its own events, after a read-only sweep over 1 GiB (more than L2 + the 256 MB
+    Infinity Cache) that evicts without leaving dirty lines: everything the launch reads comes from HBM."""
+    evs = []
+    for _ in range(reps):
+        flush.sum()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record(stream)
+        bound.step(stream)
+        b.record(stream)
+        evs.append((a, b))
+    torch.cuda.synchronize()
+    return np.array([a.elapsed_time(b) for a, b in evs])
+
+
+def roofline_of(bound, kernel_ms, cold_ms, kernel_name, probes):
+    """The roofline object of one workload.  HBM-bound: `frac` is the COLD figure (caches emptied before the
+    launch), the back-to-back one is `frac_hot`.  MFMA-bound: the hot figure (a block-dense matrix and its B
+    fit the Infinity Cache and an application multiplying repeatedly keeps them there); cold beside it."""
+    d = bound.derived()
+    w = bound.w
+    out = {"kernel": kernel_name, "traffic": None,
+           "traffic_note": f"HBM-side bytes per launch (rocprofv3 FETCH_SIZE / WRITE_SIZE) are in {PROFILE_OF.get(bound.name)}"}
+    if d["mfma_bound"]:
+        hot = d["issued_flop"] / (kernel_ms * 1e-3) / 1e12
+        out.update({"bound": "mfma", "achieved": hot, "peak": d["mfma_peak"], "unit": "TFLOP/s", "frac": hot / d["mfma_peak"],
+                    "flops_issued": d["issued_flop"], "cache": "hot"})
+        if cold_ms is not None:
+            out["frac_cold"] = d["issued_flop"] / (cold_ms * 1e-3) / 1e12 / d["mfma_peak"]
+        if probes:
+            out["frac_of_measured_mfma"] = hot / probes["mfma_16x16x32_f16_tflops"]
+    else:
+        hot = d["bytes_alg"] / (kernel_ms * 1e-3) / 1e9
+        t = cold_ms if cold_ms is not None else kernel_ms
+        ach = d["bytes_alg"] / (t * 1e-3) / 1e9
+        out.update({"bound": "hbm", "achieved": ach, "peak": HBM_PEAK_GBS, "unit": "GB/s", "frac": ach / HBM_PEAK_GBS,
+                    "cache": "cold" if cold_ms is not None else "hot",
+                    "achieved_hot": hot, "frac_hot": hot / HBM_PEAK_GBS, "bytes_algorithmic": d["bytes_alg"],
+                    # the same launch priced at the bytes of the paper's BCSR (516 per stored block), which the
+                    # device layout does not have to read: above 1 means faster than streaming that format allows
+                    "frac_at_bcsr_format_bytes": d["bytes_bcsr"] / (t * 1e-3) / 1e9 / HBM_PEAK_GBS})
+        if probes:
+            # what the launch pulls through the L1s (named rows of B + the stream of A) against the bare gather
+            # of rows of that size from a table of B's size, and against the measured streaming read
+            piece = min(256, w.N * bound.es)
+            key, rate = gather_probe_for(probes, piece, w.K * w.N * bound.es)
+            fills = d["b_gather_bytes"] + bound.layout["value_bytes"] + bound.layout["table_bytes"]
+            out["l1_fill_gbs"] = fills / (kernel_ms * 1e-3) / 1e9
+            out["gather_probe"] = key
+            out["frac_of_measured_gather"] = out["l1_fill_gbs"] / rate
+            out["frac_of_measured_hbm_read"] = ach / probes["read_2GiB_gbs"]
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
-    ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--config", default="uniform", choices=list(WORKLOAD_TEXT))
+    ap.add_argument("--steps", type=int, default=100)
+    ap.add_argument("--warmup", type=int, default=10)
+    ap.add_argument("--config", default=HEADLINE, choices=list(WORKLOAD_TEXT))
     ap.add_argument("--seed", type=int, default=0)
     ap.add_argument("--dtype", default=None, choices=["f16", "bf16", "e4m3", "e5m2", "i8"],
                     help="re-round the workload's values to another operand type of the matrix units "
@@ -108,16 +242,14 @@ def main():
     ap.add_argument("--dense-tiles", type=int, default=0, choices=[-1, 0, 1],
                     help="block-dense tile kernel: 0 automatic (default), 1 wherever it applies, -1 never")
     ap.add_argument("--no-cold", dest="cold", action="store_false",
-                    help="skip the second timing with the caches flushed between launches")
-    ap.add_argument("--probes", action="store_true",
-                    help="also time the library's probe kernels (streaming read, row gather, MFMA loop): what this GPU "
-                         "delivers for the access patterns the SpMM kernels are made of")
+                    help="skip the timings with the caches flushed before every launch")
+    ap.add_argument("--no-probes", dest="probes", action="store_false",
+                    help="skip the library's probe kernels (streaming read, row gather, MFMA loop)")
+    ap.add_argument("--no-all-configs", dest="all_configs", action="store_false",
+                    help="time the headline workload only (profiler runs)")
     ap.add_argument("--reorder", type=int, default=1, choices=[0, 1, 2],
                     help="reordering of the preprocessing: 1 Jaccard clustering of the rows with the identity guard (default), "
                          "0 none, 2 rows and then columns (the variant the paper set aside)")
-    ap.add_argument("--vendor", action="store_true",
-                    help="also time the vendor's CSR SpMM on the same matrix (hipSPARSE through torch.sparse.mm, "
-                         "fp32: it offers no 16-bit CSR SpMM here)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="run one 256 MiB device-to-device copy first (known traffic, scales the profiler's byte counters)")
     args = ap.parse_args()
@@ -128,31 +260,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py: no GPU visible; the SpMM path has no CPU fallback")
     import paper_2408_11551_amd as S
-    from workloads import make_config, recast
 
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    w = make_config(args.config, seed=args.seed)
-    recast_to = args.dtype if args.dtype and args.dtype != w.dtype else None
-    if recast_to:
-        w = recast(w, recast_to, a_scale=127.0 if recast_to == "i8" else 1.0, b_scale=40.0 if recast_to == "i8" else 1.0)
-    es = w.b_bits.dtype.itemsize                   # bytes per value of A and B
-    mfma_peak = MFMA_PEAK_TFLOPS if es == 2 else MFMA_PEAK_TFLOPS_8BIT
-
-    t0 = time.perf_counter()
-    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=args.dense_tiles,
-                          reorder=args.reorder)
-    t_pre = time.perf_counter() - t0
-    info = S.smat_get_info(h)
-    layout = S.smat_get_layout_info(h)
-    ws = torch.empty(S.smat_device_bytes(h), dtype=torch.uint8, device=dev)
-    torch.cuda.synchronize()
-    t0 = time.perf_counter()
-    S.smat_bind_device(h, ws)
-    t_bind = time.perf_counter() - t0
-
-    B = torch.from_numpy(w.b_bits.view(np.int16 if es == 2 else np.uint8).reshape(w.K, w.N)).to(dev)
-    C = torch.empty((w.M, w.N), dtype=torch.int32 if w.dtype == "i8" else torch.float32, device=dev)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
@@ -162,95 +272,64 @@ def main():
         torch.cuda.synchronize()
         del src, dst
 
-    for _ in range(args.warmup):
-        S.smat_spmm(h, B, C, w.N, stream)
-    torch.cuda.synchronize()
+    probes = run_probes(S, torch, dev, stream) if args.probes else None
+    flush = torch.zeros(1 << 28, dtype=torch.int32, device=dev) if args.cold else None
 
-    # timed region: exactly K steps; HIP events on the launch stream bracket the region
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    t0 = time.perf_counter()
-    ev0.record(stream)
-    for _ in range(args.steps):
-        S.smat_spmm(h, B, C, w.N, stream)
-    ev1.record(stream)
-    torch.cuda.synchronize()
-    wall = time.perf_counter() - t0
-    ev_ms = ev0.elapsed_time(ev1)
+    # ---------------------------------------------------------------- the headline workload
+    head = Bound(S, torch, dev, args.config, args.seed, args.dtype, args.reorder, args.dense_tiles)
+    w, info, layout, es = head.w, head.info, head.layout, head.es
+    ms_per_step, kernel_ms = timed_hot(torch, stream, head, args.steps, args.warmup)     # the timed region: exactly K steps
     kernel_name = S.smat_last_kernel()
-
-    ms_per_step = wall * 1e3 / args.steps
-    kernel_ms = ev_ms / args.steps                 # average launch duration on the stream
-    useful_flop = 2.0 * w.nnz * w.N
-    stored_flop = 2.0 * info["n_blocks"] * 256 * w.N
-    issued_flop = 2.0 * layout["n_packs"] * 16 * 32 * (-(-w.N // 16) * 16)      # one MFMA 16x16x32 per pack and 16 columns
-    bytes_alg = algorithmic_bytes(layout, w.K, w.N, w.M, es)
-    bytes_bcsr = bcsr_format_bytes(info["n_blocks"], info["n_block_rows"], w.M, w.K, w.N, es)
-    achieved_gbs = bytes_alg / (kernel_ms * 1e-3) / 1e9
-    issued_tflops = issued_flop / (kernel_ms * 1e-3) / 1e12
-    # the roofline that binds: time at peak for the bytes against time at peak for the flops
-    mfma_bound = issued_flop / (mfma_peak * 1e12) > bytes_alg / (HBM_PEAK_GBS * 1e9)
-    traffic = MEASURED_TRAFFIC_BYTES.get(f"{args.config}:{recast_to}" if recast_to else args.config)
+    d = head.derived()
 
     # the paper's protocol (Methodology): one warm-up, ten timed launches, each between its own events
     evs = []
     for _ in range(10):
         a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
         a.record(stream)
-        S.smat_spmm(h, B, C, w.N, stream)
+        head.step(stream)
         b.record(stream)
         evs.append((a, b))
     torch.cuda.synchronize()
     single = np.array([a.elapsed_time(b) for a, b in evs])
 
-    rp, _, _ = S.smat_export_bcsr(h, with_vals=False)
+    rp, _, _ = S.smat_export_bcsr(head.h, with_vals=False)
     per_row = np.diff(rp)
 
-    extra = {}
-    if args.cold:
-        # read-only sweep over 1 GiB (> L2 + 256 MB Infinity Cache): evicts without leaving dirty lines
-        flush = torch.zeros(1 << 28, dtype=torch.int32, device=dev)
-        evs = []
-        for _ in range(min(args.steps, 20)):
-            flush.sum()
-            a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-            a.record(stream)
-            S.smat_spmm(h, B, C, w.N, stream)
-            b.record(stream)
-            evs.append((a, b))
-        torch.cuda.synchronize()
-        cold = np.array([a.elapsed_time(b) for a, b in evs])
-        # same launch with L2 and Infinity Cache emptied first: everything comes from HBM
-        extra["cold"] = {"ms_mean": float(cold.mean()), "ms_min": float(cold.min()),
-                         "hbm_gbs": bytes_alg / (float(cold.mean()) * 1e-3) / 1e9,
-                         "hbm_frac": bytes_alg / (float(cold.mean()) * 1e-3) / 1e9 / HBM_PEAK_GBS,
-                         "useful_tflops": useful_flop / (float(cold.mean()) * 1e-3) / 1e12}
-        del flush
+    cold = timed_cold(torch, stream, head, flush, min(args.steps, 20)) if args.cold else None
+    cold_ms = float(cold.mean()) if cold is not None else None
+    roofline = roofline_of(head, kernel_ms, cold_ms, kernel_name, probes)
 
-    if args.probes:
-        extra["probes"] = run_probes(S, torch, dev, stream)
+    def summary(bound, ms_wall, k_ms, c_ms, name):
+        dd = bound.derived()
+        roof = roofline_of(bound, k_ms, c_ms, name, probes)
+        s = {"workload": WORKLOAD_TEXT[bound.name], "dtype": bound.w.dtype, "kernel": name,
+             "ms": k_ms, "cold_ms": c_ms, "useful_tflops": dd["useful_flop"] / (k_ms * 1e-3) / 1e12,
+             "bytes_algorithmic": dd["bytes_alg"], "flops_issued": dd["issued_flop"], "b_gather_bytes": dd["b_gather_bytes"],
+             "n_packs": bound.layout["n_packs"], "n_blocks": bound.info["n_blocks"], "nnz": bound.w.nnz,
+             "preprocess_s": bound.t_pre, "bind_s": bound.t_bind,
+             "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "cache") if k in roof}}
+        for k in ("frac_hot", "frac_cold", "frac_of_measured_gather", "frac_of_measured_mfma", "frac_of_measured_hbm_read", "l1_fill_gbs"):
+            if k in roof:
+                s["roofline"][k] = roof[k]
+        if dd["mfma_bound"]:
+            # block-dense: every block is stored, so these are the flops of the stored blocks
+            s["stored_block_tflops"] = dd["issued_flop"] / (k_ms * 1e-3) / 1e12
+        return s
 
-    if args.vendor:
-        # the same product through the vendor's sparse library; values widened to fp32 (exact)
-        from workloads import from_bits
-        a32 = torch.from_numpy(from_bits(w.a_bits, w.dtype)).to(torch.float32)
-        A_csr = torch.sparse_csr_tensor(torch.from_numpy(w.row_ptr), torch.from_numpy(w.col_idx.astype(np.int64)), a32,
-                                        size=(w.M, w.K), device=dev)
-        B32 = torch.from_numpy(from_bits(w.b_bits.reshape(-1), w.dtype).reshape(w.K, w.N)).to(torch.float32).to(dev)
-        for _ in range(3):
-            torch.sparse.mm(A_csr, B32)
-        torch.cuda.synchronize()
-        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        reps = 20
-        a.record(stream)
-        for _ in range(reps):
-            torch.sparse.mm(A_csr, B32)
-        b.record(stream)
-        torch.cuda.synchronize()
-        vendor_ms = a.elapsed_time(b) / reps
-        extra["vendor_csr_spmm"] = {"library": "hipSPARSE CSR SpMM through torch.sparse.mm", "dtype": "f32", "ms": vendor_ms,
-                                    "useful_tflops": useful_flop / (vendor_ms * 1e-3) / 1e12,
-                                    "times_slower_than_this_library": vendor_ms / kernel_ms}
-        del A_csr, B32
+    all_configs = None
+    if args.all_configs and not head.recast_to and args.reorder == 1 and args.dense_tiles == 0:
+        all_configs = {args.config: summary(head, ms_per_step, kernel_ms, cold_ms, kernel_name)}
+        for name in WORKLOAD_TEXT:
+            if name == args.config:
+                continue
+            other = Bound(S, torch, dev, name, args.seed)
+            _, k_ms = timed_hot(torch, stream, other, args.steps, args.warmup)
+            nm = S.smat_last_kernel()
+            c = timed_cold(torch, stream, other, flush, min(args.steps, 10)) if args.cold else None
+            all_configs[name] = summary(other, None, k_ms, float(c.mean()) if c is not None else None, nm)
+            other.close()
+            del other
 
     cpu = None
     if not args.no_cpu_baseline:
@@ -274,7 +353,7 @@ def main():
 
     out = {
         "metric": "SpMM useful TFLOP/s (2*nnz*N)",
-        "value": useful_flop / (ms_per_step * 1e-3) / 1e12,
+        "value": d["useful_flop"] / (ms_per_step * 1e-3) / 1e12,
         "unit": "TFLOP/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -286,7 +365,7 @@ def main():
         "dtype": w.dtype,
         "data": "synthetic",
         "config": {
-            "workload": WORKLOAD_TEXT[args.config] + (f", values re-rounded to {recast_to}" if recast_to else ""),
+            "workload": WORKLOAD_TEXT[args.config] + (f", values re-rounded to {head.recast_to}" if head.recast_to else ""),
             "name": args.config, "seed": args.seed,
             "M": w.M, "K": w.K, "N": w.N, "nnz": w.nnz,
             "n_blocks": info["n_blocks"], "n_blocks_identity": info["n_blocks_identity"],
@@ -295,34 +374,30 @@ def main():
             "blocks_per_row_std": float(per_row.std()) if per_row.size else 0.0,
             "blocks_per_row_max": int(per_row.max()) if per_row.size else 0,
             "reorder": args.reorder,
-            "preprocess_s": t_pre, "bind_s": t_bind, "kernel": kernel_name, "cache": "hot (back-to-back launches)",
+            "preprocess_s": head.t_pre, "bind_s": head.t_bind, "kernel": kernel_name,
+            "cache": "value and ms_per_step: back-to-back launches (hot); roofline.frac of an HBM-bound launch: caches emptied first (cold)",
         },
-        "stored_block_tflops": stored_flop / (kernel_ms * 1e-3) / 1e12,
         "kernel_ms_events": kernel_ms,
         "single_launch_ms": {"mean": float(single.mean()), "median": float(np.median(single)),
                              "min": float(single.min()), "cv": float(single.std() / single.mean())},
-        "roofline": ({
-            "bound": "mfma", "achieved": issued_tflops, "peak": mfma_peak, "unit": "TFLOP/s",
-            "frac": issued_tflops / mfma_peak, "traffic": traffic,
-            "flops_issued": issued_flop, "kernel": kernel_name,
-        } if mfma_bound else {
-            "bound": "hbm", "achieved": achieved_gbs, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved_gbs / HBM_PEAK_GBS,
-            "traffic": traffic,
-            "bytes_algorithmic": bytes_alg, "kernel": kernel_name,
-            # the same launch priced at the bytes of the paper's BCSR (516 per stored block), which the
-            # device layout does not have to read: above 1 means faster than streaming that format allows
-            "frac_at_bcsr_format_bytes": bytes_bcsr / (kernel_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
-        }),
+        "roofline": roofline,
         "layout": {"n_packs": layout["n_packs"], "value_bytes": layout["value_bytes"],
                    "table_bytes": layout["table_bytes"], "rows_of_b_named": layout["n_columns"],
-                   "b_gather_bytes": layout["n_columns"] * w.N * es,
-                   "mfma_issued_tflops": issued_tflops, "hbm_gbs": achieved_gbs,
-                   "bcsr_format_bytes": bytes_bcsr, "bcsr_format_gbs": bytes_bcsr / (kernel_ms * 1e-3) / 1e9},
+                   "b_gather_bytes": d["b_gather_bytes"],
+                   "mfma_issued_tflops": d["issued_flop"] / (kernel_ms * 1e-3) / 1e12,
+                   "bcsr_format_bytes": d["bytes_bcsr"], "bcsr_format_gbs": d["bytes_bcsr"] / (kernel_ms * 1e-3) / 1e9},
         "cpu_baseline": cpu,
     }
-    out.update(extra)
-    S.smat_destroy(h)
+    if cold is not None:
+        out["cold"] = {"ms_mean": cold_ms, "ms_min": float(cold.min()),
+                       "hbm_gbs": d["bytes_alg"] / (cold_ms * 1e-3) / 1e9,
+                       "hbm_frac": d["bytes_alg"] / (cold_ms * 1e-3) / 1e9 / HBM_PEAK_GBS,
+                       "useful_tflops": d["useful_flop"] / (cold_ms * 1e-3) / 1e12}
+    if probes:
+        out["probes"] = probes
+    if all_configs:
+        out["all_configs"] = all_configs
+    head.close()
     print(json.dumps(out))
 
 

@@ -73,9 +73,17 @@ typedef struct {
                            1 = take it wherever it applies, -1 = never.  It reads B in
                            whole block columns, so it is not used once reorder = 2 has
                            kept a column order, and 1 together with reorder = 2 is refused */
+    int concurrent_streams; /* 1..16: on how many streams smat_spmm calls on this handle may be in
+                           flight at the same time with the full choice of launches.  A launch
+                           with few block-dense tiles splits every tile over several workgroups
+                           and keeps their partial tiles in the workspace; each of the first
+                           concurrent_streams distinct streams the handle sees owns an area of
+                           32 MiB for them (part of smat_device_bytes when the matrix has
+                           block-dense parts).  Calls on further streams are still correct:
+                           they run such launches unsplit                                    */
 } smat_options_t;
 
-/* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0. */
+/* Default options: 16 x 16 blocks, reordering on, tau = 0.7, dense_tiles = 0, concurrent_streams = 2. */
 void smat_default_options(smat_options_t *opt);
 
 /*
@@ -107,6 +115,10 @@ smat_status_t smat_preprocess(int64_t M, int64_t K,
  * and whether the identity order was kept.  Any out pointer may be NULL. */
 smat_status_t smat_get_info(const smat_handle_t *h, int64_t *n_block_rows, int64_t *n_blocks,
                             int64_t *n_blocks_identity, int *used_identity);
+
+/* Shape and storage type the handle was made for (what smat_spmm expects of B and C): rows M
+ * and columns K of A, and the smat_dtype_t.  Any out pointer may be NULL. */
+smat_status_t smat_get_dims(const smat_handle_t *h, int64_t *M, int64_t *K, int *dtype);
 
 /* perm: HOST int32[M], perm[new_row] = old_row (A' = P A, Overview section). */
 smat_status_t smat_export_perm(const smat_handle_t *h, int32_t *perm);
@@ -180,9 +192,12 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
  *        are used when N, ldb and the base address allow it
  *   stream  hipStream_t; the call only enqueues work (no synchronisation)
  *
- * Calls on DIFFERENT handles may run concurrently on different streams.  Two calls on the
- * same handle must not overlap in time: the handle's workspace holds the scratch area in
- * which a launch with few block-dense tiles keeps partial tiles.
+ * Stream-ordered and re-entrant: calls on different handles, and calls on the SAME handle on
+ * different streams with different C, may be in flight at the same time (from one host thread
+ * or several).  The only state a call uses besides its arguments is an area of partial tiles
+ * for launches with few block-dense tiles; every stream has its own (option concurrent_streams),
+ * and a call on a stream without one runs such a launch unsplit -- the same product, summed in
+ * another order.  For a given handle, stream and arguments the result is bitwise reproducible.
  * Limits: the bytes of B that are addressed, ((K-1)*ldb + N) * bytes per value, must stay below 2 GiB;
  * ldb < 2^23; N <= 1048560.
  */
@@ -198,48 +213,6 @@ const char *smat_last_error(void);
 /* Name of the SpMM kernel variant chosen by the last smat_spmm on this thread
  * (for profiles and logs). */
 const char *smat_last_kernel(void);
-
-/*
- * Ablation (Performance model section, figure of measured against modelled time; Implementation
- * section, optimisation steps B and T): the same product from the canonical BCSR arrays of the
- * handle (rowPtr, col, 256 values per block) with fewer of the optimisations, to be timed next
- * to smat_spmm.  fp16 / bf16 handles only; one wavefront per (block row, 16 columns of C), no
- * pipelining.
- *   level 0   every block of the grid is visited and its presence looked up in a dense block
- *             map (no BCSR iteration), scalar multiply-adds in fp32
- *   level 1   "B": iteration over the stored blocks through rowPtr / col, scalar multiply-adds
- *   level 2   "B + T": the same iteration, one MFMA 16x16x16 per stored block
- * smat_ablation_bytes   bytes of DEVICE memory smat_ablation_bind needs (the block values in
- *                       canonical layout, 512 bytes per stored block, plus the block map when
- *                       the block grid has at most 2^26 entries; without it level 0 is refused)
- * smat_ablation_bind    fills that area (256-byte aligned, caller-owned, alive until
- *                       smat_destroy); the handle must already be bound with smat_bind_device,
- *                       whose rowPtr / col / permutation copies the kernels share; synchronises
- * smat_ablation_spmm    arguments as smat_spmm; only enqueues
- */
-smat_status_t smat_ablation_bytes(const smat_handle_t *h, size_t *bytes);
-smat_status_t smat_ablation_bind(smat_handle_t *h, void *dev_area, size_t bytes, void *stream);
-smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *dB, int64_t ldb,
-                                 void *dC, int64_t ldc, int64_t N, void *stream);
-
-/*
- * Probes: three kernels that measure what the device delivers for the access patterns the SpMM
- * kernels are made of (bench.py --probes times them and prints the rates next to the
- * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.
- *
- *   smat_probe_read    reads `bytes` (a multiple of 8 KiB is read) from dev_buf once, streaming
- *   smat_probe_gather  `waves` wavefronts each fetch `packs` groups of 32 rows named by dev_idx
- *                      (uint32[waves * packs * 32], row numbers into a table of row_bytes-byte
- *                      rows): 16 lanes x bytes_per_lane (8 or 16) bytes from the start of
- *                      every row, eight row loads in flight per lane as in the SpMM kernel
- *   smat_probe_mfma    workgroups x 4 waves issue iters x 16 MFMA 16x16x32 (fp16) each on
- *                      register operands: 2 * 16*16*32 flop per instruction and wave
- *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
- */
-smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
-smat_status_t smat_probe_gather(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
-                                int packs, int bytes_per_lane, void *dev_sink, void *stream);
-smat_status_t smat_probe_mfma(int workgroups, int iters, void *dev_sink, void *stream);
 
 #ifdef __cplusplus
 }

@@ -32,7 +32,8 @@ UNITS = {
     "probes": ("probes.hip", []),
     "ablation": ("ablation.hip", []),
 }
-HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h")]
+HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h"),
+           os.path.join("..", "..", "include", "smat_bench.h"), "mfma_types.h"]
 
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [

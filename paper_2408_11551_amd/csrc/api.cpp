@@ -2,6 +2,7 @@
 // host <-> device copies.  All arithmetic of the method lives in preprocess.cpp
 // (host, integers) and kernels.hip (device).
 #include "../../include/smat.h"
+#include "../../include/smat_bench.h"
 
 #include <hip/hip_runtime_api.h>
 
@@ -11,6 +12,7 @@
 #include <cstdio>
 #include <cstring>
 #include <memory>
+#include <mutex>
 #include <new>
 #include <stdexcept>
 #include <string>
@@ -66,6 +68,13 @@ struct smat_handle {
     // canonical BCSR on the device, for the ablation kernels (smat_ablation_bind)
     smat::CanonicalBcsr ablation;
     bool ablation_bound = false;
+    // Areas of partial tiles (split dense launches), one per stream: entry i names the stream
+    // that owns area i of the workspace.  A stream keeps its area for the life of the handle;
+    // calls on one stream are ordered, so an area is never used by two launches at once.
+    int n_scratch_areas = 2;             // option concurrent_streams
+    char* scratch_base = nullptr;        // first area (device), set by smat_bind_device
+    mutable std::mutex scratch_mutex;
+    mutable std::vector<const void*> scratch_owner;
 };
 
 namespace {
@@ -85,9 +94,10 @@ smat_status_t hip_fail(const char* what, int err)
 }
 
 constexpr size_t kAlign = 256;
-// Partial tiles of dense launches that split a tile's steps over several workgroups: at most
-// 512 partial tiles of 256 x 128 floats are ever in use.
-constexpr size_t kTileScratchBytes = size_t{512} * 256 * 128 * 4;
+// Partial tiles of dense launches that split a tile's steps over several workgroups: a launch
+// splits only while tiles x workgroups per tile stays within the 256 compute units, so at most
+// 256 partial tiles of 256 x 128 words are in use per launch.  One such area per stream.
+constexpr size_t kTileScratchBytes = size_t{256} * 256 * 128 * 4;
 size_t align_up(size_t x) { return (x + kAlign - 1) / kAlign * kAlign; }
 
 // Workspace layout, every section aligned to 256 bytes.
@@ -125,7 +135,7 @@ Layout make_layout(const smat_handle& h)
     l.t_rows = take(h.step_rows.size() * sizeof(uint32_t));
     l.t_base = take(h.step_base.size() * sizeof(uint32_t));
     l.t_vals = take(static_cast<size_t>(h.dense_slots) * 1024);
-    l.t_scratch = take(h.dense_super.empty() ? 0 : kTileScratchBytes);
+    l.t_scratch = take(h.dense_super.empty() ? 0 : kTileScratchBytes * static_cast<size_t>(h.n_scratch_areas));
     l.total = off ? off : kAlign;
     return l;
 }
@@ -336,6 +346,7 @@ void smat_default_options(smat_options_t* opt)
     opt->reorder = 1;
     opt->tau_permille = 700;
     opt->dense_tiles = 0;
+    opt->concurrent_streams = 2;
 }
 
 smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, const int32_t* col_idx,
@@ -357,6 +368,8 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
             return fail(SMAT_ERR_UNSUPPORTED, "the dense-tile kernel reads B in whole block columns: not with a column permutation");
         if (o.tau_permille < 0 || o.tau_permille > 1000) return fail(SMAT_ERR_INVALID_ARG, "tau_permille must be in 0..1000");
         if (o.dense_tiles < -1 || o.dense_tiles > 1) return fail(SMAT_ERR_INVALID_ARG, "dense_tiles must be -1, 0 or 1");
+        if (o.concurrent_streams == 0) o.concurrent_streams = 2;      // a zeroed options struct: the default
+        if (o.concurrent_streams < 1 || o.concurrent_streams > 16) return fail(SMAT_ERR_INVALID_ARG, "concurrent_streams must be in 1..16");
         if (M >= (int64_t{1} << 31) - 16 || K >= (int64_t{1} << 31) - 16)
             return fail(SMAT_ERR_UNSUPPORTED, "M and K must be below 2^31 - 16");
         if ((M + 15) / 16 >= (int64_t{1} << 28)) return fail(SMAT_ERR_UNSUPPORTED, "more than 2^28 block rows");
@@ -373,6 +386,7 @@ smat_status_t smat_preprocess(int64_t M, int64_t K, const int64_t* row_ptr, cons
         h->dtype = dtype;
         h->elem_bytes = narrow ? 1 : 2;
         h->dense_mode = o.dense_tiles;
+        h->n_scratch_areas = o.concurrent_streams;
         h->csr.M = M;
         h->csr.K = K;
         h->csr.row_ptr.assign(row_ptr, row_ptr + M + 1);
@@ -409,6 +423,15 @@ smat_status_t smat_get_info(const smat_handle_t* h, int64_t* n_block_rows, int64
     if (n_blocks) *n_blocks = h->bcsr.n_blocks;
     if (n_blocks_identity) *n_blocks_identity = h->bcsr.n_blocks_identity;
     if (used_identity) *used_identity = h->bcsr.used_identity ? 1 : 0;
+    return SMAT_OK;
+}
+
+smat_status_t smat_get_dims(const smat_handle_t* h, int64_t* M, int64_t* K, int* dtype)
+{
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (M) *M = h->csr.M;
+    if (K) *K = h->csr.K;
+    if (dtype) *dtype = static_cast<int>(h->dtype);
     return SMAT_OK;
 }
 
@@ -581,8 +604,8 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.step_rows = reinterpret_cast<const uint32_t*>(base + l.t_rows);
         tiles.step_base = reinterpret_cast<const uint32_t*>(base + l.t_base);
         tiles.vals = base + l.t_vals;
-        tiles.scratch = h->dense_super.empty() ? nullptr : base + l.t_scratch;
-        tiles.scratch_bytes = h->dense_super.empty() ? 0 : kTileScratchBytes;
+        tiles.scratch = nullptr;           // a call takes the area of its stream
+        tiles.scratch_bytes = 0;
         tiles.n = static_cast<int32_t>(h->dense_super.size());
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
         tiles.cols_per_step = h->elem_bytes == 1 ? 4 : 2;
@@ -602,6 +625,11 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         h->dev = d;
         h->dev_rest = d_rest;
         h->tiles = tiles;
+        {
+            std::lock_guard<std::mutex> lock(h->scratch_mutex);
+            h->scratch_base = h->dense_super.empty() ? nullptr : base + l.t_scratch;
+            h->scratch_owner.clear();
+        }
         h->bound = true;
         return SMAT_OK;
     } catch (const std::bad_alloc&) {
@@ -690,20 +718,27 @@ smat_status_t smat_export_device_vals(const smat_handle_t* h, void* vals, void* 
     }
 }
 
-smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
-                        int64_t N, void* stream)
+}  // extern "C"
+
+namespace {
+
+// The area of partial tiles that belongs to `stream`: the one it already owns, else the first
+// free one, else none.
+char* scratch_area_of(const smat_handle* h, const void* stream)
 {
-    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
-    if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "smat_spmm called before smat_bind_device");
-    if (N < 0) return fail(SMAT_ERR_INVALID_ARG, "N is negative");
-    if (N == 0 || h->csr.M == 0) return SMAT_OK;
-    if (!dC || (!dB && h->csr.K > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL matrix pointer");
-    if (ldb < N || ldc < N) return fail(SMAT_ERR_INVALID_ARG, "leading dimension smaller than N");
-    if (N > 16 * 65535) return fail(SMAT_ERR_UNSUPPORTED, "N above 1048560");
-    const int64_t K = h->csr.K;
-    if (K > 0 && ((K - 1) * ldb + N) * h->elem_bytes >= (int64_t{1} << 31))
-        return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
-    if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
+    if (!h->scratch_base) return nullptr;
+    std::lock_guard<std::mutex> lock(h->scratch_mutex);
+    for (size_t i = 0; i < h->scratch_owner.size(); ++i)
+        if (h->scratch_owner[i] == stream) return h->scratch_base + i * kTileScratchBytes;
+    if (static_cast<int>(h->scratch_owner.size()) >= h->n_scratch_areas) return nullptr;
+    h->scratch_owner.push_back(stream);
+    return h->scratch_base + (h->scratch_owner.size() - 1) * kTileScratchBytes;
+}
+
+// smat_spmm with the area for partial tiles given by the caller of this function.
+smat_status_t spmm_with_scratch(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
+                                int64_t N, void* stream, void* scratch, size_t scratch_bytes)
+{
     // The dense path fetches B in 16-byte pieces (8 columns, or 16 for the 8-bit types) that must lie
     // wholly inside or outside the N columns; otherwise every block row goes through the per-row kernel.  It also has to pay: a tile walks its steps at about
     // 0.7 us each with little to overlap them, so few tiles leave most of the chip idle, while
@@ -713,12 +748,15 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     const int piece = 16 / h->elem_bytes;           // columns of B in 16 bytes
     bool use_tiles = h->tiles.n > 0 && N % piece == 0 && ldb % piece == 0 && reinterpret_cast<uintptr_t>(dB) % 16 == 0;
     if (h->dense_mode < 0) use_tiles = false;
+    smat::DenseTiles tiles = h->tiles;
+    tiles.scratch = scratch;
+    tiles.scratch_bytes = scratch ? scratch_bytes : 0;
     if (use_tiles && h->dense_mode == 0) {
-        const double tiles = static_cast<double>(h->tiles.n) * static_cast<double>((N + 127) / 128);
-        const int ks = smat::dense_split(h->tiles, N);
+        const double n_tiles = static_cast<double>(tiles.n) * static_cast<double>((N + 127) / 128);
+        const int ks = smat::dense_split(tiles, N);
         const double step_us = h->elem_bytes == 1 ? 1.0 : 0.7;     // an 8-bit step covers twice the block columns
-        double t_tiles = std::ceil(tiles * ks / 256.0) * (h->tiles.mean_steps / ks * step_us + 4.0);
-        if (ks > 1) t_tiles += 3.0 + tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
+        double t_tiles = std::ceil(n_tiles * ks / 256.0) * (tiles.mean_steps / ks * step_us + 4.0);
+        if (ks > 1) t_tiles += 3.0 + n_tiles * (ks + 1) * 256.0 * 128.0 * 4.0 * 2.0 / 4.0e6;     // partial tiles out and in again
         // (two bytes per value also for the 8-bit types: on block-dense rows the per-row kernel did not
         // get faster with them -- 35.6 us against 35 on the band workload -- while the tile kernel did)
         const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
@@ -731,7 +769,7 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
         if (h->dev_rest.n_order > 0)
             e = smat::launch_spmm(h->dev_rest, h->dtype, dB, ldb, dC, ldc, N, stream, &variant);
         const char* dense_variant = "";
-        if (!e) e = smat::launch_spmm_dense(h->dev, h->tiles, h->dtype, dB, ldb, dC, ldc, N, stream, &dense_variant);
+        if (!e) e = smat::launch_spmm_dense(h->dev, tiles, h->dtype, dB, ldb, dC, ldc, N, stream, &dense_variant);
         name = std::string(dense_variant) + (h->dev_rest.n_order > 0 ? std::string("+") + variant : std::string());
         g_kernel = name.c_str();
     } else {
@@ -740,6 +778,38 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     }
     if (e) return hip_fail("launch spmm", e);
     return SMAT_OK;
+}
+
+// Argument checks of smat_spmm; SMAT_OK with *nothing_to_do set for an empty product.
+smat_status_t check_spmm_args(const smat_handle_t* h, const void* dB, int64_t ldb, const void* dC, int64_t ldc,
+                              int64_t N, bool* nothing_to_do)
+{
+    *nothing_to_do = false;
+    if (!h) return fail(SMAT_ERR_INVALID_ARG, "handle is NULL");
+    if (!h->bound) return fail(SMAT_ERR_NOT_BOUND, "smat_spmm called before smat_bind_device");
+    if (N < 0) return fail(SMAT_ERR_INVALID_ARG, "N is negative");
+    if (N == 0 || h->csr.M == 0) { *nothing_to_do = true; return SMAT_OK; }
+    if (!dC || (!dB && h->csr.K > 0)) return fail(SMAT_ERR_INVALID_ARG, "NULL matrix pointer");
+    if (ldb < N || ldc < N) return fail(SMAT_ERR_INVALID_ARG, "leading dimension smaller than N");
+    if (N > 16 * 65535) return fail(SMAT_ERR_UNSUPPORTED, "N above 1048560");
+    const int64_t K = h->csr.K;
+    if (K > 0 && ((K - 1) * ldb + N) * h->elem_bytes >= (int64_t{1} << 31))
+        return fail(SMAT_ERR_UNSUPPORTED, "B larger than 2 GiB is not supported");
+    if (ldb >= (int64_t{1} << 23)) return fail(SMAT_ERR_UNSUPPORTED, "ldb must be below 2^23");
+    return SMAT_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
+                        int64_t N, void* stream)
+{
+    bool nothing = false;
+    const smat_status_t st = check_spmm_args(h, dB, ldb, dC, ldc, N, &nothing);
+    if (st != SMAT_OK || nothing) return st;
+    return spmm_with_scratch(h, dB, ldb, dC, ldc, N, stream, scratch_area_of(h, stream), kTileScratchBytes);
 }
 
 // Largest block grid for which the ablation keeps a dense block map (level 0).

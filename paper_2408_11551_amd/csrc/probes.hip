@@ -6,7 +6,7 @@
 
 #include <cstdint>
 
-#include "../../include/smat.h"
+#include "../../include/smat_bench.h"
 
 namespace {
 

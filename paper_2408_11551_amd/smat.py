@@ -45,7 +45,8 @@ class SmatError(RuntimeError):
 
 class _Options(ctypes.Structure):
     _fields_ = [("block_h", ctypes.c_int), ("block_w", ctypes.c_int),
-                ("reorder", ctypes.c_int), ("tau_permille", ctypes.c_int), ("dense_tiles", ctypes.c_int)]
+                ("reorder", ctypes.c_int), ("tau_permille", ctypes.c_int), ("dense_tiles", ctypes.c_int),
+                ("concurrent_streams", ctypes.c_int)]
 
 
 def lib_path() -> str:
@@ -76,6 +77,8 @@ def _load():
     lib.smat_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_get_layout_info.restype = ctypes.c_int
     lib.smat_get_layout_info.argtypes = [vp] + [ctypes.POINTER(i64)] * 4
+    lib.smat_get_dims.restype = ctypes.c_int
+    lib.smat_get_dims.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(ctypes.c_int)]
     lib.smat_get_info.restype = ctypes.c_int
     lib.smat_get_info.argtypes = [vp, ctypes.POINTER(i64), ctypes.POINTER(i64), ctypes.POINTER(i64),
                                   ctypes.POINTER(ctypes.c_int)]
@@ -142,11 +145,11 @@ def smat_default_options() -> dict:
     o = _Options()
     _lib.smat_default_options(ctypes.byref(o))
     return {"block_h": o.block_h, "block_w": o.block_w, "reorder": o.reorder, "tau_permille": o.tau_permille,
-            "dense_tiles": o.dense_tiles}
+            "dense_tiles": o.dense_tiles, "concurrent_streams": o.concurrent_streams}
 
 
 def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
-                    block_h=16, block_w=16, dense_tiles=0) -> int:
+                    block_h=16, block_w=16, dense_tiles=0, concurrent_streams=2) -> int:
     """row_ptr int64[M+1], col_idx int32[nnz], vals_bits uint16[nnz] (uint8 for the 8-bit types)
     (HOST) -> opaque handle."""
     rp, rp_p = _host(row_ptr, np.int64)
@@ -160,10 +163,51 @@ def smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_
     nnz = int(rp[-1]) if rp.size else 0
     if ci.size < nnz or vb.size < nnz:
         raise ValueError("col_idx / vals shorter than row_ptr[M]")
-    opt = _Options(block_h, block_w, reorder, tau_permille, dense_tiles)
+    opt = _Options(block_h, block_w, reorder, tau_permille, dense_tiles, concurrent_streams)
     out = ctypes.c_void_p()
     _check(_lib.smat_preprocess(M, K, rp_p, ci_p, vb_p, _dtype_code(dtype), ctypes.byref(opt), ctypes.byref(out)))
     return out.value
+
+
+def smat_get_dims(h) -> dict:
+    """Shape and storage type the handle was made for: {"M", "K", "dtype" (a smat_dtype_t number), "elem_bytes"}."""
+    M, K, dt = ctypes.c_int64(), ctypes.c_int64(), ctypes.c_int()
+    _check(_lib.smat_get_dims(h, ctypes.byref(M), ctypes.byref(K), ctypes.byref(dt)))
+    return {"M": M.value, "K": K.value, "dtype": dt.value, "elem_bytes": 1 if dt.value in (SMAT_E4M3, SMAT_E5M2, SMAT_I8) else 2}
+
+
+def _check_device_operands(h, B, C, N, elem_sizes=(1, 2)):
+    """Raises ValueError unless B and C are device tensors on one device that hold what the kernels
+    will address for this handle: K rows of N elements of the handle's size in B, M rows of N 4-byte
+    elements in C.  The library bounds its loads and stores by M, K, N and the leading dimensions it
+    is given, not by the tensors, so this is checked here, before any launch.  Returns (N, ldb, ldc)."""
+    dims = smat_get_dims(h)
+    if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
+        raise ValueError("B and C must be 2-D with unit column stride")
+    if dims["elem_bytes"] not in elem_sizes:
+        raise ValueError("this call does not take the handle's storage type")
+    if B.element_size() != dims["elem_bytes"]:
+        raise ValueError(f"B must hold {dims['elem_bytes']}-byte elements for this handle, not {B.element_size()}-byte ones")
+    if C.element_size() != 4:
+        raise ValueError("C must hold 4-byte elements")
+    if N is None:
+        N = B.shape[1]
+    N = int(N)
+    if N > B.shape[1] or N > C.shape[1]:            # a negative N is the library's to refuse
+        raise ValueError(f"N = {N} exceeds the columns of B ({B.shape[1]}) or C ({C.shape[1]})")
+    if B.shape[0] < dims["K"]:
+        raise ValueError(f"B has {B.shape[0]} rows, the matrix has K = {dims['K']} columns")
+    if C.shape[0] < dims["M"]:
+        raise ValueError(f"C has {C.shape[0]} rows, the matrix has M = {dims['M']} rows")
+    ldb = B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N)
+    ldc = C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N)
+    if (dims["K"] > 1 and ldb < N) or (dims["M"] > 1 and ldc < N):
+        raise ValueError("rows of B or C overlap (row stride below N)")
+    if not (B.is_cuda and C.is_cuda):
+        raise ValueError("B and C must be device tensors")
+    if B.device != C.device:
+        raise ValueError(f"B is on {B.device} and C on {C.device}")
+    return N, ldb, ldc
 
 
 def smat_get_info(h) -> dict:
@@ -194,12 +238,16 @@ def smat_export_col_perm(h, K):
     return q, n_rows.value
 
 
-def smat_export_bcsr(h, with_vals=True, dtype="f16"):
-    """dtype: the handle's dtype (decides the element size of vals)."""
+def smat_export_bcsr(h, with_vals=True, dtype=None):
+    """vals come back as uint16 or uint8 bit patterns by the HANDLE's storage type; dtype, if given,
+    must name a type of that size (kept for callers that state it)."""
     info = smat_get_info(h)
+    elem = np.uint8 if smat_get_dims(h)["elem_bytes"] == 1 else np.uint16
+    if dtype is not None and np.dtype(_elem_type(dtype)) != np.dtype(elem):
+        raise ValueError(f"dtype {dtype!r} does not have the element size of the handle's storage type")
     row_ptr = np.empty(info["n_block_rows"] + 1, dtype=np.int32)
     col_idx = np.empty(info["n_blocks"], dtype=np.int32)
-    vals = np.empty((info["n_blocks"], 16, 16), dtype=_elem_type(dtype)) if with_vals else None
+    vals = np.empty((info["n_blocks"], 16, 16), dtype=elem) if with_vals else None
     _check(_lib.smat_export_bcsr(h, row_ptr.ctypes.data_as(ctypes.c_void_p),
                                  col_idx.ctypes.data_as(ctypes.c_void_p),
                                  vals.ctypes.data_as(ctypes.c_void_p) if with_vals else None))
@@ -218,9 +266,12 @@ def smat_bind_device(h, workspace, stream=None):
                                  workspace.numel() * workspace.element_size(), _stream_ptr(stream)))
 
 
-def smat_export_device_vals(h, stream=None, dtype="f16") -> np.ndarray:
+def smat_export_device_vals(h, stream=None, dtype=None) -> np.ndarray:
     n_e = smat_get_info(h)["n_blocks"]
-    vals = np.empty((n_e, 16, 16), dtype=_elem_type(dtype))
+    elem = np.uint8 if smat_get_dims(h)["elem_bytes"] == 1 else np.uint16
+    if dtype is not None and np.dtype(_elem_type(dtype)) != np.dtype(elem):
+        raise ValueError(f"dtype {dtype!r} does not have the element size of the handle's storage type")
+    vals = np.empty((n_e, 16, 16), dtype=elem)
     _check(_lib.smat_export_device_vals(h, vals.ctypes.data_as(ctypes.c_void_p), _stream_ptr(stream)))
     return vals
 
@@ -228,16 +279,11 @@ def smat_export_device_vals(h, stream=None, dtype="f16") -> np.ndarray:
 def smat_spmm(h, B, C, N=None, stream=None):
     """B: device tensor [K, >=N] of the handle's element size (2 bytes, or 1 for the 8-bit
     types; the library does not know the tensor's type, the caller must match the handle);
-    C: device tensor [M, >=N] of 4-byte elements (float32, int32 for "i8"); rows contiguous."""
-    if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
-        raise ValueError("B and C must be 2-D with unit column stride")
-    if B.element_size() not in (1, 2) or C.element_size() != 4:
-        raise ValueError("B must hold 1- or 2-byte elements and C 4-byte elements")
-    if N is None:
-        N = B.shape[1]
-    _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
-                          ctypes.c_void_p(C.data_ptr()), C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N),
-                          N, _stream_ptr(stream)))
+    C: device tensor [M, >=N] of 4-byte elements (float32, int32 for "i8"); rows contiguous.
+    Shapes, devices and element sizes are checked against the handle before the call (ValueError)."""
+    N, ldb, ldc = _check_device_operands(h, B, C, N)
+    _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), ldb, ctypes.c_void_p(C.data_ptr()), ldc, N,
+                          _stream_ptr(stream)))
 
 
 def smat_ablation_bytes(h) -> int:
@@ -254,16 +300,9 @@ def smat_ablation_bind(h, area, stream=None):
 
 def smat_ablation_spmm(h, level, B, C, N=None, stream=None):
     """As smat_spmm, through the ablation kernel of the given level (0, 1 or 2)."""
-    if B.dim() != 2 or C.dim() != 2 or B.stride(1) != 1 or C.stride(1) != 1:
-        raise ValueError("B and C must be 2-D with unit column stride")
-    if B.element_size() != 2 or C.element_size() != 4:
-        raise ValueError("B must hold 2-byte elements and C 4-byte elements")
-    if N is None:
-        N = B.shape[1]
-    _check(_lib.smat_ablation_spmm(h, level, ctypes.c_void_p(B.data_ptr()),
-                                   B.stride(0) if B.shape[0] > 1 else max(B.shape[1], N),
-                                   ctypes.c_void_p(C.data_ptr()),
-                                   C.stride(0) if C.shape[0] > 1 else max(C.shape[1], N), N, _stream_ptr(stream)))
+    N, ldb, ldc = _check_device_operands(h, B, C, N, elem_sizes=(2,))
+    _check(_lib.smat_ablation_spmm(h, level, ctypes.c_void_p(B.data_ptr()), ldb, ctypes.c_void_p(C.data_ptr()), ldc, N,
+                                   _stream_ptr(stream)))
 
 
 def smat_probe_read(buf, sink, stream=None):
@@ -291,10 +330,11 @@ class SmatMatrix:
     """Owns a handle and the torch workspace tensor it is bound to (memory plumbing only)."""
 
     def __init__(self, M, K, row_ptr, col_idx, vals_bits, dtype, *, reorder=1, tau_permille=700,
-                 dense_tiles=0, device="cuda:0", bind=True):
+                 dense_tiles=0, concurrent_streams=2, device="cuda:0", bind=True):
         self.M, self.K, self.dtype = M, K, dtype
         self.handle = smat_preprocess(M, K, row_ptr, col_idx, vals_bits, dtype,
-                                      reorder=reorder, tau_permille=tau_permille, dense_tiles=dense_tiles)
+                                      reorder=reorder, tau_permille=tau_permille, dense_tiles=dense_tiles,
+                                      concurrent_streams=concurrent_streams)
         self.workspace = None
         self.info = smat_get_info(self.handle)
         if bind:
@@ -312,8 +352,6 @@ class SmatMatrix:
         import torch
         if N is None:
             N = B.shape[1]
-        if B.element_size() != np.dtype(_elem_type(self.dtype)).itemsize:
-            raise ValueError(f"B must hold {np.dtype(_elem_type(self.dtype)).itemsize}-byte elements for dtype {self.dtype!r}")
         if C is None:
             C = torch.empty((self.M, N), dtype=torch.int32 if _dtype_code(self.dtype) == SMAT_I8 else torch.float32,
                             device=B.device)

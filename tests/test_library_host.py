@@ -14,14 +14,69 @@ from workloads import OCCUPANCY_SPEC, occupancy_csr, random_csr, band_csr, make_
 ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 
 
-def test_library_exports_every_declared_symbol():
-    header = open(os.path.join(ROOT, "include", "smat.h")).read()
+def _declared(header_name):
+    header = open(os.path.join(ROOT, "include", header_name)).read()
     header = re.sub(r"/\*.*?\*/", "", header, flags=re.S)
-    names = sorted(set(re.findall(r"\b(smat_[a-z_]+)\s*\(", header)))
-    assert {"smat_preprocess", "smat_spmm", "smat_bind_device", "smat_export_bcsr"} <= set(names)
+    return set(re.findall(r"\b(smat_[a-z_]+)\s*\(", header))
+
+
+def test_library_exports_every_declared_symbol():
+    method, bench = _declared("smat.h"), _declared("smat_bench.h")
+    assert {"smat_preprocess", "smat_spmm", "smat_bind_device", "smat_export_bcsr", "smat_get_dims"} <= method
+    # the measurement entry points live in their own header, not in the method's
+    assert {"smat_probe_read", "smat_probe_gather", "smat_probe_mfma", "smat_ablation_bytes", "smat_ablation_bind",
+            "smat_ablation_spmm"} == bench
+    assert not any(n.startswith(("smat_probe", "smat_ablation")) for n in method)
     lib = ctypes.CDLL(S.lib_path())
-    for n in names:
+    for n in sorted(method | bench):
         assert hasattr(lib, n), n
+
+
+def test_binding_refuses_operands_that_do_not_fit_the_handle():
+    """The kernels bound their loads and stores by the handle's M and K and by the N and leading
+    dimensions they are given; the binding therefore checks the tensors against the handle and raises
+    before anything is launched (here on CPU tensors: the device check comes last)."""
+    import torch
+    w = random_csr(40, 50, 8, 0.1, seed=3)
+    h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    assert S.smat_get_dims(h) == {"M": 40, "K": 50, "dtype": S.SMAT_F16, "elem_bytes": 2}
+    b = torch.zeros((50, 8), dtype=torch.int16)
+    c = torch.zeros((40, 8), dtype=torch.float32)
+    cases = [
+        (torch.zeros((49, 8), dtype=torch.int16), c, 8, "B has 49 rows"),
+        (b, torch.zeros((39, 8), dtype=torch.float32), 8, "C has 39 rows"),
+        (b, c, 9, "N = 9 exceeds"),
+        (b, torch.zeros((40, 4), dtype=torch.float32), 8, "N = 8 exceeds"),
+        (torch.zeros((50, 8), dtype=torch.int8), c, 8, "2-byte elements"),
+        (b, torch.zeros((40, 8), dtype=torch.float16), 8, "4-byte elements"),
+        (b.t().contiguous().t(), c, 8, "unit column stride"),
+        (torch.zeros((50, 8, 1), dtype=torch.int16), c, 8, "2-D"),
+        (b, c, 8, "device tensors"),
+    ]
+    try:
+        for bb, cc, n, text in cases:
+            with pytest.raises(ValueError, match=text):
+                S.smat_spmm(h, bb, cc, n)
+            with pytest.raises(ValueError, match=text):
+                S.smat_ablation_spmm(h, 1, bb, cc, n)
+        # the export buffers are sized from the handle's storage type, whatever the caller names
+        with pytest.raises(ValueError, match="element size"):
+            S.smat_export_bcsr(h, dtype="i8")
+        assert S.smat_export_bcsr(h)[2].dtype == np.uint16
+    finally:
+        S.smat_destroy(h)
+    w8 = recast(w, "e4m3")
+    h8 = S.smat_preprocess(w8.M, w8.K, w8.row_ptr, w8.col_idx, w8.a_bits, "e4m3")
+    try:
+        assert S.smat_export_bcsr(h8)[2].dtype == np.uint8 and S.smat_get_dims(h8)["elem_bytes"] == 1
+        with pytest.raises(ValueError, match="element size"):
+            S.smat_export_bcsr(h8, dtype="f16")
+        with pytest.raises(ValueError, match="1-byte elements"):
+            S.smat_spmm(h8, b, c, 8)
+        with pytest.raises(ValueError, match="storage type"):
+            S.smat_ablation_spmm(h8, 1, torch.zeros((50, 8), dtype=torch.int8), c, 8)
+    finally:
+        S.smat_destroy(h8)
 
 
 def _oracle_structure(w, tau, reorder=True):
@@ -234,9 +289,28 @@ def test_spmm_without_bind_is_an_error_not_a_fallback():
     S.smat_destroy(h)
 
 
+def test_concurrent_streams_option_sizes_the_workspace():
+    w = random_csr(512, 1100, 16, 0.12, seed=32, dtype="bf16")                   # block-dense: has tile scratch
+    sizes = []
+    for n in (1, 2, 5):
+        h = S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1, concurrent_streams=n)
+        sizes.append(S.smat_device_bytes(h))
+        S.smat_destroy(h)
+    assert sizes[1] - sizes[0] == 32 << 20 and sizes[2] - sizes[1] == 3 * (32 << 20)
+    for bad in (-1, 17):
+        _expect("SMAT_ERR_INVALID_ARG", lambda: S.smat_preprocess(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype,
+                                                                   concurrent_streams=bad))
+    ws = random_csr(64, 64, 16, 0.02, seed=1)                                    # no block-dense part: no scratch at all
+    a = S.smat_preprocess(ws.M, ws.K, ws.row_ptr, ws.col_idx, ws.a_bits, ws.dtype, concurrent_streams=1)
+    b = S.smat_preprocess(ws.M, ws.K, ws.row_ptr, ws.col_idx, ws.a_bits, ws.dtype, concurrent_streams=16)
+    assert S.smat_device_bytes(a) == S.smat_device_bytes(b)
+    S.smat_destroy(a)
+    S.smat_destroy(b)
+
+
 def test_default_options():
     assert S.smat_default_options() == {"block_h": 16, "block_w": 16, "reorder": 1, "tau_permille": 700,
-                                        "dense_tiles": 0}
+                                        "dense_tiles": 0, "concurrent_streams": 2}
 
 
 def _greedy_packs(w, perm, elem_bytes=2):

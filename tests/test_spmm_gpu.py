@@ -300,7 +300,9 @@ def test_graph_capture_and_replay(oracle_c):
     cases = [(random_csr(300, 500, 72, 0.02, seed=3, dtype="f16", b_dist="normal"), 0),
              (random_csr(256, 4112, 72, 0.1, seed=4, dtype="bf16", b_dist="normal"), 1)]
     for w, dense in cases:
-        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=dense)
+        # three streams see the handle (the default one, the warm-up stream, the graph's capture
+        # stream): with an area of partial tiles for each, all three take the same launch
+        m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=dense, concurrent_streams=3)
         b = _dev_b(w)
         eager = m.spmm(b).clone()
         torch.cuda.synchronize()
@@ -542,6 +544,68 @@ def test_two_handles_on_two_streams_and_rebinding(oracle_c):
     _check_c(c2.cpu().numpy(), r2[0], r2[1], w2)
     m1.close()
     m2.close()
+
+
+def test_one_handle_on_several_streams_at_once(oracle_c):
+    # smat_spmm is re-entrant: ONE handle, calls in flight on three streams with three C buffers, on a
+    # matrix whose launch splits its tiles over workgroups (partial tiles in the workspace).  The first
+    # two streams (concurrent_streams = 2) own an area for partial tiles each, the third runs unsplit.
+    w = random_csr(512, 1100, 264, 0.12, seed=32, dtype="bf16", b_dist="normal")
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1)
+    b = _dev_b(w)
+    streams = [torch.cuda.Stream() for _ in range(3)]
+    cs = [torch.full((w.M, w.N), float("nan"), dtype=torch.float32, device="cuda") for _ in range(3)]
+    torch.cuda.synchronize()
+    names = [None] * 3
+    for _ in range(25):
+        for k in range(3):
+            S.smat_spmm(m.handle, b, cs[k], w.N, streams[k])
+            names[k] = S.smat_last_kernel()
+    torch.cuda.synchronize()
+    assert names == ["spmm_dense_bf16_g2k4", "spmm_dense_bf16_g2k4", "spmm_dense_bf16_g2"], names
+    c_ref, s_ref = _oracle_c(oracle_c, w)
+    got = [c.cpu().numpy() for c in cs]
+    for g in got:
+        _check_c(g, c_ref, s_ref, w)
+    assert np.array_equal(got[0], got[1])                    # same launch, different areas: the same bits
+    # once more, one stream at a time: every stream reproduces its own bits
+    for k in range(3):
+        cs[k].fill_(float("nan"))
+        S.smat_spmm(m.handle, b, cs[k], w.N, streams[k])
+        streams[k].synchronize()
+        assert np.array_equal(cs[k].cpu().numpy(), got[k])
+    m.close()
+    # with one area only, the second stream is the one that runs unsplit
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1, concurrent_streams=1)
+    for k in range(2):
+        cs[k].fill_(float("nan"))
+        S.smat_spmm(m.handle, b, cs[k], w.N, streams[k])
+        names[k] = S.smat_last_kernel()
+    torch.cuda.synchronize()
+    assert names[:2] == ["spmm_dense_bf16_g2k4", "spmm_dense_bf16_g2"], names
+    for k in range(2):
+        assert np.array_equal(cs[k].cpu().numpy(), got[2 * k])
+    m.close()
+
+
+def test_binding_checks_device_operands_before_launching():
+    w = random_csr(64, 80, 16, 0.1, seed=5)
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype)
+    b = _dev_b(w)
+    c = torch.zeros((w.M, w.N), dtype=torch.float32, device="cuda")
+    with pytest.raises(ValueError, match="B has 79 rows"):
+        S.smat_spmm(m.handle, b[:79], c, w.N)
+    with pytest.raises(ValueError, match="C has 63 rows"):
+        S.smat_spmm(m.handle, b, c[:63], w.N)
+    with pytest.raises(ValueError, match="exceeds"):
+        S.smat_spmm(m.handle, b, c, w.N + 1)
+    with pytest.raises(ValueError, match="device tensors"):
+        S.smat_spmm(m.handle, b.cpu(), c, w.N)
+    with pytest.raises(ValueError, match="device tensors"):
+        m.spmm(b, c.cpu())
+    torch.cuda.synchronize()
+    assert not c.any()                                       # nothing was launched
+    m.close()
 
 
 def test_wide_and_odd_output_widths(oracle_c):
