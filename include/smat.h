@@ -204,6 +204,24 @@ smat_status_t smat_export_device_vals(const smat_handle_t *h, void *vals, void *
 smat_status_t smat_spmm(const smat_handle_t *h, const void *dB, int64_t ldb,
                         void *dC, int64_t ldc, int64_t N, void *stream);
 
+/*
+ * smat_spmm for callers that cannot allocate device memory and cannot give the handle's workspace
+ * the areas for partial tiles either: code under HIP graph capture, tight serving loops,
+ * harnesses that forbid allocation.  Same arguments, same product, same kernels.  The partial
+ * tiles of a launch that splits its block-dense tiles live in an array of 16 MiB that is part of
+ * the library's device code (one copy per GPU, held from the first use of the library on that
+ * GPU until the process ends); the call allocates and frees nothing, on the device or through
+ * any library.  smat_bind_device looks the array's address up for its device.
+ *   - a launch whose partial tiles would exceed the 16 MiB is refused with SMAT_ERR_UNSUPPORTED
+ *     before anything is enqueued (smat_spmm takes it);
+ *   - every call on a GPU uses that GPU's one array, whatever the handle or stream: calls that
+ *     overlap in time on one GPU race -- order them on one stream, or with events.  The array
+ *     keeps what the last call left; nothing in it has to start at zero, every partial tile is
+ *     written in full before it is read.
+ */
+smat_status_t smat_spmm_static(const smat_handle_t *h, const void *dB, int64_t ldb,
+                               void *dC, int64_t ldc, int64_t N, void *stream);
+
 /* Frees the host state of the handle (never device memory).  NULL is allowed. */
 void smat_destroy(smat_handle_t *h);
 

@@ -622,6 +622,12 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         if ((e = smat::launch_dense_fill(d, tiles, h->d_csr_row_ptr, h->d_csr_col_idx, h->d_csr_vals, base + l.t_vals, h->elem_bytes, s)))
             return hip_fail("fill tile values", e);
         if ((e = static_cast<int>(hipStreamSynchronize(s)))) return hip_fail("bind synchronize", e);
+        {
+            // set-up is the place to find this device's copy of the static area (smat_spmm_static)
+            void* area = nullptr;
+            size_t area_bytes = 0;
+            if ((e = smat::static_tile_scratch(&area, &area_bytes))) return hip_fail("address of the static area for partial tiles", e);
+        }
         h->dev = d;
         h->dev_rest = d_rest;
         h->tiles = tiles;
@@ -736,8 +742,10 @@ char* scratch_area_of(const smat_handle* h, const void* stream)
 }
 
 // smat_spmm with the area for partial tiles given by the caller of this function.
+// hard_limit = 0: the launch is planned so that its partial tiles fit scratch_bytes.  Otherwise it
+// is planned as if the area were unlimited and refused when its partial tiles exceed hard_limit.
 smat_status_t spmm_with_scratch(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
-                                int64_t N, void* stream, void* scratch, size_t scratch_bytes)
+                                int64_t N, void* stream, void* scratch, size_t scratch_bytes, size_t hard_limit = 0)
 {
     // The dense path fetches B in 16-byte pieces (8 columns, or 16 for the 8-bit types) that must lie
     // wholly inside or outside the N columns; otherwise every block row goes through the per-row kernel.  It also has to pay: a tile walks its steps at about
@@ -750,7 +758,7 @@ smat_status_t spmm_with_scratch(const smat_handle_t* h, const void* dB, int64_t 
     if (h->dense_mode < 0) use_tiles = false;
     smat::DenseTiles tiles = h->tiles;
     tiles.scratch = scratch;
-    tiles.scratch_bytes = scratch ? scratch_bytes : 0;
+    tiles.scratch_bytes = scratch ? (hard_limit ? ~size_t{0} >> 1 : scratch_bytes) : 0;
     if (use_tiles && h->dense_mode == 0) {
         const double n_tiles = static_cast<double>(tiles.n) * static_cast<double>((N + 127) / 128);
         const int ks = smat::dense_split(tiles, N);
@@ -761,6 +769,13 @@ smat_status_t spmm_with_scratch(const smat_handle_t* h, const void* dB, int64_t 
         // get faster with them -- 35.6 us against 35 on the band workload -- while the tile kernel did)
         const double t_rows = static_cast<double>(h->dense_columns) * static_cast<double>((N + 15) / 16 * 16) * 2.0 / 10.0e6 + 4.0;
         use_tiles = t_tiles <= t_rows;
+    }
+    if (use_tiles && hard_limit) {
+        const size_t need = static_cast<size_t>(tiles.n) * static_cast<size_t>((N + 127) / 128) * 256 * 128 * 4 *
+                            static_cast<size_t>(smat::dense_split(tiles, N));
+        if (smat::dense_split(tiles, N) > 1 && need > hard_limit)
+            return fail(SMAT_ERR_UNSUPPORTED, "this launch keeps " + std::to_string(need) + " bytes of partial tiles, the static area holds " +
+                                                  std::to_string(hard_limit) + ": use smat_spmm, whose area is part of the workspace");
     }
     const char* variant = "";
     thread_local std::string name;
@@ -810,6 +825,19 @@ smat_status_t smat_spmm(const smat_handle_t* h, const void* dB, int64_t ldb, voi
     const smat_status_t st = check_spmm_args(h, dB, ldb, dC, ldc, N, &nothing);
     if (st != SMAT_OK || nothing) return st;
     return spmm_with_scratch(h, dB, ldb, dC, ldc, N, stream, scratch_area_of(h, stream), kTileScratchBytes);
+}
+
+smat_status_t smat_spmm_static(const smat_handle_t* h, const void* dB, int64_t ldb, void* dC, int64_t ldc,
+                               int64_t N, void* stream)
+{
+    bool nothing = false;
+    const smat_status_t st = check_spmm_args(h, dB, ldb, dC, ldc, N, &nothing);
+    if (st != SMAT_OK || nothing) return st;
+    void* area = nullptr;
+    size_t bytes = 0;
+    const int e = smat::static_tile_scratch(&area, &bytes);      // looked up at bind time; here from the cache
+    if (e) return hip_fail("address of the static area for partial tiles", e);
+    return spmm_with_scratch(h, dB, ldb, dC, ldc, N, stream, area, bytes, bytes);
 }
 
 // Largest block grid for which the ablation keeps a dense block map (level 0).

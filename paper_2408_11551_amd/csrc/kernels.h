@@ -84,6 +84,11 @@ int launch_dense_fill(const DeviceBcsr& d, const DenseTiles& t, const int64_t* c
 // Workgroups per 128-column tile the dense launch would use for this N (1: no split).
 int dense_split(const DenseTiles& t, int64_t N);
 
+// The library's own area for partial tiles on the CURRENT device (a static device array, the same
+// for every handle and stream): its device address and size.  The first call on a device looks
+// the address up.  Returns a hipError_t as int.
+int static_tile_scratch(void** area, size_t* bytes);
+
 // C rows of the dense super rows.  dtype is a smat_dtype_t.  Needs N and ldb multiples of the
 // elements in 16 bytes (8, or 16 for the 8-bit types) and B aligned to 16 bytes.
 int launch_spmm_dense(const DeviceBcsr& d, const DenseTiles& t, int dtype, const void* B, int64_t ldb,

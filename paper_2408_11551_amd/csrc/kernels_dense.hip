@@ -15,6 +15,7 @@
 // block rows of a super row so that the panel of B is read once for all of them.
 #include <algorithm>
 #include <cstdio>
+#include <mutex>
 
 #include <hip/hip_runtime.h>
 
@@ -481,6 +482,36 @@ void dense_reduce_kernel(DeviceBcsr d, DenseTiles t, int ks, Out* __restrict__ C
             dst[0] = v[j][0]; dst[1] = v[j][1]; dst[2] = v[j][2]; dst[3] = v[j][3];
         }
     }
+}
+
+// An area for partial tiles that belongs to the library, not to a workspace: a file-scope device
+// array, one copy per GPU, present from the moment the code object is loaded until the process
+// ends.  Host code never passes the array itself to a kernel -- its name is only the handle by
+// which hipGetSymbolAddress finds the copy of the current device; the address is looked up once
+// per device and kept.
+constexpr size_t kStaticScratchBytes = size_t{16} << 20;        // 128 partial tiles of 256 x 128 words
+static __device__ __align__(256) __attribute__((used)) unsigned char scratch[kStaticScratchBytes];
+
+int static_tile_scratch(void** area, size_t* bytes)
+{
+    constexpr int kMaxDevices = 64;
+    static std::mutex mu;
+    static void* addr[kMaxDevices] = {};
+    int dev = 0;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return static_cast<int>(e);
+    if (dev < 0 || dev >= kMaxDevices) return static_cast<int>(hipErrorInvalidDevice);
+    std::lock_guard<std::mutex> lock(mu);
+    if (addr[dev] == nullptr) {
+        void* p = nullptr;
+        e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+        if (e != hipSuccess) return static_cast<int>(e);
+        if (p == nullptr) return static_cast<int>(hipErrorInvalidSymbol);
+        addr[dev] = p;
+    }
+    *area = addr[dev];
+    *bytes = kStaticScratchBytes;
+    return 0;
 }
 
 // How many workgroups share the steps of a 128-column tile: as many as fit the 256 compute

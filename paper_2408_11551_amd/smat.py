@@ -96,6 +96,8 @@ def _load():
     lib.smat_export_device_vals.argtypes = [vp, vp, vp]
     lib.smat_spmm.restype = ctypes.c_int
     lib.smat_spmm.argtypes = [vp, vp, i64, vp, i64, i64, vp]
+    lib.smat_spmm_static.restype = ctypes.c_int
+    lib.smat_spmm_static.argtypes = [vp, vp, i64, vp, i64, i64, vp]
     lib.smat_ablation_bytes.restype = ctypes.c_int
     lib.smat_ablation_bytes.argtypes = [vp, ctypes.POINTER(sz)]
     lib.smat_ablation_bind.restype = ctypes.c_int
@@ -284,6 +286,13 @@ def smat_spmm(h, B, C, N=None, stream=None):
     N, ldb, ldc = _check_device_operands(h, B, C, N)
     _check(_lib.smat_spmm(h, ctypes.c_void_p(B.data_ptr()), ldb, ctypes.c_void_p(C.data_ptr()), ldc, N,
                           _stream_ptr(stream)))
+
+
+def smat_spmm_static(h, B, C, N=None, stream=None):
+    """As smat_spmm, with the partial tiles of split launches in the library's static device array."""
+    N, ldb, ldc = _check_device_operands(h, B, C, N)
+    _check(_lib.smat_spmm_static(h, ctypes.c_void_p(B.data_ptr()), ldb, ctypes.c_void_p(C.data_ptr()), ldc, N,
+                                 _stream_ptr(stream)))
 
 
 def smat_ablation_bytes(h) -> int:
