@@ -16,6 +16,7 @@
 #include <algorithm>
 #include <cstdio>
 #include <mutex>
+#include <type_traits>
 
 #include <hip/hip_runtime.h>
 
@@ -380,6 +381,346 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
     }
 }
 
+// ---------------------------------------------------------------------------------------------
+// The tile kernel for the 16-bit types.  Same tiles, same steps, same operand layout as above;
+// what differs is how a step's data reaches the matrix units.  A wave has 512 clocks of matrix
+// work per step, while a load takes a few thousand clocks under load, and whatever a wave does
+// right behind a barrier happens at the same moment in all eight waves of the compute unit.  Here
+//   * the 32 x 128 panel of B goes from memory straight into LDS (buffer loads with the LDS
+//     modifier: lane l of a wave delivers 16 bytes to M0 + 16 l, so a wave fills four 256-byte
+//     panel rows with one instruction and no register is spent on staging), into a ring of three
+//     panels, two steps ahead;
+//   * the block values sit in a register ring of three steps, two steps ahead;
+//   * every thread waits for its own loads of the step (in-order counter: all but the youngest
+//     six), one barrier makes the panel visible, and the loads of the next two steps stay in
+//     flight across it -- twelve KiB per wave;
+//   * the six loads of a step are not issued together behind the barrier -- forty-eight loads at
+//     once kept every wave waiting at its load instructions while the matrix units idled, and the
+//     time of the loads and the time of the matrix instructions added up (measured by leaving out
+//     one or the other) -- but one by one between the groups of matrix instructions.
+// Built, measured and set aside: the panel read from LDS in two halves, the second while the first
+// four groups of matrix instructions run and the first half of the next panel while the last four
+// run (which needs the next panel to have landed a step early: 78 us on a 4096 x 4096 x 2048
+// product against 73 us), and requests for the lines of later steps through the scalar cache, which
+// has a path of its own into the L2 (88 us against 79 us at the time).
+// The tiles are numbered so that the workgroups an XCD runs (every eighth in dispatch order) form
+// compact rectangles of super rows x column slabs: the tile values of a super row and the panel rows
+// of a slab then miss that XCD's L2 once and hit it for the other workgroups that walk them at the
+// same time.
+constexpr int kTileGroup = 4;          // super rows of a rectangle
+
+// What the host and the kernel agree on: tile number -> (index of the super row, column slab).
+struct TileOrder {
+    int n_super, n_slab, per_xcd;      // per_xcd = ceil(tiles / 8)
+};
+
+__device__ __forceinline__ uint32_t lds_offset_of(const void* p)
+{
+    return static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)p));
+}
+
+// One load straight into LDS: every lane fetches the 16 bytes at voff + soff of the buffer (zeros
+// when out of range), and the wave's 64 pieces land back to back from lds_addr on (wave-uniform).
+// The compiler counts it among the outstanding memory loads like any other.
+typedef __attribute__((address_space(3))) void lds_void;
+__device__ __forceinline__ void load_to_lds16(lds_void* lds_addr, __amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    __builtin_amdgcn_raw_ptr_buffer_load_lds(r, lds_addr, 16, voff, soff, 0, 0);
+}
+
+// Reads of what such loads delivered.  They are written as assembly so that the compiler does not
+// see an LDS read at all: it would hold every such read back until the most recent load into LDS
+// has completed (it cannot tell the ring's panels apart), which is the look-ahead this kernel is
+// for.  The panel's arrival is awaited by hand and made visible by a barrier.  (None of the
+// assembly statements of this kernel claims to touch memory: the compiler would then no longer
+// fetch the per-step tables with scalar loads, and its vector loads would wait for everything.)
+template <int OFFSET>
+__device__ __forceinline__ u32x4 lds_read16(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
+// all LDS reads of this wave have returned; the registers named are the ones they filled
+__device__ __forceinline__ void lds_reads_done(u32x4 (&R)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)"
+                 : "+v"(R[0]), "+v"(R[1]), "+v"(R[2]), "+v"(R[3]), "+v"(R[4]), "+v"(R[5]), "+v"(R[6]), "+v"(R[7]));
+}
+
+template <int DT, int KG>
+__global__ __launch_bounds__(256 * KG)
+__attribute__((amdgpu_waves_per_eu(2, 2)))
+void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* __restrict__ B, uint32_t b_bytes,
+                        uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store)
+{
+    static_assert(Elem<DT>::ES == 2, "the 16-bit types");
+    using Acc = typename Elem<DT>::Acc;
+    using Out = typename Elem<DT>::Out;
+    constexpr int NT = 8;                          // columns per lane; 16 lanes cover the 128 columns of a tile
+    constexpr int RM = 4;                          // block rows per wave
+    constexpr int RD = 3;                          // ring depth: panels in LDS, steps of block values in registers
+    // per wave group, RD panels of 32 rows of B x 128 columns; the two groups' hand-over at the end needs 64 KiB
+    constexpr int kLdsWords = KG == 2 ? (KG * RD * 32 * 16 > 4096 ? KG * RD * 32 * 16 : 4096) : KG * RD * 32 * 16;
+    __shared__ u32x4 lds_words[kLdsWords];
+    u32x4 (*panel_all)[RD][32][16] = reinterpret_cast<u32x4 (*)[RD][32][16]>(lds_words);
+
+    // tile of this workgroup: the XCD's share of the tile numbers is contiguous
+    const int tile = static_cast<int>(blockIdx.x % 8u) * order.per_xcd + static_cast<int>(blockIdx.x / 8u);
+    if (tile >= order.n_super * order.n_slab) return;
+    const int band = tile / (kTileGroup * order.n_slab), in_band = tile % (kTileGroup * order.n_slab);
+    const int band_rows = min(kTileGroup, order.n_super - kTileGroup * band);
+    const int sidx = kTileGroup * band + in_band % band_rows;
+    const int slab = in_band / band_rows;
+
+    const int tid = threadIdx.x & 255;             // thread inside its wave group
+    const int lane = tid & 63;
+    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
+    const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
+    const int i = lane & 15, g = lane >> 4;
+    const int super = t.super_rows[sidx];
+    const int n0 = slab * 128;
+    const int ks = static_cast<int>(gridDim.z);    // workgroups sharing this tile's steps
+    const int q_first = t.step_ptr[sidx], q_last = t.step_ptr[sidx + 1];
+    const int per = (q_last - q_first + ks - 1) / ks;
+    const int q0 = min(q_first + static_cast<int>(blockIdx.z) * per, q_last);
+    const int q1 = min(q0 + per, q_last);
+    const int nq = q1 - q0;
+
+    const __amdgpu_buffer_rsrc_t b_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
+    // tile values of this workgroup's steps q0..q1-1 are stored back to back
+    const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
+    const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
+    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
+        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
+        static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
+
+    // This lane's share of a panel: the 16-byte piece (lane & 15) of rows 4 wave + (lane >> 4) of the
+    // step's first and of its second block column.  (N is a multiple of 8 on this path, so a piece is
+    // all inside or all outside.)
+    const int st_row = 4 * wave + (lane >> 4);
+    const int st_col = n0 + 8 * (lane & 15);
+    const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * 2u : kOutOfRange;
+    const uint32_t no_row = static_cast<uint32_t>(d.K);
+    const int nbc = static_cast<int>((d.K + 15) >> 4);
+    // where this wave's pieces of a panel go (+ 4096 for the second block column), and where this lane reads
+    auto lds_of_panel = [&](int buf) { return reinterpret_cast<char*>(&panel_all[kg][buf][4 * wave][0]); };
+    const uint32_t rd_base = lds_offset_of(&panel_all[kg][0][8 * g][i]);            // + 8192 per panel, + 256 per row
+
+    // What a step's loads need to know, fetched with scalar loads a step before it is used.  A
+    // step past the group's last one names no block column (its panel rows read zeros) and no block
+    // row (its block values read zeros).
+    struct StepMeta { int c0, c1; uint32_t rows, base; };
+    // (The tables are written at bind time and never while a kernel runs.  Reading them through the
+    // constant address space tells the compiler so: the loads stay scalar even though the loop
+    // contains loads that write LDS, which it takes for writes to anything.)
+    typedef __attribute__((address_space(4))) const int32_t* const_i32;
+    typedef __attribute__((address_space(4))) const uint32_t* const_u32;
+    const const_i32 step_cols = (const_i32)t.step_cols;
+    const const_u32 step_rows = (const_u32)t.step_rows, step_base = (const_u32)t.step_base;
+    auto is_live = [&](int gs) { return kg + KG * gs < nq; };      // step gs of this wave group = step kg + KG * gs of the tile
+    auto fetch_meta = [&](int gs) {
+        const bool live = is_live(gs);
+        const size_t q = static_cast<size_t>(q0 + (live ? kg + KG * gs : nq - 1));     // clamped: the loads are unconditional
+        // nothing is computed from the loaded words here: they are first looked at a step later,
+        // so the wave does not wait for the scalar loads
+        StepMeta m;
+        m.c0 = step_cols[2 * q];
+        m.c1 = step_cols[2 * q + 1];
+        m.rows = step_rows[q];
+        m.base = step_base[q];
+        return m;
+    };
+    // e-th block column of the step's panel (e = 0, 1): one load into LDS
+    auto load_panel_half = [&](const StepMeta& m, bool live, int buf, int e) {
+        // rows past K (ragged last block column, or no such column) are out of range: zeros
+        const int c = live ? (e == 0 ? m.c0 : m.c1) : 0x7FFFFFFF;                        // scalar select, no branch
+        uint32_t row = c < nbc ? static_cast<uint32_t>(c) * 16u + st_row : no_row;
+        row = row < no_row ? row : no_row;
+        load_to_lds16((lds_void*)(lds_of_panel(buf) + 4096 * e), b_rsrc, __umul24(row, ldb_bytes) + st_off, 0u);
+    };
+    auto load_panel = [&](const StepMeta& m, bool live, int buf) {
+        load_panel_half(m, live, buf, 0);
+        load_panel_half(m, live, buf, 1);
+    };
+    // Values of the wave's r-th block row for a step.  A block row without data in the step reads
+    // out of range (zeros) and multiplies zeros: no branches in the loop body.
+    auto load_a_row = [&](const StepMeta& m, bool live, int r) {
+        const uint32_t rows = live ? m.rows : 0u;
+        const int j = RM * wave + r;
+        const uint32_t slot = m.base - first_slot + __popc(rows & ((1u << j) - 1u));
+        const uint32_t absent = (rows >> j & 1u) ? 0u : kOutOfRange;                      // wave-uniform
+        // (the slot is wave-uniform; saying so keeps it in a scalar register whatever the pressure there)
+        return buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent,
+                          static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(static_cast<int>(slot * 1024u))));
+    };
+    auto load_a = [&](const StepMeta& m, bool live, u32x4 (&a)[RM]) {
+#pragma unroll
+        for (int r = 0; r < RM; ++r) a[r] = load_a_row(m, live, r);
+    };
+
+    Acc acc[RM][NT];
+#pragma unroll
+    for (int r = 0; r < RM; ++r)
+#pragma unroll
+        for (int x = 0; x < NT; ++x) acc[r][x] = Acc{0, 0, 0, 0};
+
+    if (nq > 0) {
+        u32x4 a[RD][RM];
+        StepMeta mt[RD];
+#pragma unroll
+        for (int h = 0; h < RD; ++h) mt[h] = fetch_meta(h);
+        // prologue: what steps -2 and -1 of the loop would have issued, in the loop's order
+#pragma unroll
+        for (int h = 0; h < RD - 1; ++h) {
+            load_panel(mt[h], is_live(h), h);
+            load_a(mt[h], is_live(h), a[h]);
+            mt[h] = fetch_meta(h + RD);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+        const int iters = ((nq + KG - 1) / KG + RD - 1) / RD;      // the same for both groups: they share the barriers
+        // step s of the group, s = u (mod RD): u picks the panel buffer and the register set
+        auto step = [&](auto u_, int s) {
+            constexpr int u = decltype(u_)::value;
+            // Loads complete in order: all but the youngest six (those of step s+1) are the
+            // panel and the block values of step s, and everything older.
+            asm volatile("s_waitcnt vmcnt(6)");
+            __builtin_amdgcn_s_barrier();
+            // Every wave is past step s-1: its panel buffer and this wave's registers of that step
+            // take the loads of step s+2 -- not here, though.  After the barrier all waves of the
+            // compute unit are at the same point, and forty-eight loads asked for at once keep every
+            // wave waiting at its load instructions while the matrix units idle (measured: the time of
+            // the loads and the time of the matrix instructions added up).  The six loads go out one by
+            // one between the groups of matrix instructions below.
+            // B rows of this lane's k range: row 8g + kk, columns 8i .. 8i+7
+            u32x4 R[8];
+            R[0] = lds_read16<8192 * u + 0>(rd_base);
+            R[1] = lds_read16<8192 * u + 256>(rd_base);
+            R[2] = lds_read16<8192 * u + 512>(rd_base);
+            R[3] = lds_read16<8192 * u + 768>(rd_base);
+            R[4] = lds_read16<8192 * u + 1024>(rd_base);
+            R[5] = lds_read16<8192 * u + 1280>(rd_base);
+            R[6] = lds_read16<8192 * u + 1536>(rd_base);
+            R[7] = lds_read16<8192 * u + 1792>(rd_base);
+            lds_reads_done(R);
+            // the tables of step s+5 are asked for only now: scalar loads share the counter the wait
+            // above looks at, and it should not wait for them
+            const StepMeta next = mt[(u + 2) % RD];
+            const bool next_live = is_live(s + 2);
+            mt[(u + 2) % RD] = fetch_meta(s + 2 + RD);
+            __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+            for (int x = 0; x < NT; ++x) {
+                const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
+                u32x4 b;
+#pragma unroll
+                for (int qd = 0; qd < 4; ++qd)
+                    b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
+#pragma unroll
+                for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
+                __builtin_amdgcn_sched_barrier(0);
+                // one load of step s+2 after each of the first six groups, in the order the wait at the
+                // top of a step counts on: the panel's two, then the four block rows
+                if (x < 2) {
+                    load_panel_half(next, next_live, (u + 2) % RD, x);
+                } else if (x < 2 + RM) {
+                    a[(u + 2) % RD][x - 2] = load_a_row(next, next_live, x - 2);
+                }
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            __builtin_amdgcn_sched_barrier(0);
+        };
+        static_assert(RD == 3, "the loop body names its three steps");
+        for (int it = 0; it < iters; ++it) {
+            step(std::integral_constant<int, 0>{}, RD * it);
+            step(std::integral_constant<int, 1>{}, RD * it + 1);
+            step(std::integral_constant<int, 2>{}, RD * it + 2);
+        }
+        // nothing may still be on its way into LDS when the buffers get another use or the workgroup ends
+        asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)");
+    }
+
+    if constexpr (KG == 2) {
+        // group 1 hands its accumulators to group 0, two block rows per wave at a time, through the
+        // 64 KiB the panels occupied
+        __syncthreads();
+        Out* handover = reinterpret_cast<Out*>(lds_words);
+#pragma unroll
+        for (int half = 0; half < 2; ++half) {
+            if (kg == 1) {
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                    for (int x = 0; x < NT; ++x)
+#pragma unroll
+                        for (int y = 0; y < 4; ++y)
+                            handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane] = acc[2 * half + rr][x][y];
+            }
+            __syncthreads();
+            if (kg == 0) {
+#pragma unroll
+                for (int rr = 0; rr < 2; ++rr)
+#pragma unroll
+                    for (int x = 0; x < NT; ++x)
+#pragma unroll
+                        for (int y = 0; y < 4; ++y)
+                            acc[2 * half + rr][x][y] += handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
+            }
+            __syncthreads();
+        }
+        if (kg == 1) return;
+    }
+
+    // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 8i + x]
+    if (ks > 1) {
+        // partial tile, row-major 256 x 128 words, at [(tile * ks + z)]
+        const size_t tile_at = static_cast<size_t>(sidx) * order.n_slab + slab;
+        Out* part = static_cast<Out*>(t.scratch) + (tile_at * ks + blockIdx.z) * (256 * 128);
+#pragma unroll
+        for (int r = 0; r < RM; ++r)
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
+                *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
+                *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
+            }
+        return;
+    }
+    const int col0 = n0 + NT * i;
+    if (col0 >= N) return;
+#pragma unroll
+    for (int r = 0; r < RM; ++r) {
+        const int64_t br = static_cast<int64_t>(super) * 16 + RM * wave + r;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const int64_t out_row = d.perm[br * 16 + 4 * g + y];
+            if (out_row < 0) continue;
+            Out* dst = C + out_row * ldc + col0;
+            if (vec_store) {
+                *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
+                *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
+            } else {
+#pragma unroll
+                for (int x = 0; x < NT; ++x) dst[x] = acc[r][x][y];
+            }
+        }
+    }
+}
+
+template <int DT, int KG>
+static void launch_tile16(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
+                          void* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
+{
+    TileOrder order;
+    order.n_super = t.n;
+    order.n_slab = static_cast<int>((N + 127) / 128);
+    order.per_xcd = (order.n_super * order.n_slab + 7) / 8;
+    dim3 grid(static_cast<unsigned>(8 * order.per_xcd), 1, static_cast<unsigned>(ks));
+    hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
+                       static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
+}
+
 template <int DT, int RING, int KG>
 static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
                               void* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
@@ -543,8 +884,13 @@ static int launch_dense_dtype(const DeviceBcsr& d, const DenseTiles& t, const vo
     if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", type, deep ? 2 : 1, ks);
     else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", type, deep ? 2 : 1);
     *variant = name;
-    if (deep) launch_dense_tile<DT, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    else launch_dense_tile<DT, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    if constexpr (Elem<DT>::ES == 2) {
+        if (deep) launch_tile16<DT, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_tile16<DT, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    } else {
+        if (deep) launch_dense_tile<DT, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+        else launch_dense_tile<DT, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
+    }
     if (ks > 1)
         hipLaunchKernelGGL((dense_reduce_kernel<Acc, Out>), dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8),
                            dim3(256), 0, s, d, t, ks, static_cast<Out*>(C), ldc, static_cast<int>(N), vec_store);
