@@ -22,6 +22,7 @@ UNITS = {
     "api": ("api.cpp", []),
     "preprocess": ("preprocess.cpp", []),
     "kernels": ("kernels.hip", PRELOAD),
+    "kernels_narrow": ("kernels_narrow.hip", PRELOAD),
     # the per-row kernel for the 8-bit operand types: one object per type, built side by side
     "kernels_e4m3": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=2", *PRELOAD]),
     "kernels_e5m2": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=3", *PRELOAD]),

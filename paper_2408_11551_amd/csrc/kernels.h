@@ -69,6 +69,11 @@ int launch_bcsr_fill(const DeviceBcsr& d, const int64_t* csr_row_ptr, const int3
 // a hipError_t as int; *variant receives a static string naming the kernel.
 int launch_spmm(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
                 int64_t N, void* stream, const char** variant);
+// The variant for matrices with entry rows at N <= 16, fp16 and bf16 (kernels_narrow.hip).
+// Returns kNotNarrow where it does not apply (other types, wider or odd N above 8, no entry rows).
+constexpr int kNotNarrow = -1;
+int launch_spmm_narrow(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void* C, int64_t ldc,
+                       int64_t N, void* stream, const char** variant);
 // the 8-bit types (kernels_8bit.hip, compiled once per type)
 int launch_spmm_e4m3(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
                      int64_t N, void* stream, const char** variant);

@@ -107,6 +107,8 @@ int launch_spmm(const DeviceBcsr& d, int dtype, const void* B, int64_t ldb, void
                 int64_t N, void* stream, const char** variant)
 {
     hipStream_t s = static_cast<hipStream_t>(stream);
+    const int narrow = launch_spmm_narrow(d, dtype, B, ldb, C, ldc, N, stream, variant);
+    if (narrow != kNotNarrow) return narrow;
     switch (dtype) {
     case kF16: return launch_dtype<kF16>(d, B, ldb, C, ldc, N, s, variant);
     case kBF16: return launch_dtype<kBF16>(d, B, ldb, C, ldc, N, s, variant);

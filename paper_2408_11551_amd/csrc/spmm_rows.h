@@ -372,7 +372,168 @@ __device__ __forceinline__ void walk_row_deep(const RowWalk& w, __amdgpu_buffer_
     }
 }
 
-template <int NT, int KW, int SW, int NCH, int LMAX, int DT>
+// ---------------------------------------------------------------------------
+// Entry rows at N = 1, 2, 4, 8, 16 (16-bit types)
+// ---------------------------------------------------------------------------
+// With few columns the walk above asks the memory pipeline for next to nothing per request: a
+// row load of lane (g, i) is one element, a pack costs eight such requests plus two for its
+// slots and values.  Here every lane fetches the whole piece of ONE row of B with one load of W
+// bytes instead -- the row of "its" entry, all N columns at N <= 8 (W = 2 N, two packs per
+// round, PK = 2), eight of the sixteen at N = 16 (one pack per round, PK = 1) -- plus that
+// entry's slot word and value, so a round of 64 (32) entries takes three requests per lane.
+// Both operands of the multiply then go through the wave's own part of LDS:
+//   - the pieces, from where lane (g, i) of the multiply reads the eight elements of its column,
+//     one per entry of its lane group.  The piece of entry (g, kk) lies at 16-byte (PK = 1:
+//     32-byte) position 8 c + ((kk + c) mod 8), c the number of the lane group among the
+//     round's eight (four): one read instruction (a fixed kk) touches every LDS bank once;
+//   - the left operand as the multiply wants it, 16 bytes per lane: the lane that holds entry
+//     (g, kk) with row number i' stores its value at element kk of lane (g, i')'s sixteen bytes
+//     (it learns i' from the slot word of entry (g, kk / 2), a neighbour lane), and puts the
+//     zero back once the round is multiplied.
+//
+// PK = 2: columns 0..7 of the multiply's right operand belong to the first pack of the round
+// (lanes i < 8) and columns 8..15 to the second (lanes i >= 8, column i - 8).  The first pack's
+// left operand accumulates into one tile, the second pack's into another, both with the same
+// right operand: the first tile is right in its columns 0..7 and the second in its columns
+// 8..15, the rest of each is never used, and the two halves are added at the end of the row.
+//
+// What this buys is bounded by the gather itself: 4.2 M random 16-byte pieces out of a 4 MB
+// array take 22 us on this chip whatever the load width or cache policy (each costs the L2 a
+// whole 128-byte line); the walk above needs 36.7 us for that many entries at N = 8, this one 29.
+template <int PK> constexpr int narrow_lds_bytes() { return 1024 + PK * 1024; }
+
+template <int KW, int PK, int W, int DT>
+__device__ __forceinline__ void walk_entries_narrow(const RowWalk& w, __amdgpu_buffer_rsrc_t b_rsrc,
+                                                    typename Elem<DT>::Acc& acc)
+{
+    using Acc = typename Elem<DT>::Acc;
+    static_assert(Elem<DT>::ES == 2, "16-bit operand types only");
+    static_assert((PK == 2 && (W == 2 || W == 4 || W == 8 || W == 16)) || (PK == 1 && W == 16),
+                  "two packs of pieces of W bytes per round, or one pack of 32-byte pieces");
+    constexpr int RW = W >= 4 ? W / 4 : 1;         // registers of a piece
+    constexpr int AREA = narrow_lds_bytes<PK>();
+    __shared__ __attribute__((aligned(16))) uint8_t narrow_lds[KW * AREA];
+    const int rounds = (w.npacks + PK - 1) / PK;
+    if (w.ks >= rounds) return;
+    const int count = (rounds - w.ks + KW - 1) / KW;       // rounds of this wave
+    uint8_t* lds_b = narrow_lds + w.ks * AREA;              // pieces of B
+    uint8_t* lds_a = lds_b + 1024;                          // left operands: PK x 64 lanes x 16 bytes
+    const int lane = w.lane, g = lane >> 4, i = lane & 15;
+
+    // what this lane fetches: entry l_e of pack l_sp of the round, columns from 8 l_half on
+    const int l_sp = PK == 2 ? (lane >> 3) & 1 : 0;
+    const int l_e = PK == 2 ? 8 * g + (lane & 7) : lane >> 1;
+    const int l_half = PK == 2 ? 0 : lane & 1;
+    const int l_g = l_e >> 3, l_kk = l_e & 7;
+    const int l_c = PK == 2 ? 4 * l_sp + l_g : l_g;        // lane group of the entry among the round's
+    const uint32_t wr_b = PK == 2 ? static_cast<uint32_t>(8 * l_c + ((l_kk + l_c) & 7)) * 16u
+                                  : static_cast<uint32_t>(8 * l_c + ((l_kk + l_c) & 7)) * 32u + 16u * l_half;
+    const uint32_t l_idx = static_cast<uint32_t>(l_sp * 32 + l_e);
+    const bool owner = l_half == 0;                        // one lane per entry places the value
+    // the lane that holds the slot word with this entry's row number, and where the number is in it
+    const int nib_from = (PK == 2 ? ((lane & ~7) | (l_kk >> 1)) : 2 * ((l_e & ~7) | (l_kk >> 1))) * 4;
+    const uint32_t nib_shift = 24u + 4u * (l_kk & 1);
+    const uint32_t wr_a0 = static_cast<uint32_t>(l_sp * 4 + l_g) * 256u + 2u * l_kk;
+    // what this lane reads for the multiply: column rd_col / 2 of the entries of lane group rd_c
+    const int rd_c = PK == 2 ? 4 * (i >> 3) + g : g;
+    const uint32_t rd_col = PK == 2 ? 2u * (i & 7) : 2u * i;
+    uint32_t rd_b[8];
+#pragma unroll
+    for (int kk = 0; kk < 8; ++kk)
+        rd_b[kk] = static_cast<uint32_t>(8 * rd_c + ((kk + rd_c) & 7)) * (PK == 2 ? 16u : 32u) + rd_col;
+
+    const __amdgpu_buffer_rsrc_t slots_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint32_t*>(w.slots), 0, w.npacks * 128, kRsrcFlags);
+    const __amdgpu_buffer_rsrc_t vals_rsrc =
+        __builtin_amdgcn_make_buffer_rsrc(const_cast<uint8_t*>(w.vals), 0, w.npacks * 64, kRsrcFlags);
+
+#pragma unroll
+    for (int x = 0; x < PK; ++x) *reinterpret_cast<u32x4*>(lds_a + x * 1024 + lane * 16) = u32x4{0u, 0u, 0u, 0u};
+
+    // slot word and value of the lane's entry in round r (zeros past the row's last pack)
+    auto load_meta = [&](int r, uint32_t& m, uint32_t& v) {
+        const uint32_t idx = static_cast<uint32_t>(PK * r) * 32u + l_idx;    // beyond the tables: range-checked to zero
+        BLoad<4>::ld(&m, slots_rsrc, idx * 4u, 0u);
+        BLoad<2>::ld(&v, vals_rsrc, idx * 2u, 0u);
+    };
+    // Requests the lane's piece of B (an entry past the row's last pack names row K: zeros, no
+    // access) and returns where the entry's value goes in the left operands.
+    auto load_piece = [&](int r, uint32_t m, uint32_t (&P)[RW]) -> uint32_t {
+        const bool valid = PK * r + l_sp < w.npacks;
+        BLoad<W>::ld(P, b_rsrc, __umul24(valid ? m : w.no_row, w.ldb_bytes) + 16u * l_half, 0u);
+        const uint32_t word = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(nib_from, static_cast<int>(m)));
+        return wr_a0 + ((word >> nib_shift) & 15u) * 16u;
+    };
+    auto stash = [&](const uint32_t (&P)[RW], uint32_t wr_a, uint32_t v) {
+        if (owner) *reinterpret_cast<uint16_t*>(lds_a + wr_a) = static_cast<uint16_t>(v);
+        if constexpr (W == 16) *reinterpret_cast<u32x4*>(lds_b + wr_b) = u32x4{P[0], P[1], P[2], P[3]};
+        else if constexpr (W == 8) *reinterpret_cast<u32x2*>(lds_b + wr_b) = u32x2{P[0], P[1]};
+        else if constexpr (W == 4) *reinterpret_cast<uint32_t*>(lds_b + wr_b) = P[0];
+        else *reinterpret_cast<uint16_t*>(lds_b + wr_b) = static_cast<uint16_t>(P[0]);
+    };
+    Acc acc2 = Acc{0, 0, 0, 0};
+    auto multiply = [&](uint32_t wr_a) {
+        u32x4 b;
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            const uint32_t lo = *reinterpret_cast<const uint16_t*>(lds_b + rd_b[2 * q]);
+            const uint32_t hi = *reinterpret_cast<const uint16_t*>(lds_b + rd_b[2 * q + 1]);
+            b[q] = lo | (hi << 16);
+        }
+        const u32x4 a0 = *reinterpret_cast<const u32x4*>(lds_a + lane * 16);
+        acc = mfma_pack<DT>(a0, b, acc);
+        if constexpr (PK == 2) {
+            const u32x4 a1 = *reinterpret_cast<const u32x4*>(lds_a + 1024 + lane * 16);
+            acc2 = mfma_pack<DT>(a1, b, acc2);
+        }
+        if (owner) *reinterpret_cast<uint16_t*>(lds_a + wr_a) = 0;     // the operands start every round as zeros
+    };
+
+    // Round x of this wave: its slot words and values are requested two steps ahead, the pieces
+    // they name one step ahead; all of it goes to LDS right before the multiply.  Two steps per
+    // loop body, no exit in the middle (a step past the last round multiplies zeros).
+    uint32_t M0, V0, M1, V1, A0, A1;
+    uint32_t P0[RW], P1[RW];
+    int r = w.ks;
+    load_meta(r, M0, V0);
+    load_meta(r + KW, M1, V1);
+    __builtin_amdgcn_sched_barrier(0);
+    A0 = load_piece(r, M0, P0);
+    const int iters = (count + 1) >> 1;
+    for (int it = 0; it < iters; ++it) {
+        const uint32_t v0 = V0;
+        load_meta(r + 2 * KW, M0, V0);
+        __builtin_amdgcn_sched_barrier(0);
+        A1 = load_piece(r + KW, M1, P1);
+        __builtin_amdgcn_sched_barrier(0);
+        stash(P0, A0, v0);
+        __builtin_amdgcn_wave_barrier();
+        multiply(A0);
+        __builtin_amdgcn_sched_barrier(0);
+        const uint32_t v1 = V1;
+        load_meta(r + 3 * KW, M1, V1);
+        __builtin_amdgcn_sched_barrier(0);
+        A0 = load_piece(r + 2 * KW, M0, P0);
+        __builtin_amdgcn_sched_barrier(0);
+        stash(P1, A1, v1);
+        __builtin_amdgcn_wave_barrier();
+        multiply(A1);
+        __builtin_amdgcn_sched_barrier(0);
+        r += 2 * KW;
+    }
+    if constexpr (PK == 2) {
+        // columns 8..15 of the second tile are columns 0..7 of the row's result
+        const int from = ((lane + 8) & 63) * 4;
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const float mine = acc2[y];            // a scalar copy: the cast below must see one element
+            acc[y] += __int_as_float(__builtin_amdgcn_ds_bpermute(from, __float_as_int(mine)));
+        }
+    }
+}
+
+// NARROW: 0, or 100 * PK + W of walk_entries_narrow for the entry rows (then NT = SW = NCH = 1).
+template <int NT, int KW, int SW, int NCH, int LMAX, int DT, int NARROW = 0>
 __global__ __launch_bounds__(KW * SW * 64)
 void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ slots, const void* __restrict__ vals,
                  const int32_t* __restrict__ perm, const void* __restrict__ B, uint32_t b_bytes, uint32_t ldb_bytes,
@@ -447,7 +608,14 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
 
     if constexpr (LMAX >= 8) {
         if (cls == 2) walk_row<NT, KW, 8, NCH, DT>(w, rsrc, acc);
-        if (cls == kEntryClass) walk_row<NT, KW, 8, NCH, DT, true>(w, rsrc, acc);
+        if (cls == kEntryClass) {
+            if constexpr (NARROW != 0) {
+                static_assert(NT == 1 && SW == 1 && NCH == 1, "the narrow walk covers one slab of 16 columns");
+                walk_entries_narrow<KW, NARROW / 100, NARROW % 100, DT>(w, rsrc, acc[0]);
+            } else {
+                walk_row<NT, KW, 8, NCH, DT, true>(w, rsrc, acc);
+            }
+        }
     }
     if constexpr (LMAX >= 4) {
         if (cls == 1) walk_row_deep<NT, KW, 4, NCH, DT>(w, rsrc, acc);
@@ -540,7 +708,7 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
     }
 }
 
-template <int NT, int KW, int SW, int NCH, int LMAX, int DT>
+template <int NT, int KW, int SW, int NCH, int LMAX, int DT, int NARROW = 0>
 static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
                           int64_t N, hipStream_t stream)
 {
@@ -558,7 +726,7 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, void*
     // not push it out: then C is stored past the cache (measured: -7 % where B is 4 MiB, no gain
     // or a loss where B is 16 MiB and more).
     if (static_cast<double>(d.K) * static_cast<double>(N) * ES <= 8.0e6) stream_hint |= 2;
-    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, DT>), grid, dim3(KW * SW * 64), 0, stream,
+    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, DT, NARROW>), grid, dim3(KW * SW * 64), 0, stream,
                        d.work, d.slots, d.vals, d.perm, B, b_bytes, static_cast<uint32_t>(ldb * ES), static_cast<uint32_t>(d.K),
                        static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());

@@ -608,6 +608,65 @@ def test_binding_checks_device_operands_before_launching():
     m.close()
 
 
+def _rows_of_few_entries(M, K, per_row, seed, dtype):
+    """M x K with per_row entries per row at random columns (duplicates dropped), small integers."""
+    from workloads import to_bits
+    rng = np.random.default_rng([seed, 77, M, K])
+    cols = np.sort(rng.integers(0, K, size=(M, per_row)), axis=1)
+    keep = np.ones(cols.shape, dtype=bool)
+    keep[:, 1:] = cols[:, 1:] != cols[:, :-1]
+    row_ptr = np.concatenate([[0], np.cumsum(keep.sum(axis=1))]).astype(np.int64)
+    col_idx = cols[keep].astype(np.int32)
+    v = rng.integers(1, 5, size=col_idx.size) * rng.choice([-1.0, 1.0], size=col_idx.size)
+    b = rng.integers(-4, 5, size=(K, 16)).astype(np.float64)
+    return row_ptr, col_idx, to_bits(v, dtype), to_bits(b, dtype)
+
+
+# rows, entries per row, waves per block row the launch is expected to pick
+FEW_COLUMN_SHAPES = [(98304 - 5, 12, 1), (49152 - 3, 22, 2), (16384, 64, 4)]
+
+
+@pytest.mark.parametrize("shape", FEW_COLUMN_SHAPES, ids=lambda s: f"{s[0]}x{s[1]}")
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_few_columns_take_one_piece_of_b_per_lane(shape, dtype, oracle_c):
+    # Matrices kept by entry with more than 24576 packs: at N = 1, 2, 4, 8, 16 with rows of B
+    # aligned to the piece the launch takes the variant that loads one piece per lane ("_t8", "_t16");
+    # other N, rows that do not start on a multiple of the piece, or a view that starts off it take
+    # the general walk.  Small integers: every result is exact, so a misplaced entry, a wrong row
+    # number or a wrong half of a tile cannot hide.  The last rows of B are named by entries, and
+    # the padding between rows holds NaN.
+    M, per_row, kw = shape
+    K = 50000 + M % 1000
+    row_ptr, col_idx, a_bits, b16 = _rows_of_few_entries(M, K, per_row, seed=per_row, dtype=dtype)
+    m = S.SmatMatrix(M, K, row_ptr, col_idx, a_bits, dtype)
+    assert S.smat_get_layout_info(m.handle)["n_packs"] >= 24576
+    a = R.decode16(a_bits, dtype)
+    b_full = R.decode16(b16, dtype).reshape(K, 16)
+    cases = [(1, 1, 0), (2, 2, 0), (4, 4, 0), (8, 8, 0), (16, 16, 0),      # N, ldb, first column of the view
+             (8, 24, 0), (2, 6, 0), (16, 40, 8), (1, 3, 1),                 # aligned rows inside a wider array
+             (5, 5, 0), (12, 12, 0), (3, 8, 0),                             # other N: the general walk
+             (8, 12, 0), (4, 6, 0), (8, 16, 4), (2, 3, 0)]                  # rows or view off the piece
+    for N, ldb, first in cases:
+        piece = 16 if N == 16 else 2 * N
+        narrow = N in (1, 2, 4, 8, 16) and (2 * ldb) % piece == 0 and (2 * first) % piece == 0
+        full = torch.full((K, ldb), 0x7E00, dtype=torch.int16)
+        full[:, first:first + N] = torch.from_numpy(b16.view(np.int16).reshape(K, 16)[:, :N].copy())
+        b = full.cuda()[:, first:first + N]
+        c = torch.full((M, N + 1), float("nan"), dtype=torch.float32, device="cuda")
+        S.smat_spmm(m.handle, b, c[:, :N], N)
+        torch.cuda.synchronize()
+        name = S.smat_last_kernel()
+        if narrow:
+            assert f"_t{16 if N == 16 else 8}w{piece}k{kw}" in name, (N, ldb, first, name)
+        else:
+            assert "_n1k" in name or "_n2k" in name or "_n4k" in name, (N, ldb, first, name)
+        got = c.cpu().numpy()
+        assert np.isnan(got[:, N]).all()
+        c_ref, _ = oracle_c.spmm_ref_c(M, K, N, row_ptr, col_idx, a, np.ascontiguousarray(b_full[:, :N]))
+        assert np.array_equal(got[:, :N].astype(np.float64), c_ref), (N, ldb, first, name)
+    m.close()
+
+
 def test_wide_and_odd_output_widths(oracle_c):
     # thousands of columns that are no multiple of anything: many column slabs per block row, the
     # narrowest loads, a leading dimension far larger than N
