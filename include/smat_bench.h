@@ -38,7 +38,7 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
                                  void *dC, int64_t ldc, int64_t N, void *stream);
 
 /*
- * Probes: three kernels that measure what the device delivers for the access patterns the SpMM
+ * Probes: four kernels that measure what the device delivers for the access patterns the SpMM
  * kernels are made of (bench.py --probes times them and prints the rates next to the
  * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.
  *
@@ -47,6 +47,12 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
  *                      (uint32[waves * packs * 32], row numbers into a table of row_bytes-byte
  *                      rows): 16 lanes x bytes_per_lane (8 or 16) bytes from the start of
  *                      every row, eight row loads in flight per lane as in the SpMM kernel
+ *   smat_probe_pieces  every lane of `waves` wavefronts fetches `per_lane` pieces of
+ *                      bytes_per_lane (2, 4, 8 or 16) bytes, one from the start of each row named
+ *                      by dev_idx (uint32[waves * per_lane * 64], row numbers into a table of
+ *                      row_bytes-byte rows; row_bytes a multiple of bytes_per_lane; per_lane a
+ *                      multiple of 4): the fetch of the SpMM kernel at N = 1, 2, 4, 8, 16,
+ *                      where a lane loads the whole piece of the row of B of one entry
  *   smat_probe_mfma    workgroups x 4 waves issue iters x 16 MFMA 16x16x32 (fp16) each on
  *                      register operands: 2 * 16*16*32 flop per instruction and wave
  *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
@@ -54,6 +60,8 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
 smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
 smat_status_t smat_probe_gather(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
                                 int packs, int bytes_per_lane, void *dev_sink, void *stream);
+smat_status_t smat_probe_pieces(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
+                                int per_lane, int bytes_per_lane, void *dev_sink, void *stream);
 smat_status_t smat_probe_mfma(int workgroups, int iters, void *dev_sink, void *stream);
 
 #ifdef __cplusplus

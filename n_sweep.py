@@ -85,10 +85,31 @@ def main():
                 err = np.abs(got[k] - ref)
                 assert np.all(err <= 1e-2 * bound + 1e-30), f"parity failed: {name} N={N} row {r}"
                 worst = max(worst, float(np.max(err / np.maximum(bound, 1e-300))))
+            # where the launch took the walk with one piece of B per lane and entry: the time of
+            # nothing but that fetch (as many random pieces of the same size out of a table of B's size)
+            bare = None
+            if "_t8w" in S.smat_last_kernel() or "_t16w" in S.smat_last_kernel():
+                piece = min(N * es, 16)          # N = 16: the second half of a row comes from the same cache line
+                per_lane = 16
+                waves = max(1, layout["n_columns"] // (64 * per_lane))
+                idx = torch.from_numpy(rng.integers(0, w.K, size=waves * per_lane * 64, dtype=np.int64).astype(np.int32)).to(dev)
+                sink = torch.zeros(4, dtype=torch.int32, device=dev)
+                S.smat_probe_pieces(B, N * es, idx, waves, per_lane, piece, sink, stream)       # checks idx against B
+                for _ in range(3):
+                    S.smat_probe_pieces(B, N * es, idx, waves, per_lane, piece, sink, stream, checked=True)
+                torch.cuda.synchronize()
+                e0.record(stream)
+                for _ in range(args.reps):
+                    S.smat_probe_pieces(B, N * es, idx, waves, per_lane, piece, sink, stream, checked=True)
+                e1.record(stream)
+                torch.cuda.synchronize()
+                bare = e0.elapsed_time(e1) / args.reps * 1e-3
+                del idx
             moved = layout["value_bytes"] + layout["table_bytes"] + w.K * N * es + w.M * N * 4
             rec = {"config": name, "dtype": w.dtype, "N": N, "seconds": sec, "kernel": S.smat_last_kernel(),
                    "useful_tflops": 2.0 * w.nnz * N / sec / 1e12, "bytes_alg": moved, "hbm_gbs": moved / sec / 1e9,
-                   "b_gather_bytes": layout["n_columns"] * N * es, "max_err_over_bound": worst}
+                   "b_gather_bytes": layout["n_columns"] * N * es, "max_err_over_bound": worst,
+                   "bare_piece_fetch_seconds": bare}
             emit(rec)
             table.setdefault(name, []).append(rec)
             del B, C
@@ -97,9 +118,11 @@ def main():
         torch.cuda.empty_cache()
 
     for name, recs in table.items():
-        print(f"\n{name}\n| N | kernel | us | useful TFLOP/s | bytes_alg GB/s | gathered B MB |\n|---|---|---|---|---|---|")
+        print(f"\n{name}\n| N | kernel | us | useful TFLOP/s | bytes_alg GB/s | gathered B (MB) | bare fetch of the pieces (us) |\n|---|---|---|---|---|---|---|")
         for r in recs:
-            print(f"| {r['N']} | `{r['kernel']}` | {r['seconds']*1e6:.1f} | {r['useful_tflops']:.2f} | {r['hbm_gbs']:.0f} | {r['b_gather_bytes']/1e6:.0f} |")
+            bare = r.get("bare_piece_fetch_seconds")
+            print(f"| {r['N']} | `{r['kernel']}` | {r['seconds']*1e6:.1f} | {r['useful_tflops']:.2f} | {r['hbm_gbs']:.0f} | "
+                  f"{r['b_gather_bytes']/1e6:.0f} | {'' if bare is None else format(bare * 1e6, '.1f')} |")
     if out:
         out.close()
 

@@ -1,6 +1,6 @@
-// Three small kernels that measure what this GPU delivers for the access patterns the SpMM
+// Four small kernels that measure what this GPU delivers for the access patterns the SpMM
 // kernels consist of, so that the figures quoted next to the rooflines can be reproduced:
-// a streaming read, a random gather of rows (the way rows of B are fetched), and a
+// a streaming read, two random gathers of rows (the ways rows of B are fetched), and a
 // register-resident MFMA loop.  They compute nothing of the method.
 #include <hip/hip_runtime.h>
 
@@ -58,6 +58,32 @@ __global__ __launch_bounds__(64) void probe_gather_kernel(const unsigned char* _
     if (acc == 0x12345678u) sink[0] = 1u;
 }
 
+// One wave per workgroup; every lane fetches per_lane pieces of VEC bytes, piece x of lane l from
+// the start of row idx[(wave * per_lane + x) * 64 + l], four loads in flight per lane.
+template <int VEC>
+__global__ __launch_bounds__(64) void probe_pieces_kernel(const unsigned char* __restrict__ table, uint32_t row_bytes,
+                                                          const uint32_t* __restrict__ idx, int per_lane, uint32_t* sink)
+{
+    const uint32_t* my = idx + static_cast<size_t>(blockIdx.x) * per_lane * 64 + threadIdx.x;
+    uint32_t acc = 0u;
+    for (int x = 0; x < per_lane; x += 4) {
+        uint32_t v[4][VEC >= 4 ? VEC / 4 : 1];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const unsigned char* at = table + static_cast<size_t>(my[(x + u) * 64]) * row_bytes;
+            if constexpr (VEC == 2) v[u][0] = *reinterpret_cast<const uint16_t*>(at);
+            else if constexpr (VEC == 4) v[u][0] = *reinterpret_cast<const uint32_t*>(at);
+            else if constexpr (VEC == 8) { const u32x2 t = *reinterpret_cast<const u32x2*>(at); v[u][0] = t[0]; v[u][1] = t[1]; }
+            else { const u32x4 t = *reinterpret_cast<const u32x4*>(at); v[u][0] = t[0]; v[u][1] = t[1]; v[u][2] = t[2]; v[u][3] = t[3]; }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+#pragma unroll
+            for (int y = 0; y < (VEC >= 4 ? VEC / 4 : 1); ++y) acc ^= v[u][y];
+    }
+    if ((acc & 0xFFFFu) == 0x5678u) sink[0] = 1u;              // never true for the probe's data; keeps the loads
+}
+
 // 16 independent accumulators per wave, operands in registers: nothing but MFMA 16x16x32
 __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
 {
@@ -101,6 +127,23 @@ smat_status_t smat_probe_gather(const void* dev_table, uint32_t row_bytes, const
     else
         hipLaunchKernelGGL(probe_gather_kernel<16>, dim3(waves), dim3(64), 0, s, static_cast<const unsigned char*>(dev_table),
                            row_bytes, dev_idx, packs, static_cast<uint32_t*>(dev_sink));
+    return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
+}
+
+smat_status_t smat_probe_pieces(const void* dev_table, uint32_t row_bytes, const uint32_t* dev_idx, int waves, int per_lane,
+                                int bytes_per_lane, void* dev_sink, void* stream)
+{
+    if (!dev_table || !dev_idx || !dev_sink || waves <= 0 || per_lane <= 0 || per_lane % 4 != 0) return SMAT_ERR_INVALID_ARG;
+    const int v = bytes_per_lane;
+    if ((v != 2 && v != 4 && v != 8 && v != 16) || row_bytes < static_cast<uint32_t>(v) || row_bytes % static_cast<uint32_t>(v) != 0)
+        return SMAT_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const unsigned char* table = static_cast<const unsigned char*>(dev_table);
+    uint32_t* sink = static_cast<uint32_t*>(dev_sink);
+    if (v == 2) hipLaunchKernelGGL(probe_pieces_kernel<2>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
+    else if (v == 4) hipLaunchKernelGGL(probe_pieces_kernel<4>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
+    else if (v == 8) hipLaunchKernelGGL(probe_pieces_kernel<8>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
+    else hipLaunchKernelGGL(probe_pieces_kernel<16>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
     return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
 }
 

@@ -73,6 +73,8 @@ def _load():
     lib.smat_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
     lib.smat_probe_gather.restype = ctypes.c_int
     lib.smat_probe_gather.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.smat_probe_pieces.restype = ctypes.c_int
+    lib.smat_probe_pieces.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_probe_mfma.restype = ctypes.c_int
     lib.smat_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_get_layout_info.restype = ctypes.c_int
@@ -324,6 +326,21 @@ def smat_probe_gather(table, row_bytes, idx, waves, packs, bytes_per_lane, sink,
     """table: device bytes of rows; idx: device int32/uint32 tensor [waves * packs * 32] of row numbers."""
     _check(_lib.smat_probe_gather(ctypes.c_void_p(table.data_ptr()), row_bytes, ctypes.c_void_p(idx.data_ptr()),
                                   waves, packs, bytes_per_lane, ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
+
+
+def smat_probe_pieces(table, row_bytes, idx, waves, per_lane, bytes_per_lane, sink, stream=None, checked=False):
+    """table: device bytes of rows; idx: device int32/uint32 tensor [waves * per_lane * 64] of row numbers.
+    Unless `checked` (the caller has made this call before with the same table and idx), verifies
+    with a device sync that every named row lies inside the table before launching."""
+    if idx.numel() < waves * per_lane * 64 or idx.element_size() != 4:
+        raise ValueError("smat_probe_pieces: idx holds fewer than waves * per_lane * 64 32-bit row numbers")
+    if not checked:
+        rows = table.numel() * table.element_size() // row_bytes
+        lo, hi = int(idx.min()), int(idx.max())
+        if lo < 0 or hi >= rows:
+            raise ValueError("smat_probe_pieces: a row number lies outside the table")
+    _check(_lib.smat_probe_pieces(ctypes.c_void_p(table.data_ptr()), row_bytes, ctypes.c_void_p(idx.data_ptr()),
+                                  waves, per_lane, bytes_per_lane, ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
 
 
 def smat_probe_mfma(workgroups, iters, sink, stream=None):

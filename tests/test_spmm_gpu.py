@@ -342,8 +342,19 @@ def test_probe_kernels_run():
     S.smat_probe_gather(buf, 256, idx, 64, 3, 16, sink)
     S.smat_probe_gather(buf, 256, idx, 64, 3, 8, sink)
     S.smat_probe_mfma(8, 10, sink)
+    pidx = torch.randint(0, (buf.numel() * 4) // 16, (5 * 8 * 64,), dtype=torch.int32).cuda()
+    for piece in (2, 4, 8, 16):
+        S.smat_probe_pieces(buf, 16, pidx, 5, 8, piece, sink)
     torch.cuda.synchronize()
     assert int(sink[0]) == 0
+    with pytest.raises(S.SmatError):
+        S.smat_probe_pieces(buf, 16, pidx, 5, 8, 3, sink)        # no such load
+    with pytest.raises(S.SmatError):
+        S.smat_probe_pieces(buf, 24, pidx // 2, 5, 8, 16, sink)  # rows that do not start on a multiple of the piece
+    with pytest.raises(ValueError):
+        S.smat_probe_pieces(buf[:1024], 16, pidx, 5, 8, 16, sink)   # row numbers beyond the table
+    with pytest.raises(ValueError):
+        S.smat_probe_pieces(buf, 16, pidx, 6, 8, 16, sink)       # more pieces than row numbers
     with pytest.raises(S.SmatError):
         S.smat_probe_gather(buf, 64, idx, 64, 3, 16, sink)        # rows shorter than 16 lanes x 16 bytes
     with pytest.raises(S.SmatError):
