@@ -96,6 +96,17 @@ def run_probes(S, torch, dev, stream):
     wgs, iters = 2048, 1000
     sec = timed(lambda: S.smat_probe_mfma(wgs, iters, sink, stream), reps=5)
     out["mfma_16x16x32_f16_tflops"] = wgs * 4 * iters * 16 * 2.0 * 16 * 16 * 32 / sec / 1e12
+    # the step of the 16-bit tile kernel on L1-resident data, put together piece by piece (256 workgroups of two
+    # wave groups, 66 steps each: a tile of 132 steps)
+    buf = torch.zeros(1 << 18, dtype=torch.int32, device=dev)
+    steps = 66
+    labels = {0: "mfma_and_permutes", 1: "plus_value_loads", 2: "plus_lds_reads", 6: "plus_lds_reads_barrier",
+              7: "plus_value_loads_lds_reads_barrier", 14: "plus_lds_reads_barrier_lds_loads", 15: "whole_step",
+              31: "whole_step_loads_in_a_burst"}
+    out["tile_step_tflops"] = {}
+    for parts, label in labels.items():
+        sec = timed(lambda: S.smat_probe_tile_step(256, steps, parts, buf, sink, stream), reps=5)
+        out["tile_step_tflops"][label] = 256 * 8 * steps * 32 * 2.0 * 16 * 16 * 32 / sec / 1e12
     return out
 
 

@@ -38,7 +38,7 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
                                  void *dC, int64_t ldc, int64_t N, void *stream);
 
 /*
- * Probes: four kernels that measure what the device delivers for the access patterns the SpMM
+ * Probes: five kernels that measure what the device delivers for the access patterns the SpMM
  * kernels are made of (bench.py --probes times them and prints the rates next to the
  * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.
  *
@@ -55,6 +55,14 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
  *                      where a lane loads the whole piece of the row of B of one entry
  *   smat_probe_mfma    workgroups x 4 waves issue iters x 16 MFMA 16x16x32 (fp16) each on
  *                      register operands: 2 * 16*16*32 flop per instruction and wave
+ *   smat_probe_tile_step  workgroups x 8 waves run `steps` (a multiple of 3) steps of the 16-bit tile
+ *                      kernel's loop on data that stays in the L1 (dev_buf, at least 1 MiB, read only):
+ *                      per wave and step 32 MFMA 16x16x32 with four byte permutes per operand, plus the
+ *                      parts named by the bits of `parts`: 1 = four 1 KiB loads of block values into a
+ *                      register ring, 2 = eight 16-byte LDS reads of the panel, 4 = the barrier, 8 = two
+ *                      1 KiB loads straight into LDS, 16 = the loads issued together behind the barrier
+ *                      instead of between the groups of matrix instructions.  Built for parts = 0, 1, 2,
+ *                      3, 6, 7, 12, 14, 15, 31; 2 * 16*16*32 * 32 flop per wave and step
  *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
  */
 smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
@@ -62,6 +70,8 @@ smat_status_t smat_probe_gather(const void *dev_table, uint32_t row_bytes, const
                                 int packs, int bytes_per_lane, void *dev_sink, void *stream);
 smat_status_t smat_probe_pieces(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
                                 int per_lane, int bytes_per_lane, void *dev_sink, void *stream);
+smat_status_t smat_probe_tile_step(int workgroups, int steps, int parts, const void *dev_buf, size_t bytes,
+                                   void *dev_sink, void *stream);
 smat_status_t smat_probe_mfma(int workgroups, int iters, void *dev_sink, void *stream);
 
 #ifdef __cplusplus

@@ -30,7 +30,8 @@ UNITS = {
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
     "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
-    "probes": ("probes.hip", []),
+    # the tile-step probe is the tile kernel's loop: same flag
+    "probes": ("probes.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
     "ablation": ("ablation.hip", []),
 }
 HEADERS = ["kernels.h", "preprocess.h", "pack_layout.h", "spmm_rows.h", os.path.join("..", "..", "include", "smat.h"),

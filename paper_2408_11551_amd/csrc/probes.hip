@@ -1,10 +1,11 @@
-// Four small kernels that measure what this GPU delivers for the access patterns the SpMM
+// Five small kernels that measure what this GPU delivers for the access patterns the SpMM
 // kernels consist of, so that the figures quoted next to the rooflines can be reproduced:
-// a streaming read, two random gathers of rows (the ways rows of B are fetched), and a
-// register-resident MFMA loop.  They compute nothing of the method.
+// a streaming read, two random gathers of rows (the ways rows of B are fetched), a
+// register-resident MFMA loop, and the step of the tile kernel put together piece by piece.  They compute nothing of the method.
 #include <hip/hip_runtime.h>
 
 #include <cstdint>
+#include <type_traits>
 
 #include "../../include/smat_bench.h"
 
@@ -14,6 +15,9 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) void lds_void;
 
 // every thread reads eight 16-byte words per pass; a wave covers eight contiguous KiB
 __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ src, size_t n16, uint32_t* sink)
@@ -102,6 +106,111 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
     if (s == -1.f) sink[0] = s;
 }
 
+// The step of the 16-bit tile kernel (kernels_dense.hip) on data that never leaves the L1: two
+// groups of four waves, per wave and step 32 MFMA 16x16x32 (four block rows x eight groups of 16
+// columns) whose right operands are built with four byte permutes each.  PARTS adds the rest of a
+// step bit by bit: 1 = the four 1 KiB loads of block values into a register ring of three, 2 = the
+// eight 16-byte LDS reads of the panel, 4 = the barrier, 8 = the two 1 KiB loads straight into LDS,
+// 16 = all loads of a step issued together behind the barrier instead of one after each group of
+// matrix instructions.  The rate it reaches says what the structure of the step costs when memory
+// costs nothing.
+template <int OFFSET>
+__device__ __forceinline__ u32x4 probe_lds_read16(uint32_t addr)
+{
+    u32x4 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
+__device__ __forceinline__ void probe_lds_reads_done(u32x4 (&R)[8])
+{
+    asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(R[0]), "+v"(R[1]), "+v"(R[2]), "+v"(R[3]), "+v"(R[4]), "+v"(R[5]), "+v"(R[6]), "+v"(R[7]));
+}
+__device__ __forceinline__ u32x4 probe_ld16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
+{
+    const i32x4 v = __builtin_amdgcn_raw_buffer_load_b128(r, voff, soff, 0);
+    return u32x4{static_cast<uint32_t>(v[0]), static_cast<uint32_t>(v[1]), static_cast<uint32_t>(v[2]), static_cast<uint32_t>(v[3])};
+}
+
+constexpr uint32_t kTileStepBytes = 1u << 20;      // what the probe reads from (all of it stays in the L1/L2)
+
+template <int PARTS>
+__global__ __launch_bounds__(512) __attribute__((amdgpu_waves_per_eu(2, 2)))
+void probe_tile_step_kernel(int steps, const u32x4* __restrict__ src, float* sink)
+{
+    __shared__ u32x4 lds[2 * 3 * 512];             // per group a ring of three 8 KiB panels
+    const int lane = threadIdx.x & 63, wave = (threadIdx.x >> 6) & 3, kg = threadIdx.x >> 8;
+    const __amdgpu_buffer_rsrc_t rs = __builtin_amdgcn_make_buffer_rsrc(const_cast<u32x4*>(src), 0, static_cast<int>(kTileStepBytes), 0x00020000);
+    for (int k = threadIdx.x; k < 2 * 3 * 512; k += 512) lds[k] = u32x4{0u, 0u, 0u, 0u};
+    __syncthreads();
+    const uint32_t lds_base =
+        static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)lds)) + kg * 3 * 8192;
+    const uint32_t rd = lds_base + (lane >> 4) * 2048 + (lane & 15) * 16;
+    u32x4 a[3][4];
+    for (int u = 0; u < 3; ++u)
+        for (int r = 0; r < 4; ++r) a[u][r] = probe_ld16(rs, lane * 16, (wave * 4 + r) * 1024);
+    u32x4 fixed[8];
+    for (int k = 0; k < 8; ++k) fixed[k] = probe_ld16(rs, lane * 16, 16384 + k * 1024);
+    f32x4 acc[4][8];
+    for (int r = 0; r < 4; ++r)
+        for (int x = 0; x < 8; ++x) acc[r][x] = f32x4{0.f, 0.f, 0.f, 0.f};
+    auto step = [&](auto uc, int s) {
+        constexpr int u = decltype(uc)::value;
+        // the loads of this step's data were issued two steps ago: all but the youngest step's have to be back
+        if constexpr ((PARTS & 9) == 9) asm volatile("s_waitcnt vmcnt(6)");
+        else if constexpr (PARTS & 8) asm volatile("s_waitcnt vmcnt(2)");
+        else if constexpr (PARTS & 1) asm volatile("s_waitcnt vmcnt(4)");
+        if constexpr (PARTS & 4) __builtin_amdgcn_s_barrier();
+        u32x4 R[8];
+        if constexpr (PARTS & 2) {
+            const uint32_t p = rd + u * 8192;
+            R[0] = probe_lds_read16<0>(p); R[1] = probe_lds_read16<256>(p); R[2] = probe_lds_read16<512>(p); R[3] = probe_lds_read16<768>(p);
+            R[4] = probe_lds_read16<1024>(p); R[5] = probe_lds_read16<1280>(p); R[6] = probe_lds_read16<1536>(p); R[7] = probe_lds_read16<1792>(p);
+            probe_lds_reads_done(R);
+        } else {
+#pragma unroll
+            for (int k = 0; k < 8; ++k) R[k] = fixed[k];
+        }
+        const uint32_t soff = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(((s & 7) * 16 + wave * 4) * 1024));
+        auto issue = [&](int x) {
+            if constexpr (PARTS & 8)
+                if (x < 2)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(uintptr_t)(lds_base + ((u + 2) % 3) * 8192 + x * 4096 + wave * 1024),
+                                                             16, lane * 16, 32768 + wave * 1024 + x * 4096, 0, 0);
+            if constexpr (PARTS & 1)
+                if (x >= 2 && x < 6) a[(u + 2) % 3][x - 2] = probe_ld16(rs, lane * 16, soff + (x - 2) * 1024);
+        };
+        if constexpr (PARTS & 16) {
+            for (int x = 0; x < 6; ++x) issue(x);
+            __builtin_amdgcn_sched_barrier(0);
+        }
+#pragma unroll
+        for (int x = 0; x < 8; ++x) {
+            const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
+            u32x4 b;
+#pragma unroll
+            for (int q = 0; q < 4; ++q) b[q] = __builtin_amdgcn_perm(R[2 * q + 1][x >> 1], R[2 * q][x >> 1], pick);
+#pragma unroll
+            for (int r = 0; r < 4; ++r)
+                acc[r][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u][r]), __builtin_bit_cast(bf16x8, b), acc[r][x], 0, 0, 0);
+            __builtin_amdgcn_sched_barrier(0);
+            if constexpr (!(PARTS & 16)) {
+                if (x < 6) issue(x);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+        }
+    };
+    for (int s = 0; s < steps; s += 3) {           // every wave runs the same number of steps: the barriers match
+        step(std::integral_constant<int, 0>{}, s);
+        step(std::integral_constant<int, 1>{}, s + 1);
+        step(std::integral_constant<int, 2>{}, s + 2);
+    }
+    asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)");
+    float sum = 0.f;
+    for (int r = 0; r < 4; ++r)
+        for (int x = 0; x < 8; ++x) sum += acc[r][x][0] + acc[r][x][3];
+    if (sum == -1.2345f) sink[0] = sum;
+}
+
 }  // namespace
 
 extern "C" {
@@ -144,6 +253,25 @@ smat_status_t smat_probe_pieces(const void* dev_table, uint32_t row_bytes, const
     else if (v == 4) hipLaunchKernelGGL(probe_pieces_kernel<4>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
     else if (v == 8) hipLaunchKernelGGL(probe_pieces_kernel<8>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
     else hipLaunchKernelGGL(probe_pieces_kernel<16>, dim3(waves), dim3(64), 0, s, table, row_bytes, dev_idx, per_lane, sink);
+    return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
+}
+
+smat_status_t smat_probe_tile_step(int workgroups, int steps, int parts, const void* dev_buf, size_t bytes, void* dev_sink,
+                                   void* stream)
+{
+    if (workgroups <= 0 || steps <= 0 || steps % 3 != 0 || !dev_buf || !dev_sink || bytes < kTileStepBytes)
+        return SMAT_ERR_INVALID_ARG;
+    hipStream_t s = static_cast<hipStream_t>(stream);
+    const u32x4* src = static_cast<const u32x4*>(dev_buf);
+    float* sink = static_cast<float*>(dev_sink);
+#define SMAT_TILE_STEP(P) \
+    case P: hipLaunchKernelGGL(probe_tile_step_kernel<P>, dim3(workgroups), dim3(512), 0, s, steps, src, sink); break
+    switch (parts) {
+    SMAT_TILE_STEP(0); SMAT_TILE_STEP(1); SMAT_TILE_STEP(2); SMAT_TILE_STEP(3); SMAT_TILE_STEP(6); SMAT_TILE_STEP(7);
+    SMAT_TILE_STEP(12); SMAT_TILE_STEP(14); SMAT_TILE_STEP(15); SMAT_TILE_STEP(31);
+    default: return SMAT_ERR_INVALID_ARG;
+    }
+#undef SMAT_TILE_STEP
     return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
 }
 

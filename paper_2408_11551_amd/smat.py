@@ -75,6 +75,8 @@ def _load():
     lib.smat_probe_gather.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_probe_pieces.restype = ctypes.c_int
     lib.smat_probe_pieces.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
+    lib.smat_probe_tile_step.restype = ctypes.c_int
+    lib.smat_probe_tile_step.argtypes = [ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, ctypes.c_size_t, vp, vp]
     lib.smat_probe_mfma.restype = ctypes.c_int
     lib.smat_probe_mfma.argtypes = [ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_get_layout_info.restype = ctypes.c_int
@@ -341,6 +343,12 @@ def smat_probe_pieces(table, row_bytes, idx, waves, per_lane, bytes_per_lane, si
             raise ValueError("smat_probe_pieces: a row number lies outside the table")
     _check(_lib.smat_probe_pieces(ctypes.c_void_p(table.data_ptr()), row_bytes, ctypes.c_void_p(idx.data_ptr()),
                                   waves, per_lane, bytes_per_lane, ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
+
+
+def smat_probe_tile_step(workgroups, steps, parts, buf, sink, stream=None):
+    """buf: device tensor of at least 1 MiB (read only); parts: bit set of the pieces of the tile kernel's step."""
+    _check(_lib.smat_probe_tile_step(workgroups, steps, parts, ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
+                                     ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
 
 
 def smat_probe_mfma(workgroups, iters, sink, stream=None):

@@ -359,6 +359,15 @@ def test_probe_kernels_run():
         S.smat_probe_gather(buf, 64, idx, 64, 3, 16, sink)        # rows shorter than 16 lanes x 16 bytes
     with pytest.raises(S.SmatError):
         S.smat_probe_mfma(0, 10, sink)
+    for parts in (0, 7, 15, 31):
+        S.smat_probe_tile_step(4, 6, parts, buf, sink)
+    torch.cuda.synchronize()
+    with pytest.raises(S.SmatError):
+        S.smat_probe_tile_step(4, 7, 15, buf, sink)               # steps come in threes
+    with pytest.raises(S.SmatError):
+        S.smat_probe_tile_step(4, 6, 5, buf, sink)                # a combination that is not built
+    with pytest.raises(S.SmatError):
+        S.smat_probe_tile_step(4, 6, 15, buf[:1000], sink)        # less than the 1 MiB the probe reads from
 
 
 def test_empty_and_degenerate_inputs(oracle_c):
