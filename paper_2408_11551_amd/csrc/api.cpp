@@ -57,6 +57,7 @@ struct smat_handle {
     std::vector<uint32_t> step_rows, step_base;
     std::vector<uint8_t> row_dense;      // [nbr]
     uint64_t dense_slots = 0;
+    bool dense_all_full = false;         // every step of every dense super row: all sixteen block rows, block columns 2q and 2q+1
     int64_t dense_columns = 0;           // occupied columns over the blocks of the dense super rows
     smat::DeviceBcsr dev;                // launch over every block row
     smat::DeviceBcsr dev_rest;           // launch over the block rows the dense path does not cover
@@ -152,7 +153,9 @@ void plan_dense_tiles(smat_handle& h)
     const int64_t nbr = b.nbr;
     h.row_dense.assign(static_cast<size_t>(nbr), 0);
     h.step_ptr.assign(1, 0);
+    h.dense_all_full = false;
     if (h.dense_mode < 0) return;
+    h.dense_all_full = true;             // until a step says otherwise
     std::vector<int32_t> uni;
     // block columns per step: the 32 k slots of a 16-bit MFMA are two block columns; the 8-bit types
     // take four per step (two MFMA 16x16x32 per output tile between barriers), so that a step moves
@@ -184,6 +187,7 @@ void plan_dense_tiles(smat_handle& h)
                     if (std::binary_search(first, last, cols[e])) rows |= 1u << j;
             }
             for (int64_t e = 0; e < cps; ++e) h.step_cols.push_back(cols[e]);
+            if (rows != 0xFFFFu || cps != 2 || cols[0] != 2 * q || cols[1] != 2 * q + 1) h.dense_all_full = false;
             h.step_rows.push_back(rows);
             h.step_base.push_back(static_cast<uint32_t>(h.dense_slots));
             h.dense_slots += static_cast<uint64_t>(__builtin_popcount(rows));
@@ -609,6 +613,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.n = static_cast<int32_t>(h->dense_super.size());
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
         tiles.cols_per_step = h->elem_bytes == 1 ? 4 : 2;
+        tiles.all_full = h->dense_all_full && tiles.n > 0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);

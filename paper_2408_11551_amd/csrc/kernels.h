@@ -54,6 +54,8 @@ struct DenseTiles {
     int32_t n = 0;
     double mean_steps = 0;                 // steps per super row, on average
     int cols_per_step = 2;
+    bool all_full = false;                 // 16-bit types: every step has all sixteen block rows and the block columns 2q, 2q+1
+                                           // (q counted inside the super row), so the kernel needs none of the per-step tables
 };
 
 // Sets n16 16-byte words at dst to zero.

@@ -448,7 +448,7 @@ __device__ __forceinline__ void lds_reads_done(u32x4 (&R)[8])
                  : "+v"(R[0]), "+v"(R[1]), "+v"(R[2]), "+v"(R[3]), "+v"(R[4]), "+v"(R[5]), "+v"(R[6]), "+v"(R[7]));
 }
 
-template <int DT, int KG>
+template <int DT, int KG, bool FULL = false>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
 void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* __restrict__ B, uint32_t b_bytes,
@@ -526,6 +526,16 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         // nothing is computed from the loaded words here: they are first looked at a step later,
         // so the wave does not wait for the scalar loads
         StepMeta m;
+        if constexpr (FULL) {
+            // a matrix all of whose blocks are stored: step q of the super row has the block columns
+            // 2q and 2q+1 and a block of every block row -- nothing to look up (3 % of a launch)
+            const int rel = static_cast<int>(q) - q_first;
+            m.c0 = 2 * rel;
+            m.c1 = 2 * rel + 1;
+            m.rows = 0xFFFFu;
+            m.base = first_slot + 16u * static_cast<uint32_t>(static_cast<int>(q) - q0);
+            return m;
+        }
         m.c0 = step_cols[2 * q];
         m.c1 = step_cols[2 * q + 1];
         m.rows = step_rows[q];
@@ -717,8 +727,12 @@ static void launch_tile16(const DeviceBcsr& d, const DenseTiles& t, int ks, cons
     order.n_slab = static_cast<int>((N + 127) / 128);
     order.per_xcd = (order.n_super * order.n_slab + 7) / 8;
     dim3 grid(static_cast<unsigned>(8 * order.per_xcd), 1, static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
-                       static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
+    if (t.all_full)
+        hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG, true>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
+                           static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
+    else
+        hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG, false>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
+                           static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
 }
 
 template <int DT, int RING, int KG>
