@@ -391,6 +391,11 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 //     panel rows with one instruction and no register is spent on staging), into a ring of three
 //     panels, two steps ahead;
 //   * the block values sit in a register ring of three steps, two steps ahead;
+//   * the right operand of a matrix instruction -- eight k-consecutive values of one column per
+//     lane, out of a panel that holds rows of B -- comes from two transposing LDS reads
+//     (ds_read_b64_tr_b16) per group of sixteen columns, asked for one group ahead of its use: no
+//     byte permutes, no registers for the panel's rows, and the first matrix instruction of a step
+//     waits for two reads instead of eight (a 4096 x 4096 x 2048 product: 70 -> 63 us);
 //   * every thread waits for its own loads of the step (in-order counter: all but the youngest
 //     six), one barrier makes the panel visible, and the loads of the next two steps stay in
 //     flight across it -- twelve KiB per wave;
@@ -434,18 +439,24 @@ __device__ __forceinline__ void load_to_lds16(lds_void* lds_addr, __amdgpu_buffe
 // for.  The panel's arrival is awaited by hand and made visible by a barrier.  (None of the
 // assembly statements of this kernel claims to touch memory: the compiler would then no longer
 // fetch the per-step tables with scalar loads, and its vector loads would wait for everything.)
+//
+// Transposing read (gfx950): every lane names eight bytes (four 16-bit elements of one row); inside
+// each group of sixteen lanes, lane i receives element i % 4 of the pieces named by lanes i / 4,
+// i / 4 + 4, i / 4 + 8 and i / 4 + 12, in that order -- four k-consecutive elements of one column
+// when those four lanes name four consecutive rows.
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
 template <int OFFSET>
-__device__ __forceinline__ u32x4 lds_read16(uint32_t addr)
+__device__ __forceinline__ u32x2_t lds_read_tr(uint32_t addr)
 {
-    u32x4 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    u32x2_t v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
     return v;
 }
-// all LDS reads of this wave have returned; the registers named are the ones they filled
-__device__ __forceinline__ void lds_reads_done(u32x4 (&R)[8])
+// the two reads into lo and hi have returned once at most YOUNGER later LDS reads are outstanding
+template <int YOUNGER>
+__device__ __forceinline__ void lds_pair_done(u32x2_t& lo, u32x2_t& hi)
 {
-    asm volatile("s_waitcnt lgkmcnt(0)"
-                 : "+v"(R[0]), "+v"(R[1]), "+v"(R[2]), "+v"(R[3]), "+v"(R[4]), "+v"(R[5]), "+v"(R[6]), "+v"(R[7]));
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(YOUNGER));
 }
 
 template <int DT, int KG, bool FULL = false>
@@ -500,13 +511,25 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
     // step's first and of its second block column.  (N is a multiple of 8 on this path, so a piece is
     // all inside or all outside.)
     const int st_row = 4 * wave + (lane >> 4);
-    const int st_col = n0 + 8 * (lane & 15);
+    // The piece that lands at position p of row r of the panel is piece p ^ 2 (r & 3) of that row of B,
+    // so that the sixteen lanes of a transposing read (four rows x 32 bytes) hit every bank once.
+    const int st_col = n0 + 8 * ((lane & 15) ^ (2 * ((lane >> 4) & 3)));
     const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * 2u : kOutOfRange;
     const uint32_t no_row = static_cast<uint32_t>(d.K);
     const int nbc = static_cast<int>((d.K + 15) >> 4);
     // where this wave's pieces of a panel go (+ 4096 for the second block column), and where this lane reads
     auto lds_of_panel = [&](int buf) { return reinterpret_cast<char*>(&panel_all[kg][buf][4 * wave][0]); };
-    const uint32_t rd_base = lds_offset_of(&panel_all[kg][0][8 * g][i]);            // + 8192 per panel, + 256 per row
+    // Where this lane reads (+ 8192 per panel): lane (g, j) names row 8 g + j / 4 (+ 4 for the second
+    // read, + 1024 bytes) and, for the group of columns 16 x .. 16 x + 15, the eight bytes of columns
+    // 16 x + 4 (j % 4) ..: piece 2 x + (j % 4) / 2 of the row, which lies at position
+    // (2 x + (j % 4) / 2) ^ 2 (j / 4).
+    uint32_t tr_addr[8];
+    {
+        const int e = i >> 2, qq = i & 3;
+#pragma unroll
+        for (int x = 0; x < 8; ++x)
+            tr_addr[x] = lds_offset_of(&panel_all[kg][0][8 * g + e][0]) + 32u * (x ^ e) + 16u * (qq >> 1) + 8u * (qq & 1);
+    }
 
     // What a step's loads need to know, fetched with scalar loads a step before it is used.  A
     // step past the group's last one names no block column (its panel rows read zeros) and no block
@@ -603,35 +626,29 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
             // wave waiting at its load instructions while the matrix units idle (measured: the time of
             // the loads and the time of the matrix instructions added up).  The six loads go out one by
             // one between the groups of matrix instructions below.
-            // B rows of this lane's k range: row 8g + kk, columns 8i .. 8i+7
-            u32x4 R[8];
-            R[0] = lds_read16<8192 * u + 0>(rd_base);
-            R[1] = lds_read16<8192 * u + 256>(rd_base);
-            R[2] = lds_read16<8192 * u + 512>(rd_base);
-            R[3] = lds_read16<8192 * u + 768>(rd_base);
-            R[4] = lds_read16<8192 * u + 1024>(rd_base);
-            R[5] = lds_read16<8192 * u + 1280>(rd_base);
-            R[6] = lds_read16<8192 * u + 1536>(rd_base);
-            R[7] = lds_read16<8192 * u + 1792>(rd_base);
-            lds_reads_done(R);
-            // the tables of step s+5 are asked for only now: scalar loads share the counter the wait
-            // above looks at, and it should not wait for them
+            // Right operands by transposing reads, two per group of sixteen columns (k 0..3 and 4..7 of
+            // the lane group), asked for one group ahead.  (The wait counts LDS reads, which return in
+            // order; scalar loads of the tables that are still out only make it wait longer.)
             const StepMeta next = mt[(u + 2) % RD];
             const bool next_live = is_live(s + 2);
             mt[(u + 2) % RD] = fetch_meta(s + 2 + RD);
             __builtin_amdgcn_sched_barrier(0);
+            u32x2_t lo[2], hi[2];
+            lo[0] = lds_read_tr<8192 * u>(tr_addr[0]);
+            hi[0] = lds_read_tr<8192 * u + 1024>(tr_addr[0]);
 #pragma unroll
             for (int x = 0; x < NT; ++x) {
-                const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
-                u32x4 b;
-#pragma unroll
-                for (int qd = 0; qd < 4; ++qd)
-                    b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
+                if (x + 1 < NT) {
+                    lo[(x + 1) & 1] = lds_read_tr<8192 * u>(tr_addr[(x + 1) & 7]);
+                    hi[(x + 1) & 1] = lds_read_tr<8192 * u + 1024>(tr_addr[(x + 1) & 7]);
+                    lds_pair_done<2>(lo[x & 1], hi[x & 1]);
+                } else {
+                    lds_pair_done<0>(lo[x & 1], hi[x & 1]);
+                }
+                const u32x4 b = u32x4{lo[x & 1][0], lo[x & 1][1], hi[x & 1][0], hi[x & 1][1]};
 #pragma unroll
                 for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
                 __builtin_amdgcn_sched_barrier(0);
-                // one load of step s+2 after each of the first six groups, in the order the wait at the
-                // top of a step counts on: the panel's two, then the four block rows
                 if (x < 2) {
                     load_panel_half(next, next_live, (u + 2) % RD, x);
                 } else if (x < 2 + RM) {
@@ -682,7 +699,7 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         if (kg == 1) return;
     }
 
-    // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 8i + x]
+    // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
     if (ks > 1) {
         // partial tile, row-major 256 x 128 words, at [(tile * ks + z)]
         const size_t tile_at = static_cast<size_t>(sidx) * order.n_slab + slab;
@@ -691,14 +708,14 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         for (int r = 0; r < RM; ++r)
 #pragma unroll
             for (int y = 0; y < 4; ++y) {
-                Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
-                *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
-                *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
+                Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + i;
+#pragma unroll
+                for (int x = 0; x < NT; ++x) dst[16 * x] = acc[r][x][y];
             }
         return;
     }
-    const int col0 = n0 + NT * i;
-    if (col0 >= N) return;
+    // sixteen lanes store 64 consecutive bytes of a row of C; the eight groups of columns of a lane
+    // lie 64 bytes apart
 #pragma unroll
     for (int r = 0; r < RM; ++r) {
         const int64_t br = static_cast<int64_t>(super) * 16 + RM * wave + r;
@@ -706,14 +723,10 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         for (int y = 0; y < 4; ++y) {
             const int64_t out_row = d.perm[br * 16 + 4 * g + y];
             if (out_row < 0) continue;
-            Out* dst = C + out_row * ldc + col0;
-            if (vec_store) {
-                *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
-                *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
-            } else {
+            Out* dst = C + out_row * ldc + n0 + i;
 #pragma unroll
-                for (int x = 0; x < NT; ++x) dst[x] = acc[r][x][y];
-            }
+            for (int x = 0; x < NT; ++x)
+                if (n0 + 16 * x + i < N) dst[16 * x] = acc[r][x][y];
         }
     }
 }
