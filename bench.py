@@ -102,7 +102,8 @@ def run_probes(S, torch, dev, stream):
     steps = 66
     labels = {0: "mfma_and_permutes", 1: "plus_value_loads", 2: "plus_lds_reads", 6: "plus_lds_reads_barrier",
               7: "plus_value_loads_lds_reads_barrier", 14: "plus_lds_reads_barrier_lds_loads", 15: "whole_step",
-              31: "whole_step_loads_in_a_burst"}
+              31: "whole_step_loads_in_a_burst", 32: "mfma_and_transposing_reads", 36: "transposing_reads_barrier",
+              37: "transposing_reads_barrier_value_loads", 45: "whole_step_transposing_reads"}
     out["tile_step_tflops"] = {}
     for parts, label in labels.items():
         sec = timed(lambda: S.smat_probe_tile_step(256, steps, parts, buf, sink, stream), reps=5)

@@ -61,8 +61,10 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
  *                      parts named by the bits of `parts`: 1 = four 1 KiB loads of block values into a
  *                      register ring, 2 = eight 16-byte LDS reads of the panel, 4 = the barrier, 8 = two
  *                      1 KiB loads straight into LDS, 16 = the loads issued together behind the barrier
- *                      instead of between the groups of matrix instructions.  Built for parts = 0, 1, 2,
- *                      3, 6, 7, 12, 14, 15, 31; 2 * 16*16*32 * 32 flop per wave and step
+ *                      instead of between the groups of matrix instructions, 32 = right operands by
+ *                      transposing LDS reads one group of columns ahead instead of part 2 and the
+ *                      permutes.  Built for parts = 0, 1, 2, 3, 6, 7, 12, 14, 15, 31, 32, 36, 37, 45;
+ *                      2 * 16*16*32 * 32 flop per wave and step
  *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
  */
 smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);

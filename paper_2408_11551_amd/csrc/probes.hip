@@ -112,7 +112,9 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
 // step bit by bit: 1 = the four 1 KiB loads of block values into a register ring of three, 2 = the
 // eight 16-byte LDS reads of the panel, 4 = the barrier, 8 = the two 1 KiB loads straight into LDS,
 // 16 = all loads of a step issued together behind the barrier instead of one after each group of
-// matrix instructions.  The rate it reaches says what the structure of the step costs when memory
+// matrix instructions, 32 = the right operands by transposing LDS reads, two per group of sixteen
+// columns and one group ahead, instead of the eight reads of the panel and the permutes (as the
+// kernel does now; replaces part 2).  The rate it reaches says what the structure of the step costs when memory
 // costs nothing.
 template <int OFFSET>
 __device__ __forceinline__ u32x4 probe_lds_read16(uint32_t addr)
@@ -124,6 +126,18 @@ __device__ __forceinline__ u32x4 probe_lds_read16(uint32_t addr)
 __device__ __forceinline__ void probe_lds_reads_done(u32x4 (&R)[8])
 {
     asm volatile("s_waitcnt lgkmcnt(0)" : "+v"(R[0]), "+v"(R[1]), "+v"(R[2]), "+v"(R[3]), "+v"(R[4]), "+v"(R[5]), "+v"(R[6]), "+v"(R[7]));
+}
+template <int OFFSET>
+__device__ __forceinline__ u32x2 probe_lds_read_tr(uint32_t addr)
+{
+    u32x2 v;
+    asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
+template <int YOUNGER>
+__device__ __forceinline__ void probe_lds_pair_done(u32x2& lo, u32x2& hi)
+{
+    asm volatile("s_waitcnt lgkmcnt(%2)" : "+v"(lo), "+v"(hi) : "n"(YOUNGER));
 }
 __device__ __forceinline__ u32x4 probe_ld16(__amdgpu_buffer_rsrc_t r, uint32_t voff, uint32_t soff)
 {
@@ -145,6 +159,11 @@ void probe_tile_step_kernel(int steps, const u32x4* __restrict__ src, float* sin
     const uint32_t lds_base =
         static_cast<uint32_t>(reinterpret_cast<uintptr_t>((__attribute__((address_space(3))) const char*)lds)) + kg * 3 * 8192;
     const uint32_t rd = lds_base + (lane >> 4) * 2048 + (lane & 15) * 16;
+    uint32_t tr[8];                                // transposing reads: where lane (g, j) reads for column group x
+    {
+        const int g = lane >> 4, j = lane & 15, e = j >> 2, q = j & 3;
+        for (int x = 0; x < 8; ++x) tr[x] = lds_base + (8 * g + e) * 256 + 32 * (x ^ e) + 16 * (q >> 1) + 8 * (q & 1);
+    }
     u32x4 a[3][4];
     for (int u = 0; u < 3; ++u)
         for (int r = 0; r < 4; ++r) a[u][r] = probe_ld16(rs, lane * 16, (wave * 4 + r) * 1024);
@@ -160,6 +179,38 @@ void probe_tile_step_kernel(int steps, const u32x4* __restrict__ src, float* sin
         else if constexpr (PARTS & 8) asm volatile("s_waitcnt vmcnt(2)");
         else if constexpr (PARTS & 1) asm volatile("s_waitcnt vmcnt(4)");
         if constexpr (PARTS & 4) __builtin_amdgcn_s_barrier();
+        const uint32_t soff = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(((s & 7) * 16 + wave * 4) * 1024));
+        auto issue = [&](int x) {
+            if constexpr (PARTS & 8)
+                if (x < 2)
+                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(uintptr_t)(lds_base + ((u + 2) % 3) * 8192 + x * 4096 + wave * 1024),
+                                                             16, lane * 16, 32768 + wave * 1024 + x * 4096, 0, 0);
+            if constexpr (PARTS & 1)
+                if (x >= 2 && x < 6) a[(u + 2) % 3][x - 2] = probe_ld16(rs, lane * 16, soff + (x - 2) * 1024);
+        };
+        if constexpr (PARTS & 32) {
+            u32x2 lo[2], hi[2];
+            lo[0] = probe_lds_read_tr<8192 * u>(tr[0]);
+            hi[0] = probe_lds_read_tr<8192 * u + 1024>(tr[0]);
+#pragma unroll
+            for (int x = 0; x < 8; ++x) {
+                if (x < 7) {
+                    lo[(x + 1) & 1] = probe_lds_read_tr<8192 * u>(tr[(x + 1) & 7]);
+                    hi[(x + 1) & 1] = probe_lds_read_tr<8192 * u + 1024>(tr[(x + 1) & 7]);
+                    probe_lds_pair_done<2>(lo[x & 1], hi[x & 1]);
+                } else {
+                    probe_lds_pair_done<0>(lo[x & 1], hi[x & 1]);
+                }
+                const u32x4 b = u32x4{lo[x & 1][0], lo[x & 1][1], hi[x & 1][0], hi[x & 1][1]};
+#pragma unroll
+                for (int r = 0; r < 4; ++r)
+                    acc[r][x] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a[u][r]), __builtin_bit_cast(bf16x8, b), acc[r][x], 0, 0, 0);
+                __builtin_amdgcn_sched_barrier(0);
+                if (x < 6) issue(x);
+                __builtin_amdgcn_sched_barrier(0);
+            }
+            return;
+        }
         u32x4 R[8];
         if constexpr (PARTS & 2) {
             const uint32_t p = rd + u * 8192;
@@ -170,15 +221,6 @@ void probe_tile_step_kernel(int steps, const u32x4* __restrict__ src, float* sin
 #pragma unroll
             for (int k = 0; k < 8; ++k) R[k] = fixed[k];
         }
-        const uint32_t soff = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(((s & 7) * 16 + wave * 4) * 1024));
-        auto issue = [&](int x) {
-            if constexpr (PARTS & 8)
-                if (x < 2)
-                    __builtin_amdgcn_raw_ptr_buffer_load_lds(rs, (lds_void*)(uintptr_t)(lds_base + ((u + 2) % 3) * 8192 + x * 4096 + wave * 1024),
-                                                             16, lane * 16, 32768 + wave * 1024 + x * 4096, 0, 0);
-            if constexpr (PARTS & 1)
-                if (x >= 2 && x < 6) a[(u + 2) % 3][x - 2] = probe_ld16(rs, lane * 16, soff + (x - 2) * 1024);
-        };
         if constexpr (PARTS & 16) {
             for (int x = 0; x < 6; ++x) issue(x);
             __builtin_amdgcn_sched_barrier(0);
@@ -269,6 +311,7 @@ smat_status_t smat_probe_tile_step(int workgroups, int steps, int parts, const v
     switch (parts) {
     SMAT_TILE_STEP(0); SMAT_TILE_STEP(1); SMAT_TILE_STEP(2); SMAT_TILE_STEP(3); SMAT_TILE_STEP(6); SMAT_TILE_STEP(7);
     SMAT_TILE_STEP(12); SMAT_TILE_STEP(14); SMAT_TILE_STEP(15); SMAT_TILE_STEP(31);
+    SMAT_TILE_STEP(32); SMAT_TILE_STEP(36); SMAT_TILE_STEP(37); SMAT_TILE_STEP(45);
     default: return SMAT_ERR_INVALID_ARG;
     }
 #undef SMAT_TILE_STEP

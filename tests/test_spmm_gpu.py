@@ -359,7 +359,7 @@ def test_probe_kernels_run():
         S.smat_probe_gather(buf, 64, idx, 64, 3, 16, sink)        # rows shorter than 16 lanes x 16 bytes
     with pytest.raises(S.SmatError):
         S.smat_probe_mfma(0, 10, sink)
-    for parts in (0, 7, 15, 31):
+    for parts in (0, 7, 15, 31, 32, 45):
         S.smat_probe_tile_step(4, 6, parts, buf, sink)
     torch.cuda.synchronize()
     with pytest.raises(S.SmatError):
