@@ -187,7 +187,9 @@ void plan_dense_tiles(smat_handle& h)
                     if (std::binary_search(first, last, cols[e])) rows |= 1u << j;
             }
             for (int64_t e = 0; e < cps; ++e) h.step_cols.push_back(cols[e]);
-            if (rows != 0xFFFFu || cps != 2 || cols[0] != 2 * q || cols[1] != 2 * q + 1) h.dense_all_full = false;
+            for (int64_t e = 0; e < cps; ++e)
+                if (cols[e] != cps * q + e) h.dense_all_full = false;
+            if (rows != 0xFFFFu) h.dense_all_full = false;
             h.step_rows.push_back(rows);
             h.step_base.push_back(static_cast<uint32_t>(h.dense_slots));
             h.dense_slots += static_cast<uint64_t>(__builtin_popcount(rows));

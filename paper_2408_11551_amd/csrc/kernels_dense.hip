@@ -38,364 +38,43 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
 
 }  // namespace
 
-// C rows of the dense super rows, 128 columns per workgroup; 4 waves, wave w owns block rows
-// 4w..4w+3 of the super row.  With gridDim.z > 1 the steps of a tile are split over that many
-// workgroups; each writes its partial 256 x 128 tile to the scratch area and a second kernel
-// adds the partial tiles in a fixed order (reproducible; fp32 atomics on C were measured at
-// three times the cost of the idle compute units they were meant to fill).
-//
-// RING is the depth of the prefetch (see below); every variant stays within 256 registers, so
-// that a SIMD holds two waves whose LDS reads, barrier waits and matrix instructions overlap.
-// Launched with RING = 2: a ring of 3 (two wave groups) measured 80.0 us against 79.4 us on a
-// 4096 x 4096 x 2048 product, a ring of 4 needs more than 256 registers and, one wave per SIMD,
-// took 93.8 us.
+// ---------------------------------------------------------------------------------------------
+// The tile kernel: C rows of the dense super rows, 128 columns per workgroup; 4 waves per group,
+// wave w owns block rows 4w..4w+3 of the super row.  With gridDim.z > 1 the steps of a tile are
+// split over that many workgroups; each writes its partial 256 x 128 tile to the scratch area
+// and a second kernel adds the partial tiles in a fixed order (reproducible; fp32 atomics on C
+// were measured at three times the cost of the idle compute units they were meant to fill).
 //
 // KG = 1: one group of four waves per workgroup, two workgroups per compute unit; for super
 // rows of few steps, where the start and the write of C of one workgroup overlap the loop of
 // the other.  KG = 2 puts two groups of four waves into one workgroup: group 0 walks the even
 // steps of the tile, group 1 the odd ones, each with its own panel buffers, and at the end
 // group 1 hands its accumulators to group 0 through LDS; for long super rows, also when every
-// compute unit gets only one tile.  (A 256-column tile with 256 accumulators per lane in the
-// accumulation registers was built as well: 9 % faster than one group at N = 4096, slower than
-// two groups, and removed.)
+// compute unit gets only one tile.  Every variant stays within 256 registers, so that a SIMD
+// holds two waves whose waits and matrix instructions overlap.
 //
-// DT is the operand type.  The 8-bit types run the same walk with elements of one byte and
-// steps of four block columns (KS = 2 sub-steps of 32 k slots, i.e. two MFMA 16x16x32 per output
-// tile between barriers): a block row's values for a step are again 1 KiB (sixteen bytes per
-// lane, eight per sub-step), the panel of B is 64 rows of 128 bytes, staged in two 16-byte
-// pieces per thread, and the operand of MFMA x is byte x of the lane's eight rows of a sub-step.
-// A step thus moves the same bytes as a 16-bit one and a tile has half as many steps.  int8 has
-// an instruction with k = 64 (16x16x64, sixteen bytes per lane and operand) that takes both
-// sub-steps at once at twice the rate; the floating-point 8-bit types have none of that shape.
-template <int DT, int RING, int KG>
-__global__ __launch_bounds__(256 * KG)
-__attribute__((amdgpu_waves_per_eu(2, 2)))
-void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, uint32_t b_bytes,
-                       uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store)
-{
-    static_assert(RING == 2 || RING == 3, "at most 256 registers per lane");
-    using Acc = typename Elem<DT>::Acc;
-    using Out = typename Elem<DT>::Out;
-    constexpr int ES = Elem<DT>::ES;               // bytes per element of A and B
-    constexpr int NT = 8;                          // columns per lane; 16 lanes cover a 128-column chunk
-    constexpr int RM = 4;                          // block rows per wave
-    constexpr int NCH = 1;                         // 128-column chunks per workgroup
-    constexpr int KS = ES == 1 ? 2 : 1;            // sub-steps of 32 k slots (two block columns) per step
-    constexpr int NS = 2 * NCH;                    // 16-byte pieces of the panel a thread stages per step
-    constexpr int PW = 8 * ES * NCH;               // 16-byte pieces per panel row (128 * NCH elements)
-    constexpr int NBUF = RING == 3 ? 3 : 2;        // panel buffers; the loop body of RING steps keeps their indices constant
-    __shared__ u32x4 panel_all[KG][NBUF][32 * KS][PW];  // per wave group, buffers of 32 KS rows of B x (128 * NCH) elements
-
-    const int tid = threadIdx.x & 255;             // thread inside its wave group
-    const int lane = tid & 63;
-    const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
-    const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
-    u32x4 (*panel)[32 * KS][PW] = panel_all[kg];
-    const int i = lane & 15, g = lane >> 4;
-    const int sidx = blockIdx.x;
-    const int super = t.super_rows[sidx];
-    const int n0 = blockIdx.y * (128 * NCH);
-    const int ks = static_cast<int>(gridDim.z);    // workgroups sharing this tile's steps
-    const int q_first = t.step_ptr[sidx], q_last = t.step_ptr[sidx + 1];
-    const int per = (q_last - q_first + ks - 1) / ks;
-    const int q0 = min(q_first + static_cast<int>(blockIdx.z) * per, q_last);
-    const int q1 = min(q0 + per, q_last);
-    const int nq = q1 - q0;
-
-    const __amdgpu_buffer_rsrc_t b_rsrc =
-        __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
-    // tile values of this workgroup's steps q0..q1-1 are stored back to back
-    const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
-    const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
-    const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
-        static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
-
-    // staging of the B panel, 16 bytes per piece.  16-bit types: thread tid copies, per chunk, the
-    // pieces of rows (tid >> 4) and 16 + (tid >> 4) at column 8 * (tid & 15); 8-bit types: the
-    // pieces of rows (tid >> 3) and 32 + (tid >> 3) at column 16 * (tid & 7).  (N is a multiple of
-    // the columns of a piece on this path, so a piece is all inside or all outside.)
-    const int st_row = ES == 2 ? tid >> 4 : tid >> 3, st_chunk = ES == 2 ? tid & 15 : tid & 7;
-    uint32_t st_off[NCH];
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int st_col = n0 + 128 * c + (16 / ES) * st_chunk;
-        st_off[c] = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
-    }
-    const uint32_t no_row = static_cast<uint32_t>(d.K);
-    const int nbc = static_cast<int>((d.K + 15) >> 4);
-
-    // What a step's loads need to know, fetched with scalar loads one step before it is used:
-    // a scalar load that is waited for right away costs a few hundred cycles in which the wave,
-    // alone on its SIMD, does nothing.
-    struct StepMeta { int c[2 * KS]; uint32_t rows, base; };
-    auto fetch_meta = [&](int q) {
-        StepMeta m;
-#pragma unroll
-        for (int e = 0; e < 2 * KS; ++e) m.c[e] = t.step_cols[(2 * KS) * static_cast<size_t>(q) + e];
-        m.rows = t.step_rows[q];
-        m.base = t.step_base[q];
-        return m;
-    };
-    auto load_panel = [&](const StepMeta& m, u32x4 (&stage)[NS]) {
-        // rows past K (ragged last block column, or no such column) are out of range: zeros
-        if constexpr (ES == 2) {
-            const int c0 = m.c[0], c1 = m.c[1];
-            uint32_t row0 = c0 < nbc ? static_cast<uint32_t>(c0) * 16u + st_row : no_row;
-            uint32_t row1 = c1 < nbc ? static_cast<uint32_t>(c1) * 16u + st_row : no_row;
-            row0 = row0 < no_row ? row0 : no_row;
-            row1 = row1 < no_row ? row1 : no_row;
-            const uint32_t off0 = __umul24(row0, ldb_bytes), off1 = __umul24(row1, ldb_bytes);
-#pragma unroll
-            for (int c = 0; c < NCH; ++c) {
-                stage[2 * c] = buf_load16(b_rsrc, off0 + st_off[c], 0u);
-                stage[2 * c + 1] = buf_load16(b_rsrc, off1 + st_off[c], 0u);
-            }
-        } else {
-#pragma unroll
-            for (int j = 0; j < KS; ++j) {
-                const int col = st_row < 16 ? m.c[2 * j] : m.c[2 * j + 1];
-                uint32_t row = col < nbc ? static_cast<uint32_t>(col) * 16u + (st_row & 15) : no_row;
-                row = row < no_row ? row : no_row;
-                const uint32_t off = __umul24(row, ldb_bytes);
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) stage[KS * c + j] = buf_load16(b_rsrc, off + st_off[c], 0u);
-            }
-        }
-    };
-    auto store_panel = [&](int buf, const u32x4 (&stage)[NS]) {
-#pragma unroll
-        for (int c = 0; c < NCH; ++c) {
-            if constexpr (ES == 2) {
-                panel[buf][st_row][16 * c + st_chunk] = stage[2 * c];
-                panel[buf][16 + st_row][16 * c + st_chunk] = stage[2 * c + 1];
-            } else {
-#pragma unroll
-                for (int j = 0; j < KS; ++j) panel[buf][32 * j + st_row][8 * c + st_chunk] = stage[KS * c + j];
-            }
-        }
-    };
-    // Values of the wave's four block rows for step q.  A block row without data in the step
-    // (or any block row in a step past the last one, `live` false) reads out of range (zeros)
-    // and multiplies zeros: no branches in the loop body.
-    auto load_a = [&](const StepMeta& m, bool live, u32x4 (&a)[RM]) {
-        const uint32_t rows = m.rows;
-        const uint32_t base = m.base - first_slot;
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const int j = RM * wave + r;
-            const uint32_t slot = base + __popc(rows & ((1u << j) - 1u));
-            const uint32_t absent = (live && (rows >> j & 1u)) ? 0u : kOutOfRange;      // wave-uniform
-            a[r] = buf_load16(a_rsrc, (static_cast<uint32_t>(lane) * 16u) | absent, slot * 1024u);
-        }
-    };
-
-    Acc acc[RM][NCH * NT];
-#pragma unroll
-    for (int r = 0; r < RM; ++r)
-#pragma unroll
-        for (int x = 0; x < NCH * NT; ++x) acc[r][x] = Acc{0, 0, 0, 0};
-
-    // Software pipeline with register rings of RING slots (no copies; the loop body is RING steps
-    // without an exit; steps past the last one read zeros as block values).  While step s is
-    // multiplied, the B panels and block values of the next RING-1 steps are on their way from
-    // memory; the panel of step s+1 is copied into the other LDS buffer at the end of step s.
-    if (nq > 0) {
-        u32x4 stage[RING][NS];
-        u32x4 a[RING][RM];
-        // step s of this wave group is step kg + KG * s of the tile
-        auto live_step = [&](int s) { return kg + KG * s < nq; };
-        auto step_of = [&](int s) { return q0 + (live_step(s) ? kg + KG * s : nq - 1); };   // clamped: a cache hit, unused
-        // prologue: steps 0..RING-2 requested, panel of step 0 in LDS
-#pragma unroll
-        for (int h = 0; h < RING - 1; ++h) {
-            const StepMeta m = fetch_meta(step_of(h));
-            load_panel(m, stage[h]);
-            load_a(m, live_step(h), a[h]);
-            __builtin_amdgcn_sched_barrier(0);
-        }
-        StepMeta meta = fetch_meta(step_of(RING - 1));
-        store_panel(0, stage[0]);
-        __syncthreads();
-        const int iters = ((nq + KG - 1) / KG + RING - 1) / RING;      // the same for both groups: they share the barriers
-        int s0 = 0;
-        for (int it = 0; it < iters; ++it) {
-#pragma unroll
-            for (int u = 0; u < RING; ++u) {
-                const int s = s0 + u;
-                const int buf = u % NBUF;
-                load_panel(meta, stage[(u + RING - 1) % RING]);
-                load_a(meta, live_step(s + RING - 1), a[(u + RING - 1) % RING]);
-                meta = fetch_meta(step_of(s + RING));
-#pragma unroll
-                for (int c = 0; c < NCH; ++c) {
-                    // B rows of this lane's k range: row 8g + kk, columns 128c + 8i .. 128c + 8i+7
-                    if constexpr (ES == 2) {
-                        u32x4 R[8];
-#pragma unroll
-                        for (int kk = 0; kk < 8; ++kk) R[kk] = panel[buf][8 * g + kk][16 * c + i];
-                        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int x = 0; x < NT; ++x) {
-                            const uint32_t pick = (x & 1) ? 0x07060302u : 0x05040100u;
-                            u32x4 b;
-#pragma unroll
-                            for (int qd = 0; qd < 4; ++qd)
-                                b[qd] = __builtin_amdgcn_perm(R[2 * qd + 1][x >> 1], R[2 * qd][x >> 1], pick);
-#pragma unroll
-                            for (int r = 0; r < RM; ++r)
-                                acc[r][c * NT + x] = mfma_pack<DT>(a[u][r], b, acc[r][c * NT + x]);
-                        }
-                    } else if constexpr (DT == kI8) {
-                        // int8: one MFMA 16x16x64 per output tile takes both sub-steps at once (the
-                        // lane's sixteen block values as they lie; operand dwords 2j, 2j+1 = byte x of
-                        // the eight rows of sub-step j)
-                        u32x2 R[KS][8];
-#pragma unroll
-                        for (int j = 0; j < KS; ++j)
-#pragma unroll
-                            for (int kk = 0; kk < 8; ++kk)
-                                R[j][kk] = reinterpret_cast<const u32x2*>(&panel[buf][32 * j + 8 * g + kk][8 * c])[i];
-                        __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                        for (int x = 0; x < NT; ++x) {
-                            const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
-                            u32x4 b;
-#pragma unroll
-                            for (int j = 0; j < KS; ++j)
-#pragma unroll
-                                for (int qd = 0; qd < 2; ++qd) {
-                                    const uint32_t lo = __builtin_amdgcn_perm(R[j][4 * qd + 1][x >> 2], R[j][4 * qd][x >> 2], pair);
-                                    const uint32_t hi = __builtin_amdgcn_perm(R[j][4 * qd + 3][x >> 2], R[j][4 * qd + 2][x >> 2], pair);
-                                    b[2 * j + qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                                }
-#pragma unroll
-                            for (int r = 0; r < RM; ++r) acc[r][c * NT + x] = mfma_i8_k64(a[u][r], b, acc[r][c * NT + x]);
-                        }
-                        __builtin_amdgcn_sched_barrier(0);
-                    } else {
-                        // per sub-step, eight bytes per row: the lane's eight columns; operand dword =
-                        // byte x of four rows.  The lane's block values of sub-step j are dwords 2j, 2j+1.
-#pragma unroll
-                        for (int j = 0; j < KS; ++j) {
-                            u32x2 R[8];
-#pragma unroll
-                            for (int kk = 0; kk < 8; ++kk)
-                                R[kk] = reinterpret_cast<const u32x2*>(&panel[buf][32 * j + 8 * g + kk][8 * c])[i];
-                            __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-                            for (int x = 0; x < NT; ++x) {
-                                const uint32_t pair = 0x0C0C0400u + static_cast<uint32_t>(x & 3) * 0x0101u;
-                                u32x4 b = u32x4{0u, 0u, 0u, 0u};
-#pragma unroll
-                                for (int qd = 0; qd < 2; ++qd) {
-                                    const uint32_t lo = __builtin_amdgcn_perm(R[4 * qd + 1][x >> 2], R[4 * qd][x >> 2], pair);
-                                    const uint32_t hi = __builtin_amdgcn_perm(R[4 * qd + 3][x >> 2], R[4 * qd + 2][x >> 2], pair);
-                                    b[qd] = __builtin_amdgcn_perm(hi, lo, 0x05040100u);
-                                }
-#pragma unroll
-                                for (int r = 0; r < RM; ++r) {
-                                    const u32x4 aj = u32x4{a[u][r][2 * j], a[u][r][2 * j + 1], 0u, 0u};
-                                    acc[r][c * NT + x] = mfma_pack<DT>(aj, b, acc[r][c * NT + x]);
-                                }
-                            }
-                            __builtin_amdgcn_sched_barrier(0);
-                        }
-                    }
-                    __builtin_amdgcn_sched_barrier(0);
-                }
-                store_panel((u + 1) % NBUF, stage[(u + 1) % RING]);
-                __syncthreads();
-            }
-            s0 += RING;
-        }
-    }
-
-    if constexpr (KG == 2) {
-        // group 1 hands its accumulators to group 0, two block rows per wave at a time (64 KiB)
-        __shared__ Out handover[4 * 2 * NT * 4 * 64];
-#pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            if (kg == 1) {
-#pragma unroll
-                for (int rr = 0; rr < 2; ++rr)
-#pragma unroll
-                    for (int x = 0; x < NT; ++x)
-#pragma unroll
-                        for (int y = 0; y < 4; ++y)
-                            handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane] = acc[2 * half + rr][x][y];
-            }
-            __syncthreads();
-            if (kg == 0) {
-#pragma unroll
-                for (int rr = 0; rr < 2; ++rr)
-#pragma unroll
-                    for (int x = 0; x < NT; ++x)
-#pragma unroll
-                        for (int y = 0; y < 4; ++y)
-                            acc[2 * half + rr][x][y] += handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
-            }
-            __syncthreads();
-        }
-        if (kg == 1) return;
-    }
-
-    // acc[r][c*8 + x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 128c + 8i + x]
-    {
-        if (ks > 1) {
-            // partial tile, row-major 256 x 128 floats, at [(tile * ks + z)]
-            const size_t tile = static_cast<size_t>(sidx) * gridDim.y + blockIdx.y;
-            Out* part = static_cast<Out*>(t.scratch) + (tile * ks + blockIdx.z) * (256 * 128);
-#pragma unroll
-            for (int r = 0; r < RM; ++r)
-#pragma unroll
-                for (int y = 0; y < 4; ++y) {
-                    Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + NT * i;
-                    *reinterpret_cast<Acc*>(dst) = Acc{acc[r][0][y], acc[r][1][y], acc[r][2][y], acc[r][3][y]};
-                    *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][4][y], acc[r][5][y], acc[r][6][y], acc[r][7][y]};
-                }
-            return;
-        }
-    }
-#pragma unroll
-    for (int c = 0; c < NCH; ++c) {
-        const int col0 = n0 + 128 * c + NT * i;
-        if (col0 >= N) continue;
-#pragma unroll
-        for (int r = 0; r < RM; ++r) {
-            const int64_t br = static_cast<int64_t>(super) * 16 + RM * wave + r;
-#pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                const int64_t out_row = d.perm[br * 16 + 4 * g + y];
-                if (out_row < 0) continue;
-                Out* dst = C + out_row * ldc + col0;
-                if (vec_store) {
-                    *reinterpret_cast<Acc*>(dst) = Acc{acc[r][c * NT][y], acc[r][c * NT + 1][y], acc[r][c * NT + 2][y], acc[r][c * NT + 3][y]};
-                    *reinterpret_cast<Acc*>(dst + 4) = Acc{acc[r][c * NT + 4][y], acc[r][c * NT + 5][y], acc[r][c * NT + 6][y], acc[r][c * NT + 7][y]};
-                } else {
-#pragma unroll
-                    for (int x = 0; x < NT; ++x) dst[x] = acc[r][c * NT + x][y];
-                }
-            }
-        }
-    }
-}
-
-// ---------------------------------------------------------------------------------------------
-// The tile kernel for the 16-bit types.  Same tiles, same steps, same operand layout as above;
-// what differs is how a step's data reaches the matrix units.  A wave has 512 clocks of matrix
-// work per step, while a load takes a few thousand clocks under load, and whatever a wave does
-// right behind a barrier happens at the same moment in all eight waves of the compute unit.  Here
-//   * the 32 x 128 panel of B goes from memory straight into LDS (buffer loads with the LDS
-//     modifier: lane l of a wave delivers 16 bytes to M0 + 16 l, so a wave fills four 256-byte
-//     panel rows with one instruction and no register is spent on staging), into a ring of three
-//     panels, two steps ahead;
+// DT is the operand type.  A step of the 16-bit types is two block columns (the 32 k slots of
+// one MFMA 16x16x32); the 8-bit types take four (two sub-steps of 32 k slots): a block row's
+// values for a step are again 1 KiB (sixteen bytes per lane, eight per sub-step), the panel of B
+// is 64 rows of 128 bytes, so a step moves the same bytes as a 16-bit one and a tile has half as
+// many steps.  int8 multiplies both sub-steps with one instruction (16x16x64, sixteen bytes per
+// lane and operand, twice the rate); the 8-bit floats take two MFMA 16x16x32.
+//
+// A wave has 512 clocks of matrix work per step, while a load takes a few thousand clocks under
+// load, and whatever a wave does right behind a barrier happens at the same moment in all eight
+// waves of the compute unit.  So
+//   * the panel of B goes from memory straight into LDS (buffer loads with the LDS modifier:
+//     lane l of a wave delivers 16 bytes to M0 + 16 l, so a wave fills 1 KiB of panel rows with
+//     one instruction and no register is spent on staging), into a ring of three panels, two
+//     steps ahead;
 //   * the block values sit in a register ring of three steps, two steps ahead;
 //   * the right operand of a matrix instruction -- eight k-consecutive values of one column per
 //     lane, out of a panel that holds rows of B -- comes from two transposing LDS reads
-//     (ds_read_b64_tr_b16) per group of sixteen columns, asked for one group ahead of its use: no
-//     byte permutes, no registers for the panel's rows, and the first matrix instruction of a step
-//     waits for two reads instead of eight (a 4096 x 4096 x 2048 product: 70 -> 63 us);
+//     (ds_read_b64_tr_b16 / _b8) per group of sixteen columns, asked for one group ahead of its
+//     use: no byte permutes, no registers for the panel's rows, and the first matrix instruction
+//     of a step waits for two reads instead of the whole panel (a 4096 x 4096 x 2048 product:
+//     bf16 70 -> 63 us; e4m3 66 -> 53 us and int8 56 -> 40 us against the kernel that staged the
+//     panel through registers and built operands with permutes);
 //   * every thread waits for its own loads of the step (in-order counter: all but the youngest
 //     six), one barrier makes the panel visible, and the loads of the next two steps stay in
 //     flight across it -- twelve KiB per wave;
@@ -403,11 +82,12 @@ void spmm_dense_kernel(DeviceBcsr d, DenseTiles t, const void* __restrict__ B, u
 //     once kept every wave waiting at its load instructions while the matrix units idled, and the
 //     time of the loads and the time of the matrix instructions added up (measured by leaving out
 //     one or the other) -- but one by one between the groups of matrix instructions.
-// Built, measured and set aside: the panel read from LDS in two halves, the second while the first
-// four groups of matrix instructions run and the first half of the next panel while the last four
-// run (which needs the next panel to have landed a step early: 78 us on a 4096 x 4096 x 2048
-// product against 73 us), and requests for the lines of later steps through the scalar cache, which
-// has a path of its own into the L2 (88 us against 79 us at the time).
+// Built, measured and set aside: the panel staged through registers with operands by byte permutes
+// (the first form of this kernel), with prefetch rings of two to four steps; a 256-column tile with
+// 256 accumulators per lane in the accumulation registers (9 % faster than one group at N = 4096,
+// slower than two); the panel read from LDS in two halves around the matrix instructions; requests
+// for the lines of later steps through the scalar cache (88 us against 79 us at the time);
+// transposing reads two groups ahead (65 against 63 us).
 // The tiles are numbered so that the workgroups an XCD runs (every eighth in dispatch order) form
 // compact rectangles of super rows x column slabs: the tile values of a super row and the panel rows
 // of a slab then miss that XCD's L2 once and hit it for the other workgroups that walk them at the
@@ -452,6 +132,16 @@ __device__ __forceinline__ u32x2_t lds_read_tr(uint32_t addr)
     asm volatile("ds_read_b64_tr_b16 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
     return v;
 }
+// The same for bytes: a lane names eight bytes of a row, and lane i receives byte i % 8 of the pieces
+// named by lanes i / 8, i / 8 + 2, ..., i / 8 + 14 -- eight k-consecutive bytes of one column when
+// those eight lanes name eight consecutive rows.
+template <int OFFSET>
+__device__ __forceinline__ u32x2_t lds_read_tr8(uint32_t addr)
+{
+    u32x2_t v;
+    asm volatile("ds_read_b64_tr_b8 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET));
+    return v;
+}
 // the two reads into lo and hi have returned once at most YOUNGER later LDS reads are outstanding
 template <int YOUNGER>
 __device__ __forceinline__ void lds_pair_done(u32x2_t& lo, u32x2_t& hi)
@@ -462,19 +152,20 @@ __device__ __forceinline__ void lds_pair_done(u32x2_t& lo, u32x2_t& hi)
 template <int DT, int KG, bool FULL = false>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
-void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* __restrict__ B, uint32_t b_bytes,
-                        uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N, int vec_store)
+void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* __restrict__ B, uint32_t b_bytes,
+                        uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N)
 {
-    static_assert(Elem<DT>::ES == 2, "the 16-bit types");
     using Acc = typename Elem<DT>::Acc;
     using Out = typename Elem<DT>::Out;
-    constexpr int NT = 8;                          // columns per lane; 16 lanes cover the 128 columns of a tile
+    constexpr int ES = Elem<DT>::ES;               // bytes per element of A and B
+    constexpr int KS = ES == 1 ? 2 : 1;            // sub-steps of 32 k slots (two block columns) per step
+    constexpr int NT = 8;                          // groups of 16 columns: 128 columns per tile
     constexpr int RM = 4;                          // block rows per wave
     constexpr int RD = 3;                          // ring depth: panels in LDS, steps of block values in registers
-    // per wave group, RD panels of 32 rows of B x 128 columns; the two groups' hand-over at the end needs 64 KiB
+    // per wave group, RD panels of 8 KiB: 32 rows of B x 128 columns of two bytes, or 64 rows x 128 columns of one
+    // byte; the two groups' hand-over at the end needs 64 KiB
     constexpr int kLdsWords = KG == 2 ? (KG * RD * 32 * 16 > 4096 ? KG * RD * 32 * 16 : 4096) : KG * RD * 32 * 16;
     __shared__ u32x4 lds_words[kLdsWords];
-    u32x4 (*panel_all)[RD][32][16] = reinterpret_cast<u32x4 (*)[RD][32][16]>(lds_words);
 
     // tile of this workgroup: the XCD's share of the tile numbers is contiguous
     const int tile = static_cast<int>(blockIdx.x % 8u) * order.per_xcd + static_cast<int>(blockIdx.x / 8u);
@@ -507,34 +198,50 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
         static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
 
-    // This lane's share of a panel: the 16-byte piece (lane & 15) of rows 4 wave + (lane >> 4) of the
-    // step's first and of its second block column.  (N is a multiple of 8 on this path, so a piece is
-    // all inside or all outside.)
-    const int st_row = 4 * wave + (lane >> 4);
-    // The piece that lands at position p of row r of the panel is piece p ^ 2 (r & 3) of that row of B,
-    // so that the sixteen lanes of a transposing read (four rows x 32 bytes) hit every bank once.
-    const int st_col = n0 + 8 * ((lane & 15) ^ (2 * ((lane >> 4) & 3)));
-    const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * 2u : kOutOfRange;
+    // A wave's share of a panel is two loads of 1 KiB, lane l delivering the 16 bytes at position 16 l.
+    // 16-bit types: panel rows of 256 bytes, rows 0..15 the step's first block column, 16..31 its second;
+    // load e brings rows 4 wave .. 4 wave + 3 of block column e, lane l the piece l & 15 of row l >> 4.
+    // 8-bit types: panel rows of 128 bytes, rows 16 c .. 16 c + 15 the step's c-th block column (c < 4);
+    // the wave brings block column `wave`, load e its rows 8 e .. 8 e + 7, lane l the piece l & 7 of row l >> 3.
+    // (N is a multiple of the columns of a piece on this path, so a piece is all inside or all outside.)
+    const int st_row = ES == 2 ? 4 * wave + (lane >> 4) : lane >> 3;
+    // The piece that lands at position p of row r of the panel is piece p ^ 2 (r & 3) of that row of B
+    // (8-bit: p ^ (r & 7)), so that the sixteen lanes of a transposing read -- four rows x 32 bytes, or
+    // eight rows x 16 bytes -- hit every bank once.
+    const int st_piece = ES == 2 ? (lane & 15) ^ (2 * ((lane >> 4) & 3)) : (lane & 7) ^ ((lane >> 3) & 7);
+    const int st_col = n0 + (16 / ES) * st_piece;
+    const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
     const uint32_t no_row = static_cast<uint32_t>(d.K);
     const int nbc = static_cast<int>((d.K + 15) >> 4);
-    // where this wave's pieces of a panel go (+ 4096 for the second block column), and where this lane reads
-    auto lds_of_panel = [&](int buf) { return reinterpret_cast<char*>(&panel_all[kg][buf][4 * wave][0]); };
-    // Where this lane reads (+ 8192 per panel): lane (g, j) names row 8 g + j / 4 (+ 4 for the second
-    // read, + 1024 bytes) and, for the group of columns 16 x .. 16 x + 15, the eight bytes of columns
+    const uint32_t panels = lds_offset_of(lds_words) + static_cast<uint32_t>(kg) * (RD * 8192);   // this group's ring
+    // where load e of this wave goes in panel buf
+    auto lds_of_load = [&](int buf, int e) {
+        return panels + static_cast<uint32_t>(buf) * 8192u + (ES == 2 ? 4096u * e + 1024u * wave : 2048u * wave + 1024u * e);
+    };
+    // Where this lane reads (+ 8192 per panel).  16-bit: lane (g, j) names row 8 g + j / 4 (+ 4 for the
+    // second read, + 1024 bytes) and, for the group of columns 16 x .. 16 x + 15, the eight bytes of columns
     // 16 x + 4 (j % 4) ..: piece 2 x + (j % 4) / 2 of the row, which lies at position
-    // (2 x + (j % 4) / 2) ^ 2 (j / 4).
+    // (2 x + (j % 4) / 2) ^ 2 (j / 4).  8-bit: row 8 g + j / 2 of the first sub-step (the second: + 32 rows,
+    // + 4096 bytes), the eight bytes of columns 16 x + 8 (j % 2) ..: half j % 2 of piece x, at position x ^ (j / 2).
+    constexpr uint32_t kSecondRead = ES == 2 ? 1024u : 4096u;
     uint32_t tr_addr[8];
     {
-        const int e = i >> 2, qq = i & 3;
 #pragma unroll
-        for (int x = 0; x < 8; ++x)
-            tr_addr[x] = lds_offset_of(&panel_all[kg][0][8 * g + e][0]) + 32u * (x ^ e) + 16u * (qq >> 1) + 8u * (qq & 1);
+        for (int x = 0; x < 8; ++x) {
+            if constexpr (ES == 2) {
+                const int e = i >> 2, qq = i & 3;
+                tr_addr[x] = panels + (8 * g + e) * 256u + 32u * (x ^ e) + 16u * (qq >> 1) + 8u * (qq & 1);
+            } else {
+                const int e = i >> 1, qq = i & 1;
+                tr_addr[x] = panels + (8 * g + e) * 128u + 16u * (x ^ e) + 8u * qq;
+            }
+        }
     }
 
     // What a step's loads need to know, fetched with scalar loads a step before it is used.  A
     // step past the group's last one names no block column (its panel rows read zeros) and no block
     // row (its block values read zeros).
-    struct StepMeta { int c0, c1; uint32_t rows, base; };
+    struct StepMeta { int c[2 * KS]; uint32_t rows, base; };
     // (The tables are written at bind time and never while a kernel runs.  Reading them through the
     // constant address space tells the compiler so: the loads stay scalar even though the loop
     // contains loads that write LDS, which it takes for writes to anything.)
@@ -551,27 +258,30 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
         StepMeta m;
         if constexpr (FULL) {
             // a matrix all of whose blocks are stored: step q of the super row has the block columns
-            // 2q and 2q+1 and a block of every block row -- nothing to look up (3 % of a launch)
+            // 2q and 2q+1 (8-bit: 4q .. 4q+3) and a block of every block row -- nothing to look up (3 % of a launch)
             const int rel = static_cast<int>(q) - q_first;
-            m.c0 = 2 * rel;
-            m.c1 = 2 * rel + 1;
+#pragma unroll
+            for (int e = 0; e < 2 * KS; ++e) m.c[e] = 2 * KS * rel + e;
             m.rows = 0xFFFFu;
             m.base = first_slot + 16u * static_cast<uint32_t>(static_cast<int>(q) - q0);
             return m;
         }
-        m.c0 = step_cols[2 * q];
-        m.c1 = step_cols[2 * q + 1];
+#pragma unroll
+        for (int e = 0; e < 2 * KS; ++e) m.c[e] = step_cols[(2 * KS) * q + e];
         m.rows = step_rows[q];
         m.base = step_base[q];
         return m;
     };
-    // e-th block column of the step's panel (e = 0, 1): one load into LDS
+    // e-th load of the wave's share of the step's panel (e = 0, 1): one load into LDS
     auto load_panel_half = [&](const StepMeta& m, bool live, int buf, int e) {
         // rows past K (ragged last block column, or no such column) are out of range: zeros
-        const int c = live ? (e == 0 ? m.c0 : m.c1) : 0x7FFFFFFF;                        // scalar select, no branch
-        uint32_t row = c < nbc ? static_cast<uint32_t>(c) * 16u + st_row : no_row;
+        int c;                                                                           // scalar selects, no branch
+        if constexpr (ES == 2) c = e == 0 ? m.c[0] : m.c[1];
+        else c = wave == 0 ? m.c[0] : wave == 1 ? m.c[1] : wave == 2 ? m.c[2] : m.c[3];
+        c = live ? c : 0x7FFFFFFF;
+        uint32_t row = c < nbc ? static_cast<uint32_t>(c) * 16u + (ES == 2 ? 0 : 8 * e) + st_row : no_row;
         row = row < no_row ? row : no_row;
-        load_to_lds16((lds_void*)(lds_of_panel(buf) + 4096 * e), b_rsrc, __umul24(row, ldb_bytes) + st_off, 0u);
+        load_to_lds16((lds_void*)(uintptr_t)lds_of_load(buf, e), b_rsrc, __umul24(row, ldb_bytes) + st_off, 0u);
     };
     auto load_panel = [&](const StepMeta& m, bool live, int buf) {
         load_panel_half(m, live, buf, 0);
@@ -634,20 +344,39 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
             mt[(u + 2) % RD] = fetch_meta(s + 2 + RD);
             __builtin_amdgcn_sched_barrier(0);
             u32x2_t lo[2], hi[2];
-            lo[0] = lds_read_tr<8192 * u>(tr_addr[0]);
-            hi[0] = lds_read_tr<8192 * u + 1024>(tr_addr[0]);
+            auto read_pair = [&](int x, u32x2_t& l, u32x2_t& h) {
+                if constexpr (ES == 2) {
+                    l = lds_read_tr<8192 * u>(tr_addr[x]);
+                    h = lds_read_tr<8192 * u + kSecondRead>(tr_addr[x]);
+                } else {
+                    l = lds_read_tr8<8192 * u>(tr_addr[x]);
+                    h = lds_read_tr8<8192 * u + kSecondRead>(tr_addr[x]);
+                }
+            };
+            read_pair(0, lo[0], hi[0]);
 #pragma unroll
             for (int x = 0; x < NT; ++x) {
                 if (x + 1 < NT) {
-                    lo[(x + 1) & 1] = lds_read_tr<8192 * u>(tr_addr[(x + 1) & 7]);
-                    hi[(x + 1) & 1] = lds_read_tr<8192 * u + 1024>(tr_addr[(x + 1) & 7]);
+                    read_pair((x + 1) & 7, lo[(x + 1) & 1], hi[(x + 1) & 1]);
                     lds_pair_done<2>(lo[x & 1], hi[x & 1]);
                 } else {
                     lds_pair_done<0>(lo[x & 1], hi[x & 1]);
                 }
+                // 16-bit: the two reads are k 0..3 and 4..7 of the lane group; 8-bit: the two sub-steps, which
+                // the int8 instruction with k = 64 takes at once and the 8-bit floats one after the other
+                // (the lane's block values of sub-step j are dwords 2j, 2j+1)
                 const u32x4 b = u32x4{lo[x & 1][0], lo[x & 1][1], hi[x & 1][0], hi[x & 1][1]};
 #pragma unroll
-                for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
+                for (int r = 0; r < RM; ++r) {
+                    if constexpr (ES == 2) {
+                        acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
+                    } else if constexpr (DT == kI8) {
+                        acc[r][x] = mfma_i8_k64(a[u][r], b, acc[r][x]);
+                    } else {
+                        acc[r][x] = mfma_pack<DT>(u32x4{a[u][r][0], a[u][r][1], 0u, 0u}, u32x4{b[0], b[1], 0u, 0u}, acc[r][x]);
+                        acc[r][x] = mfma_pack<DT>(u32x4{a[u][r][2], a[u][r][3], 0u, 0u}, u32x4{b[2], b[3], 0u, 0u}, acc[r][x]);
+                    }
+                }
                 __builtin_amdgcn_sched_barrier(0);
                 if (x < 2) {
                     load_panel_half(next, next_live, (u + 2) % RD, x);
@@ -732,8 +461,8 @@ void spmm_tile16_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void*
 }
 
 template <int DT, int KG>
-static void launch_tile16(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
-                          void* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
+static void launch_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
+                          void* C, int64_t ldc, int64_t N, hipStream_t s)
 {
     TileOrder order;
     order.n_super = t.n;
@@ -741,31 +470,13 @@ static void launch_tile16(const DeviceBcsr& d, const DenseTiles& t, int ks, cons
     order.per_xcd = (order.n_super * order.n_slab + 7) / 8;
     dim3 grid(static_cast<unsigned>(8 * order.per_xcd), 1, static_cast<unsigned>(ks));
     if (t.all_full)
-        hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG, true>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
-                           static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
+        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, true>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
+                           static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N));
     else
-        hipLaunchKernelGGL((spmm_tile16_kernel<DT, KG, false>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
-                           static_cast<uint32_t>(ldb * 2), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store);
+        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, false>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
+                           static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N));
 }
 
-template <int DT, int RING, int KG>
-static void launch_dense_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
-                              void* C, int64_t ldc, int64_t N, int vec_store, hipStream_t s)
-{
-    dim3 grid(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), static_cast<unsigned>(ks));
-    hipLaunchKernelGGL((spmm_dense_kernel<DT, RING, KG>), grid, dim3(256 * KG), 0, s, d, t, B, b_bytes,
-                       static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc,
-                       static_cast<int>(N), vec_store);
-}
-
-
-// Scatter of the CSR values into the tile layout: one thread per row of a dense super row.
-// A tile step q holds, for every block row of the super row that has one of the step's two
-// block columns, 1 KiB.  16-bit types (two block columns per step): lane l = 16 g + i owns values
-// [8 l, 8 l + 8) = row i, columns 8g..8g+7 of the 32 columns of the step.  8-bit types (four block
-// columns per step, two sub-steps of 32 columns): lane l owns bytes [16 l, 16 l + 16): eight of
-// sub-step 0, then eight of sub-step 1, each row i, columns 8g..8g+7 of the sub-step.  T is the
-// stored element (the 8-bit types keep the low byte of the 16-bit words the CSR values arrive in).
 template <typename T>
 __global__ void dense_fill_kernel(DeviceBcsr d, DenseTiles t, const int64_t* __restrict__ csr_row_ptr,
                                   const int32_t* __restrict__ csr_col_idx, const uint16_t* __restrict__ csr_vals,
@@ -911,13 +622,8 @@ static int launch_dense_dtype(const DeviceBcsr& d, const DenseTiles& t, const vo
     if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", type, deep ? 2 : 1, ks);
     else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", type, deep ? 2 : 1);
     *variant = name;
-    if constexpr (Elem<DT>::ES == 2) {
-        if (deep) launch_tile16<DT, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_tile16<DT, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    } else {
-        if (deep) launch_dense_tile<DT, 2, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-        else launch_dense_tile<DT, 2, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, vec_store, s);
-    }
+    if (deep) launch_tile<DT, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, s);
+    else launch_tile<DT, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, s);
     if (ks > 1)
         hipLaunchKernelGGL((dense_reduce_kernel<Acc, Out>), dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8),
                            dim3(256), 0, s, d, t, ks, static_cast<Out*>(C), ldc, static_cast<int>(N), vec_store);
