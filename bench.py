@@ -96,7 +96,7 @@ def run_probes(S, torch, dev, stream):
     wgs, iters = 2048, 1000
     sec = timed(lambda: S.smat_probe_mfma(wgs, iters, sink, stream), reps=5)
     out["mfma_16x16x32_f16_tflops"] = wgs * 4 * iters * 16 * 2.0 * 16 * 16 * 32 / sec / 1e12
-    # the step of the 16-bit tile kernel on L1-resident data, put together piece by piece (256 workgroups of two
+    # the step of the tile kernel (16-bit operands) on L1-resident data, put together piece by piece (256 workgroups of two
     # wave groups, 66 steps each: a tile of 132 steps)
     buf = torch.zeros(1 << 18, dtype=torch.int32, device=dev)
     steps = 66

@@ -106,7 +106,7 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* sink)
     if (s == -1.f) sink[0] = s;
 }
 
-// The step of the 16-bit tile kernel (kernels_dense.hip) on data that never leaves the L1: two
+// The step of the tile kernel (kernels_dense.hip, 16-bit operands) on data that never leaves the L1: two
 // groups of four waves, per wave and step 32 MFMA 16x16x32 (four block rows x eight groups of 16
 // columns) whose right operands are built with four byte permutes each.  PARTS adds the rest of a
 // step bit by bit: 1 = the four 1 KiB loads of block values into a register ring of three, 2 = the
