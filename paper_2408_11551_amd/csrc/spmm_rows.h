@@ -708,9 +708,53 @@ void spmm_kernel(const int32_t* __restrict__ work, const uint32_t* __restrict__ 
     }
 }
 
+// How many workgroups of a launch a compute unit should hold at a time.  The registers of the wide
+// variants allow three waves per SIMD; with block rows of about the same length, whole cache lines
+// of B per row and slab and one slab per workgroup, TWO are as fast or faster: all waves walk their
+// rows at about the same pace, so at any moment the chip gathers from a window of B's rows, and
+// fewer rows in flight keep that window narrower for the L2s.  Measured, three -> two waves per SIMD:
+// a 32768 x 32768 matrix of 2048 block rows of ~21 packs 58.3 -> 50.2 us at N = 256, 100.5 -> 75.5 at
+// N = 384, 124.9 -> 99.8 at 512, 202.8 -> 151.7 at 768 (at N = 256 also ten / six / five workgroups
+// per unit: 56.3 / 61.4 / 67.0 us); random matrices of 64-400 entries per row, a band and a pruned
+// weight matrix on this kernel, and all of them in 8-bit types: within 2 % either way.  It loses
+// where the rows differ in length (power-law degrees: 81.6 -> 87-109 us for any limit), with two
+// slabs per workgroup and with rows of B off the cache lines (N = 1000: 347 -> 438 us), which is
+// why the caller asks for it only in the case above.  The limit is set by asking for LDS with the
+// launch that the kernel does not touch: that many bytes per workgroup that two waves per SIMD fit
+// a compute unit's 160 KiB and no more.  Returns the bytes to ask for, or 0 to leave the launch alone.
+struct Residency {
+    int resident = 0;          // workgroups of the kernel a compute unit holds (0: not known)
+    int64_t static_lds = 0;    // LDS bytes the kernel declares
+};
+static Residency query_residency(const void* kernel, int waves_per_group)
+{
+    Residency r;
+    hipFuncAttributes attr;
+    if (hipOccupancyMaxActiveBlocksPerMultiprocessor(&r.resident, kernel, waves_per_group * 64, 0) != hipSuccess ||
+        hipFuncGetAttributes(&attr, kernel) != hipSuccess || r.resident <= 0) {
+        (void)hipGetLastError();
+        r.resident = 0;
+        return r;
+    }
+    r.static_lds = static_cast<int64_t>(attr.sharedSizeBytes);
+    return r;
+}
+static size_t lds_to_limit_residency(const Residency& info, int waves_per_group, int64_t groups, bool even)
+{
+    if (!even || groups <= 0 || info.resident <= 0) return 0;
+    const int64_t resident = info.resident;
+    constexpr int64_t kUnits = 256, kLdsBytes = 160 * 1024;
+    const int64_t best = (8 + waves_per_group - 1) / waves_per_group;           // two waves per SIMD
+    if (best >= resident || groups < kUnits * best) return 0;                   // nothing to limit, or the chip would not fill
+    const int64_t per_group = kLdsBytes / best / 512 * 512;                      // best groups fit, best + 1 do not
+    if (kLdsBytes / per_group != best || per_group > 64 * 1024) return 0;
+    const int64_t extra = per_group - info.static_lds;
+    return extra > 0 ? static_cast<size_t>(extra) : 0;
+}
+
 template <int NT, int KW, int SW, int NCH, int LMAX, int DT, int NARROW = 0>
 static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, void* C, int64_t ldc,
-                          int64_t N, hipStream_t stream)
+                          int64_t N, hipStream_t stream, bool even_rows = false)
 {
     constexpr int ES = Elem<DT>::ES;
     const int64_t per_group = 16 * NT * NCH * SW;          // columns of one workgroup
@@ -726,7 +770,10 @@ static int launch_variant(const DeviceBcsr& d, const void* B, int64_t ldb, void*
     // not push it out: then C is stored past the cache (measured: -7 % where B is 4 MiB, no gain
     // or a loss where B is 16 MiB and more).
     if (static_cast<double>(d.K) * static_cast<double>(N) * ES <= 8.0e6) stream_hint |= 2;
-    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, DT, NARROW>), grid, dim3(KW * SW * 64), 0, stream,
+    // asked once per kernel and process (the devices of a process are taken to be alike)
+    static const Residency info = query_residency(reinterpret_cast<const void*>(&spmm_kernel<NT, KW, SW, NCH, LMAX, DT, NARROW>), KW * SW);
+    const size_t lds = lds_to_limit_residency(info, KW * SW, static_cast<int64_t>(grid.x) * grid.y, even_rows);
+    hipLaunchKernelGGL((spmm_kernel<NT, KW, SW, NCH, LMAX, DT, NARROW>), grid, dim3(KW * SW * 64), lds, stream,
                        d.work, d.slots, d.vals, d.perm, B, b_bytes, static_cast<uint32_t>(ldb * ES), static_cast<uint32_t>(d.K),
                        static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N), vec_store, stream_hint);
     return static_cast<int>(hipGetLastError());
@@ -789,10 +836,12 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     while (kw < 8 && d.mean_row_packs >= 4.0 * kw &&
            ((skewed && longest_us / kw > 0.5 * (stream_us + gather_us)) || groups * sw * kw < wave_target)) kw *= 2;
     if (nch == 2 && kw > 4) kw = 4;
+    // rows of about the same length: the launch may hold fewer workgroups per compute unit (launch_variant)
+    const bool even = !skewed && d.mean_row_packs >= 16.0 && whole_lines && sw == 1;
 #define SMAT_LAUNCH(KW_, SW_, NCH_)                                                             \
     do {                                                                                        \
         *variant = variant_name<DT>(NT, KW_, SW_, NCH_, LMAX);                                  \
-        return launch_variant<NT, KW_, SW_, NCH_, LMAX, DT>(d, B, ldb, C, ldc, N, stream);      \
+        return launch_variant<NT, KW_, SW_, NCH_, LMAX, DT>(d, B, ldb, C, ldc, N, stream, even); \
     } while (0)
     if constexpr (kTwoChunks) {
         if (nch == 2) {
