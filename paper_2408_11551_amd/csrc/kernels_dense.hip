@@ -87,7 +87,8 @@ __device__ __forceinline__ u32x4 buf_load16(__amdgpu_buffer_rsrc_t r, uint32_t v
 // 256 accumulators per lane in the accumulation registers (9 % faster than one group at N = 4096,
 // slower than two); the panel read from LDS in two halves around the matrix instructions; requests
 // for the lines of later steps through the scalar cache (88 us against 79 us at the time);
-// transposing reads two groups ahead (65 against 63 us).
+// transposing reads two groups ahead (65 against 63 us); a ring of four steps with the transposing reads (no
+// change, hot or on flushed caches).
 // The tiles are numbered so that the workgroups an XCD runs (every eighth in dispatch order) form
 // compact rectangles of super rows x column slabs: the tile values of a super row and the panel rows
 // of a slab then miss that XCD's L2 once and hit it for the other workgroups that walk them at the
