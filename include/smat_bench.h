@@ -2,7 +2,7 @@
  * smat_bench.h -- measurement entry points of the MI355X (gfx950) blocked SpMM library.
  *
  * Not part of the method's interface (that is smat.h): the reduced kernels of the paper's
- * optimisation-step comparison, and three probe kernels that measure what the device delivers
+ * optimisation-step comparison, and five probe kernels that measure what the device delivers
  * for the access patterns the SpMM kernels are made of.  Conventions as in smat.h.
  */
 #ifndef SMAT_BENCH_H
