@@ -57,7 +57,8 @@ struct smat_handle {
     std::vector<uint32_t> step_rows, step_base;
     std::vector<uint8_t> row_dense;      // [nbr]
     uint64_t dense_slots = 0;
-    bool dense_all_full = false;         // every step of every dense super row: all sixteen block rows, block columns 2q and 2q+1
+    bool dense_all_full = false;         // every step of every dense super row: all sixteen block rows, block columns 2q and 2q+1,
+                                         // and every dense super row has the same number of steps
     int64_t dense_columns = 0;           // occupied columns over the blocks of the dense super rows
     smat::DeviceBcsr dev;                // launch over every block row
     smat::DeviceBcsr dev_rest;           // launch over the block rows the dense path does not cover
@@ -195,6 +196,7 @@ void plan_dense_tiles(smat_handle& h)
             h.dense_slots += static_cast<uint64_t>(__builtin_popcount(rows));
         }
         h.step_ptr.push_back(static_cast<int32_t>(h.step_rows.size()));
+        if (steps != h.step_ptr[1]) h.dense_all_full = false;      // the first dense super row's count
     }
 }
 
@@ -616,6 +618,7 @@ smat_status_t smat_bind_device(smat_handle_t* h, void* dev_workspace, size_t byt
         tiles.mean_steps = tiles.n ? static_cast<double>(h->step_rows.size()) / tiles.n : 0.0;
         tiles.cols_per_step = h->elem_bytes == 1 ? 4 : 2;
         tiles.all_full = h->dense_all_full && tiles.n > 0;
+        tiles.full_steps = tiles.all_full ? h->step_ptr[1] : 0;
         h->d_csr_row_ptr = reinterpret_cast<const int64_t*>(base + l.csr_row_ptr);
         h->d_csr_col_idx = reinterpret_cast<const int32_t*>(base + l.csr_col_idx);
         h->d_csr_vals = reinterpret_cast<const uint16_t*>(base + l.csr_vals);

@@ -54,8 +54,11 @@ struct DenseTiles {
     int32_t n = 0;
     double mean_steps = 0;                 // steps per super row, on average
     int cols_per_step = 2;
-    bool all_full = false;                 // 16-bit types: every step has all sixteen block rows and the block columns 2q, 2q+1
-                                           // (q counted inside the super row), so the kernel needs none of the per-step tables
+    bool all_full = false;                 // every step has all sixteen block rows and the block columns 2q, 2q+1 (8-bit types:
+                                           // 4q .. 4q+3; q counted inside the super row) and every super row has full_steps
+                                           // steps: step q of super row i is step i full_steps + q and its values start at slot
+                                           // 16 (i full_steps + q), so the kernel needs none of the step tables
+    int32_t full_steps = 0;
 };
 
 // Sets n16 16-byte words at dst to zero.

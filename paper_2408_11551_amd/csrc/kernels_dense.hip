@@ -184,7 +184,10 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     const int super = t.super_rows[sidx];
     const int n0 = slab * 128;
     const int ks = static_cast<int>(gridDim.z);    // workgroups sharing this tile's steps
-    const int q_first = t.step_ptr[sidx], q_last = t.step_ptr[sidx + 1];
+    // (a matrix all of whose blocks are stored: the tables would say what can be computed, at the price of two
+    // dependent round trips to memory before the first load of the tile can be issued)
+    const int q_first = FULL ? sidx * t.full_steps : t.step_ptr[sidx];
+    const int q_last = FULL ? q_first + t.full_steps : t.step_ptr[sidx + 1];
     const int per = (q_last - q_first + ks - 1) / ks;
     const int q0 = min(q_first + static_cast<int>(blockIdx.z) * per, q_last);
     const int q1 = min(q0 + per, q_last);
@@ -193,8 +196,8 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     const __amdgpu_buffer_rsrc_t b_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
     // tile values of this workgroup's steps q0..q1-1 are stored back to back
-    const uint32_t first_slot = nq > 0 ? t.step_base[q0] : 0u;
-    const uint32_t end_slot = nq > 0 ? t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]) : 0u;
+    const uint32_t first_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q0) : t.step_base[q0];
+    const uint32_t end_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q1) : t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]);
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
         static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
         static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
@@ -398,6 +401,15 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)");
     }
 
+    // where the lane's sixteen rows of C' go, asked for before the hand-over so that the stores do not wait for it
+    int32_t out_rows[RM][4];
+    if (ks == 1 && kg == 0) {
+#pragma unroll
+        for (int r = 0; r < RM; ++r)
+#pragma unroll
+            for (int y = 0; y < 4; ++y)
+                out_rows[r][y] = d.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
+    }
     if constexpr (KG == 2) {
         // group 1 hands its accumulators to group 0, two block rows per wave at a time, through the
         // 64 KiB the panels occupied
@@ -449,10 +461,9 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     // rows of 512 bytes, was slower: 63.0 against 62.0 us hot, 71.5 against 68.7 us on flushed caches.)
 #pragma unroll
     for (int r = 0; r < RM; ++r) {
-        const int64_t br = static_cast<int64_t>(super) * 16 + RM * wave + r;
 #pragma unroll
         for (int y = 0; y < 4; ++y) {
-            const int64_t out_row = d.perm[br * 16 + 4 * g + y];
+            const int64_t out_row = out_rows[r][y];
             if (out_row < 0) continue;
             Out* dst = C + out_row * ldc + n0 + i;
 #pragma unroll

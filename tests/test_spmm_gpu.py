@@ -150,6 +150,33 @@ def test_block_dense_path(shape, oracle_c):
         x.close()
 
 
+@pytest.mark.parametrize("dtype", ["f16", "bf16"])
+def test_full_blocks_with_unequal_super_rows(dtype, oracle_c):
+    """Every block stored, but the first super row has eight block columns and the second sixteen: the
+    instantiation of the tile kernel that computes its step tables assumes equal super rows and must not be
+    taken; whichever runs, the product is exact on small integers."""
+    w = random_csr(512, 256, 136, 0.6, seed=77, dtype=dtype, values="smallint", b_dist="smallint")
+    rows = np.repeat(np.arange(w.M), np.diff(w.row_ptr))
+    keep = ~((rows < 256) & (w.col_idx >= 128))
+    row_ptr = np.concatenate([[0], np.cumsum(np.bincount(rows[keep], minlength=w.M))]).astype(np.int64)
+    ws = Workload("staircase", dtype, w.M, w.K, w.N, row_ptr, w.col_idx[keep], w.a_bits[keep], w.b_bits)
+    for reorder in (0, 1):
+        m = S.SmatMatrix(ws.M, ws.K, ws.row_ptr, ws.col_idx, ws.a_bits, ws.dtype, reorder=reorder, dense_tiles=1)
+        c = m.spmm(_dev_b(ws))
+        torch.cuda.synchronize()
+        assert S.smat_last_kernel().startswith("spmm_dense"), S.smat_last_kernel()
+        c_ref, _ = _oracle_c(oracle_c, ws)
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+        m.close()
+    # the same with equal super rows (all of K in both): the computed tables
+    mf = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, reorder=0, dense_tiles=1)
+    c = mf.spmm(_dev_b(w))
+    torch.cuda.synchronize()
+    c_ref, _ = _oracle_c(oracle_c, w)
+    assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+    mf.close()
+
+
 @pytest.mark.parametrize("N", [8, 40, 128, 272])
 @pytest.mark.parametrize("dtype", ["f16", "bf16"])
 def test_pack_boundaries_and_mixed_row_classes(N, dtype, oracle_c):
