@@ -29,7 +29,7 @@ UNITS = {
     "kernels_i8": ("kernels_8bit.hip", ["-DSMAT_8BIT_DT=4", *PRELOAD]),
     # the dense kernel keeps 128 accumulator registers per lane next to ~90 others: have the
     # MFMA results live in ordinary VGPRs instead of being shuffled between the two register files
-    "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
+    "kernels_dense": ("kernels_dense.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1", *PRELOAD]),
     # the tile-step probe is the tile kernel's loop: same flag
     "probes": ("probes.hip", ["-mllvm", "-amdgpu-mfma-vgpr-form=1"]),
     "ablation": ("ablation.hip", []),

@@ -99,6 +99,14 @@ constexpr int kTileGroup = 4;          // super rows of a rectangle
 struct TileOrder {
     int n_super, n_slab, per_xcd;      // per_xcd = ceil(tiles / 8)
 };
+// What the tile kernel needs later than its first loads (DenseTiles and DeviceBcsr have the rest).
+struct TileTables {
+    const int32_t* step_cols;
+    const uint32_t* step_rows;
+    const uint32_t* step_base;
+    const int32_t* perm;
+    void* scratch;
+};
 
 __device__ __forceinline__ uint32_t lds_offset_of(const void* p)
 {
@@ -153,9 +161,18 @@ __device__ __forceinline__ void lds_pair_done(u32x2_t& lo, u32x2_t& hi)
 template <int DT, int KG, bool FULL = false>
 __global__ __launch_bounds__(256 * KG)
 __attribute__((amdgpu_waves_per_eu(2, 2)))
-void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* __restrict__ B, uint32_t b_bytes,
-                        uint32_t ldb_bytes, typename Elem<DT>::Out* __restrict__ C, int64_t ldc, int N)
+void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t* __restrict__ super_rows,
+                      const void* steps_arg, const void* __restrict__ B, const void* __restrict__ tile_vals,
+                      uint32_t ldb_bytes, uint32_t K, TileTables tab, typename Elem<DT>::Out* __restrict__ C, int64_t ldc)
 {
+    // The fourteen words in front are what the first loads of a tile are computed from; the compiler is asked (build
+    // flag) to have the dispatcher place them in scalar registers, so that a workgroup does not begin by waiting
+    // for a load of its own arguments.  n_super, n_slab, per_xcd: the tile order; steps_arg: the table of the super
+    // rows' first steps, or (FULL, where the tables are computed) the number of steps of every super row; K: rows of B.
+    const int32_t* __restrict__ step_ptr = static_cast<const int32_t*>(steps_arg);
+    const int full_steps = static_cast<int>(reinterpret_cast<uintptr_t>(steps_arg));
+    constexpr uint32_t kElemBytes = Elem<DT>::ES;
+    const uint32_t b_bytes = K > 0u ? (K - 1u) * ldb_bytes + static_cast<uint32_t>(N) * kElemBytes : 0u;   // the rows' padding after the last row is not B's
     using Acc = typename Elem<DT>::Acc;
     using Out = typename Elem<DT>::Out;
     constexpr int ES = Elem<DT>::ES;               // bytes per element of A and B
@@ -169,10 +186,10 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     __shared__ u32x4 lds_words[kLdsWords];
 
     // tile of this workgroup: the XCD's share of the tile numbers is contiguous
-    const int tile = static_cast<int>(blockIdx.x % 8u) * order.per_xcd + static_cast<int>(blockIdx.x / 8u);
-    if (tile >= order.n_super * order.n_slab) return;
-    const int band = tile / (kTileGroup * order.n_slab), in_band = tile % (kTileGroup * order.n_slab);
-    const int band_rows = min(kTileGroup, order.n_super - kTileGroup * band);
+    const int tile = static_cast<int>(blockIdx.x % 8u) * per_xcd + static_cast<int>(blockIdx.x / 8u);
+    if (tile >= n_super * n_slab) return;
+    const int band = tile / (kTileGroup * n_slab), in_band = tile % (kTileGroup * n_slab);
+    const int band_rows = min(kTileGroup, n_super - kTileGroup * band);
     const int sidx = kTileGroup * band + in_band % band_rows;
     const int slab = in_band / band_rows;
 
@@ -181,13 +198,13 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);             // wave inside its group
     const int kg = KG == 1 ? 0 : __builtin_amdgcn_readfirstlane(static_cast<int>(threadIdx.x) >> 8);
     const int i = lane & 15, g = lane >> 4;
-    const int super = t.super_rows[sidx];
+    const int super = super_rows[sidx];
     const int n0 = slab * 128;
     const int ks = static_cast<int>(gridDim.z);    // workgroups sharing this tile's steps
     // (a matrix all of whose blocks are stored: the tables would say what can be computed, at the price of two
     // dependent round trips to memory before the first load of the tile can be issued)
-    const int q_first = FULL ? sidx * t.full_steps : t.step_ptr[sidx];
-    const int q_last = FULL ? q_first + t.full_steps : t.step_ptr[sidx + 1];
+    const int q_first = FULL ? sidx * full_steps : step_ptr[sidx];
+    const int q_last = FULL ? q_first + full_steps : step_ptr[sidx + 1];
     const int per = (q_last - q_first + ks - 1) / ks;
     const int q0 = min(q_first + static_cast<int>(blockIdx.z) * per, q_last);
     const int q1 = min(q0 + per, q_last);
@@ -196,10 +213,10 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     const __amdgpu_buffer_rsrc_t b_rsrc =
         __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(B), 0, static_cast<int>(b_bytes), kRsrcFlags);
     // tile values of this workgroup's steps q0..q1-1 are stored back to back
-    const uint32_t first_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q0) : t.step_base[q0];
-    const uint32_t end_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q1) : t.step_base[q1 - 1] + __popc(t.step_rows[q1 - 1]);
+    const uint32_t first_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q0) : tab.step_base[q0];
+    const uint32_t end_slot = nq <= 0 ? 0u : FULL ? 16u * static_cast<uint32_t>(q1) : tab.step_base[q1 - 1] + __popc(tab.step_rows[q1 - 1]);
     const __amdgpu_buffer_rsrc_t a_rsrc = __builtin_amdgcn_make_buffer_rsrc(
-        static_cast<uint8_t*>(const_cast<void*>(t.vals)) + static_cast<size_t>(first_slot) * 1024, 0,
+        static_cast<uint8_t*>(const_cast<void*>(tile_vals)) + static_cast<size_t>(first_slot) * 1024, 0,
         static_cast<int>((end_slot - first_slot) * 1024u), kRsrcFlags);
 
     // A wave's share of a panel is two loads of 1 KiB, lane l delivering the 16 bytes at position 16 l.
@@ -215,8 +232,8 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     const int st_piece = ES == 2 ? (lane & 15) ^ (2 * ((lane >> 4) & 3)) : (lane & 7) ^ ((lane >> 3) & 7);
     const int st_col = n0 + (16 / ES) * st_piece;
     const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
-    const uint32_t no_row = static_cast<uint32_t>(d.K);
-    const int nbc = static_cast<int>((d.K + 15) >> 4);
+    const uint32_t no_row = K;
+    const int nbc = static_cast<int>((K + 15u) >> 4);
     const uint32_t panels = lds_offset_of(lds_words) + static_cast<uint32_t>(kg) * (RD * 8192);   // this group's ring
     // where load e of this wave goes in panel buf
     auto lds_of_load = [&](int buf, int e) {
@@ -251,8 +268,8 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     // contains loads that write LDS, which it takes for writes to anything.)
     typedef __attribute__((address_space(4))) const int32_t* const_i32;
     typedef __attribute__((address_space(4))) const uint32_t* const_u32;
-    const const_i32 step_cols = (const_i32)t.step_cols;
-    const const_u32 step_rows = (const_u32)t.step_rows, step_base = (const_u32)t.step_base;
+    const const_i32 step_cols = (const_i32)tab.step_cols;
+    const const_u32 step_rows = (const_u32)tab.step_rows, step_base = (const_u32)tab.step_base;
     auto is_live = [&](int gs) { return kg + KG * gs < nq; };      // step gs of this wave group = step kg + KG * gs of the tile
     auto fetch_meta = [&](int gs) {
         const bool live = is_live(gs);
@@ -408,7 +425,7 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
         for (int r = 0; r < RM; ++r)
 #pragma unroll
             for (int y = 0; y < 4; ++y)
-                out_rows[r][y] = d.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
+                out_rows[r][y] = tab.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
     }
     if constexpr (KG == 2) {
         // group 1 hands its accumulators to group 0, two block rows per wave at a time, through the
@@ -444,8 +461,8 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
     // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
     if (ks > 1) {
         // partial tile, row-major 256 x 128 words, at [(tile * ks + z)]
-        const size_t tile_at = static_cast<size_t>(sidx) * order.n_slab + slab;
-        Out* part = static_cast<Out*>(t.scratch) + (tile_at * ks + blockIdx.z) * (256 * 128);
+        const size_t tile_at = static_cast<size_t>(sidx) * n_slab + slab;
+        Out* part = static_cast<Out*>(tab.scratch) + (tile_at * ks + blockIdx.z) * (256 * 128);
 #pragma unroll
         for (int r = 0; r < RM; ++r)
 #pragma unroll
@@ -474,7 +491,7 @@ void spmm_tile_kernel(DeviceBcsr d, DenseTiles t, TileOrder order, const void* _
 }
 
 template <int DT, int KG>
-static void launch_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, uint32_t b_bytes, int64_t ldb,
+static void launch_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const void* B, int64_t ldb,
                           void* C, int64_t ldc, int64_t N, hipStream_t s)
 {
     TileOrder order;
@@ -482,12 +499,17 @@ static void launch_tile(const DeviceBcsr& d, const DenseTiles& t, int ks, const 
     order.n_slab = static_cast<int>((N + 127) / 128);
     order.per_xcd = (order.n_super * order.n_slab + 7) / 8;
     dim3 grid(static_cast<unsigned>(8 * order.per_xcd), 1, static_cast<unsigned>(ks));
+    const TileTables tab{t.step_cols, t.step_rows, t.step_base, d.perm, t.scratch};
+    const uint32_t ldb_bytes = static_cast<uint32_t>(ldb * Elem<DT>::ES);
+    auto* out = static_cast<typename Elem<DT>::Out*>(C);
     if (t.all_full)
-        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, true>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
-                           static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N));
+        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, true>), grid, dim3(256 * KG), 0, s, order.n_super, order.n_slab, order.per_xcd,
+                           static_cast<int>(N), t.super_rows, reinterpret_cast<const void*>(static_cast<uintptr_t>(t.full_steps)), B,
+                           t.vals, ldb_bytes, static_cast<uint32_t>(d.K), tab, out, ldc);
     else
-        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, false>), grid, dim3(256 * KG), 0, s, d, t, order, B, b_bytes,
-                           static_cast<uint32_t>(ldb * Elem<DT>::ES), static_cast<typename Elem<DT>::Out*>(C), ldc, static_cast<int>(N));
+        hipLaunchKernelGGL((spmm_tile_kernel<DT, KG, false>), grid, dim3(256 * KG), 0, s, order.n_super, order.n_slab, order.per_xcd,
+                           static_cast<int>(N), t.super_rows, static_cast<const void*>(t.step_ptr), B,
+                           t.vals, ldb_bytes, static_cast<uint32_t>(d.K), tab, out, ldc);
 }
 
 template <typename T>
@@ -625,7 +647,6 @@ static int launch_dense_dtype(const DeviceBcsr& d, const DenseTiles& t, const vo
 {
     using Out = typename Elem<DT>::Out;
     using Acc = typename Elem<DT>::Acc;
-    const uint32_t b_bytes = d.K > 0 ? static_cast<uint32_t>(((d.K - 1) * ldb + N) * Elem<DT>::ES) : 0u;
     const int vec_store = (ldc % 4 == 0 && reinterpret_cast<uintptr_t>(C) % 16 == 0 && N % 4 == 0) ? 1 : 0;
     // long super rows: two wave groups per workgroup; short ones: one group, two workgroups per CU
     const bool deep = t.mean_steps >= 32.0;
@@ -635,8 +656,8 @@ static int launch_dense_dtype(const DeviceBcsr& d, const DenseTiles& t, const vo
     if (ks > 1) snprintf(name, sizeof(name), "spmm_dense_%s_g%dk%d", type, deep ? 2 : 1, ks);
     else snprintf(name, sizeof(name), "spmm_dense_%s_g%d", type, deep ? 2 : 1);
     *variant = name;
-    if (deep) launch_tile<DT, 2>(d, t, ks, B, b_bytes, ldb, C, ldc, N, s);
-    else launch_tile<DT, 1>(d, t, ks, B, b_bytes, ldb, C, ldc, N, s);
+    if (deep) launch_tile<DT, 2>(d, t, ks, B, ldb, C, ldc, N, s);
+    else launch_tile<DT, 1>(d, t, ks, B, ldb, C, ldc, N, s);
     if (ks > 1)
         hipLaunchKernelGGL((dense_reduce_kernel<Acc, Out>), dim3(static_cast<unsigned>(t.n), static_cast<unsigned>((N + 127) / 128), 8),
                            dim3(256), 0, s, d, t, ks, static_cast<Out*>(C), ldc, static_cast<int>(N), vec_store);
