@@ -427,9 +427,37 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
             for (int y = 0; y < 4; ++y)
                 out_rows[r][y] = tab.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
     }
+    // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
+    auto store_block_row = [&](int r) {
+        if (ks > 1) {
+            // partial tile, row-major 256 x 128 words, at [(tile * ks + z)]
+            const size_t tile_at = static_cast<size_t>(sidx) * n_slab + slab;
+            Out* part = static_cast<Out*>(tab.scratch) + (tile_at * ks + blockIdx.z) * (256 * 128);
+#pragma unroll
+            for (int y = 0; y < 4; ++y) {
+                Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + i;
+#pragma unroll
+                for (int x = 0; x < NT; ++x) dst[16 * x] = acc[r][x][y];
+            }
+            return;
+        }
+        // sixteen lanes store 64 consecutive bytes of a row of C; the eight groups of columns of a lane
+        // lie 64 bytes apart.  (Turning the tile over through LDS first, to store 16 bytes per lane and whole
+        // rows of 512 bytes, was slower: 63.0 against 62.0 us hot, 71.5 against 68.7 us on flushed caches.)
+#pragma unroll
+        for (int y = 0; y < 4; ++y) {
+            const int64_t out_row = out_rows[r][y];
+            if (out_row < 0) continue;
+            Out* dst = C + out_row * ldc + n0 + i;
+#pragma unroll
+            for (int x = 0; x < NT; ++x)
+                if (n0 + 16 * x + i < N) dst[16 * x] = acc[r][x][y];
+        }
+    };
     if constexpr (KG == 2) {
         // group 1 hands its accumulators to group 0, two block rows per wave at a time, through the
-        // 64 KiB the panels occupied
+        // 64 KiB the panels occupied; group 0 sends the first two block rows on their way to memory
+        // while group 1 writes the other two into LDS
         __syncthreads();
         Out* handover = reinterpret_cast<Out*>(lds_words);
 #pragma unroll
@@ -453,41 +481,16 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
                         for (int y = 0; y < 4; ++y)
                             acc[2 * half + rr][x][y] += handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
             }
-            __syncthreads();
-        }
-        if (kg == 1) return;
-    }
-
-    // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
-    if (ks > 1) {
-        // partial tile, row-major 256 x 128 words, at [(tile * ks + z)]
-        const size_t tile_at = static_cast<size_t>(sidx) * n_slab + slab;
-        Out* part = static_cast<Out*>(tab.scratch) + (tile_at * ks + blockIdx.z) * (256 * 128);
-#pragma unroll
-        for (int r = 0; r < RM; ++r)
-#pragma unroll
-            for (int y = 0; y < 4; ++y) {
-                Out* dst = part + (64 * wave + 16 * r + 4 * g + y) * 128 + i;
-#pragma unroll
-                for (int x = 0; x < NT; ++x) dst[16 * x] = acc[r][x][y];
+            if (half == 0) __syncthreads();        // the area is free for the second half
+            if (kg == 0) {
+                store_block_row(2 * half);
+                store_block_row(2 * half + 1);
             }
+        }
         return;
     }
-    // sixteen lanes store 64 consecutive bytes of a row of C; the eight groups of columns of a lane
-    // lie 64 bytes apart.  (Turning the tile over through LDS first, to store 16 bytes per lane and whole
-    // rows of 512 bytes, was slower: 63.0 against 62.0 us hot, 71.5 against 68.7 us on flushed caches.)
 #pragma unroll
-    for (int r = 0; r < RM; ++r) {
-#pragma unroll
-        for (int y = 0; y < 4; ++y) {
-            const int64_t out_row = out_rows[r][y];
-            if (out_row < 0) continue;
-            Out* dst = C + out_row * ldc + n0 + i;
-#pragma unroll
-            for (int x = 0; x < NT; ++x)
-                if (n0 + 16 * x + i < N) dst[16 * x] = acc[r][x][y];
-        }
-    }
+    for (int r = 0; r < RM; ++r) store_block_row(r);
 }
 
 template <int DT, int KG>
