@@ -172,7 +172,10 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     const int32_t* __restrict__ step_ptr = static_cast<const int32_t*>(steps_arg);
     const int full_steps = static_cast<int>(reinterpret_cast<uintptr_t>(steps_arg));
     constexpr uint32_t kElemBytes = Elem<DT>::ES;
-    const uint32_t b_bytes = K > 0u ? (K - 1u) * ldb_bytes + static_cast<uint32_t>(N) * kElemBytes : 0u;   // the rows' padding after the last row is not B's
+    // (the rows' padding after the last row is not B's.  Said to be wave-uniform in so many words: the compiler has
+    // computed it on the vector unit and then wrapped every load through the descriptor into a loop over lanes.)
+    const uint32_t b_bytes = static_cast<uint32_t>(__builtin_amdgcn_readfirstlane(
+        static_cast<int>(K > 0u ? (K - 1u) * ldb_bytes + static_cast<uint32_t>(N) * kElemBytes : 0u)));
     using Acc = typename Elem<DT>::Acc;
     using Out = typename Elem<DT>::Out;
     constexpr int ES = Elem<DT>::ES;               // bytes per element of A and B
@@ -226,12 +229,22 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     // the wave brings block column `wave`, load e its rows 8 e .. 8 e + 7, lane l the piece l & 7 of row l >> 3.
     // (N is a multiple of the columns of a piece on this path, so a piece is all inside or all outside.)
     const int st_row = ES == 2 ? 4 * wave + (lane >> 4) : lane >> 3;
-    // The piece that lands at position p of row r of the panel is piece p ^ 2 (r & 3) of that row of B
-    // (8-bit: p ^ (r & 7)), so that the sixteen lanes of a transposing read -- four rows x 32 bytes, or
-    // eight rows x 16 bytes -- hit every bank once.
-    const int st_piece = ES == 2 ? (lane & 15) ^ (2 * ((lane >> 4) & 3)) : (lane & 7) ^ ((lane >> 3) & 7);
-    const int st_col = n0 + (16 / ES) * st_piece;
-    const uint32_t st_off = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
+    // The piece that lands at position p of row r of the panel is piece p ^ 2 (r & 3) ^ 8 (r / 8 & 1) of that
+    // row of B (8-bit: p ^ (r / 2 & 7)).  LDS has 64 banks of four bytes and serves 32 lanes of an 8-byte read
+    // per clock; the 32 lanes of a transposing read name rows 8 g + e of two lane groups g -- four rows e x
+    // 32 bytes each with 256-byte rows, eight rows x 16 bytes with 128-byte rows -- and with this placement
+    // they hit every bank once.  (Placed for sixteen lanes only, p ^ 2 (r & 3) and p ^ (r & 7), the two
+    // lane groups met in the same banks: the counters showed a bank conflict in 47 % of the LDS cycles.)
+    // (16-bit: r = 16 e + 4 wave + lane / 16 for load e; 8-bit: r = 16 wave + 8 e + lane / 8, so the two loads of a
+    // wave differ in the placement)
+    uint32_t st_off_of[2];
+#pragma unroll
+    for (int e = 0; e < 2; ++e) {
+        const int st_piece = ES == 2 ? (lane & 15) ^ (2 * ((lane >> 4) & 3)) ^ (8 * ((wave >> 1) & 1))
+                                     : (lane & 7) ^ (4 * e + (lane >> 4));
+        const int st_col = n0 + (16 / ES) * st_piece;
+        st_off_of[e] = st_col < N ? static_cast<uint32_t>(st_col) * ES : kOutOfRange;
+    }
     const uint32_t no_row = K;
     const int nbc = static_cast<int>((K + 15u) >> 4);
     const uint32_t panels = lds_offset_of(lds_words) + static_cast<uint32_t>(kg) * (RD * 8192);   // this group's ring
@@ -242,8 +255,9 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     // Where this lane reads (+ 8192 per panel).  16-bit: lane (g, j) names row 8 g + j / 4 (+ 4 for the
     // second read, + 1024 bytes) and, for the group of columns 16 x .. 16 x + 15, the eight bytes of columns
     // 16 x + 4 (j % 4) ..: piece 2 x + (j % 4) / 2 of the row, which lies at position
-    // (2 x + (j % 4) / 2) ^ 2 (j / 4).  8-bit: row 8 g + j / 2 of the first sub-step (the second: + 32 rows,
-    // + 4096 bytes), the eight bytes of columns 16 x + 8 (j % 2) ..: half j % 2 of piece x, at position x ^ (j / 2).
+    // (2 x + (j % 4) / 2) ^ 2 (j / 4) ^ 8 (g & 1).  8-bit: row 8 g + j / 2 of the first sub-step (the second: + 32 rows,
+    // + 4096 bytes), the eight bytes of columns 16 x + 8 (j % 2) ..: half j % 2 of piece x, at position
+    // x ^ (4 (g & 1) + j / 4).
     constexpr uint32_t kSecondRead = ES == 2 ? 1024u : 4096u;
     uint32_t tr_addr[8];
     {
@@ -251,10 +265,10 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
         for (int x = 0; x < 8; ++x) {
             if constexpr (ES == 2) {
                 const int e = i >> 2, qq = i & 3;
-                tr_addr[x] = panels + (8 * g + e) * 256u + 32u * (x ^ e) + 16u * (qq >> 1) + 8u * (qq & 1);
+                tr_addr[x] = panels + (8 * g + e) * 256u + 32u * (x ^ e ^ (4 * (g & 1))) + 16u * (qq >> 1) + 8u * (qq & 1);
             } else {
                 const int e = i >> 1, qq = i & 1;
-                tr_addr[x] = panels + (8 * g + e) * 128u + 16u * (x ^ e) + 8u * qq;
+                tr_addr[x] = panels + (8 * g + e) * 128u + 16u * (x ^ (4 * (g & 1) + (e >> 1))) + 8u * qq;
             }
         }
     }
@@ -262,7 +276,8 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     // What a step's loads need to know, fetched with scalar loads a step before it is used.  A
     // step past the group's last one names no block column (its panel rows read zeros) and no block
     // row (its block values read zeros).
-    struct StepMeta { int c[2 * KS]; uint32_t rows, base; };
+    // (c: the block columns this wave brings into LDS -- both of a 16-bit step, or the wave's one of an 8-bit step's four)
+    struct StepMeta { int c[2]; uint32_t rows, base; };
     // (The tables are written at bind time and never while a kernel runs.  Reading them through the
     // constant address space tells the compiler so: the loads stay scalar even though the loop
     // contains loads that write LDS, which it takes for writes to anything.)
@@ -281,14 +296,14 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
             // a matrix all of whose blocks are stored: step q of the super row has the block columns
             // 2q and 2q+1 (8-bit: 4q .. 4q+3) and a block of every block row -- nothing to look up (3 % of a launch)
             const int rel = static_cast<int>(q) - q_first;
-#pragma unroll
-            for (int e = 0; e < 2 * KS; ++e) m.c[e] = 2 * KS * rel + e;
+            m.c[0] = 2 * KS * rel + (ES == 2 ? 0 : wave);
+            m.c[1] = 2 * KS * rel + 1;
             m.rows = 0xFFFFu;
             m.base = first_slot + 16u * static_cast<uint32_t>(static_cast<int>(q) - q0);
             return m;
         }
-#pragma unroll
-        for (int e = 0; e < 2 * KS; ++e) m.c[e] = step_cols[(2 * KS) * q + e];
+        m.c[0] = step_cols[(2 * KS) * q + (ES == 2 ? 0 : wave)];
+        m.c[1] = ES == 2 ? step_cols[(2 * KS) * q + 1] : 0;
         m.rows = step_rows[q];
         m.base = step_base[q];
         return m;
@@ -296,13 +311,11 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     // e-th load of the wave's share of the step's panel (e = 0, 1): one load into LDS
     auto load_panel_half = [&](const StepMeta& m, bool live, int buf, int e) {
         // rows past K (ragged last block column, or no such column) are out of range: zeros
-        int c;                                                                           // scalar selects, no branch
-        if constexpr (ES == 2) c = e == 0 ? m.c[0] : m.c[1];
-        else c = wave == 0 ? m.c[0] : wave == 1 ? m.c[1] : wave == 2 ? m.c[2] : m.c[3];
+        int c = ES == 2 && e == 1 ? m.c[1] : m.c[0];
         c = live ? c : 0x7FFFFFFF;
         uint32_t row = c < nbc ? static_cast<uint32_t>(c) * 16u + (ES == 2 ? 0 : 8 * e) + st_row : no_row;
         row = row < no_row ? row : no_row;
-        load_to_lds16((lds_void*)(uintptr_t)lds_of_load(buf, e), b_rsrc, __umul24(row, ldb_bytes) + st_off, 0u);
+        load_to_lds16((lds_void*)(uintptr_t)lds_of_load(buf, e), b_rsrc, __umul24(row, ldb_bytes) + st_off_of[e], 0u);
     };
     auto load_panel = [&](const StepMeta& m, bool live, int buf) {
         load_panel_half(m, live, buf, 0);
@@ -387,16 +400,20 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
                 // the int8 instruction with k = 64 takes at once and the 8-bit floats one after the other
                 // (the lane's block values of sub-step j are dwords 2j, 2j+1)
                 const u32x4 b = u32x4{lo[x & 1][0], lo[x & 1][1], hi[x & 1][0], hi[x & 1][1]};
+                // (the 8-bit forms with the result in the addend's registers, see mfma_types.h; the 8-bit floats
+                // take the four block rows' first sub-step and then their second, so that no instruction waits
+                // for the one before it)
+                if constexpr (ES == 2) {
 #pragma unroll
-                for (int r = 0; r < RM; ++r) {
-                    if constexpr (ES == 2) {
-                        acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
-                    } else if constexpr (DT == kI8) {
-                        acc[r][x] = mfma_i8_k64(a[u][r], b, acc[r][x]);
-                    } else {
-                        acc[r][x] = mfma_pack<DT>(u32x4{a[u][r][0], a[u][r][1], 0u, 0u}, u32x4{b[0], b[1], 0u, 0u}, acc[r][x]);
-                        acc[r][x] = mfma_pack<DT>(u32x4{a[u][r][2], a[u][r][3], 0u, 0u}, u32x4{b[2], b[3], 0u, 0u}, acc[r][x]);
-                    }
+                    for (int r = 0; r < RM; ++r) acc[r][x] = mfma_pack<DT>(a[u][r], b, acc[r][x]);
+                } else if constexpr (DT == kI8) {
+#pragma unroll
+                    for (int r = 0; r < RM; ++r) mfma_i8_k64_in_place(a[u][r], b, acc[r][x]);
+                } else {
+#pragma unroll
+                    for (int r = 0; r < RM; ++r) mfma_pack8_in_place<DT>(a[u][r], b, false, acc[r][x]);
+#pragma unroll
+                    for (int r = 0; r < RM; ++r) mfma_pack8_in_place<DT>(a[u][r], b, true, acc[r][x]);
                 }
                 __builtin_amdgcn_sched_barrier(0);
                 if (x < 2) {
@@ -416,16 +433,23 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
         }
         // nothing may still be on its way into LDS when the buffers get another use or the workgroup ends
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)");
+        // the last matrix instructions written out by hand have finished before anything reads their result
+        if constexpr (ES == 1) asm volatile("s_nop 15\n\ts_nop 15");
     }
 
-    // where the lane's sixteen rows of C' go, asked for before the hand-over so that the stores do not wait for it
+    // Where the lane's sixteen rows of C' go, asked for before the hand-over so that the stores do not wait for it --
+    // but not before the loop: the sixteen registers are free only now that the ring of block values is dead.  (The
+    // empty statement makes the super row's number a value the compiler knows only from here on; with the loads
+    // hoisted above the loop the 8-bit instantiations spilled registers inside it and ran 79 instead of 53 us.)
     int32_t out_rows[RM][4];
+    int super_now = super;
+    asm volatile("" : "+s"(super_now));
     if (ks == 1 && kg == 0) {
 #pragma unroll
         for (int r = 0; r < RM; ++r)
 #pragma unroll
             for (int y = 0; y < 4; ++y)
-                out_rows[r][y] = tab.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
+                out_rows[r][y] = tab.perm[(static_cast<int64_t>(super_now) * 16 + RM * wave + r) * 16 + 4 * g + y];
     }
     // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
     auto store_block_row = [&](int r) {

@@ -52,4 +52,25 @@ __device__ __forceinline__ i32x4 mfma_i8_k64(u32x4 a, u32x4 b, i32x4 c)
     return __builtin_amdgcn_mfma_i32_16x16x64_i8(__builtin_bit_cast(i32x4, a), __builtin_bit_cast(i32x4, b), c, 0, 0, 0);
 }
 
+// The same instructions for the 8-bit types written out, with the result in the registers of the addend.  The
+// compiler's own choice for these forms (unlike the 16-bit ones) is a result apart from the addend: a loop with 128
+// accumulators per lane then drifts through some 45 further registers and, at the limit of 256, spills inside the
+// loop.  The compiler does not see a matrix instruction here and adds none of the waits it would put in front of a
+// later ordinary instruction that reads the result (up to 18 clocks): whoever uses these leaves that distance.
+// `second` picks dwords 2, 3 of a and b (the second sub-step of 32 k slots) instead of 0, 1.
+template <int DT>
+__device__ __forceinline__ void mfma_pack8_in_place(u32x4 a, u32x4 b, bool second, typename Elem<DT>::Acc& c)
+{
+    static_assert(DT == kE4M3 || DT == kE5M2 || DT == kI8, "8-bit operand types");
+    const u32x2 a8 = second ? u32x2{a[2], a[3]} : u32x2{a[0], a[1]};
+    const u32x2 b8 = second ? u32x2{b[2], b[3]} : u32x2{b[0], b[1]};
+    if constexpr (DT == kE4M3) asm("v_mfma_f32_16x16x32_fp8_fp8 %0, %1, %2, %0" : "+v"(c) : "v"(a8), "v"(b8));
+    else if constexpr (DT == kE5M2) asm("v_mfma_f32_16x16x32_bf8_bf8 %0, %1, %2, %0" : "+v"(c) : "v"(a8), "v"(b8));
+    else asm("v_mfma_i32_16x16x32_i8 %0, %1, %2, %0" : "+v"(c) : "v"(a8), "v"(b8));
+}
+__device__ __forceinline__ void mfma_i8_k64_in_place(u32x4 a, u32x4 b, i32x4& c)
+{
+    asm("v_mfma_i32_16x16x64_i8 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+
 }  // namespace smat

@@ -162,7 +162,7 @@ void probe_tile_step_kernel(int steps, const u32x4* __restrict__ src, float* sin
     uint32_t tr[8];                                // transposing reads: where lane (g, j) reads for column group x
     {
         const int g = lane >> 4, j = lane & 15, e = j >> 2, q = j & 3;
-        for (int x = 0; x < 8; ++x) tr[x] = lds_base + (8 * g + e) * 256 + 32 * (x ^ e) + 16 * (q >> 1) + 8 * (q & 1);
+        for (int x = 0; x < 8; ++x) tr[x] = lds_base + (8 * g + e) * 256 + 32 * (x ^ e ^ (4 * (g & 1))) + 16 * (q >> 1) + 8 * (q & 1);
     }
     u32x4 a[3][4];
     for (int u = 0; u < 3; ++u)

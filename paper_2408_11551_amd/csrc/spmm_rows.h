@@ -846,8 +846,12 @@ static int launch_shape(const DeviceBcsr& d, const void* B, int64_t ldb, void* C
     if constexpr (kTwoChunks) {
         if (nch == 2) {
             if (sw == 2) {
-                if (kw >= 4) SMAT_LAUNCH(4, 2, 2);
-                if (kw == 2) SMAT_LAUNCH(2, 2, 2);
+                // (eight waves per workgroup leave a wave 256 registers; with packs of up to sixteen columns the
+                // two-chunk walk wants some 270 and would spill inside its loop: two waves per row there)
+                if constexpr (LMAX < 4) {
+                    if (kw >= 4) SMAT_LAUNCH(4, 2, 2);
+                }
+                if (kw >= 2) SMAT_LAUNCH(2, 2, 2);
                 SMAT_LAUNCH(1, 2, 2);
             }
             if (kw >= 4) SMAT_LAUNCH(4, 1, 2);

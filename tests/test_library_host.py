@@ -20,6 +20,24 @@ def _declared(header_name):
     return set(re.findall(r"\b(smat_[a-z_]+)\s*\(", header))
 
 
+def test_kernels_that_count_their_loads_do_not_spill():
+    """The build's report of what the compiler gave every kernel: the SpMM kernels wait for their loads by count, and a
+    register spilled inside their loops adds loads that the count does not know of (correct, but the prefetch is gone)."""
+    import json
+    from paper_2408_11551_amd import build
+    if not os.path.exists(build.RESOURCES):
+        pytest.skip("the library was built elsewhere: no report")
+    if os.path.getmtime(build.RESOURCES) + 60 < os.path.getmtime(S.lib_path()):
+        pytest.skip("the report is older than the library")
+    usage = json.load(open(build.RESOURCES))
+    hot = {k: u for k, u in usage.items() if any(n in k for n in build.NO_SPILL)}
+    assert len(hot) > 100                       # the instantiations of the per-row and the tile kernel
+    assert any("spmm_tile_kernelILi4E" in k for k in hot) and any("spmm_tile_kernelILi2E" in k for k in hot)
+    for k, u in hot.items():
+        assert u.get("ScratchSize", 0) == 0 and u.get("VGPRs Spill", 0) == 0, (k, u)
+        assert u["VGPRs"] <= 256, (k, u)
+
+
 def test_library_exports_every_declared_symbol():
     method, bench = _declared("smat.h"), _declared("smat_bench.h")
     assert {"smat_preprocess", "smat_spmm", "smat_bind_device", "smat_export_bcsr", "smat_get_dims"} <= method
