@@ -184,8 +184,8 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     constexpr int RM = 4;                          // block rows per wave
     constexpr int RD = 3;                          // ring depth: panels in LDS, steps of block values in registers
     // per wave group, RD panels of 8 KiB: 32 rows of B x 128 columns of two bytes, or 64 rows x 128 columns of one
-    // byte; the two groups' hand-over at the end needs 64 KiB
-    constexpr int kLdsWords = KG == 2 ? (KG * RD * 32 * 16 > 4096 ? KG * RD * 32 * 16 : 4096) : KG * RD * 32 * 16;
+    // byte; the two groups' hand-over at the end needs 128 KiB
+    constexpr int kLdsWords = KG == 2 ? (KG * RD * 32 * 16 > 8192 ? KG * RD * 32 * 16 : 8192) : KG * RD * 32 * 16;
     __shared__ u32x4 lds_words[kLdsWords];
 
     // tile of this workgroup: the XCD's share of the tile numbers is contiguous
@@ -441,15 +441,18 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
     // but not before the loop: the sixteen registers are free only now that the ring of block values is dead.  (The
     // empty statement makes the super row's number a value the compiler knows only from here on; with the loads
     // hoisted above the loop the 8-bit instantiations spilled registers inside it and ran 79 instead of 53 us.)
+    // (with two groups a lane stores two of its four block rows: group 0 the first two, group 1 the others)
     int32_t out_rows[RM][4];
     int super_now = super;
     asm volatile("" : "+s"(super_now));
-    if (ks == 1 && kg == 0) {
+    if (ks == 1) {
 #pragma unroll
         for (int r = 0; r < RM; ++r)
+            if (KG == 1 || (r >> 1) == kg) {
 #pragma unroll
-            for (int y = 0; y < 4; ++y)
-                out_rows[r][y] = tab.perm[(static_cast<int64_t>(super_now) * 16 + RM * wave + r) * 16 + 4 * g + y];
+                for (int y = 0; y < 4; ++y)
+                    out_rows[r][y] = tab.perm[(static_cast<int64_t>(super_now) * 16 + RM * wave + r) * 16 + 4 * g + y];
+            }
     }
     // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
     auto store_block_row = [&](int r) {
@@ -479,37 +482,38 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
         }
     };
     if constexpr (KG == 2) {
-        // group 1 hands its accumulators to group 0, two block rows per wave at a time, through the
-        // 64 KiB the panels occupied; group 0 sends the first two block rows on their way to memory
-        // while group 1 writes the other two into LDS
+        // The two groups hold partial sums of the same tile (even and odd steps).  Each hands two of its four block
+        // rows per wave to the other through LDS -- group 1 its first two, group 0 its last two, 64 KiB each way --
+        // and adds and stores the two it keeps: one barrier, and all eight waves store.
         __syncthreads();
-        Out* handover = reinterpret_cast<Out*>(lds_words);
+        Out* handover = reinterpret_cast<Out*>(lds_words) + (kg == 0 ? 16384 : 0);      // where this group writes
+        const Out* incoming = reinterpret_cast<const Out*>(lds_words) + (kg == 0 ? 0 : 16384);
 #pragma unroll
-        for (int half = 0; half < 2; ++half) {
-            if (kg == 1) {
+        for (int rr = 0; rr < 2; ++rr)
 #pragma unroll
-                for (int rr = 0; rr < 2; ++rr)
+            for (int x = 0; x < NT; ++x)
 #pragma unroll
-                    for (int x = 0; x < NT; ++x)
+                for (int y = 0; y < 4; ++y) {
+                    const Out v = kg == 0 ? acc[2 + rr][x][y] : acc[rr][x][y];
+                    handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane] = v;
+                }
+        __syncthreads();
 #pragma unroll
-                        for (int y = 0; y < 4; ++y)
-                            handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane] = acc[2 * half + rr][x][y];
-            }
-            __syncthreads();
-            if (kg == 0) {
+        for (int rr = 0; rr < 2; ++rr)
 #pragma unroll
-                for (int rr = 0; rr < 2; ++rr)
+            for (int x = 0; x < NT; ++x)
 #pragma unroll
-                    for (int x = 0; x < NT; ++x)
-#pragma unroll
-                        for (int y = 0; y < 4; ++y)
-                            acc[2 * half + rr][x][y] += handover[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
-            }
-            if (half == 0) __syncthreads();        // the area is free for the second half
-            if (kg == 0) {
-                store_block_row(2 * half);
-                store_block_row(2 * half + 1);
-            }
+                for (int y = 0; y < 4; ++y) {
+                    const Out v = incoming[(((wave * 2 + rr) * NT + x) * 4 + y) * 64 + lane];
+                    if (kg == 0) acc[rr][x][y] += v;
+                    else acc[2 + rr][x][y] += v;
+                }
+        if (kg == 0) {
+            store_block_row(0);
+            store_block_row(1);
+        } else {
+            store_block_row(2);
+            store_block_row(3);
         }
         return;
     }
