@@ -83,6 +83,12 @@ def run_probes(S, torch, dev, stream):
         buf = torch.ones(nbytes // 4, dtype=torch.int32, device=dev)
         out[label] = nbytes / timed(lambda: S.smat_probe_read(buf, sink, stream)) / 1e9
         del buf
+    # what the L2s deliver to the L1s: 8192 waves each read the same 2 MiB (resident in every XCD's L2, of no use to
+    # the 32 KiB L1s) from another starting point
+    buf = torch.ones((2 << 20) // 4, dtype=torch.int32, device=dev)
+    waves = 8192
+    out["l2_read_2MiB_window_gbs"] = waves * (2 << 20) / timed(lambda: S.smat_probe_read_window(buf, 2 << 20, waves, sink, stream), reps=3) / 1e9
+    del buf
     g = torch.Generator(device="cpu").manual_seed(1)
     waves, packs = 16384, 9
     for row_bytes, lane_bytes in ((128, 8), (256, 16)):
@@ -217,6 +223,16 @@ def roofline_of(bound, kernel_ms, cold_ms, kernel_name, probes):
             out["frac_cold"] = d["issued_flop"] / (cold_ms * 1e-3) / 1e12 / d["mfma_peak"]
         if probes:
             out["frac_of_measured_mfma"] = hot / probes["mfma_16x16x32_f16_tflops"]
+        # what the tile kernel pulls through the L1s, where that can be counted from here (every block of the grid
+        # stored, so every 256 x 128 tile walks K / 32 steps of 16 KiB of block values and an 8 KiB panel of B;
+        # 16-bit types): against the rate at which the L2s fed the L1s in the probe
+        full_grid = bound.info["n_blocks"] == -(-w.M // 16) * -(-w.K // 16) and w.M % 256 == 0 and w.K % 32 == 0
+        if kernel_name.startswith("spmm_dense") and "+" not in kernel_name and full_grid and bound.es == 2:
+            fills = (w.M // 256) * -(-w.N // 128) * (w.K // 32) * 24576
+            out["l1_fill_bytes"] = fills
+            out["l1_fill_gbs"] = fills / (kernel_ms * 1e-3) / 1e9
+            if probes and "l2_read_2MiB_window_gbs" in probes:
+                out["frac_of_measured_l2_read"] = out["l1_fill_gbs"] / probes["l2_read_2MiB_window_gbs"]
     else:
         hot = d["bytes_alg"] / (kernel_ms * 1e-3) / 1e9
         t = cold_ms if cold_ms is not None else kernel_ms
@@ -321,7 +337,8 @@ def main():
              "n_packs": bound.layout["n_packs"], "n_blocks": bound.info["n_blocks"], "nnz": bound.w.nnz,
              "preprocess_s": bound.t_pre, "bind_s": bound.t_bind,
              "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "cache") if k in roof}}
-        for k in ("frac_hot", "frac_cold", "frac_of_measured_gather", "frac_of_measured_mfma", "frac_of_measured_hbm_read", "l1_fill_gbs"):
+        for k in ("frac_hot", "frac_cold", "frac_of_measured_gather", "frac_of_measured_mfma", "frac_of_measured_hbm_read", "l1_fill_gbs",
+                  "frac_of_measured_l2_read"):
             if k in roof:
                 s["roofline"][k] = roof[k]
         if dd["mfma_bound"]:

@@ -2,7 +2,7 @@
  * smat_bench.h -- measurement entry points of the MI355X (gfx950) blocked SpMM library.
  *
  * Not part of the method's interface (that is smat.h): the reduced kernels of the paper's
- * optimisation-step comparison, and five probe kernels that measure what the device delivers
+ * optimisation-step comparison, and six probe kernels that measure what the device delivers
  * for the access patterns the SpMM kernels are made of.  Conventions as in smat.h.
  */
 #ifndef SMAT_BENCH_H
@@ -38,11 +38,15 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
                                  void *dC, int64_t ldc, int64_t N, void *stream);
 
 /*
- * Probes: five kernels that measure what the device delivers for the access patterns the SpMM
+ * Probes: six kernels that measure what the device delivers for the access patterns the SpMM
  * kernels are made of (bench.py --probes times them and prints the rates next to the
  * rooflines).  They compute nothing of the method.  All pointers DEVICE, calls only enqueue.
  *
  *   smat_probe_read    reads `bytes` (a multiple of 8 KiB is read) from dev_buf once, streaming
+ *   smat_probe_read_window  `waves` wavefronts (a multiple of 4) each read the first window_bytes (a
+ *                      multiple of 8 KiB, at most 1 GiB) of dev_buf once, every wave beginning at
+ *                      another place and wrapping round: with a window that fits an XCD's L2
+ *                      this is the rate at which the L2s feed the L1s (waves * window_bytes moved)
  *   smat_probe_gather  `waves` wavefronts each fetch `packs` groups of 32 rows named by dev_idx
  *                      (uint32[waves * packs * 32], row numbers into a table of row_bytes-byte
  *                      rows): 16 lanes x bytes_per_lane (8 or 16) bytes from the start of
@@ -68,6 +72,8 @@ smat_status_t smat_ablation_spmm(const smat_handle_t *h, int level, const void *
  *   dev_sink           4 bytes the kernels may write (they never do for the probe's data)
  */
 smat_status_t smat_probe_read(const void *dev_buf, size_t bytes, void *dev_sink, void *stream);
+smat_status_t smat_probe_read_window(const void *dev_buf, size_t window_bytes, int waves, void *dev_sink,
+                                     void *stream);
 smat_status_t smat_probe_gather(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,
                                 int packs, int bytes_per_lane, void *dev_sink, void *stream);
 smat_status_t smat_probe_pieces(const void *dev_table, uint32_t row_bytes, const uint32_t *dev_idx, int waves,

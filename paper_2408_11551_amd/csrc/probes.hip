@@ -36,6 +36,28 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
     if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) sink[0] = 1u;   // never true for the probe's data; keeps the loads
 }
 
+// Every wave reads the same window of `chunks` x 8 KiB once, beginning at a chunk of its own and wrapping
+// round: the window stays in every XCD's L2 (if it is small enough) while a compute unit's waves, each at
+// another place of it, get nothing out of the 32 KiB L1 -- what the L2s deliver to the L1s for plain
+// 16-byte loads of whole lines.
+__global__ __launch_bounds__(256) void probe_read_window_kernel(const u32x4* __restrict__ src, uint32_t chunks, uint32_t* sink)
+{
+    const uint32_t wave = (blockIdx.x * blockDim.x + threadIdx.x) >> 6;
+    const int lane = threadIdx.x & 63;
+    u32x4 acc = {0u, 0u, 0u, 0u};
+    uint32_t at = (wave * 37u) % chunks;
+    for (uint32_t c = 0; c < chunks; ++c) {
+        const u32x4* from = src + static_cast<size_t>(at) * 512;
+        u32x4 v[8];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) v[u] = from[u * 64 + lane];
+#pragma unroll
+        for (int u = 0; u < 8; ++u) acc ^= v[u];
+        at = at + 1 == chunks ? 0u : at + 1;
+    }
+    if ((acc[0] ^ acc[1] ^ acc[2] ^ acc[3]) == 0x12345678u) sink[0] = 1u;
+}
+
 // One wave per workgroup walks `packs` groups of 32 row numbers; lane (g, i) loads VEC bytes at
 // offset VEC * i of rows idx[8 g + kk], kk = 0..7 -- eight loads in flight per group, four rows
 // per load, as in the SpMM kernel with VEC / 2 columns per lane.
@@ -262,6 +284,16 @@ smat_status_t smat_probe_read(const void* dev_buf, size_t bytes, void* dev_sink,
     if (!dev_buf || !dev_sink || bytes < 8192) return SMAT_ERR_INVALID_ARG;
     hipLaunchKernelGGL(probe_read_kernel, dim3(4096), dim3(256), 0, static_cast<hipStream_t>(stream),
                        static_cast<const u32x4*>(dev_buf), bytes / 16, static_cast<uint32_t*>(dev_sink));
+    return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
+}
+
+smat_status_t smat_probe_read_window(const void* dev_buf, size_t window_bytes, int waves, void* dev_sink, void* stream)
+{
+    if (!dev_buf || !dev_sink || window_bytes < 8192 || window_bytes % 8192 != 0 || window_bytes > (size_t{1} << 30) ||
+        waves < 4 || waves % 4 != 0)
+        return SMAT_ERR_INVALID_ARG;
+    hipLaunchKernelGGL(probe_read_window_kernel, dim3(static_cast<unsigned>(waves / 4)), dim3(256), 0, static_cast<hipStream_t>(stream),
+                       static_cast<const u32x4*>(dev_buf), static_cast<uint32_t>(window_bytes / 8192), static_cast<uint32_t*>(dev_sink));
     return hipGetLastError() == hipSuccess ? SMAT_OK : SMAT_ERR_HIP;
 }
 

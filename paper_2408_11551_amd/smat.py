@@ -71,6 +71,8 @@ def _load():
                                     ctypes.POINTER(vp)]
     lib.smat_probe_read.restype = ctypes.c_int
     lib.smat_probe_read.argtypes = [vp, ctypes.c_size_t, vp, vp]
+    lib.smat_probe_read_window.restype = ctypes.c_int
+    lib.smat_probe_read_window.argtypes = [vp, ctypes.c_size_t, ctypes.c_int, vp, vp]
     lib.smat_probe_gather.restype = ctypes.c_int
     lib.smat_probe_gather.argtypes = [vp, ctypes.c_uint32, vp, ctypes.c_int, ctypes.c_int, ctypes.c_int, vp, vp]
     lib.smat_probe_pieces.restype = ctypes.c_int
@@ -322,6 +324,14 @@ def smat_probe_read(buf, sink, stream=None):
     """buf: device tensor read once end to end; sink: device tensor of >= 4 bytes."""
     _check(_lib.smat_probe_read(ctypes.c_void_p(buf.data_ptr()), buf.numel() * buf.element_size(),
                                 ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
+
+
+def smat_probe_read_window(buf, window_bytes, waves, sink, stream=None):
+    """buf: device tensor whose first window_bytes every one of `waves` wavefronts reads once."""
+    if not buf.is_cuda or not sink.is_cuda or window_bytes > buf.numel() * buf.element_size():
+        raise ValueError("smat_probe_read_window: device tensors, and a window inside buf")
+    _check(_lib.smat_probe_read_window(ctypes.c_void_p(buf.data_ptr()), window_bytes, waves,
+                                       ctypes.c_void_p(sink.data_ptr()), _stream_ptr(stream)))
 
 
 def smat_probe_gather(table, row_bytes, idx, waves, packs, bytes_per_lane, sink, stream=None):

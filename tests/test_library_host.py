@@ -42,7 +42,7 @@ def test_library_exports_every_declared_symbol():
     method, bench = _declared("smat.h"), _declared("smat_bench.h")
     assert {"smat_preprocess", "smat_spmm", "smat_bind_device", "smat_export_bcsr", "smat_get_dims"} <= method
     # the measurement entry points live in their own header, not in the method's
-    assert {"smat_probe_read", "smat_probe_gather", "smat_probe_pieces", "smat_probe_tile_step", "smat_probe_mfma", "smat_ablation_bytes", "smat_ablation_bind",
+    assert {"smat_probe_read", "smat_probe_read_window", "smat_probe_gather", "smat_probe_pieces", "smat_probe_tile_step", "smat_probe_mfma", "smat_ablation_bytes", "smat_ablation_bind",
             "smat_ablation_spmm"} == bench
     assert not any(n.startswith(("smat_probe", "smat_ablation")) for n in method)
     lib = ctypes.CDLL(S.lib_path())

@@ -364,6 +364,9 @@ def test_probe_kernels_run():
     sink = torch.zeros(4, dtype=torch.int32, device="cuda")
     buf = torch.ones(1 << 20, dtype=torch.int32, device="cuda")
     S.smat_probe_read(buf, sink)
+    S.smat_probe_read_window(buf, 1 << 20, 64, sink)
+    with pytest.raises(ValueError):
+        S.smat_probe_read_window(buf, 8 << 20, 64, sink)          # window larger than the buffer
     rows = (buf.numel() * 4) // 256
     idx = torch.randint(0, rows, (64 * 3 * 32,), dtype=torch.int32).cuda()
     S.smat_probe_gather(buf, 256, idx, 64, 3, 16, sink)
