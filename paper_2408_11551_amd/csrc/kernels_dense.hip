@@ -343,6 +343,17 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
 #pragma unroll
         for (int x = 0; x < NT; ++x) acc[r][x] = Acc{0, 0, 0, 0};
 
+    int32_t out_rows[RM][4];
+    if constexpr (KG == 1) {
+        if (ks == 1) {
+#pragma unroll
+            for (int r = 0; r < RM; ++r)
+#pragma unroll
+                for (int y = 0; y < 4; ++y)
+                    out_rows[r][y] = tab.perm[(static_cast<int64_t>(super) * 16 + RM * wave + r) * 16 + 4 * g + y];
+        }
+    }
+
     if (nq > 0) {
         u32x4 a[RD][RM];
         StepMeta mt[RD];
@@ -437,22 +448,24 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
         if constexpr (ES == 1) asm volatile("s_nop 15\n\ts_nop 15");
     }
 
-    // Where the lane's sixteen rows of C' go, asked for before the hand-over so that the stores do not wait for it --
-    // but not before the loop: the sixteen registers are free only now that the ring of block values is dead.  (The
-    // empty statement makes the super row's number a value the compiler knows only from here on; with the loads
-    // hoisted above the loop the 8-bit instantiations spilled registers inside it and ran 79 instead of 53 us.)
-    // (with two groups a lane stores two of its four block rows: group 0 the first two, group 1 the others)
-    int32_t out_rows[RM][4];
-    int super_now = super;
-    asm volatile("" : "+s"(super_now));
-    if (ks == 1) {
+    // Where the lane's rows of C' go.  One group per workgroup: already asked for before the loop (the registers are
+    // there, and the stores then begin without one more trip to memory -- which a short tile on cold caches feels).
+    // Two groups: asked for when the loop ends, ahead of the hand-over, which hides the trip; a lane then stores two
+    // of its four block rows (group 0 the first two, group 1 the others).  (The empty statement makes the super
+    // row's number a value the compiler knows only from here on, so that it cannot move these loads above the loop:
+    // there the 8-bit instantiations once spilled registers inside it and ran 79 instead of 53 us.)
+    if constexpr (KG == 2) {
+        int super_now = super;
+        asm volatile("" : "+s"(super_now));
+        if (ks == 1) {
 #pragma unroll
-        for (int r = 0; r < RM; ++r)
-            if (KG == 1 || (r >> 1) == kg) {
+            for (int r = 0; r < RM; ++r)
+                if ((r >> 1) == kg) {
 #pragma unroll
-                for (int y = 0; y < 4; ++y)
-                    out_rows[r][y] = tab.perm[(static_cast<int64_t>(super_now) * 16 + RM * wave + r) * 16 + 4 * g + y];
-            }
+                    for (int y = 0; y < 4; ++y)
+                        out_rows[r][y] = tab.perm[(static_cast<int64_t>(super_now) * 16 + RM * wave + r) * 16 + 4 * g + y];
+                }
+        }
     }
     // acc[r][x][y] = C'[16 * (16 super + 4 wave + r) + 4g + y][n0 + 16x + i]
     auto store_block_row = [&](int r) {
