@@ -192,6 +192,23 @@ def timed_hot(torch, stream, bound, steps, warmup):
     return wall * 1e3 / steps, ev0.elapsed_time(ev1) / steps
 
 
+def timed_after_idle(torch, stream, bound, reps=10, idle_s=0.3):
+    """`reps` back-to-back launches (the second to the eleventh) between two events after idle_s seconds without work: the chip's power management
+    has let go by then, and the launches run at the clock it grants at first (a launch that keeps the matrix units busy
+    is slowed in two steps within about 3 ms of sustained work; the rocprofv3 traces under profiles/ show the steps)."""
+    bound.step(stream)                       # caches as in the timed region
+    torch.cuda.synchronize()
+    time.sleep(idle_s)
+    bound.step(stream)                       # the launch that wakes the chip up is not timed (it takes 10-20 us longer)
+    a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    a.record(stream)
+    for _ in range(reps):
+        bound.step(stream)
+    b.record(stream)
+    torch.cuda.synchronize()
+    return a.elapsed_time(b) / reps
+
+
 def timed_cold(torch, stream, bound, flush, reps):
     """Each launch between its own events, after a read-only sweep over 1 GiB (more than L2 + the 256 MB
     Infinity Cache) that evicts without leaving dirty lines: everything the launch reads comes from HBM."""
@@ -207,7 +224,7 @@ def timed_cold(torch, stream, bound, flush, reps):
     return np.array([a.elapsed_time(b) for a, b in evs])
 
 
-def roofline_of(bound, kernel_ms, cold_ms, kernel_name, probes):
+def roofline_of(bound, kernel_ms, cold_ms, kernel_name, probes, idle_ms=None):
     """The roofline object of one workload.  HBM-bound: `frac` is the COLD figure (caches emptied before the
     launch), the back-to-back one is `frac_hot`.  MFMA-bound: the hot figure (a block-dense matrix and its B
     fit the Infinity Cache and an application multiplying repeatedly keeps them there); cold beside it."""
@@ -221,6 +238,9 @@ def roofline_of(bound, kernel_ms, cold_ms, kernel_name, probes):
                     "flops_issued": d["issued_flop"], "cache": "hot"})
         if cold_ms is not None:
             out["frac_cold"] = d["issued_flop"] / (cold_ms * 1e-3) / 1e12 / d["mfma_peak"]
+        if idle_ms is not None:
+            # ten launches after a pause: before the power management lowers the clock (the peak is quoted at 2.4 GHz)
+            out["frac_first_launches_after_idle"] = d["issued_flop"] / (idle_ms * 1e-3) / 1e12 / d["mfma_peak"]
         if probes:
             out["frac_of_measured_mfma"] = hot / probes["mfma_16x16x32_f16_tflops"]
         # what the tile kernel pulls through the L1s, where that can be counted from here (every block of the grid
@@ -326,19 +346,20 @@ def main():
 
     cold = timed_cold(torch, stream, head, flush, min(args.steps, 20)) if args.cold else None
     cold_ms = float(cold.mean()) if cold is not None else None
-    roofline = roofline_of(head, kernel_ms, cold_ms, kernel_name, probes)
+    idle_ms = timed_after_idle(torch, stream, head)
+    roofline = roofline_of(head, kernel_ms, cold_ms, kernel_name, probes, idle_ms)
 
-    def summary(bound, ms_wall, k_ms, c_ms, name):
+    def summary(bound, ms_wall, k_ms, c_ms, name, i_ms=None):
         dd = bound.derived()
-        roof = roofline_of(bound, k_ms, c_ms, name, probes)
+        roof = roofline_of(bound, k_ms, c_ms, name, probes, i_ms)
         s = {"workload": WORKLOAD_TEXT[bound.name], "dtype": bound.w.dtype, "kernel": name,
-             "ms": k_ms, "cold_ms": c_ms, "useful_tflops": dd["useful_flop"] / (k_ms * 1e-3) / 1e12,
+             "ms": k_ms, "cold_ms": c_ms, "first_launches_after_idle_ms": i_ms, "useful_tflops": dd["useful_flop"] / (k_ms * 1e-3) / 1e12,
              "bytes_algorithmic": dd["bytes_alg"], "flops_issued": dd["issued_flop"], "b_gather_bytes": dd["b_gather_bytes"],
              "n_packs": bound.layout["n_packs"], "n_blocks": bound.info["n_blocks"], "nnz": bound.w.nnz,
              "preprocess_s": bound.t_pre, "bind_s": bound.t_bind,
              "roofline": {k: roof[k] for k in ("bound", "achieved", "peak", "unit", "frac", "cache") if k in roof}}
         for k in ("frac_hot", "frac_cold", "frac_of_measured_gather", "frac_of_measured_mfma", "frac_of_measured_hbm_read", "l1_fill_gbs",
-                  "frac_of_measured_l2_read"):
+                  "frac_of_measured_l2_read", "frac_first_launches_after_idle"):
             if k in roof:
                 s["roofline"][k] = roof[k]
         if dd["mfma_bound"]:
@@ -348,7 +369,7 @@ def main():
 
     all_configs = None
     if args.all_configs and not head.recast_to and args.reorder == 1 and args.dense_tiles == 0:
-        all_configs = {args.config: summary(head, ms_per_step, kernel_ms, cold_ms, kernel_name)}
+        all_configs = {args.config: summary(head, ms_per_step, kernel_ms, cold_ms, kernel_name, idle_ms)}
         for name in WORKLOAD_TEXT:
             if name == args.config:
                 continue
@@ -356,7 +377,8 @@ def main():
             _, k_ms = timed_hot(torch, stream, other, args.steps, args.warmup)
             nm = S.smat_last_kernel()
             c = timed_cold(torch, stream, other, flush, min(args.steps, 10)) if args.cold else None
-            all_configs[name] = summary(other, None, k_ms, float(c.mean()) if c is not None else None, nm)
+            all_configs[name] = summary(other, None, k_ms, float(c.mean()) if c is not None else None, nm,
+                                        timed_after_idle(torch, stream, other))
             other.close()
             del other
 
@@ -407,6 +429,7 @@ def main():
             "cache": "value and ms_per_step: back-to-back launches (hot); roofline.frac of an HBM-bound launch: caches emptied first (cold)",
         },
         "kernel_ms_events": kernel_ms,
+        "first_launches_after_idle_ms": idle_ms,
         "single_launch_ms": {"mean": float(single.mean()), "median": float(np.median(single)),
                              "min": float(single.min()), "cv": float(single.std() / single.mean())},
         "roofline": roofline,
