@@ -367,7 +367,11 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
             mt[h] = fetch_meta(h + RD);
             __builtin_amdgcn_sched_barrier(0);
         }
-        const int iters = ((nq + KG - 1) / KG + RD - 1) / RD;      // the same for both groups: they share the barriers
+        // steps of a group (the same count for both: they share the barriers; with an odd number of steps the
+        // second group's last one multiplies zeros): whole passes of the three-step loop body, and one or two
+        // steps behind the loop, so that no pass ends in steps that are not there
+        const int gsteps = (nq + KG - 1) / KG;
+        const int iters = gsteps / RD, rem = gsteps % RD;
         // step s of the group, s = u (mod RD): u picks the panel buffer and the register set
         auto step = [&](auto u_, int s) {
             constexpr int u = decltype(u_)::value;
@@ -442,6 +446,8 @@ void spmm_tile_kernel(int n_super, int n_slab, int per_xcd, int N, const int32_t
             step(std::integral_constant<int, 1>{}, RD * it + 1);
             step(std::integral_constant<int, 2>{}, RD * it + 2);
         }
+        if (rem >= 1) step(std::integral_constant<int, 0>{}, RD * iters);
+        if (rem >= 2) step(std::integral_constant<int, 1>{}, RD * iters + 1);
         // nothing may still be on its way into LDS when the buffers get another use or the workgroup ends
         asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)");
         // the last matrix instructions written out by hand have finished before anything reads their result
