@@ -596,6 +596,33 @@ def test_two_handles_on_two_streams_and_rebinding(oracle_c):
     m2.close()
 
 
+@pytest.mark.parametrize("steps", [64, 65, 66, 67, 68, 69])
+def test_tile_kernel_every_tail_of_its_step_loop(steps, oracle_c):
+    """A tile of `steps` steps on the two-group kernel: each group walks ceil(steps / 2) of them, 32 ... 35, i.e. ten
+    or eleven passes of the three-step loop body and zero, one or two steps behind the loop, with an even and an odd
+    total (the second group's last step is then empty).  Once with the steps of a tile split over workgroups (first
+    stream: partial tiles, at most two passes per workgroup) and once unsplit (a second stream on a handle that has one
+    area for partial tiles).  Small integers: the products are exact, so a step left out or taken twice shows."""
+    M, K, N = 512, 32 * steps, 136
+    dtype = "bf16" if steps % 2 else "f16"
+    w = random_csr(M, K, N, 0.12, seed=900 + steps, dtype=dtype, values="smallint", b_dist="smallint")
+    m = S.SmatMatrix(w.M, w.K, w.row_ptr, w.col_idx, w.a_bits, w.dtype, dense_tiles=1, concurrent_streams=1)
+    b = _dev_b(w)
+    c_ref, _ = _oracle_c(oracle_c, w)
+    second = torch.cuda.Stream()
+    cs = [torch.full((w.M, w.N), float("nan"), dtype=torch.float32, device="cuda") for _ in range(2)]
+    torch.cuda.synchronize()
+    S.smat_spmm(m.handle, b, cs[0], w.N)
+    first_name = S.smat_last_kernel()
+    S.smat_spmm(m.handle, b, cs[1], w.N, second)
+    second_name = S.smat_last_kernel()
+    torch.cuda.synchronize()
+    assert first_name == f"spmm_dense_{dtype}_g2k8" and second_name == f"spmm_dense_{dtype}_g2", (first_name, second_name)
+    for c in cs:
+        assert np.array_equal(c.cpu().numpy().astype(np.float64), c_ref)
+    m.close()
+
+
 def test_one_handle_on_several_streams_at_once(oracle_c):
     # smat_spmm is re-entrant: ONE handle, calls in flight on three streams with three C buffers, on a
     # matrix whose launch splits its tiles over workgroups (partial tiles in the workspace).  The first
