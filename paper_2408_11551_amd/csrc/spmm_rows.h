@@ -136,14 +136,14 @@ struct PackOps {
     static constexpr int NQ = (AB + 3) / 4;               // operand dwords that carry data
     __amdgpu_buffer_rsrc_t slots_rsrc, vals_rsrc, none_rsrc, b_rsrc;
     uint32_t slots_voff, vals_voff, lane_off[NCH], ldb_bytes, no_row, row_match;
-    int last;
+    int last, lane_in_wave, group_base;     // group_base: byte address, for ds_bpermute, of the lane that holds the group's entry 0
     bool stream;
 
     __device__ __forceinline__ PackOps(const RowWalk& w, __amdgpu_buffer_rsrc_t b)
         : b_rsrc(b), slots_voff(static_cast<uint32_t>(w.g) * 4u * L),
           vals_voff(ENTRY ? static_cast<uint32_t>(w.g) * EB : static_cast<uint32_t>(w.lane) * AB),
           ldb_bytes(w.ldb_bytes), no_row(w.no_row), row_match(static_cast<uint32_t>(w.lane & 15) * 0x11111111u),
-          last(w.npacks - 1), stream(w.stream)
+          last(w.npacks - 1), lane_in_wave(w.lane), group_base(4 * 8 * w.g), stream(w.stream)
     {
 #pragma unroll
         for (int c = 0; c < NCH; ++c) lane_off[c] = w.lane_off[c];
@@ -168,6 +168,26 @@ struct PackOps {
                 else BLoad<16>::ld(m + x, slots_rsrc, slots_voff + 4u * x, soff);
             }
         }
+    }
+    // The same table for L = 8 with one request of four bytes per lane instead of two of sixteen: lane l fetches
+    // entry l mod 32 of the pack's 32 (the memory pipeline spends its time per lane and byte asked for, also where
+    // sixteen lanes ask for the same bytes: 4 clocks against 32 of the 176 a pack costs it in all), and expand_slots
+    // hands every lane the eight entries of its lane group through the LDS crossbar (no LDS memory involved).
+    __device__ __forceinline__ uint32_t load_slots_compact(int p) const
+    {
+        static_assert(L == 8, "the compact table load is for packs of 32 slots");
+        const uint32_t soff = clamp(p) * 128u;
+        const uint32_t voff = static_cast<uint32_t>(lane_in_wave & 31) * 4u;
+        uint32_t r[1];
+        if (stream) SLoad<4>::ld(r, slots_rsrc, voff, soff);
+        else BLoad<4>::ld(r, slots_rsrc, voff, soff);
+        return r[0];
+    }
+    __device__ __forceinline__ void expand_slots(uint32_t raw, uint32_t (&m)[L]) const
+    {
+#pragma unroll
+        for (int kk = 0; kk < L; ++kk)
+            m[kk] = static_cast<uint32_t>(__builtin_amdgcn_ds_bpermute(group_base + 4 * kk, static_cast<int>(raw)));
     }
     // block values: the lane's L elements (the other operand dwords multiply nothing and stay
     // zero); `live` false (a step past the wave's last pack) reads zeros instead
@@ -286,25 +306,28 @@ __device__ __forceinline__ void walk_row(const RowWalk& w, __amdgpu_buffer_rsrc_
     const int count = (w.npacks - w.ks + KW - 1) / KW;     // packs of this wave
     const int iters = (count + 1) >> 1;
     uint32_t R0[L][NCH][Ops::ND], R1[L][NCH][Ops::ND];
-    uint32_t m0[L], m1[L];
+    uint32_t m[L];
     int p = w.ks;
-    ops.load_slots(p, m0);
+    uint32_t raw0 = ops.load_slots_compact(p);
     __builtin_amdgcn_sched_barrier(0);
-    ops.load_slots(p + KW, m1);
+    uint32_t raw1 = ops.load_slots_compact(p + KW);
     u32x4 a0 = ops.load_a(p, true);
-    int l0 = ops.issue_b(m0, R0), l1;                      // level of the pack (entry rows: its row numbers)
+    ops.expand_slots(raw0, m);
+    int l0 = ops.issue_b(m, R0), l1;                       // level of the pack (entry rows: its row numbers)
     __builtin_amdgcn_sched_barrier(0);
     u32x4 a1 = ops.load_a(p + KW, count > 1);
     for (int it = 0; it < iters; ++it) {
         const int h = 2 * it;                              // pack of this wave multiplied first
-        ops.load_slots(p + 2 * KW, m0);
-        l1 = ops.issue_b(m1, R1);
+        raw0 = ops.load_slots_compact(p + 2 * KW);
+        ops.expand_slots(raw1, m);
+        l1 = ops.issue_b(m, R1);
         __builtin_amdgcn_sched_barrier(0);
         ops.multiply(a0, R0, l0, acc);
         __builtin_amdgcn_sched_barrier(0);
         a0 = ops.load_a(p + 2 * KW, h + 2 < count);
-        ops.load_slots(p + 3 * KW, m1);
-        l0 = ops.issue_b(m0, R0);
+        raw1 = ops.load_slots_compact(p + 3 * KW);
+        ops.expand_slots(raw0, m);
+        l0 = ops.issue_b(m, R0);
         __builtin_amdgcn_sched_barrier(0);
         ops.multiply(a1, R1, l1, acc);
         __builtin_amdgcn_sched_barrier(0);
