@@ -26,7 +26,8 @@
 //
 // Slot table: for every pack, 4 lane groups x L entries of 32 bits; entry [g][kk] is the row
 // of B that slot (g, kk) multiplies, or K (one past the last row) for an empty slot.  A lane
-// reads its group's L entries with one or two loads.
+// reads its group's L entries with one load (L = 2, 4); with L = 8 a lane fetches one entry of the pack's 32 and the
+// lane groups get their eight through the LDS crossbar.
 //
 // Entry rows.  A block row whose occupied columns hold hardly more than one stored entry each
 // (nnz <= 9/8 of the occupied columns, or 3/2 for matrices too large to stay cached; graphs,
